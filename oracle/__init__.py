@@ -1,0 +1,263 @@
+"""CPU oracle (test infrastructure only) for the RNS-CKKS ct-pt MAC + lazy-rescale path.
+
+NumPy front end of ``he_oracle.c`` (plain C, ``unsigned __int128 %`` arithmetic).  Only tests,
+the smoke check and the benchmark's CPU-baseline leg may import this package; the GPU library
+never does, and nothing here imports the GPU package.
+
+Tensors are C-contiguous ``numpy.uint64`` arrays shaped ``[ct][2][limbs][N]``; every residue of
+limb ``i`` lies in ``[0, q[i])``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+PT_SCALAR = 0
+PT_POLY = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "he_oracle.c")
+_LIB = os.path.join(_HERE, "libhe_oracle.so")
+_lib = None
+
+_u64p = ctypes.POINTER(ctypes.c_uint64)
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+
+
+def build(force: bool = False) -> str:
+    """Compile he_oracle.c with gcc -O2 (the optimisation level the paper's evaluation used)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    u64, u32, i32, dbl = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_double
+    sigs = {
+        "orc_mulmod": (u64, [u64, u64, u64]),
+        "orc_powmod": (u64, [u64, u64, u64]),
+        "orc_invmod": (u64, [u64, u64]),
+        "orc_is_prime": (i32, [u64]),
+        "orc_find_psi": (u64, [u64, u64]),
+        "orc_ntt_fwd_direct": (None, [_u64p, _u64p, u64, u64, u64]),
+        "orc_ntt_inv_direct": (None, [_u64p, _u64p, u64, u64, u64]),
+        "orc_ntt_fwd_rows": (None, [_u64p, u64, u32, u64, _u64p, _u64p]),
+        "orc_ntt_inv_rows": (None, [_u64p, u64, u32, u64, _u64p, _u64p]),
+        "orc_encode_scalar": (i32, [dbl, dbl, _u64p, u32, _u64p]),
+        "orc_add": (None, [_u64p, u64, u32, u64, _u64p, _u64p, i32]),
+        "orc_mac": (None, [u64, u32, _u64p, _u64p, _u32p, _u32p, _u32p, u32, _u64p, i32, _u64p, _u64p]),
+        "orc_divide_round": (None, [_u64p, _u64p, u64, u32, u64, _u64p]),
+        "orc_rescale": (None, [u64, u32, _u64p, _u64p, _u64p, _u64p, u64]),
+        "orc_layer": (u32, [u64, u32, _u64p, _u64p, _u64p, _u32p, _u32p, _u32p, u32, _u64p, i32,
+                            _u64p, _u64p]),
+        "orc_set_threads": (i32, [i32]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _a64(x) -> np.ndarray:
+    return np.ascontiguousarray(x, dtype=np.uint64)
+
+
+def _a32(x) -> np.ndarray:
+    return np.ascontiguousarray(x, dtype=np.uint32)
+
+
+def _p64(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_u64p)
+
+
+def _p32(a: np.ndarray):
+    return a.ctypes.data_as(_u32p)
+
+
+# ----------------------------------------------------------------------------- scalars
+
+def mulmod(a: int, b: int, q: int) -> int:
+    return int(_load().orc_mulmod(a, b, q))
+
+
+def powmod(a: int, e: int, q: int) -> int:
+    return int(_load().orc_powmod(a, e, q))
+
+
+def invmod(a: int, q: int) -> int:
+    return int(_load().orc_invmod(a, q))
+
+
+def is_prime(q: int) -> bool:
+    return bool(_load().orc_is_prime(q))
+
+
+def find_psi(q: int, N: int) -> int:
+    """Smallest psi in [2, q) with psi^N = -1 mod q (the root the NTT entry points use)."""
+    psi = int(_load().orc_find_psi(q, N))
+    if psi == 0:
+        raise ValueError(f"no primitive 2N-th root of unity mod {q} for N={N}")
+    return psi
+
+
+def find_psis(q: Sequence[int], N: int) -> list:
+    return [find_psi(int(qi), N) for qi in q]
+
+
+def set_threads(n: int) -> int:
+    """Set the OpenMP thread count (0 = leave unchanged); returns the count in effect."""
+    return int(_load().orc_set_threads(int(n)))
+
+
+# ----------------------------------------------------------------------------- NTT
+
+def ntt_fwd_direct(a, q: int, psi: int) -> np.ndarray:
+    """O(N^2) definition: out[j] = a(psi^(2*bitrev(j)+1)) mod q."""
+    a = _a64(a)
+    out = np.empty_like(a)
+    _load().orc_ntt_fwd_direct(_p64(a), _p64(out), a.size, q, psi)
+    return out
+
+
+def ntt_inv_direct(x, q: int, psi: int) -> np.ndarray:
+    x = _a64(x)
+    out = np.empty_like(x)
+    _load().orc_ntt_inv_direct(_p64(x), _p64(out), x.size, q, psi)
+    return out
+
+
+def _rows(data, q, psi, fn_name) -> np.ndarray:
+    out = _a64(data).copy()
+    q = _a64(q)
+    psi = _a64(psi)
+    limbs = q.size
+    N = out.shape[-1]
+    rows = out.size // N
+    if out.ndim < 2 or out.shape[-2] != limbs or rows % limbs:
+        raise ValueError("expected [..., limbs, N]")
+    getattr(_load(), fn_name)(_p64(out), rows // limbs, limbs, N, _p64(q), _p64(psi))
+    return out
+
+
+def ntt_fwd(data, q, psi) -> np.ndarray:
+    """Forward negacyclic NTT of every row of a [..., limbs, N] array (returns a copy)."""
+    return _rows(data, q, psi, "orc_ntt_fwd_rows")
+
+
+def ntt_inv(data, q, psi) -> np.ndarray:
+    return _rows(data, q, psi, "orc_ntt_inv_rows")
+
+
+# ----------------------------------------------------------------------------- Alg. 2
+
+def encode_scalar(value: float, scale: float, q) -> np.ndarray:
+    """Alg. 2: [round(scale*value)]_{q_i} for each limb -> uint64[limbs] (8*limbs bytes)."""
+    q = _a64(q)
+    out = np.empty(q.size, dtype=np.uint64)
+    rc = _load().orc_encode_scalar(float(value), float(scale), _p64(q), q.size, _p64(out))
+    if rc != 0:
+        raise ValueError("scale*value is not finite")
+    return out
+
+
+def encode_scalars(values, scale: float, q) -> np.ndarray:
+    values = np.asarray(values, dtype=np.float64).ravel()
+    return np.stack([encode_scalar(v, scale, q) for v in values]) if values.size else \
+        np.empty((0, len(q)), dtype=np.uint64)
+
+
+# ----------------------------------------------------------------------------- Alg. 3/4, 7/8
+
+def add(ct, q, pt, pt_kind: int) -> np.ndarray:
+    """ct [n][2][limbs][N] + pt ([n][limbs] scalar or [n][limbs][N]) on component 0 (copy)."""
+    out = _a64(ct).copy()
+    q = _a64(q)
+    pt = _a64(pt)
+    n, two, limbs, N = out.shape
+    assert two == 2 and limbs == q.size
+    assert pt.shape == ((n, limbs) if pt_kind == PT_SCALAR else (n, limbs, N))
+    _load().orc_add(_p64(out), n, limbs, N, _p64(q), _p64(pt), pt_kind)
+    return out
+
+
+def mac(ct_in, q, off, term_ct, term_pt, pt, pt_kind: int, bias=None) -> np.ndarray:
+    """out[o] = sum_t ct_in[term_ct[t]] (*) pt[term_pt[t]] (+ bias[o] on component 0)."""
+    ct_in = _a64(ct_in)
+    q = _a64(q)
+    off, term_ct, term_pt = _a32(off), _a32(term_ct), _a32(term_pt)
+    pt = _a64(pt)
+    n_in, two, limbs, N = ct_in.shape
+    assert two == 2 and limbs == q.size
+    n_out = off.size - 1
+    assert off[0] == 0 and off[-1] == term_ct.size == term_pt.size
+    assert term_ct.size == 0 or int(term_ct.max()) < n_in
+    assert term_pt.size == 0 or int(term_pt.max()) < pt.shape[0]
+    assert pt.shape[1:] == ((limbs,) if pt_kind == PT_SCALAR else (limbs, N))
+    if bias is not None:
+        bias = _a64(bias)
+        assert bias.shape == (n_out, limbs)
+    out = np.empty((n_out, 2, limbs, N), dtype=np.uint64)
+    _load().orc_mac(N, limbs, _p64(q), _p64(ct_in), _p32(off), _p32(term_ct), _p32(term_pt), n_out,
+                    _p64(pt), pt_kind, _p64(bias), _p64(out))
+    return out
+
+
+# ----------------------------------------------------------------------------- Eq. (2)
+
+def divide_round(coef, q) -> np.ndarray:
+    """Coefficient-domain Eq. (2): [..., limbs, N] -> [..., limbs-1, N]."""
+    coef = _a64(coef)
+    q = _a64(q)
+    limbs, N = coef.shape[-2:]
+    assert limbs == q.size and limbs >= 2
+    n_polys = coef.size // (limbs * N)
+    out = np.empty(coef.shape[:-2] + (limbs - 1, N), dtype=np.uint64)
+    _load().orc_divide_round(_p64(coef), _p64(out), n_polys, limbs, N, _p64(q))
+    return out
+
+
+def rescale(ct, q, psi) -> np.ndarray:
+    """Eq. (2) on NTT-form ciphertexts: [n][2][limbs][N] -> [n][2][limbs-1][N]."""
+    ct = _a64(ct)
+    q = _a64(q)
+    psi = _a64(psi)
+    n, two, limbs, N = ct.shape
+    assert two == 2 and limbs == q.size == psi.size and limbs >= 2
+    out = np.empty((n, 2, limbs - 1, N), dtype=np.uint64)
+    _load().orc_rescale(N, limbs, _p64(q), _p64(psi), _p64(ct), _p64(out), n)
+    return out
+
+
+def layer(ct_in, q, psi, off, term_ct, term_pt, pt, pt_kind: int, bias=None):
+    """MAC -> bias -> one rescale per output.  Returns (out, number_of_rescales)."""
+    ct_in = _a64(ct_in)
+    q = _a64(q)
+    psi = _a64(psi)
+    off, term_ct, term_pt = _a32(off), _a32(term_ct), _a32(term_pt)
+    pt = _a64(pt)
+    n_in, two, limbs, N = ct_in.shape
+    assert two == 2 and limbs == q.size and limbs >= 2
+    n_out = off.size - 1
+    assert off[0] == 0 and off[-1] == term_ct.size == term_pt.size
+    assert term_ct.size == 0 or int(term_ct.max()) < n_in
+    assert term_pt.size == 0 or int(term_pt.max()) < pt.shape[0]
+    if bias is not None:
+        bias = _a64(bias)
+        assert bias.shape == (n_out, limbs)
+    out = np.empty((n_out, 2, limbs - 1, N), dtype=np.uint64)
+    n_rescales = _load().orc_layer(N, limbs, _p64(q), _p64(psi), _p64(ct_in), _p32(off), _p32(term_ct),
+                                   _p32(term_pt), n_out, _p64(pt), pt_kind, _p64(bias), _p64(out))
+    return out, int(n_rescales)
