@@ -1,0 +1,155 @@
+/*
+ * he.h -- C ABI of the MI355X (gfx950) library for the data-parallel hot path of nGraph-HE2
+ * (arXiv 1908.04172): RNS-CKKS ciphertext x plaintext multiply-accumulate over tensors of
+ * ciphertexts with scalar-encoded plaintexts, plaintext addition, and lazy rescaling.
+ *
+ * Conventions
+ *  - Residue tensors are row-major uint64 [ct][2][limbs][N]: for fixed (ciphertext, component,
+ *    limb) the N residues are contiguous.  Limb i holds residues modulo moduli[i], canonical, in
+ *    [0, q_i).  Ciphertexts are in NTT ("double-CRT") form unless a call says otherwise.
+ *    `limbs` (1..L) is the level: the first `limbs` moduli of the context are in use; a rescale
+ *    drops limb limbs-1.  Inputs outside [0, q_i) are not detected and give undefined residues.
+ *  - "dev" pointers are device (HBM) addresses on the context's GPU, 8-byte aligned; "host"
+ *    pointers are ordinary host memory.  The caller owns every buffer; the library allocates device
+ *    memory only in he_ctx_create and he_plan_create.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device work is
+ *    enqueued on it and no call synchronises with the device, except he_ctx_create,
+ *    he_plan_create and the two destroy calls.
+ *  - Every call returns HE_OK (0) or a negative he_status; nothing aborts or throws.  On an error
+ *    no device work has been enqueued by that call.
+ */
+#ifndef HE_H
+#define HE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum he_status {
+    HE_OK = 0,
+    HE_ERR_ARG = -1,       /* NULL pointer, size zero where not allowed, bad flag or kind */
+    HE_ERR_MODULUS = -2,   /* a modulus is not a prime = 1 (mod 2N) below 2^62, or repeats */
+    HE_ERR_LEVEL = -3,     /* limbs outside [1, L] (or < 2 for a rescale) */
+    HE_ERR_RANGE = -4,     /* a plan index or a size is out of range */
+    HE_ERR_DEVICE = -5,    /* a HIP call failed, or the context has no device */
+    HE_ERR_WORKSPACE = -6  /* workspace missing or too small */
+} he_status;
+
+#define HE_PT_SCALAR 0 /* plaintext = one residue per limb (Alg. 2 / 4 / 8) */
+#define HE_PT_POLY 1   /* plaintext = N residues per limb, NTT form (Alg. 3 / 7) */
+
+#define HE_RESCALE 1u  /* he_ct_pt_mac flag: finish with one lazy rescale per output */
+
+#define HE_MAX_LIMBS 16
+#define HE_MIN_LOG2N 10
+#define HE_MAX_LOG2N 14
+
+typedef struct he_ctx he_ctx;   /* moduli, roots, twiddle tables (device), per-limb constants */
+typedef struct he_plan he_plan; /* which ciphertext meets which plaintext in a layer */
+
+const char* he_strerror(int status);
+
+/*
+ * Context for ring degree N = 2^log2N and the modulus chain moduli[0..L-1] (host).  Each
+ * modulus must be a prime = 1 (mod 2N) below 2^62 ("maximum modulus of 62 bits", Sec.
+ * "Ciphertext-plaintext Multiplication"), all distinct.  For limb i the library fixes
+ * psi_i = the smallest primitive 2N-th root of unity modulo q_i; the NTT entry points are defined
+ * with respect to it.  device >= 0 selects the GPU (tables are uploaded there); device = -1 makes a
+ * host-only context on which only the *_host calls, he_ctx_info and the plan calls work.
+ */
+int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* moduli, int device);
+int he_ctx_destroy(he_ctx* ctx);
+/* Any of the outputs may be NULL.  psi: host [L]. */
+int he_ctx_info(const he_ctx* ctx, uint32_t* log2N, uint32_t* L, uint64_t* moduli, uint64_t* psi);
+
+/*
+ * Scalar encoding, Alg. 2 (Sec. "Scalar Encoding"): out[j][i] = [round(scale * values[j])]_{q_i},
+ * i < limbs.  The product is one IEEE double multiply; rounding is to nearest with halves away
+ * from zero; the residue is the non-negative one.  Products of magnitude >= 2^63 (they are exact
+ * integers m*2^e) are reduced exactly.  A non-finite product yields UINT64_MAX in every limb of
+ * that entry (never a valid residue).  Encoding at a level below L ("Depth-aware Encoding") is
+ * `limbs` < L.
+ *   he_encode_scalar:      values dev [n] double  ->  out dev [n][limbs]   (a kernel on `stream`)
+ *   he_encode_scalar_host: the same arithmetic on the host, values/out host; returns HE_ERR_ARG
+ *                          for a non-finite product.
+ */
+int he_encode_scalar(he_ctx* ctx, const double* values, size_t n, double scale, uint32_t limbs,
+                     uint64_t* out, void* stream);
+int he_encode_scalar_host(const he_ctx* ctx, const double* values, size_t n, double scale,
+                          uint32_t limbs, uint64_t* out);
+
+/*
+ * A MAC plan (Sec. "Lazy Rescaling": an FC or Convolution output is a sum over the inner
+ * dimension / window):  out[o] = sum over t in [off[o], off[o+1]) of
+ * ct_in[term_ct[t]] * pt[term_pt[t]].  All three arrays are host memory and are copied;
+ * off has n_out+1 entries, off[0] = 0, non-decreasing; term_ct[t] < n_in; term_pt[t] < n_pt.
+ * Outputs that read the same ciphertexts in the same order (the output channels of one
+ * convolution window, the outputs of a dense layer) are grouped so that each input is loaded once
+ * per group.  Needs a device context.
+ */
+int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, const uint32_t* off,
+                   const uint32_t* term_ct, const uint32_t* term_pt, he_plan** out);
+int he_plan_destroy(he_plan* plan);
+/* Device bytes he_ct_pt_mac needs in `workspace` for this plan, level and flags. */
+int he_plan_workspace_bytes(const he_plan* plan, uint32_t limbs, int pt_kind, uint32_t flags,
+                            size_t* bytes);
+
+/*
+ * Ciphertext x plaintext multiply-accumulate, Alg. 7 (HE_PT_POLY: pt dev [n_pt][limbs][N], NTT
+ * form, slot-wise product) and Alg. 8 (HE_PT_SCALAR: pt dev [n_pt][limbs]) summed per the plan;
+ * both ciphertext components are multiplied.  bias (dev [n_out][limbs] scalar residues, or NULL)
+ * is added to component 0 after the sum (Alg. 4; "addition is allowed post-multiplication,
+ * pre-rescaling").
+ *   flags = 0:          ct_out dev [n_out][2][limbs][N]
+ *   flags = HE_RESCALE: ct_out dev [n_out][2][limbs-1][N]; each output is rescaled exactly once,
+ *                       after its MACs and bias (lazy rescaling); needs limbs >= 2.
+ * ct_in dev [n_in][2][limbs][N].  ct_out must not overlap ct_in, pt or workspace.
+ * workspace: dev, at least he_plan_workspace_bytes() bytes (may be NULL if that is 0).
+ */
+int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_t* ct_in,
+                 const uint64_t* pt, int pt_kind, const uint64_t* bias, uint64_t* ct_out,
+                 uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Ciphertext + plaintext, Alg. 3 (HE_PT_POLY: pt dev [n][limbs][N]) and Alg. 4 (HE_PT_SCALAR:
+ * pt dev [n][limbs]), in place on component 0 of each of the n ciphertexts ct dev
+ * [n][2][limbs][N]; component 1 is not touched.
+ */
+int he_ct_pt_add(he_ctx* ctx, uint32_t limbs, uint64_t* ct, uint32_t n, const uint64_t* pt,
+                 int pt_kind, void* stream);
+
+/*
+ * Rescaling, Eq. (2), read as ct' = round(ct / q_{limbs-1}) on the integer coefficients:
+ * in dev [n][2][limbs][N] (NTT form) -> out dev [n][2][limbs-1][N] (NTT form), limbs >= 2.
+ * out must not overlap in.
+ */
+int he_rescale(he_ctx* ctx, uint32_t limbs, const uint64_t* in, uint64_t* out, uint32_t n,
+               void* stream);
+
+/*
+ * Negacyclic NTT (Sec. "Double-CRT Representation") in place over data dev [n_polys][limbs][N]
+ * (a [ct][2][limbs][N] tensor is n_polys = 2*ct).  Forward: coefficients in natural order ->
+ * slot j = value of the polynomial at psi_i^(2*bitrev(j)+1), bitrev over log2N bits.  Inverse:
+ * the exact inverse map (includes N^-1).  Outputs are canonical.
+ */
+int he_ntt_fwd(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, void* stream);
+int he_ntt_inv(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, void* stream);
+
+/*
+ * Host-side checks of the device arithmetic (the same inline functions the kernels use, compiled
+ * for the host): a*b mod q by 128-bit Barrett reduction (Alg. 5), and the lazy Shoup product used
+ * in the NTT butterflies.  For tests; no device needed.
+ */
+uint64_t he_host_mulmod(uint64_t a, uint64_t b, uint64_t q);
+uint64_t he_host_reduce128(uint64_t hi, uint64_t lo, uint64_t q);
+uint64_t he_host_shoup_mulmod(uint64_t y, uint64_t w, uint64_t q);
+/* The accumulator the MAC kernels use, run on the host: sum of x[t]*w[t] (n terms) mod q. */
+uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HE_H */

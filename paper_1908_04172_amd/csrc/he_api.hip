@@ -1,0 +1,533 @@
+// Context, plans, the C entry points, and the small kernels (scalar encoding, plaintext addition).
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "he_internal.h"
+
+// ------------------------------------------------------------------------------------------------
+// host number theory (context set-up only)
+
+namespace {
+
+u64 h_mulmod(u64 a, u64 b, u64 q) { return (u64)((u128)a * b % q); }
+
+u64 h_powmod(u64 b, u64 e, u64 q) {
+    u64 r = 1 % q;
+    b %= q;
+    for (; e; e >>= 1) {
+        if (e & 1) r = h_mulmod(r, b, q);
+        b = h_mulmod(b, b, q);
+    }
+    return r;
+}
+
+// Miller-Rabin with the first twelve primes as witnesses: exact for every 64-bit input.
+bool h_is_prime(u64 n) {
+    const u64 wit[12] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+    if (n < 2) return false;
+    for (u64 p : wit) {
+        if (n == p) return true;
+        if (n % p == 0) return false;
+    }
+    u64 d = n - 1;
+    int twos = 0;
+    while (!(d & 1)) { d >>= 1; ++twos; }
+    for (u64 a : wit) {
+        u64 x = h_powmod(a, d, n);
+        if (x == 1 || x == n - 1) continue;
+        bool witness = true;
+        for (int i = 1; i < twos && witness; ++i) {
+            x = h_mulmod(x, x, n);
+            if (x == n - 1) witness = false;
+        }
+        if (witness) return false;
+    }
+    return true;
+}
+
+// The least element of order 2N with psi^N = -1: take any root of x^N + 1 (a 2N-th root of a
+// non-residue-like generator power), then walk its odd powers, which are all the roots.
+u64 h_min_psi(u64 q, u32 N) {
+    const u64 cof = (q - 1) / (2ull * N);
+    u64 root = 0;
+    for (u64 g = 2; g < 4096 && root == 0; ++g) {
+        u64 cand = h_powmod(g, cof, q);
+        if (h_powmod(cand, N, q) == q - 1) root = cand;
+    }
+    if (!root) return 0;
+    const u64 step = h_mulmod(root, root, q);
+    u64 best = root, cur = root;
+    for (u32 k = 1; k < N; ++k) {
+        cur = h_mulmod(cur, step, q);
+        best = std::min(best, cur);
+    }
+    return best;
+}
+
+u64 h_shoup(u64 w, u64 q) { return (u64)(((u128)w << 64) / q); }
+
+u32 h_bitrev(u32 x, u32 bits) {
+    u32 r = 0;
+    for (u32 i = 0; i < bits; ++i) r |= ((x >> i) & 1u) << (bits - 1 - i);
+    return r;
+}
+
+void fill_limb_const(LimbConst& c, u64 q, u64 psi, u32 N) {
+    c.q = q;
+    c.two_q = 2 * q;
+    const u128 all_ones = ~(u128)0;  // floor(2^128 / q) = floor((2^128 - 1) / q) because q is odd and > 1
+    const u128 ratio = all_ones / q;
+    c.ratio_hi = (u64)(ratio >> 64);
+    c.ratio_lo = (u64)ratio;
+    c.n_inv = h_powmod(N % q, q - 2, q);
+    c.n_inv_shoup = h_shoup(c.n_inv, q);
+    const u64 psi_inv = h_powmod(psi, q - 2, q);
+    const u64 w1_inv = h_powmod(psi_inv, N / 2, q);  // psi^-bitrev(1)
+    c.w1n_inv = h_mulmod(w1_inv, c.n_inv, q);
+    c.w1n_inv_shoup = h_shoup(c.w1n_inv, q);
+    // accumulator bounds (see MacAcc): a term adds at most 2*(2^32-1)*qh to `mid`, qh = floor((q-1)/2^32)
+    const u64 qh = (q - 1) >> 32;
+    u64 fold = qh ? ((~0ull - 0xFFFFFFFFull) / (2 * 0xFFFFFFFFull * qh)) : 0x7FFFFFFFull;
+    c.fold_every = (u32)std::min<u64>(std::max<u64>(fold, 1), 0x7FFFFFFFull);
+    // q + R*(q-1)^2 must stay below 2^128
+    const u128 sq = (u128)(q - 1) * (q - 1);
+    u128 red = (all_ones - q) / sq;
+    c.reduce_every = (u32)std::min<u128>(std::max<u128>(red, 1), 0x7FFFFFFFull);
+}
+
+int check_level(const he_ctx* ctx, u32 limbs, u32 min_limbs) {
+    if (!ctx) return HE_ERR_ARG;
+    if (limbs < min_limbs || limbs > ctx->L) return HE_ERR_LEVEL;
+    return HE_OK;
+}
+
+int need_device(const he_ctx* ctx) {
+    if (ctx->device < 0) return HE_ERR_DEVICE;
+    if (hipSetDevice(ctx->device) != hipSuccess) { (void)hipGetLastError(); return HE_ERR_DEVICE; }
+    return HE_OK;
+}
+
+template <typename T>
+int upload(T** dst, const T* src, size_t n) {
+    *dst = nullptr;
+    if (n == 0) n = 1;
+    HE_HIP(hipMalloc((void**)dst, n * sizeof(T)));
+    if (src) HE_HIP(hipMemcpy(*dst, src, n * sizeof(T), hipMemcpyHostToDevice));
+    return HE_OK;
+}
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// ------------------------------------------------------------------------------------------------
+// Alg. 2 on one value (shared by the kernel and the host entry point)
+
+HE_HD bool encode_one(double value, double scale, const LimbConst* lc, u32 limbs, u64* out) {
+    const double v = value * scale;
+    const double mag = v < 0 ? -v : v;
+    if (!(mag <= 1.7976931348623157e308)) {  // NaN or infinity
+        for (u32 i = 0; i < limbs; ++i) out[i] = ~0ull;
+        return false;
+    }
+    const bool negative = v < 0;
+    for (u32 i = 0; i < limbs; ++i) {
+        const LimbConst& c = lc[i];
+        u64 r;
+        if (mag < 9223372036854775808.0) {
+            const double whole = trunc(mag);
+            u64 z = (u64)whole;
+            if (mag - whole >= 0.5) z += 1;  // mag - whole is exact; halves go away from zero
+            r = reduce64(z, c);
+        } else {
+            // mag = m * 2^e exactly, m a 53-bit integer, e >= 11
+            u64 bits;
+            __builtin_memcpy(&bits, &mag, sizeof bits);
+            const u64 m = (bits & 0xFFFFFFFFFFFFFull) | (1ull << 52);
+            u32 e = (u32)(bits >> 52) - 1075u;
+            u64 pow2 = 1, base = 2;
+            for (; e; e >>= 1) {
+                if (e & 1) pow2 = mul_mod(pow2, base, c);
+                base = mul_mod(base, base, c);
+            }
+            r = mul_mod(reduce64(m, c), pow2, c);
+        }
+        out[i] = (negative && r) ? c.q - r : r;
+    }
+    return true;
+}
+
+__global__ void __launch_bounds__(256) encode_kernel(LimbTable lt, const double* values, size_t n, double scale, u32 limbs,
+                                                     u64* out) {
+    const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    u64 tmp[HE_MAX_LIMBS];
+    encode_one(values[j], scale, lt.c, limbs, tmp);
+    for (u32 i = 0; i < limbs; ++i) out[j * limbs + i] = tmp[i];
+}
+
+// Alg. 4 / Alg. 3: component 0 of every ciphertext gets the plaintext added.  A thread handles two
+// adjacent residues (16-byte accesses); grid = ct * limbs * N/2 threads.
+template <bool POLY>
+__global__ void __launch_bounds__(256) add_kernel(LimbTable lt, u32 limbs, u32 N, u64* ct, size_t n_ct, const u64* pt) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // pair index
+    const size_t half = N / 2;
+    const size_t total = n_ct * limbs * half;
+    if (i >= total) return;
+    const size_t k2 = i % half;
+    const size_t row = i / half;  // ct * limbs + limb
+    const u32 limb = (u32)(row % limbs);
+    const size_t c_idx = row / limbs;
+    const u64 q = lt.c[limb].q;
+    ulonglong2* p = reinterpret_cast<ulonglong2*>(ct + ((c_idx * 2) * limbs + limb) * N) + k2;
+    ulonglong2 v = *p;
+    ulonglong2 a;
+    if constexpr (POLY) {
+        a = reinterpret_cast<const ulonglong2*>(pt + row * N)[k2];
+    } else {
+        a.x = a.y = pt[row];
+    }
+    v.x = add_mod(v.x, a.x, q);
+    v.y = add_mod(v.y, a.y, q);
+    *p = v;
+}
+
+// Group consecutive outputs whose term_ct lists are identical, at most `cap` per group.
+void build_tiles(const u32* off, const u32* term_ct, u32 n_out, u32 cap, std::vector<Tile>& tiles) {
+    u32 o = 0;
+    while (o < n_out) {
+        const u32 k = off[o + 1] - off[o];
+        u32 cnt = 1;
+        while (cnt < cap && o + cnt < n_out) {
+            const u32 o2 = o + cnt;
+            if (off[o2 + 1] - off[o2] != k) break;
+            if (k && memcmp(term_ct + off[o], term_ct + off[o2], (size_t)k * sizeof(u32)) != 0) break;
+            ++cnt;
+        }
+        tiles.push_back(Tile{o, cnt, off[o], k});
+        o += cnt;
+    }
+}
+
+// Stable sort of the tiles into capacity classes caps[0] < caps[1] < caps[2].
+void classify(std::vector<Tile>& tiles, const u32 caps[3], u32 class_begin[4]) {
+    std::vector<Tile> sorted;
+    sorted.reserve(tiles.size());
+    for (int cls = 0; cls < 3; ++cls) {
+        class_begin[cls] = (u32)sorted.size();
+        for (const Tile& t : tiles) {
+            const u32 lo = cls ? caps[cls - 1] : 0;
+            if (t.count > lo && t.count <= caps[cls]) sorted.push_back(t);
+        }
+    }
+    class_begin[3] = (u32)sorted.size();
+    tiles.swap(sorted);
+}
+
+const u32 CAPS_S[3] = {1, 4, 16};
+const u32 CAPS_P[3] = {1, 2, 8};
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// ABI
+
+extern "C" {
+
+const char* he_strerror(int status) {
+    switch (status) {
+        case HE_OK: return "ok";
+        case HE_ERR_ARG: return "bad argument";
+        case HE_ERR_MODULUS: return "modulus is not a distinct prime = 1 (mod 2N) below 2^62";
+        case HE_ERR_LEVEL: return "limbs out of range for this context or operation";
+        case HE_ERR_RANGE: return "index or size out of range";
+        case HE_ERR_DEVICE: return "HIP call failed or context has no device";
+        case HE_ERR_WORKSPACE: return "workspace missing or too small";
+    }
+    return "unknown status";
+}
+
+int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* moduli, int device) {
+    if (!out) return HE_ERR_ARG;
+    *out = nullptr;
+    if (!moduli || log2N < HE_MIN_LOG2N || log2N > HE_MAX_LOG2N || L < 1 || L > HE_MAX_LIMBS || device < -1)
+        return HE_ERR_ARG;
+    const u32 N = 1u << log2N;
+    for (u32 i = 0; i < L; ++i) {
+        const u64 q = moduli[i];
+        if (q >= (1ull << 62) || q < 2ull * N || (q - 1) % (2ull * N) != 0 || !h_is_prime(q)) return HE_ERR_MODULUS;
+        for (u32 j = 0; j < i; ++j)
+            if (moduli[j] == q) return HE_ERR_MODULUS;
+    }
+    he_ctx* ctx = new (std::nothrow) he_ctx();
+    if (!ctx) return HE_ERR_ARG;
+    memset(ctx, 0, sizeof *ctx);
+    ctx->device = device;
+    ctx->log2N = log2N;
+    ctx->N = N;
+    ctx->L = L;
+    for (u32 i = 0; i < L; ++i) {
+        ctx->q[i] = moduli[i];
+        ctx->psi[i] = h_min_psi(moduli[i], N);
+        if (!ctx->psi[i]) { delete ctx; return HE_ERR_MODULUS; }
+        fill_limb_const(ctx->limbs.c[i], ctx->q[i], ctx->psi[i], N);
+    }
+    for (u32 j = 0; j < L; ++j)
+        for (u32 i = 0; i < L; ++i) {
+            if (i == j) continue;
+            DropConst& d = ctx->drop[j][i];
+            const u64 qi = ctx->q[i], p = ctx->q[j];
+            d.p_inv = h_powmod(p % qi, qi - 2, qi);
+            d.p_inv_shoup = h_shoup(d.p_inv, qi);
+            d.half_mod = (p >> 1) % qi;
+        }
+    if (device >= 0) {
+        int rc = need_device(ctx);
+        if (rc != HE_OK) { delete ctx; return rc; }
+        std::vector<u64> fwd((size_t)L * N * 2), inv((size_t)L * N * 2);
+        for (u32 i = 0; i < L; ++i) {
+            const u64 q = ctx->q[i], psi = ctx->psi[i], psi_inv = h_powmod(psi, q - 2, q);
+            u64 pw = 1, pwi = 1;
+            for (u32 k = 0; k < N; ++k) {
+                const size_t slot = ((size_t)i * N + h_bitrev(k, log2N)) * 2;
+                fwd[slot] = pw;
+                fwd[slot + 1] = h_shoup(pw, q);
+                inv[slot] = pwi;
+                inv[slot + 1] = h_shoup(pwi, q);
+                pw = h_mulmod(pw, psi, q);
+                pwi = h_mulmod(pwi, psi_inv, q);
+            }
+        }
+        if (upload(&ctx->tw_fwd, fwd.data(), fwd.size()) != HE_OK || upload(&ctx->tw_inv, inv.data(), inv.size()) != HE_OK ||
+            upload(&ctx->drop_dev, &ctx->drop[0][0], (size_t)HE_MAX_LIMBS * HE_MAX_LIMBS) != HE_OK) {
+            he_ctx_destroy(ctx);
+            return HE_ERR_DEVICE;
+        }
+    }
+    *out = ctx;
+    return HE_OK;
+}
+
+int he_ctx_destroy(he_ctx* ctx) {
+    if (!ctx) return HE_ERR_ARG;
+    if (ctx->device >= 0 && hipSetDevice(ctx->device) == hipSuccess) {
+        if (ctx->tw_fwd) (void)hipFree(ctx->tw_fwd);
+        if (ctx->tw_inv) (void)hipFree(ctx->tw_inv);
+        if (ctx->drop_dev) (void)hipFree(ctx->drop_dev);
+    }
+    delete ctx;
+    return HE_OK;
+}
+
+int he_ctx_info(const he_ctx* ctx, uint32_t* log2N, uint32_t* L, uint64_t* moduli, uint64_t* psi) {
+    if (!ctx) return HE_ERR_ARG;
+    if (log2N) *log2N = ctx->log2N;
+    if (L) *L = ctx->L;
+    for (u32 i = 0; i < ctx->L; ++i) {
+        if (moduli) moduli[i] = ctx->q[i];
+        if (psi) psi[i] = ctx->psi[i];
+    }
+    return HE_OK;
+}
+
+int he_encode_scalar(he_ctx* ctx, const double* values, size_t n, double scale, uint32_t limbs, uint64_t* out,
+                     void* stream) {
+    int rc = check_level(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (n == 0) return HE_OK;
+    if (!values || !out) return HE_ERR_ARG;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    const size_t blocks = (n + 255) / 256;
+    if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
+    hipLaunchKernelGGL(encode_kernel, dim3((u32)blocks), dim3(256), 0, (hipStream_t)stream, ctx->limbs, values, n, scale,
+                       limbs, out);
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+int he_encode_scalar_host(const he_ctx* ctx, const double* values, size_t n, double scale, uint32_t limbs,
+                          uint64_t* out) {
+    int rc = check_level(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (n == 0) return HE_OK;
+    if (!values || !out) return HE_ERR_ARG;
+    bool ok = true;
+    for (size_t j = 0; j < n; ++j) ok &= encode_one(values[j], scale, ctx->limbs.c, limbs, out + j * limbs);
+    return ok ? HE_OK : HE_ERR_ARG;
+}
+
+int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, const uint32_t* off,
+                   const uint32_t* term_ct, const uint32_t* term_pt, he_plan** out) {
+    if (!out) return HE_ERR_ARG;
+    *out = nullptr;
+    if (!ctx || !off) return HE_ERR_ARG;
+    if (off[0] != 0) return HE_ERR_RANGE;
+    for (u32 o = 0; o < n_out; ++o)
+        if (off[o + 1] < off[o]) return HE_ERR_RANGE;
+    const u32 n_terms = off[n_out];
+    if (n_terms && (!term_ct || !term_pt)) return HE_ERR_ARG;
+    for (u32 t = 0; t < n_terms; ++t)
+        if (term_ct[t] >= n_in || term_pt[t] >= n_pt) return HE_ERR_RANGE;
+    int rc = need_device(ctx);
+    if (rc != HE_OK) return rc;
+    he_plan* p = new (std::nothrow) he_plan();
+    if (!p) return HE_ERR_ARG;
+    p->ctx = ctx;
+    p->n_in = n_in; p->n_out = n_out; p->n_pt = n_pt; p->n_terms = n_terms;
+    p->off.assign(off, off + n_out + 1);
+    p->tiles_s_dev = p->tiles_p_dev = nullptr;
+    p->wbase_s_dev = nullptr;
+    p->off_dev = p->term_ct_dev = p->term_pt_dev = nullptr;
+    std::vector<Tile> ts, tp;
+    build_tiles(off, term_ct, n_out, CAPS_S[2], ts);
+    build_tiles(off, term_ct, n_out, CAPS_P[2], tp);
+    classify(ts, CAPS_S, p->class_begin_s);
+    classify(tp, CAPS_P, p->class_begin_p);
+    p->n_tiles_s = (u32)ts.size();
+    p->n_tiles_p = (u32)tp.size();
+    std::vector<u64> wbase(ts.size() + 1, 0);
+    u64 elems = 0;
+    for (int cls = 0; cls < 3; ++cls)
+        for (u32 i = p->class_begin_s[cls]; i < p->class_begin_s[cls + 1]; ++i) {
+            wbase[i] = elems;
+            elems += (u64)ts[i].n_terms * CAPS_S[cls];
+        }
+    p->wtab_elems = elems;
+    if (upload(&p->tiles_s_dev, ts.data(), ts.size()) != HE_OK || upload(&p->tiles_p_dev, tp.data(), tp.size()) != HE_OK ||
+        upload(&p->wbase_s_dev, wbase.data(), ts.size()) != HE_OK || upload(&p->off_dev, off, (size_t)n_out + 1) != HE_OK ||
+        upload(&p->term_ct_dev, term_ct, n_terms) != HE_OK || upload(&p->term_pt_dev, term_pt, n_terms) != HE_OK) {
+        he_plan_destroy(p);
+        return HE_ERR_DEVICE;
+    }
+    *out = p;
+    return HE_OK;
+}
+
+int he_plan_destroy(he_plan* p) {
+    if (!p) return HE_ERR_ARG;
+    if (p->ctx && p->ctx->device >= 0 && hipSetDevice(p->ctx->device) == hipSuccess) {
+        void* bufs[] = {p->tiles_s_dev, p->tiles_p_dev, p->wbase_s_dev, p->off_dev, p->term_ct_dev, p->term_pt_dev};
+        for (void* b : bufs)
+            if (b) (void)hipFree(b);
+    }
+    delete p;
+    return HE_OK;
+}
+
+int he_plan_workspace_bytes(const he_plan* plan, uint32_t limbs, int pt_kind, uint32_t flags, size_t* bytes) {
+    if (!plan || !bytes) return HE_ERR_ARG;
+    if (pt_kind != HE_PT_SCALAR && pt_kind != HE_PT_POLY) return HE_ERR_ARG;
+    if (flags & ~HE_RESCALE) return HE_ERR_ARG;
+    int rc = check_level(plan->ctx, limbs, (flags & HE_RESCALE) ? 2 : 1);
+    if (rc != HE_OK) return rc;
+    size_t b = 0;
+    if (pt_kind == HE_PT_SCALAR) b += align256((size_t)plan->wtab_elems * limbs * sizeof(u64));
+    if (flags & HE_RESCALE) b += align256((size_t)plan->n_out * 2 * limbs * plan->ctx->N * sizeof(u64));
+    *bytes = b;
+    return HE_OK;
+}
+
+int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_t* ct_in, const uint64_t* pt,
+                 int pt_kind, const uint64_t* bias, uint64_t* ct_out, uint32_t flags, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+    if (!ctx || !plan || plan->ctx != ctx) return HE_ERR_ARG;
+    size_t need = 0;
+    int rc = he_plan_workspace_bytes(plan, limbs, pt_kind, flags, &need);
+    if (rc != HE_OK) return rc;
+    if (plan->n_out == 0) return HE_OK;
+    if (!ct_out || (plan->n_terms && (!ct_in || !pt))) return HE_ERR_ARG;
+    if (need && (!workspace || workspace_bytes < need)) return HE_ERR_WORKSPACE;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    char* ws = (char*)workspace;
+    u64* wtab = nullptr;
+    if (pt_kind == HE_PT_SCALAR) {
+        wtab = (u64*)ws;
+        ws += align256((size_t)plan->wtab_elems * limbs * sizeof(u64));
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (flags & HE_RESCALE) {
+        u64* acc = (u64*)ws;
+        if ((rc = launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, acc, wtab, s)) != HE_OK) return rc;
+        return launch_rescale(ctx, limbs, acc, ct_out, plan->n_out, s);
+    }
+    return launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, wtab, s);
+}
+
+int he_ct_pt_add(he_ctx* ctx, uint32_t limbs, uint64_t* ct, uint32_t n, const uint64_t* pt, int pt_kind,
+                 void* stream) {
+    int rc = check_level(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (pt_kind != HE_PT_SCALAR && pt_kind != HE_PT_POLY) return HE_ERR_ARG;
+    if (n == 0) return HE_OK;
+    if (!ct || !pt) return HE_ERR_ARG;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    const size_t total = (size_t)n * limbs * (ctx->N / 2);
+    const size_t blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
+    if (pt_kind == HE_PT_POLY)
+        hipLaunchKernelGGL(add_kernel<true>, dim3((u32)blocks), dim3(256), 0, (hipStream_t)stream, ctx->limbs, limbs, ctx->N,
+                           ct, (size_t)n, pt);
+    else
+        hipLaunchKernelGGL(add_kernel<false>, dim3((u32)blocks), dim3(256), 0, (hipStream_t)stream, ctx->limbs, limbs, ctx->N,
+                           ct, (size_t)n, pt);
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+int he_rescale(he_ctx* ctx, uint32_t limbs, const uint64_t* in, uint64_t* out, uint32_t n, void* stream) {
+    int rc = check_level(ctx, limbs, 2);
+    if (rc != HE_OK) return rc;
+    if (n == 0) return HE_OK;
+    if (!in || !out) return HE_ERR_ARG;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    return launch_rescale(ctx, limbs, in, out, n, (hipStream_t)stream);
+}
+
+int he_ntt_fwd(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, void* stream) {
+    int rc = check_level(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (n_polys == 0) return HE_OK;
+    if (!data) return HE_ERR_ARG;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    return launch_ntt(ctx, limbs, data, n_polys, false, (hipStream_t)stream);
+}
+
+int he_ntt_inv(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, void* stream) {
+    int rc = check_level(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (n_polys == 0) return HE_OK;
+    if (!data) return HE_ERR_ARG;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    return launch_ntt(ctx, limbs, data, n_polys, true, (hipStream_t)stream);
+}
+
+// ---- host-side checks of the device arithmetic
+
+static LimbConst host_const(u64 q) {
+    LimbConst c;
+    memset(&c, 0, sizeof c);
+    fill_limb_const(c, q, 1, 1);
+    return c;
+}
+
+uint64_t he_host_reduce128(uint64_t hi, uint64_t lo, uint64_t q) { return reduce128(hi, lo, host_const(q)); }
+
+uint64_t he_host_mulmod(uint64_t a, uint64_t b, uint64_t q) { return mul_mod(a, b, host_const(q)); }
+
+uint64_t he_host_shoup_mulmod(uint64_t y, uint64_t w, uint64_t q) { return shoup_mul(y, w, h_shoup(w, q), q); }
+
+uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q) {
+    const LimbConst c = host_const(q);
+    MacAcc a;
+    acc_clear(a);
+    u32 f = 0, r = 0;
+    for (size_t t = 0; t < n; ++t) {
+        acc_mac_s(a, x[t], w[t]);
+        if (++r == c.reduce_every) { acc_restart(a, c); r = 0; f = 0; }
+        else if (++f == c.fold_every) { acc_fold(a); f = 0; }
+    }
+    return acc_reduce(a, c);
+}
+
+}  // extern "C"

@@ -1,0 +1,71 @@
+// Internal structures shared by the translation units of the library (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <vector>
+
+#include "../../include/he.h"
+#include "he_arith.h"
+
+// Per-limb constants handed to kernels by value (16 x 80 B).
+struct LimbTable {
+    LimbConst c[HE_MAX_LIMBS];
+};
+
+// Constants for dropping limb j while keeping limb i < j (Eq. (2) in RNS form).
+struct DropConst {
+    u64 p_inv, p_inv_shoup;  // q_j^-1 mod q_i and its Shoup companion
+    u64 half_mod;            // floor(q_j / 2) mod q_i
+    u64 pad;
+};
+
+struct he_ctx {
+    int device;  // -1: host-only
+    u32 log2N, N, L;
+    u64 q[HE_MAX_LIMBS], psi[HE_MAX_LIMBS];
+    LimbTable limbs;
+    DropConst drop[HE_MAX_LIMBS][HE_MAX_LIMBS];  // [dropped j][kept i]
+    // device tables
+    u64* tw_fwd;      // [L][N][2]: (psi^brv(k), Shoup companion), k in [0, N)
+    u64* tw_inv;      // [L][N][2]: (psi^-brv(k), Shoup companion)
+    DropConst* drop_dev;  // [L][L]
+};
+
+// One group of outputs that read the same ciphertexts in the same order.
+struct Tile {
+    u32 out0;    // first output of the group; the group is out0 .. out0+count-1
+    u32 count;   // outputs in the group (1 .. 16)
+    u32 term0;   // off[out0]: where the shared term_ct list starts
+    u32 n_terms; // terms per output of the group
+};
+
+struct he_plan {
+    he_ctx* ctx;
+    u32 n_in, n_out, n_pt, n_terms;
+    std::vector<u32> off;  // host copy, for argument checks
+    // tiles sorted by class; a class-k tile is run by the kernel instance with capacity cap[k]
+    u32 class_begin_s[4];  // scalar plaintexts: capacities 1, 4, 16 outputs per thread
+    u32 class_begin_p[4];  // polynomial plaintexts: capacities 1, 2, 8 outputs per thread
+    Tile* tiles_s_dev;
+    Tile* tiles_p_dev;
+    u64* wbase_s_dev;      // per scalar tile: start of its weights in the gathered table, per limb
+    u64 wtab_elems;        // residues per limb in the gathered weight table
+    u32 n_tiles_s, n_tiles_p;
+    u32* off_dev;
+    u32* term_ct_dev;
+    u32* term_pt_dev;
+};
+
+#define HE_HIP(call)                                   \
+    do {                                               \
+        if ((call) != hipSuccess) {                    \
+            (void)hipGetLastError();                   \
+            return HE_ERR_DEVICE;                      \
+        }                                              \
+    } while (0)
+
+// kernels' launchers (defined in he_mac.hip / he_ntt.hip); all return a he_status
+int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, const u64* pt, int pt_kind,
+               const u64* bias, u64* out, u64* wtab, hipStream_t s);
+int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s);
+int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s);

@@ -1,0 +1,212 @@
+// Ciphertext x plaintext multiply-accumulate kernels (Alg. 7 / Alg. 8 summed over a plan).
+//
+// A thread owns one slot n of one (component, limb) row and the accumulators of a whole group of
+// outputs that read the same ciphertexts, so each input residue is loaded once per group and used
+// for every output of it.  Products are accumulated unreduced (MacAcc) and reduced once at the end
+// (or every LimbConst::reduce_every terms), then the bias residue is added on component 0.
+#include "he_internal.h"
+
+namespace {
+
+constexpr int MAC_THREADS = 256;
+constexpr int GATHER_BLOCKS = 8;
+constexpr int PREFETCH = 4;  // terms whose inputs are in flight while the previous ones are used
+
+template <int A>
+__device__ __forceinline__ void housekeeping(MacAcc (&acc)[A], u32& f, u32& r, const LimbConst& c) {
+    if (++r == c.reduce_every) {
+#pragma unroll
+        for (int g = 0; g < A; g++) acc_restart(acc[g], c);
+        r = 0;
+        f = 0;
+    } else if (++f == c.fold_every) {
+#pragma unroll
+        for (int g = 0; g < A; g++) acc_fold(acc[g]);
+        f = 0;
+    }
+}
+
+// Weight table for scalar plaintexts: wtab[(tile.wbase*limbs) + (limb*n_terms + t)*G + g] =
+// pt[term_pt[off[out0+g] + t]][limb], zero for g >= tile.count, so the MAC loop reads G
+// consecutive residues per term with scalar loads and needs no per-output branch.
+template <int G>
+__global__ void __launch_bounds__(256) gather_weights_kernel(const Tile* tiles, const u64* wbase, u32 n_tiles, u32 limbs,
+                                                             const u32* off, const u32* term_pt, const u64* pt, u64* wtab) {
+    const u32 tile_i = blockIdx.x / GATHER_BLOCKS;
+    const u32 sub = blockIdx.x % GATHER_BLOCKS;
+    if (tile_i >= n_tiles) return;
+    const Tile tile = tiles[tile_i];
+    const u64 per_limb = (u64)tile.n_terms * G;
+    const u64 total = per_limb * limbs;
+    u64* dst = wtab + wbase[tile_i] * limbs;
+    for (u64 i = (u64)sub * blockDim.x + threadIdx.x; i < total; i += (u64)GATHER_BLOCKS * blockDim.x) {
+        const u32 limb = (u32)(i / per_limb);
+        const u64 rem = i % per_limb;
+        const u32 t = (u32)(rem / G), g = (u32)(rem % G);
+        u64 w = 0;
+        if (g < tile.count) w = pt[(size_t)term_pt[off[tile.out0 + g] + t] * limbs + limb];
+        dst[i] = w;
+    }
+}
+
+template <int G>
+__global__ void __launch_bounds__(MAC_THREADS)
+mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u64* wbase, const u32* term_ct,
+                  const u64* wtab, const u64* ct_in, const u64* bias, u64* out) {
+    const u32 chunks = N / MAC_THREADS;
+    u32 b = blockIdx.x;
+    const u32 chunk = b % chunks; b /= chunks;
+    const u32 comp = b & 1; b >>= 1;
+    const u32 limb = b % limbs;
+    const u32 tile_i = b / limbs;
+    const Tile tile = tiles[tile_i];
+    const LimbConst& c = lt.c[limb];
+    const u32 n = chunk * MAC_THREADS + threadIdx.x;
+    const size_t ct_stride = (size_t)2 * limbs * N;
+    const u64* x_base = ct_in + ((size_t)comp * limbs + limb) * N + n;
+    const u64* w = wtab + wbase[tile_i] * limbs + (u64)limb * tile.n_terms * G;
+    const u32* tc = term_ct + tile.term0;
+    const u32 K = tile.n_terms;
+
+    MacAcc acc[G];
+#pragma unroll
+    for (int g = 0; g < G; g++) acc_clear(acc[g]);
+    u32 f = 0, r = 0;
+
+    u64 x_next[PREFETCH];
+#pragma unroll
+    for (int j = 0; j < PREFETCH; j++) x_next[j] = (u32)j < K ? x_base[(size_t)tc[j] * ct_stride] : 0;
+    for (u32 t0 = 0; t0 < K; t0 += PREFETCH) {
+        u64 x_cur[PREFETCH];
+#pragma unroll
+        for (int j = 0; j < PREFETCH; j++) {
+            x_cur[j] = x_next[j];
+            const u32 tn = t0 + PREFETCH + j;
+            x_next[j] = tn < K ? x_base[(size_t)tc[tn] * ct_stride] : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < PREFETCH; j++) {
+            const u32 t = t0 + j;
+            if (t < K) {
+                const u64* wt = w + (size_t)t * G;
+#pragma unroll
+                for (int g = 0; g < G; g++) acc_mac_s(acc[g], x_cur[j], wt[g]);
+                housekeeping<G>(acc, f, r, c);
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        if ((u32)g < tile.count) {
+            const u32 o = tile.out0 + g;
+            u64 v = acc_reduce(acc[g], c);
+            if (bias != nullptr && comp == 0) v = add_mod(v, bias[(size_t)o * limbs + limb], c.q);
+            out[(((size_t)o * 2 + comp) * limbs + limb) * N + n] = v;
+        }
+    }
+}
+
+// Full-polynomial plaintexts: the plaintext residue differs per slot, is loaded once and used for
+// both ciphertext components.  A thread owns G outputs x 2 components.
+template <int G>
+__global__ void __launch_bounds__(MAC_THREADS)
+mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u32* off, const u32* term_ct, const u32* term_pt,
+                const u64* pt, const u64* ct_in, const u64* bias, u64* out) {
+    const u32 chunks = N / MAC_THREADS;
+    u32 b = blockIdx.x;
+    const u32 chunk = b % chunks; b /= chunks;
+    const u32 limb = b % limbs;
+    const u32 tile_i = b / limbs;
+    const Tile tile = tiles[tile_i];
+    const LimbConst& c = lt.c[limb];
+    const u32 n = chunk * MAC_THREADS + threadIdx.x;
+    const size_t ct_stride = (size_t)2 * limbs * N;
+    const size_t comp_stride = (size_t)limbs * N;
+    const u64* x_base = ct_in + (size_t)limb * N + n;
+    const u64* p_base = pt + (size_t)limb * N + n;
+    const size_t pt_stride = (size_t)limbs * N;
+    const u32* tc = term_ct + tile.term0;
+    const u32 K = tile.n_terms;
+    const u32* tp[G];
+#pragma unroll
+    for (int g = 0; g < G; g++) tp[g] = term_pt + off[tile.out0 + ((u32)g < tile.count ? g : 0)];
+
+    MacAcc acc[2 * G];
+#pragma unroll
+    for (int g = 0; g < 2 * G; g++) acc_clear(acc[g]);
+    u32 f = 0, r = 0;
+#pragma unroll 2
+    for (u32 t = 0; t < K; t++) {
+        const u64* xp = x_base + (size_t)tc[t] * ct_stride;
+        const u64 x0 = xp[0], x1 = xp[comp_stride];
+        u64 p[G];
+#pragma unroll
+        for (int g = 0; g < G; g++) p[g] = (u32)g < tile.count ? p_base[(size_t)tp[g][t] * pt_stride] : 0;
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            acc_mac_v(acc[2 * g], x0, p[g]);
+            acc_mac_v(acc[2 * g + 1], x1, p[g]);
+        }
+        housekeeping<2 * G>(acc, f, r, c);
+    }
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        if ((u32)g < tile.count) {
+            const u32 o = tile.out0 + g;
+            u64 v0 = acc_reduce(acc[2 * g], c), v1 = acc_reduce(acc[2 * g + 1], c);
+            if (bias != nullptr) v0 = add_mod(v0, bias[(size_t)o * limbs + limb], c.q);
+            u64* dst = out + ((size_t)o * 2 * limbs + limb) * N + n;
+            dst[0] = v0;
+            dst[comp_stride] = v1;
+        }
+    }
+}
+
+}  // namespace
+
+// tile classes: scalar plaintexts hold up to {1,4,16} outputs per thread, polynomial ones {1,2,8}
+template <int G>
+static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, const u64* ct_in, const u64* pt,
+                               const u64* bias, u64* out, u64* wtab, hipStream_t s) {
+    const u32 begin = plan->class_begin_s[cls], count = plan->class_begin_s[cls + 1] - begin;
+    if (count == 0) return HE_OK;
+    const Tile* tiles = plan->tiles_s_dev + begin;
+    const u64* wbase = plan->wbase_s_dev + begin;
+    hipLaunchKernelGGL((gather_weights_kernel<G>), dim3(count * GATHER_BLOCKS), dim3(256), 0, s, tiles, wbase, count, limbs, plan->off_dev,
+                       plan->term_pt_dev, pt, wtab);
+    HE_HIP(hipGetLastError());
+    const u64 blocks = (u64)count * limbs * 2 * (ctx->N / MAC_THREADS);
+    if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
+    hipLaunchKernelGGL((mac_scalar_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles,
+                       wbase, plan->term_ct_dev, wtab, ct_in, bias, out);
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+template <int G>
+static int launch_poly_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, const u64* ct_in, const u64* pt,
+                             const u64* bias, u64* out, hipStream_t s) {
+    const u32 begin = plan->class_begin_p[cls], count = plan->class_begin_p[cls + 1] - begin;
+    if (count == 0) return HE_OK;
+    const u64 blocks = (u64)count * limbs * (ctx->N / MAC_THREADS);
+    if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
+    hipLaunchKernelGGL((mac_poly_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
+                       plan->tiles_p_dev + begin, plan->off_dev, plan->term_ct_dev, plan->term_pt_dev, pt, ct_in, bias, out);
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, const u64* pt, int pt_kind, const u64* bias,
+               u64* out, u64* wtab, hipStream_t s) {
+    int rc;
+    if (pt_kind == HE_PT_SCALAR) {
+        if ((rc = launch_scalar_class<1>(ctx, plan, 0, limbs, ct_in, pt, bias, out, wtab, s)) != HE_OK) return rc;
+        if ((rc = launch_scalar_class<4>(ctx, plan, 1, limbs, ct_in, pt, bias, out, wtab, s)) != HE_OK) return rc;
+        if ((rc = launch_scalar_class<16>(ctx, plan, 2, limbs, ct_in, pt, bias, out, wtab, s)) != HE_OK) return rc;
+    } else {
+        if ((rc = launch_poly_class<1>(ctx, plan, 0, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
+        if ((rc = launch_poly_class<2>(ctx, plan, 1, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
+        if ((rc = launch_poly_class<8>(ctx, plan, 2, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
+    }
+    return HE_OK;
+}

@@ -1,0 +1,276 @@
+// Negacyclic NTT / INTT and the rescale of Eq. (2) for gfx950.
+//
+// One workgroup transforms one polynomial limb (N residues).  Each of the T = N/16 threads keeps
+// 16 residues in registers and runs up to four butterfly stages on them (a "pass") before the
+// workgroup regroups the residues through LDS for the next pass.  Stage s (s = 0 .. log2N-1) pairs
+// indices that differ in bit log2N-1-s, so pass p owns index bits [log2N-1-4p .. log2N-4-4p]; the
+// last pass owns what is left at the bottom (1..4 stages) plus, to fill its 16 registers, the top
+// bits again, so that consecutive threads hold consecutive short runs and global stores stay dense.
+// Butterflies are Harvey's lazy ones (values in [0,4q) forward, [0,2q) inverse) with Shoup
+// multiplication by precomputed twiddles psi^bitrev(k); moduli are below 2^62, so 4q fits 64 bits.
+#include "he_internal.h"
+
+namespace {
+
+template <int LOGN>
+struct Geo {
+    static constexpr int N = 1 << LOGN;
+    static constexpr int T = N / 16;
+    static constexpr int NPASS = (LOGN + 3) / 4;
+    static constexpr int REM = LOGN - 4 * (NPASS - 1);  // stages of the last pass, 1..4
+};
+
+// Index of register e of thread tid while pass P is being computed.
+template <int LOGN, int P>
+__device__ __forceinline__ u32 reg_index(u32 tid, u32 e) {
+    using G = Geo<LOGN>;
+    if constexpr (P < G::NPASS - 1) {
+        constexpr int low = LOGN - 4 * (P + 1);
+        u32 hi = tid >> low, lo = tid & ((1u << low) - 1);
+        return (hi << (low + 4)) | (e << low) | lo;
+    } else if constexpr (G::REM == 4) {
+        return (tid << 4) | e;
+    } else {
+        u32 e_hi = e >> G::REM, e_lo = e & ((1u << G::REM) - 1);
+        return (e_hi << (LOGN - (4 - G::REM))) | (tid << G::REM) | e_lo;
+    }
+}
+
+// LDS placement: XOR the low index bits with higher ones so that the strided access patterns of
+// the regrouping steps spread over the banks.  A bijection on [0, N) for N >= 1024.
+__device__ __forceinline__ u32 lds_slot(u32 idx) {
+    return idx ^ (((idx >> 6) & 0xFu) << 2) ^ ((idx >> 5) & 3u);
+}
+
+template <int LOGN, int PFROM, int PTO>
+__device__ __forceinline__ void regroup(u64 (&a)[16], u64* lds, u32 tid) {
+    __syncthreads();  // earlier readers of the buffer are done
+#pragma unroll
+    for (u32 e = 0; e < 16; e++) lds[lds_slot(reg_index<LOGN, PFROM>(tid, e))] = a[e];
+    __syncthreads();
+#pragma unroll
+    for (u32 e = 0; e < 16; e++) a[e] = lds[lds_slot(reg_index<LOGN, PTO>(tid, e))];
+}
+
+struct Twiddle {
+    u64 w, w_shoup;
+};
+
+template <bool UNIFORM>
+__device__ __forceinline__ Twiddle load_twiddle(const u64* tw, u32 k) {
+    if constexpr (UNIFORM) k = __builtin_amdgcn_readfirstlane(k);
+    const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(tw + 2 * (size_t)k);
+    return Twiddle{v.x, v.y};
+}
+
+// Forward butterfly: (X, Y) -> (X + W*Y, X - W*Y), all values in [0, 4q).
+__device__ __forceinline__ void bfly_fwd(u64& x, u64& y, Twiddle t, u64 q, u64 two_q) {
+    u64 u = x >= two_q ? x - two_q : x;
+    u64 v = shoup_mul_lazy(y, t.w, t.w_shoup, q);
+    x = u + v;
+    y = u - v + two_q;
+}
+
+// Inverse butterfly: (X, Y) -> (X + Y, (X - Y) * W), all values in [0, 2q).
+__device__ __forceinline__ void bfly_inv(u64& x, u64& y, Twiddle t, u64 q, u64 two_q) {
+    u64 s = x + y;
+    u64 d = x - y + two_q;
+    x = s >= two_q ? s - two_q : s;
+    y = shoup_mul_lazy(d, t.w, t.w_shoup, q);
+}
+
+// The stages of pass P on the 16 registers of one thread.
+template <int LOGN, int P, bool INVERSE>
+__device__ __forceinline__ void run_pass(u64 (&a)[16], const u64* tw, u32 tid, const LimbConst& c) {
+    using G = Geo<LOGN>;
+    constexpr bool LAST = (P == G::NPASS - 1);
+    constexpr int NST = LAST ? G::REM : 4;
+    // twiddles are the same for the whole wave when the thread-dependent part of the group index
+    // is constant over 64 consecutive threads
+    constexpr bool UNIFORM = (P == 0) || (!LAST && (LOGN - 4 * (P + 1)) >= 6);
+#pragma unroll
+    for (int kk = 0; kk < NST; kk++) {
+        const int k = INVERSE ? NST - 1 - kk : kk;
+        const int s = 4 * P + k;       // stage
+        const int bit = NST - 1 - k;   // register-index bit that the stage pairs
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) {
+            if (e & (1u << bit)) continue;
+            const u32 j = reg_index<LOGN, P>(tid, e);
+            const u32 k_tw = (1u << s) + (j >> (LOGN - s));
+            if constexpr (INVERSE) {
+                if (s == 0) {  // merged with the multiplication by N^-1
+                    u64 sum = a[e] + a[e | (1u << bit)];
+                    u64 dif = a[e] - a[e | (1u << bit)] + c.two_q;
+                    a[e] = shoup_mul_lazy(sum, c.n_inv, c.n_inv_shoup, c.q);
+                    a[e | (1u << bit)] = shoup_mul_lazy(dif, c.w1n_inv, c.w1n_inv_shoup, c.q);
+                } else {
+                    bfly_inv(a[e], a[e | (1u << bit)], load_twiddle<UNIFORM>(tw, k_tw), c.q, c.two_q);
+                }
+            } else {
+                bfly_fwd(a[e], a[e | (1u << bit)], load_twiddle<UNIFORM>(tw, k_tw), c.q, c.two_q);
+            }
+        }
+    }
+}
+
+// Registers in pass-0 order, canonical or lazy (< 4q) -> registers in last-pass order, < 4q.
+template <int LOGN>
+__device__ __forceinline__ void ntt_forward(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
+    using G = Geo<LOGN>;
+    run_pass<LOGN, 0, false>(a, tw, tid, c);
+    if constexpr (G::NPASS > 1) { regroup<LOGN, 0, 1>(a, lds, tid); run_pass<LOGN, 1, false>(a, tw, tid, c); }
+    if constexpr (G::NPASS > 2) { regroup<LOGN, 1, 2>(a, lds, tid); run_pass<LOGN, 2, false>(a, tw, tid, c); }
+    if constexpr (G::NPASS > 3) { regroup<LOGN, 2, 3>(a, lds, tid); run_pass<LOGN, 3, false>(a, tw, tid, c); }
+}
+
+// Registers in last-pass order, < 2q -> registers in pass-0 order, < 2q, multiplied by N^-1.
+template <int LOGN>
+__device__ __forceinline__ void ntt_inverse(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
+    using G = Geo<LOGN>;
+    if constexpr (G::NPASS > 3) { run_pass<LOGN, 3, true>(a, tw, tid, c); regroup<LOGN, 3, 2>(a, lds, tid); }
+    if constexpr (G::NPASS > 2) { run_pass<LOGN, 2, true>(a, tw, tid, c); regroup<LOGN, 2, 1>(a, lds, tid); }
+    if constexpr (G::NPASS > 1) { run_pass<LOGN, 1, true>(a, tw, tid, c); regroup<LOGN, 1, 0>(a, lds, tid); }
+    run_pass<LOGN, 0, true>(a, tw, tid, c);
+}
+
+__device__ __forceinline__ u64 canon4(u64 v, u64 q, u64 two_q) {  // [0,4q) -> [0,q)
+    v = v >= two_q ? v - two_q : v;
+    return v >= q ? v - q : v;
+}
+
+template <int LOGN, bool INVERSE>
+__global__ void __launch_bounds__(Geo<LOGN>::T) ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all) {
+    using G = Geo<LOGN>;
+    extern __shared__ u64 lds[];
+    const u32 tid = threadIdx.x;
+    const u32 row = blockIdx.x;
+    const u32 limb = row % limbs;
+    const LimbConst& c = lt.c[limb];
+    const u64* tw = tw_all + (size_t)limb * G::N * 2;
+    u64* p = data + (size_t)row * G::N;
+    u64 a[16];
+    if constexpr (!INVERSE) {
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, 0>(tid, e)];
+        ntt_forward<LOGN>(a, tw, lds, tid, c);
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) p[reg_index<LOGN, G::NPASS - 1>(tid, e)] = canon4(a[e], c.q, c.two_q);
+    } else {
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, G::NPASS - 1>(tid, e)];
+        ntt_inverse<LOGN>(a, tw, lds, tid, c);
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) {
+            u64 v = a[e];
+            p[reg_index<LOGN, 0>(tid, e)] = v >= c.q ? v - c.q : v;
+        }
+    }
+}
+
+// Rescale of one polynomial (one ciphertext component) per workgroup, Eq. (2) in RNS form.  With
+// p the dropped modulus, h = floor(p/2), r the last limb's coefficients and t = (r + h) mod p:
+//   out_i = (x_i - NTT_i((t mod q_i) - (h mod q_i))) * p^-1  mod q_i      for every kept limb i,
+// which equals round(X / p) mod q_i for the integer X the residues stand for.  The inverse
+// transform of the last limb ends in the register order in which a forward transform starts, so t
+// never leaves the registers.
+template <int LOGN>
+__global__ void __launch_bounds__(Geo<LOGN>::T)
+rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_fwd, const u64* tw_inv,
+               const DropConst* drop) {
+    using G = Geo<LOGN>;
+    extern __shared__ u64 lds[];
+    const u32 tid = threadIdx.x;
+    const size_t poly = blockIdx.x;  // ct*2 + component
+    const u32 last = limbs - 1;
+    const u64* src = in + poly * limbs * G::N;
+    u64* dst = out + poly * (limbs - 1) * G::N;
+    u64 t[16];
+    {
+        const LimbConst& c = lt.c[last];
+        const u64* row = src + (size_t)last * G::N;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) t[e] = row[reg_index<LOGN, G::NPASS - 1>(tid, e)];
+        ntt_inverse<LOGN>(t, tw_inv + (size_t)last * G::N * 2, lds, tid, c);
+        const u64 half = c.q >> 1;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) {
+            u64 v = t[e];
+            v = v >= c.q ? v - c.q : v;
+            t[e] = add_mod(v, half, c.q);
+        }
+    }
+    for (u32 i = 0; i < last; i++) {
+        const LimbConst& c = lt.c[i];
+        const DropConst d = drop[last * HE_MAX_LIMBS + i];
+        u64 a[16];
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = sub_mod(reduce64(t[e], c), d.half_mod, c.q);
+        ntt_forward<LOGN>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
+        const u64* xrow = src + (size_t)i * G::N;
+        u64* orow = dst + (size_t)i * G::N;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) {
+            const u32 j = reg_index<LOGN, G::NPASS - 1>(tid, e);
+            u64 delta = canon4(a[e], c.q, c.two_q);
+            u64 diff = sub_mod(xrow[j], delta, c.q);
+            orow[j] = shoup_mul(diff, d.p_inv, d.p_inv_shoup, c.q);
+        }
+    }
+}
+
+template <int LOGN>
+int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipStream_t s) {
+    using G = Geo<LOGN>;
+    const size_t lds = (size_t)G::N * sizeof(u64);
+    if (inverse) {
+        HE_HIP(hipFuncSetAttribute((const void*)ntt_rows_kernel<LOGN, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(rows), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv);
+    } else {
+        HE_HIP(hipFuncSetAttribute((const void*)ntt_rows_kernel<LOGN, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(rows), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd);
+    }
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+template <int LOGN>
+int launch_rescale_t(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s) {
+    using G = Geo<LOGN>;
+    const size_t lds = (size_t)G::N * sizeof(u64);
+    HE_HIP(hipFuncSetAttribute((const void*)rescale_kernel<LOGN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((rescale_kernel<LOGN>), dim3(2 * n), dim3(G::T), lds, s, ctx->limbs, limbs, in, out, ctx->tw_fwd,
+                       ctx->tw_inv, ctx->drop_dev);
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+}  // namespace
+
+int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s) {
+    const u64 rows64 = (u64)n_polys * limbs;
+    if (rows64 == 0) return HE_OK;
+    if (rows64 > 0x7FFFFFFFull) return HE_ERR_RANGE;
+    const u32 rows = (u32)rows64;
+    switch (ctx->log2N) {
+        case 10: return launch_ntt_t<10>(ctx, limbs, data, rows, inverse, s);
+        case 11: return launch_ntt_t<11>(ctx, limbs, data, rows, inverse, s);
+        case 12: return launch_ntt_t<12>(ctx, limbs, data, rows, inverse, s);
+        case 13: return launch_ntt_t<13>(ctx, limbs, data, rows, inverse, s);
+        case 14: return launch_ntt_t<14>(ctx, limbs, data, rows, inverse, s);
+    }
+    return HE_ERR_ARG;
+}
+
+int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s) {
+    if (n == 0) return HE_OK;
+    if (n > 0x3FFFFFFFu) return HE_ERR_RANGE;
+    switch (ctx->log2N) {
+        case 10: return launch_rescale_t<10>(ctx, limbs, in, out, n, s);
+        case 11: return launch_rescale_t<11>(ctx, limbs, in, out, n, s);
+        case 12: return launch_rescale_t<12>(ctx, limbs, in, out, n, s);
+        case 13: return launch_rescale_t<13>(ctx, limbs, in, out, n, s);
+        case 14: return launch_rescale_t<14>(ctx, limbs, in, out, n, s);
+    }
+    return HE_ERR_ARG;
+}

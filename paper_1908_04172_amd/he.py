@@ -1,0 +1,260 @@
+"""ctypes binding of the C-ABI library (include/he.h).  Argument marshalling only: every step
+runs in the library's kernels.  Device tensors are torch int64 tensors whose bit patterns are the
+uint64 residues; torch supplies memory and the current stream, nothing else.
+
+The library is loaded from paper_1908_04172_amd/libhe_mi355x.so (built by build.py); if it is
+missing or fails to load, importing the symbols raises -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+PT_SCALAR = 0
+PT_POLY = 1
+RESCALE = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhe_mi355x.so")
+
+EXPORTS = [
+    "he_strerror", "he_ctx_create", "he_ctx_destroy", "he_ctx_info", "he_encode_scalar", "he_encode_scalar_host",
+    "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
+    "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod",
+    "he_host_mac_accumulate",
+]
+
+_lib = None
+
+
+class HeError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {lib().he_strerror(status).decode()} ({status})")
+
+
+def lib():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_1908_04172_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, u32, u64, i32, dbl, sz = (ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_double,
+                                  ctypes.c_size_t)
+    pp = ctypes.POINTER(vp)
+    sigs = {
+        "he_strerror": (ctypes.c_char_p, [i32]),
+        "he_ctx_create": (i32, [pp, u32, u32, vp, i32]),
+        "he_ctx_destroy": (i32, [vp]),
+        "he_ctx_info": (i32, [vp, vp, vp, vp, vp]),
+        "he_encode_scalar": (i32, [vp, vp, sz, dbl, u32, vp, vp]),
+        "he_encode_scalar_host": (i32, [vp, vp, sz, dbl, u32, vp]),
+        "he_plan_create": (i32, [vp, u32, u32, u32, vp, vp, vp, pp]),
+        "he_plan_destroy": (i32, [vp]),
+        "he_plan_workspace_bytes": (i32, [vp, u32, i32, u32, ctypes.POINTER(sz)]),
+        "he_ct_pt_mac": (i32, [vp, vp, u32, vp, vp, i32, vp, vp, u32, vp, sz, vp]),
+        "he_ct_pt_add": (i32, [vp, u32, vp, u32, vp, i32, vp]),
+        "he_rescale": (i32, [vp, u32, vp, vp, u32, vp]),
+        "he_ntt_fwd": (i32, [vp, u32, vp, u32, vp]),
+        "he_ntt_inv": (i32, [vp, u32, vp, u32, vp]),
+        "he_host_mulmod": (u64, [u64, u64, u64]),
+        "he_host_reduce128": (u64, [u64, u64, u64]),
+        "he_host_shoup_mulmod": (u64, [u64, u64, u64]),
+        "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise HeError(status, what)
+
+
+def _np64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.uint64)
+
+
+def _np32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.uint32)
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev_ptr(t, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous CUDA tensor")
+    if t.dtype not in (torch.int64, torch.float64, torch.uint8):
+        raise TypeError(f"{name}: unexpected dtype {t.dtype}")
+    return t.data_ptr()
+
+
+class Context:
+    """he_ctx: ring degree N = 2**log2N and the modulus chain; device=None makes a host-only context."""
+
+    def __init__(self, log2N: int, moduli: Sequence[int], device: Optional[int] = 0):
+        self.log2N, self.N, self.L = int(log2N), 1 << int(log2N), len(moduli)
+        self.moduli = [int(q) for q in moduli]
+        self.device = device
+        q = _np64(self.moduli)
+        h = ctypes.c_void_p()
+        _check(lib().he_ctx_create(ctypes.byref(h), self.log2N, self.L, q.ctypes.data, -1 if device is None else device),
+               "he_ctx_create")
+        self._h = h
+        psi = np.zeros(self.L, dtype=np.uint64)
+        _check(lib().he_ctx_info(self._h, None, None, None, psi.ctypes.data), "he_ctx_info")
+        self.psi = [int(x) for x in psi]
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().he_ctx_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- Alg. 2
+    def encode_scalar_host(self, values, scale: float, limbs: Optional[int] = None) -> np.ndarray:
+        limbs = self.L if limbs is None else limbs
+        v = np.ascontiguousarray(np.atleast_1d(values), dtype=np.float64)
+        out = np.empty((v.size, limbs), dtype=np.uint64)
+        _check(lib().he_encode_scalar_host(self._h, v.ctypes.data, v.size, float(scale), limbs, out.ctypes.data),
+               "he_encode_scalar_host")
+        return out
+
+    def encode_scalar(self, values, scale: float, limbs: Optional[int] = None, out=None):
+        """values: CUDA float64 tensor [n] -> CUDA int64 tensor [n][limbs] (he_encode_scalar)."""
+        import torch
+        limbs = self.L if limbs is None else limbs
+        n = values.numel()
+        if out is None:
+            out = torch.empty((n, limbs), dtype=torch.int64, device=values.device)
+        _check(lib().he_encode_scalar(self._h, _dev_ptr(values, "values"), n, float(scale), limbs, _dev_ptr(out, "out"),
+                                      _stream()), "he_encode_scalar")
+        return out
+
+    # -- Alg. 3 / 4
+    def ct_pt_add(self, ct, pt, pt_kind: int, limbs: Optional[int] = None):
+        limbs = ct.shape[2] if limbs is None else limbs
+        n = ct.shape[0]
+        assert tuple(ct.shape) == (n, 2, limbs, self.N)
+        assert tuple(pt.shape) == ((n, limbs) if pt_kind == PT_SCALAR else (n, limbs, self.N))
+        _check(lib().he_ct_pt_add(self._h, limbs, _dev_ptr(ct, "ct"), n, _dev_ptr(pt, "pt"), pt_kind, _stream()),
+               "he_ct_pt_add")
+        return ct
+
+    # -- Eq. (2)
+    def rescale(self, ct, out=None):
+        import torch
+        n, two, limbs, N = ct.shape
+        assert two == 2 and N == self.N
+        if out is None:
+            out = torch.empty((n, 2, limbs - 1, N), dtype=torch.int64, device=ct.device)
+        _check(lib().he_rescale(self._h, limbs, _dev_ptr(ct, "in"), _dev_ptr(out, "out"), n, _stream()), "he_rescale")
+        return out
+
+    # -- NTT
+    def ntt_fwd(self, data):
+        limbs, N = data.shape[-2:]
+        assert N == self.N
+        _check(lib().he_ntt_fwd(self._h, limbs, _dev_ptr(data, "data"), data.numel() // (limbs * N), _stream()),
+               "he_ntt_fwd")
+        return data
+
+    def ntt_inv(self, data):
+        limbs, N = data.shape[-2:]
+        assert N == self.N
+        _check(lib().he_ntt_inv(self._h, limbs, _dev_ptr(data, "data"), data.numel() // (limbs * N), _stream()),
+               "he_ntt_inv")
+        return data
+
+    # -- Alg. 7 / 8 over a plan
+    def plan(self, n_in: int, n_out: int, n_pt: int, off, term_ct, term_pt) -> "Plan":
+        return Plan(self, n_in, n_out, n_pt, off, term_ct, term_pt)
+
+    def ct_pt_mac(self, plan: "Plan", ct_in, pt, pt_kind: int, bias=None, flags: int = 0, out=None, workspace=None,
+                  limbs: Optional[int] = None):
+        import torch
+        limbs = ct_in.shape[2] if limbs is None else limbs
+        assert tuple(ct_in.shape) == (plan.n_in, 2, limbs, self.N)
+        assert tuple(pt.shape) == ((plan.n_pt, limbs) if pt_kind == PT_SCALAR else (plan.n_pt, limbs, self.N))
+        if bias is not None:
+            assert tuple(bias.shape) == (plan.n_out, limbs)
+        out_limbs = limbs - 1 if flags & RESCALE else limbs
+        if out is None:
+            out = torch.empty((plan.n_out, 2, out_limbs, self.N), dtype=torch.int64, device=ct_in.device)
+        assert tuple(out.shape) == (plan.n_out, 2, out_limbs, self.N)
+        need = plan.workspace_bytes(limbs, pt_kind, flags)
+        if workspace is None and need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=ct_in.device)
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        _check(lib().he_ct_pt_mac(self._h, plan._h, limbs, _dev_ptr(ct_in, "ct_in"), _dev_ptr(pt, "pt"), pt_kind,
+                                  _dev_ptr(bias, "bias"), _dev_ptr(out, "ct_out"), flags, _dev_ptr(workspace, "workspace"),
+                                  ws_bytes, _stream()), "he_ct_pt_mac")
+        return out
+
+
+class Plan:
+    """he_plan: out[o] = sum over t in [off[o], off[o+1]) of ct_in[term_ct[t]] * pt[term_pt[t]]."""
+
+    def __init__(self, ctx: Context, n_in: int, n_out: int, n_pt: int, off, term_ct, term_pt):
+        self.ctx, self.n_in, self.n_out, self.n_pt = ctx, int(n_in), int(n_out), int(n_pt)
+        off, term_ct, term_pt = _np32(off), _np32(term_ct), _np32(term_pt)
+        assert off.size == self.n_out + 1 and term_ct.size == term_pt.size
+        h = ctypes.c_void_p()
+        _check(lib().he_plan_create(ctx._h, self.n_in, self.n_out, self.n_pt, off.ctypes.data, term_ct.ctypes.data,
+                                    term_pt.ctypes.data, ctypes.byref(h)), "he_plan_create")
+        self._h = h
+
+    def workspace_bytes(self, limbs: int, pt_kind: int, flags: int) -> int:
+        b = ctypes.c_size_t()
+        _check(lib().he_plan_workspace_bytes(self._h, limbs, pt_kind, flags, ctypes.byref(b)), "he_plan_workspace_bytes")
+        return int(b.value)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().he_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# -- host-side checks of the device arithmetic
+
+def host_mulmod(a: int, b: int, q: int) -> int:
+    return int(lib().he_host_mulmod(a, b, q))
+
+
+def host_reduce128(hi: int, lo: int, q: int) -> int:
+    return int(lib().he_host_reduce128(hi, lo, q))
+
+
+def host_shoup_mulmod(y: int, w: int, q: int) -> int:
+    return int(lib().he_host_shoup_mulmod(y, w, q))
+
+
+def host_mac_accumulate(x, w, q: int) -> int:
+    x, w = _np64(x), _np64(w)
+    assert x.size == w.size
+    return int(lib().he_host_mac_accumulate(x.ctypes.data, w.ctypes.data, x.size, q))

@@ -1,0 +1,322 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle, element by element,
+on the same seeded inputs.  Residues must match bit-exactly (integer work); the encrypt-compute-
+decrypt check uses |err| <= 2^-10 * max(1, |value|)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1908_04172_amd import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def he():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1908_04172_amd import he as he_mod
+    he_mod.lib()  # raises if the HIP library is not built: no fallback
+    return he_mod
+
+
+def dev(a: np.ndarray):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int64)).cuda()
+
+
+def host(t) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint64)
+
+
+def compact(plan: wl.Plan, outputs):
+    """Sub-problem for the listed outputs with ct/pt indices renumbered densely."""
+    sub = plan.subset(outputs)
+    ct_ids, ct_inv = np.unique(sub.term_ct, return_inverse=True)
+    pt_ids, pt_inv = np.unique(sub.term_pt, return_inverse=True)
+    return wl.Plan(len(ct_ids), sub.n_out, len(pt_ids), sub.off, ct_inv.astype(np.uint32), pt_inv.astype(np.uint32)), ct_ids, pt_ids
+
+
+MIXED = {10: [30, 62, 50], 11: [40, 60], 12: [30, 30, 60], 13: [60, 40, 40, 40], 14: [60, 60, 50, 50, 50]}
+
+
+# ----------------------------------------------------------------------------- NTT
+
+@pytest.mark.parametrize("log2N", [10, 11, 12, 13, 14])
+def test_ntt_fwd_inv_match_oracle(he, log2N):
+    N = 1 << log2N
+    q = wl.modulus_chain(MIXED[log2N], N)
+    ctx = he.Context(log2N, q)
+    assert ctx.psi == oracle.find_psis(q, N)
+    a = wl.uniform_residues((3,), q, N, 1000 + log2N)          # 3 polys x limbs rows, ragged vs 256 CUs
+    a[0, :, :] = 0
+    a[0, :, 1] = 1                                              # the monomial X: pins root and ordering
+    d = dev(a)
+    ctx.ntt_fwd(d)
+    want = oracle.ntt_fwd(a, q, ctx.psi)
+    assert np.array_equal(host(d), want)
+    ctx.ntt_inv(d)
+    assert np.array_equal(host(d), a)
+    # lower level: only the first limbs
+    b = wl.uniform_residues((2, 2), q[:2], N, 2000 + log2N)
+    db = dev(b)
+    ctx.ntt_inv(db)
+    assert np.array_equal(host(db), oracle.ntt_inv(b, q[:2], ctx.psi[:2]))
+    # edge values q-1 everywhere
+    e = np.stack([np.full(N, qi - 1, dtype=np.uint64) for qi in q])[None]
+    de = dev(e)
+    ctx.ntt_fwd(de)
+    assert np.array_equal(host(de), oracle.ntt_fwd(e, q, ctx.psi))
+    ctx.ntt_fwd(de[:0])                                         # zero polys: a no-op
+
+
+# ----------------------------------------------------------------------------- Alg. 2
+
+def test_encode_scalar_kernel_matches_oracle(he):
+    c = wl.config(4)
+    ctx = he.Context(c.log2N, c.q)
+    rng = np.random.default_rng(7)
+    vals = np.concatenate([rng.normal(0, 0.1, 1000), [0.0, -0.0, 0.5, -0.5, 1.5, 2.5, -2.5, 0.49999999999999994, 3.0],
+                           rng.integers(-999, 999, 50) + 0.5])
+    for scale in (1.0, 2.0**24, 2.0**50, 2.0**63, 2.0**100):
+        got = host(ctx.encode_scalar(torch.from_numpy(vals).cuda(), scale))
+        want = oracle.encode_scalars(vals, scale, c.q)
+        assert np.array_equal(got, want), scale
+        assert np.array_equal(got, ctx.encode_scalar_host(vals, scale))
+    got = host(ctx.encode_scalar(torch.tensor([float("nan"), 1.0, float("inf")], dtype=torch.float64).cuda(), 2.0**30, limbs=3))
+    assert np.all(got[0] == 2**64 - 1) and np.all(got[2] == 2**64 - 1)
+    assert got[1].tolist() == [2**30 % qi for qi in c.q[:3]]
+
+
+# ----------------------------------------------------------------------------- Alg. 3 / 4
+
+@pytest.mark.parametrize("cfg", [1, 4])
+def test_ct_pt_add_matches_oracle(he, cfg):
+    c = wl.config(cfg)
+    ctx = he.Context(c.log2N, c.q)
+    n = 5
+    ct = wl.uniform_residues((n, 2), c.q, c.N, 31)
+    ct[0, 0] = np.array(c.q, dtype=np.uint64)[:, None] - 1      # wrap-around edge
+    pts = wl.uniform_residues((n,), c.q, 1, 32)[..., 0]
+    pts[0] = np.array(c.q, dtype=np.uint64) - 1
+    d = dev(ct)
+    ctx.ct_pt_add(d, dev(pts), he.PT_SCALAR)
+    assert np.array_equal(host(d), oracle.add(ct, c.q, pts, oracle.PT_SCALAR))
+    ptv = wl.uniform_residues((n,), c.q, c.N, 33)
+    d = dev(ct)
+    ctx.ct_pt_add(d, dev(ptv), he.PT_POLY)
+    assert np.array_equal(host(d), oracle.add(ct, c.q, ptv, oracle.PT_POLY))
+    # level 2 of a deeper chain
+    d = dev(ct[:, :, :2].copy())
+    ctx.ct_pt_add(d, dev(pts[:, :2].copy()), he.PT_SCALAR)
+    assert np.array_equal(host(d), oracle.add(ct[:, :, :2], c.q[:2], pts[:, :2], oracle.PT_SCALAR))
+
+
+# ----------------------------------------------------------------------------- Alg. 7 / 8 over plans
+
+def irregular_plan(n_in, seed):
+    """Outputs with 0, 1, 2, ... terms, some sharing their inputs (groups of 2..16), some not."""
+    rng = np.random.default_rng(seed)
+    off, tc, tp = [0], [], []
+    n_pt = 0
+    def add(cts):
+        nonlocal n_pt
+        tc.extend(cts)
+        tp.extend(range(n_pt, n_pt + len(cts)))
+        n_pt += len(cts)
+        off.append(len(tc))
+    add([])                                                     # empty output
+    for k in (1, 2, 3, 9):
+        add(rng.integers(0, n_in, k).tolist())
+    for group, k in ((2, 5), (4, 7), (5, 3), (16, 6), (19, 4)):  # shared input lists
+        cts = rng.integers(0, n_in, k).tolist()
+        for _ in range(group):
+            add(cts)
+    add([])
+    return wl.Plan(n_in, len(off) - 1, n_pt, np.asarray(off, np.uint32), np.asarray(tc, np.uint32), np.asarray(tp, np.uint32))
+
+
+@pytest.mark.parametrize("log2N,bits", [(10, [30, 62, 50]), (12, [60, 60, 50])])
+def test_mac_scalar_and_poly_match_oracle_on_irregular_plan(he, log2N, bits):
+    N = 1 << log2N
+    q = wl.modulus_chain(bits, N)
+    ctx = he.Context(log2N, q)
+    plan = irregular_plan(11, 5)
+    hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+    ct = wl.uniform_residues((plan.n_in, 2), q, N, 41)
+    w = wl.uniform_residues((plan.n_pt,), q, 1, 42)[..., 0]
+    bias = wl.uniform_residues((plan.n_out,), q, 1, 43)[..., 0]
+    got = host(ctx.ct_pt_mac(hp, dev(ct), dev(w), he.PT_SCALAR, bias=dev(bias)))
+    want = oracle.mac(ct, q, plan.off, plan.term_ct, plan.term_pt, w, oracle.PT_SCALAR, bias)
+    assert np.array_equal(got, want)
+    got = host(ctx.ct_pt_mac(hp, dev(ct), dev(w), he.PT_SCALAR))
+    assert np.array_equal(got, oracle.mac(ct, q, plan.off, plan.term_ct, plan.term_pt, w, oracle.PT_SCALAR))
+    wp = wl.uniform_residues((plan.n_pt,), q, N, 44)
+    got = host(ctx.ct_pt_mac(hp, dev(ct), dev(wp), he.PT_POLY, bias=dev(bias)))
+    assert np.array_equal(got, oracle.mac(ct, q, plan.off, plan.term_ct, plan.term_pt, wp, oracle.PT_POLY, bias))
+    # Alg. 8 == Alg. 7 on replicated plaintexts
+    rep = np.repeat(w[:, :, None], N, axis=2)
+    assert np.array_equal(host(ctx.ct_pt_mac(hp, dev(ct), dev(rep), he.PT_POLY)),
+                          host(ctx.ct_pt_mac(hp, dev(ct), dev(w), he.PT_SCALAR)))
+
+
+def test_mac_long_sums_of_extreme_operands(he):
+    # (q-1)*(q-1) summed 700 times: crosses every fold and reduce boundary of the accumulator
+    N = 1 << 10
+    q = wl.modulus_chain([62, 60, 50, 30], N)
+    ctx = he.Context(10, q)
+    K, M = 700, 3
+    plan = wl.dense_plan(K, M)
+    hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+    qa = np.array(q, dtype=np.uint64)
+    ct = np.broadcast_to((qa - 1)[None, None, :, None], (K, 2, len(q), N)).copy()
+    ct[:, :, :, 1::2] = wl.uniform_residues((K, 2), q, N // 2, 51)
+    w = np.broadcast_to((qa - 1)[None, :], (K * M, len(q))).copy()
+    w[1::3] = wl.uniform_residues((len(w[1::3]),), q, 1, 52)[..., 0]
+    want = oracle.mac(ct, q, plan.off, plan.term_ct, plan.term_pt, w, oracle.PT_SCALAR)
+    assert np.array_equal(host(ctx.ct_pt_mac(hp, dev(ct), dev(w), he.PT_SCALAR)), want)
+    for l in range(len(q)):
+        assert int(want[0, 0, l, 0]) == K * (q[l] - 1) ** 2 % q[l]
+    wp = np.broadcast_to((qa - 1)[None, :, None], (K * M, len(q), N)).copy()
+    wp[:, :, 1::2] = wl.uniform_residues((K * M,), q, N // 2, 53)
+    assert np.array_equal(host(ctx.ct_pt_mac(hp, dev(ct), dev(wp), he.PT_POLY)),
+                          oracle.mac(ct, q, plan.off, plan.term_ct, plan.term_pt, wp, oracle.PT_POLY))
+
+
+def test_mac_argument_errors(he):
+    c = wl.config(1)
+    ctx = he.Context(c.log2N, c.q)
+    p = wl.dense_plan(2, 2)
+    with pytest.raises(he.HeError) as e:
+        ctx.plan(p.n_in, p.n_out, p.n_pt, p.off, p.term_ct + 2, p.term_pt)       # ct index out of range
+    assert e.value.status == -4
+    hp = ctx.plan(p.n_in, p.n_out, p.n_pt, p.off, p.term_ct, p.term_pt)
+    ct = dev(wl.uniform_residues((2, 2), c.q, c.N, 1))
+    w = dev(wl.uniform_residues((4,), c.q, 1, 2)[..., 0])
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(he.HeError) as e:
+        ctx.ct_pt_mac(hp, ct, w, he.PT_SCALAR, flags=he.RESCALE, workspace=small)
+    assert e.value.status == -6
+    with pytest.raises(he.HeError) as e:                                            # rescale needs 2 limbs
+        ctx.ct_pt_mac(hp, ct[:, :, :1].contiguous(), w[:, :1].contiguous(), he.PT_SCALAR, flags=he.RESCALE)
+    assert e.value.status == -3
+
+
+# ----------------------------------------------------------------------------- Eq. (2)
+
+@pytest.mark.parametrize("cfg", [1, 2, 4])
+def test_rescale_matches_oracle(he, cfg):
+    c = wl.config(cfg)
+    ctx = he.Context(c.log2N, c.q)
+    ct = wl.uniform_residues((3, 2), c.q, c.N, 61)
+    ct[0, 0] = 0
+    ct[0, 1] = np.array(c.q, dtype=np.uint64)[:, None] - 1
+    got = host(ctx.rescale(dev(ct)))
+    assert np.array_equal(got, oracle.rescale(ct, c.q, ctx.psi))
+    if c.L >= 3:                                                # one level down: drops limb L-2
+        sub = np.ascontiguousarray(ct[:, :, : c.L - 1])
+        assert np.array_equal(host(ctx.rescale(dev(sub))), oracle.rescale(sub, c.q[:-1], ctx.psi[:-1]))
+
+
+# ----------------------------------------------------------------------------- whole layers, all five configs
+
+def run_layer(he, c, ctx, plan, ct_dev, pt_dev, pt_kind, bias_dev):
+    hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+    out = ctx.ct_pt_mac(hp, ct_dev, pt_dev, pt_kind, bias=bias_dev, flags=he.RESCALE)
+    torch.cuda.synchronize()
+    return out
+
+
+def check_outputs(c, ctx, plan, outputs, out_dev, ct_rows, pt_rows, pt_kind, bias):
+    """Oracle layer for the listed outputs on host copies of just the inputs they touch."""
+    sub, ct_ids, pt_ids = compact(plan, outputs)
+    ct = host(ct_rows(ct_ids))
+    pt = host(pt_rows(pt_ids))
+    b = None if bias is None else bias[list(outputs)]
+    want, n_rescales = oracle.layer(ct, c.q, ctx.psi, sub.off, sub.term_ct, sub.term_pt, pt, pt_kind, b)
+    assert n_rescales == len(outputs)
+    got = host(out_dev[torch.as_tensor(list(outputs), device="cuda")])
+    assert np.array_equal(got, want)
+
+
+def test_config1_dense_layer_full_parity(he):
+    c = wl.config(1)
+    ctx = he.Context(c.log2N, c.q)
+    plan = c.plan
+    ct = dev(wl.uniform_residues((plan.n_in, 2), c.q, c.N, c.seed))
+    w = torch.from_numpy(wl.normal_values(plan.n_pt, c.sigma, c.seed + 100)).cuda()
+    b = torch.from_numpy(wl.normal_values(plan.n_out, c.sigma, c.seed + 200)).cuda()
+    wenc = ctx.encode_scalar(w, 2.0**c.log2_scale)
+    benc = ctx.encode_scalar(b, 2.0**c.log2_scale)
+    out = run_layer(he, c, ctx, plan, ct, wenc, he.PT_SCALAR, benc)
+    check_outputs(c, ctx, plan, range(plan.n_out), out, lambda i: ct[i], lambda i: wenc[i], oracle.PT_SCALAR, host(benc))
+
+
+@pytest.mark.parametrize("cfg,sample", [(2, 12), (3, 5), (4, 6)])
+def test_scalar_layers_at_full_size_sampled_outputs(he, cfg, sample):
+    c = wl.config(cfg)
+    ctx = he.Context(c.log2N, c.q)
+    plan = c.plan
+    ct = wl.uniform_residues_torch((plan.n_in, 2), c.q, c.N, c.seed, "cuda")
+    w = torch.from_numpy(wl.normal_values(plan.n_pt, c.sigma, c.seed + 100)).cuda()
+    b = torch.from_numpy(wl.normal_values(plan.n_out, c.sigma, c.seed + 200)).cuda()
+    wenc = ctx.encode_scalar(w, 2.0**c.log2_scale)
+    benc = ctx.encode_scalar(b, 2.0**c.log2_scale)
+    assert np.array_equal(host(wenc[:50]), oracle.encode_scalars(w[:50].cpu().numpy(), 2.0**c.log2_scale, c.q))
+    out = run_layer(he, c, ctx, plan, ct, wenc, he.PT_SCALAR, benc)
+    rng = np.random.default_rng(c.seed)
+    outputs = sorted(set([0, plan.n_out - 1] + rng.integers(0, plan.n_out, sample).tolist()))
+    lens = np.diff(plan.off.astype(np.int64))
+    for k in np.unique(lens):                                   # every window size (padding rows/cols) is sampled
+        outputs.append(int(np.flatnonzero(lens == k)[-1]))
+    outputs = sorted(set(outputs))
+    check_outputs(c, ctx, plan, outputs, out, lambda i: ct[torch.as_tensor(i, device="cuda")],
+                  lambda i: wenc[torch.as_tensor(i, device="cuda")], oracle.PT_SCALAR, host(benc))
+    # properties that hold for every output at any size: canonical residues
+    for l in range(c.L - 1):
+        assert int(out[:, :, l].max()) < c.q[l] and int(out[:, :, l].min()) >= 0
+
+
+def test_config5_full_poly_layer_sampled_outputs(he):
+    c = wl.config(5)
+    ctx = he.Context(c.log2N, c.q)
+    plan = c.plan
+    ct = wl.uniform_residues_torch((plan.n_in, 2), c.q, c.N, c.seed, "cuda")
+    pt = wl.uniform_residues_torch((plan.n_pt,), c.q, c.N, c.seed + 100, "cuda")     # 16 GiB
+    out = run_layer(he, c, ctx, plan, ct, pt, he.PT_POLY, None)
+    outputs = [0, 37, plan.n_out - 1]
+    for o in outputs:
+        check_outputs(c, ctx, plan, [o], out, lambda i: ct[torch.as_tensor(i, device="cuda")],
+                      lambda i: pt[torch.as_tensor(i, device="cuda")], oracle.PT_POLY, None)
+    for l in range(c.L - 1):
+        assert int(out[:, :, l].max()) < c.q[l] and int(out[:, :, l].min()) >= 0
+    # the unfused route gives the same residues as the fused call
+    hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+    acc = ctx.ct_pt_mac(hp, ct, pt, he.PT_POLY)
+    assert torch.equal(ctx.rescale(acc), out)
+
+
+# ----------------------------------------------------------------------------- meaning: encrypt, compute, decrypt
+
+def test_encrypted_dense_layer_decrypts_to_float_layer(he):
+    from oracle.ckks_scaffold import Scaffold
+    c = wl.config(1)
+    ctx = he.Context(c.log2N, c.q)
+    K, M = 64, 16
+    sc = Scaffold(c.N, c.q, ctx.psi, 300)
+    rng = np.random.default_rng(301)
+    x = rng.uniform(-1, 1, size=(K, c.N // 2))
+    w = rng.normal(0, 0.1, size=(K, M))
+    b = rng.normal(0, 0.1, size=M)
+    cts = np.stack([sc.encrypt(x[k], 2.0**30) for k in range(K)])
+    plan = wl.dense_plan(K, M)
+    hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+    wenc = ctx.encode_scalar(torch.from_numpy(w.ravel()).cuda(), 2.0**24)
+    benc = ctx.encode_scalar(torch.from_numpy(b).cuda(), 2.0**54)
+    out = host(ctx.ct_pt_mac(hp, dev(cts), wenc, he.PT_SCALAR, bias=benc, flags=he.RESCALE))
+    want = x.T @ w + b
+    scale_out = 2.0**54 / c.q[-1]
+    worst = 0.0
+    for o in range(M):
+        got = sc.decrypt(out[o], scale_out).real
+        worst = max(worst, float(np.max(np.abs(got - want[:, o]) / np.maximum(1.0, np.abs(want[:, o])))))
+    assert worst <= 2.0**-10, worst

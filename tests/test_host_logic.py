@@ -1,0 +1,119 @@
+"""CPU-only checks of the library: it loads, exports every symbol include/he.h declares, and its host
+logic (modulus validation, root choice, the device arithmetic compiled for the host, scalar
+encoding) agrees with Python integers and with the oracle.  No kernel is launched here."""
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1908_04172_amd import he
+from paper_1908_04172_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "he.h")).read()
+    declared = set(re.findall(r"\b(he_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(he.EXPORTS)
+    L = he.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert he.lib().he_strerror(0) == b"ok"
+    assert b"modulus" in he.lib().he_strerror(-2)
+
+
+def primes():
+    return [wl.ntt_primes(b, 1 << 14, 1)[0] for b in (30, 40, 50, 60, 62)]
+
+
+def test_barrett_and_shoup_equal_python_mod():
+    rnd = random.Random(3)
+    for q in primes():
+        edge = [0, 1, q - 1, q - 2, q // 2]
+        for _ in range(200):
+            a, b = rnd.choice(edge + [rnd.randrange(q)]), rnd.choice(edge + [rnd.randrange(q)])
+            assert he.host_mulmod(a, b, q) == a * b % q
+            assert he.host_shoup_mulmod(a, b, q) == a * b % q
+        # the Shoup product takes any 64-bit left operand (lazy butterflies feed it values up to 4q)
+        for y in (2**64 - 1, 4 * q - 1, 2 * q, 2 * q + 1):
+            w = rnd.randrange(q)
+            assert he.host_shoup_mulmod(y, w, q) == y * w % q
+        # any 128-bit input
+        for z in [0, q, q - 1, (q - 1) ** 2, 2**64 - 1, 2**64, 2**128 - 1, 2**127] + [rnd.randrange(2**128) for _ in range(200)]:
+            assert he.host_reduce128(z >> 64, z & (2**64 - 1), q) == z % q
+
+
+def test_mac_accumulator_fold_and_reduce_schedule():
+    rnd = random.Random(4)
+    for q in primes():
+        for n in (0, 1, 2, 7, 8, 9, 16, 17, 255, 256, 257, 1000):
+            for mode in ("max", "rand"):
+                x = [q - 1] * n if mode == "max" else [rnd.randrange(q) for _ in range(n)]
+                w = [q - 1] * n if mode == "max" else [rnd.randrange(q) for _ in range(n)]
+                want = sum(a * b for a, b in zip(x, w)) % q
+                assert he.host_mac_accumulate(x, w, q) == want, (q, n, mode)
+
+
+def test_context_validates_moduli():
+    N = 1 << 12
+    good = wl.modulus_chain([30, 30], N)
+    he.Context(12, good, device=None).close()
+    bad_sets = [
+        [good[0], good[0]],                      # repeated
+        [good[0], good[1] + 2 * N],              # = 1 mod 2N but (here) composite
+        [good[0], 1073741827],                   # prime, but not 1 mod 2N
+        [good[0], (1 << 62) + 1],                # too large
+    ]
+    assert not oracle.is_prime(good[1] + 2 * N) and oracle.is_prime(1073741827)
+    for mods in bad_sets:
+        with pytest.raises(he.HeError) as e:
+            he.Context(12, mods, device=None)
+        assert e.value.status == -2
+    for log2N in (9, 15):
+        with pytest.raises(he.HeError) as e:
+            he.Context(log2N, good, device=None)
+        assert e.value.status == -1
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 4])
+def test_root_choice_matches_oracle(cfg):
+    c = wl.config(cfg)
+    ctx = he.Context(c.log2N, c.q, device=None)
+    assert ctx.psi == oracle.find_psis(c.q, c.N)
+
+
+def test_encode_scalar_host_matches_oracle():
+    c = wl.config(4)
+    ctx = he.Context(c.log2N, c.q, device=None)
+    rnd = random.Random(6)
+    vals = [0.0, -0.0, 0.5, -0.5, 1.5, 2.5, -2.5, 0.49999999999999994, 1e-30, 3.0, -3.0, 2.0**52 + 1]
+    vals += [rnd.gauss(0, 0.1) for _ in range(200)] + [rnd.randrange(-999, 999) + 0.5 for _ in range(50)]
+    for scale in (1.0, 2.0**24, 2.0**50, 2.0**62, 2.0**63, 2.0**80, 2.0**100):
+        got = ctx.encode_scalar_host(vals, scale)
+        assert got.shape == (len(vals), c.L) and got.nbytes == 8 * c.L * len(vals)   # 8*L bytes per scalar
+        for v, row in zip(vals, got):
+            assert row.tolist() == oracle.encode_scalar(v, scale, c.q).tolist(), (v, scale)
+    # depth-aware encoding: a lower level is a prefix of the limbs
+    assert np.array_equal(ctx.encode_scalar_host(vals, 2.0**50, limbs=3), ctx.encode_scalar_host(vals, 2.0**50)[:, :3])
+    with pytest.raises(he.HeError):
+        ctx.encode_scalar_host([float("nan")], 1.0)
+    with pytest.raises(he.HeError) as e:
+        ctx.encode_scalar_host([1.0], 1.0, limbs=9)
+    assert e.value.status == -3
+
+
+def test_device_calls_fail_loudly_on_a_host_only_context():
+    c = wl.config(1)
+    ctx = he.Context(c.log2N, c.q, device=None)
+    p = c.plan
+    with pytest.raises(he.HeError) as e:
+        ctx.plan(p.n_in, p.n_out, p.n_pt, p.off, p.term_ct, p.term_pt)
+    assert e.value.status == -5
+    dummy = np.zeros(4, dtype=np.uint64)
+    assert he.lib().he_rescale(ctx._h, 2, dummy.ctypes.data, dummy.ctypes.data, 1, None) == -5
+    assert he.lib().he_rescale(ctx._h, 1, dummy.ctypes.data, dummy.ctypes.data, 1, None) == -3
+    assert he.lib().he_ntt_fwd(ctx._h, 3, dummy.ctypes.data, 1, None) == -3
