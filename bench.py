@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the ct-pt MAC + lazy-rescale hot path at N = 2^14, L = 8 on one MI355X.
+
+One step = one pass of the whole path over the two N = 2^14, L = 8 workloads:
+  cfg4  conv 32x32x3 -> 16x16x16, 3x3, stride 2, same padding, scalar plaintexts:
+        scalar-encode the 432 weights and 16 biases (Alg. 2), MAC + bias (Alg. 8 / 4),
+        one lazy rescale per output ciphertext (Eq. (2)): 4096 rescaled ciphertexts
+  cfg5  dense 256 -> 64 with full-polynomial plaintexts (Alg. 7), one rescale per output: 64
+Inputs are synthetic (uniform residues, Gaussian weights), generated on the device before the timed
+region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# 256 CUs x 64 lanes x 2.4 GHz: one 32x32(+64)-bit integer multiply(-add) per lane per clock
+INT_MUL32_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+MUL32_PER_MAC = 4          # a 64x64 -> 128-bit product is four 32x32 -> 64 multiply-adds
+MUL32_PER_SHOUP = 10       # hi64(y*w') 4, lo64(y*w) 3, lo64(qh*q) 3
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-cfg4", type=int, default=64, help="cfg4 outputs the oracle is timed on")
+    ap.add_argument("--cpu-sample-cfg5", type=int, default=2, help="cfg5 outputs the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU figure exists", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_1908_04172_amd import he, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        return 1
+    he.lib()
+    dev = "cuda"
+    c4, c5 = wl.config(4), wl.config(5)
+    assert c4.q == c5.q and c4.N == c5.N
+    N, L, q = c4.N, c4.L, c4.q
+    ctx = he.Context(c4.log2N, q, device=0)
+    p4, p5 = c4.plan, c5.plan
+    hp4 = ctx.plan(p4.n_in, p4.n_out, p4.n_pt, p4.off, p4.term_ct, p4.term_pt)
+    hp5 = ctx.plan(p5.n_in, p5.n_out, p5.n_pt, p5.off, p5.term_ct, p5.term_pt)
+
+    # ---- inputs, resident in HBM before anything is timed
+    ct4 = wl.uniform_residues_torch((p4.n_in, 2), q, N, c4.seed, dev)
+    w4 = torch.from_numpy(wl.normal_values(p4.n_pt, c4.sigma, c4.seed + 100)).to(dev)
+    b4 = torch.from_numpy(wl.normal_values(p4.n_out, c4.sigma, c4.seed + 200)).to(dev)
+    ct5 = wl.uniform_residues_torch((p5.n_in, 2), q, N, c5.seed, dev)
+    pt5 = wl.uniform_residues_torch((p5.n_pt,), q, N, c5.seed + 100, dev)
+    wenc4 = torch.empty((p4.n_pt, L), dtype=torch.int64, device=dev)
+    benc4 = torch.empty((p4.n_out, L), dtype=torch.int64, device=dev)
+    acc4 = torch.empty((p4.n_out, 2, L, N), dtype=torch.int64, device=dev)
+    out4 = torch.empty((p4.n_out, 2, L - 1, N), dtype=torch.int64, device=dev)
+    acc5 = torch.empty((p5.n_out, 2, L, N), dtype=torch.int64, device=dev)
+    out5 = torch.empty((p5.n_out, 2, L - 1, N), dtype=torch.int64, device=dev)
+    ws4 = torch.empty(max(hp4.workspace_bytes(L, he.PT_SCALAR, 0), 256), dtype=torch.uint8, device=dev)
+    scale = 2.0 ** c4.log2_scale
+
+    phases = ["encode_cfg4", "mac_scalar_cfg4", "rescale_cfg4", "mac_poly_cfg5", "rescale_cfg5"]
+
+    def step(ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        ctx.encode_scalar(w4, scale, out=wenc4)
+        ctx.encode_scalar(b4, scale, out=benc4)
+        mark(1)
+        ctx.ct_pt_mac(hp4, ct4, wenc4, he.PT_SCALAR, bias=benc4, out=acc4, workspace=ws4)
+        mark(2)
+        ctx.rescale(acc4, out=out4)
+        mark(3)
+        ctx.ct_pt_mac(hp5, ct5, pt5, he.PT_POLY, out=acc5)
+        mark(4)
+        ctx.rescale(acc5, out=out5)
+        mark(5)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    phase_ms = {name: float(np.mean([events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)]))
+                for i, name in enumerate(phases)}
+
+    # ---- algorithmic work (per step)
+    ct_bytes = 2 * L * N * 8
+    out_bytes = 2 * (L - 1) * N * 8
+    bytes4 = p4.n_in * ct_bytes + p4.n_out * out_bytes + (p4.n_pt + p4.n_out) * (8 + 8 * L)
+    bytes5 = p5.n_pt * L * N * 8 + p5.n_in * ct_bytes + p5.n_out * out_bytes
+    total_bytes = bytes4 + bytes5
+    n_rescaled = p4.n_out + p5.n_out
+    value = total_bytes / (ms_per_step * 1e-3) / 1e9
+
+    def rescale_mul32(n_ct):
+        butterflies = n_ct * 2 * L * (N // 2) * c4.log2N          # one INTT + L-1 NTTs per polynomial
+        return (butterflies + n_ct * 2 * (L - 1) * N) * MUL32_PER_SHOUP
+    rooflines = {}
+    macs4 = p4.n_terms * 2 * L * N
+    macs5 = p5.n_terms * 2 * L * N
+    def alu(name, mul32):
+        a = mul32 / (phase_ms[name] * 1e-3) / 1e12
+        return {"kernel": name, "bound": "alu", "achieved": a, "peak": INT_MUL32_PEAK_TOPS, "unit": "Tmul32/s",
+                "frac": a / INT_MUL32_PEAK_TOPS, "traffic": None}
+    def hbm(name, nbytes):
+        a = nbytes / (phase_ms[name] * 1e-3) / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": a / HBM_PEAK_GBS, "traffic": None}
+    rooflines["mac_scalar_cfg4"] = alu("mac_scalar_cfg4", macs4 * MUL32_PER_MAC)
+    rooflines["rescale_cfg4"] = alu("rescale_cfg4", rescale_mul32(p4.n_out))
+    # the full-polynomial MAC streams every plaintext residue once: HBM-bound
+    mac5_bytes = p5.n_pt * L * N * 8 + p5.n_in * ct_bytes + p5.n_out * ct_bytes
+    rooflines["mac_poly_cfg5"] = hbm("mac_poly_cfg5", mac5_bytes)
+    rooflines["rescale_cfg5"] = alu("rescale_cfg5", rescale_mul32(p5.n_out))
+    dominant = max(rooflines, key=lambda k: phase_ms[k])
+
+    result = {
+        "metric": "ct-pt MAC GB/s (% HBM peak) + rescaled ciphertexts/sec at N=2^14, L=8",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "cfg4 (conv 32x32x3->16x16x16 3x3 s2 same, scalar pt: encode+MAC+bias+lazy rescale, "
+                               "4096 outputs) + cfg5 (dense 256->64, full-poly pt: MAC+lazy rescale, 64 outputs), "
+                               "N=2^14, L=8 (2x60-bit + 6x50-bit)",
+                   "value_definition": "algorithmic bytes of the step (inputs once + outputs once) / step time",
+                   "algorithmic_bytes_per_step": total_bytes},
+        "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+        "rescaled_ct_per_s": n_rescaled / (ms_per_step * 1e-3),
+        "rescale_only_ct_per_s": n_rescaled / ((phase_ms["rescale_cfg4"] + phase_ms["rescale_cfg5"]) * 1e-3),
+        "mac_poly_cfg5_GBps": rooflines["mac_poly_cfg5"]["achieved"],
+        "mac_poly_cfg5_pct_hbm_peak": 100.0 * rooflines["mac_poly_cfg5"]["frac"],
+        "mac_scalar_cfg4_Tmac_per_s": macs4 / (phase_ms["mac_scalar_cfg4"] * 1e-3) / 1e12,
+        "mac_poly_cfg5_Tmac_per_s": macs5 / (phase_ms["mac_poly_cfg5"] * 1e-3) / 1e12,
+        "phase_ms": phase_ms,
+        "roofline": {k: v for k, v in rooflines[dominant].items()},
+        "roofline_all": list(rooflines.values()),
+    }
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.set_threads(0)
+        psi = ctx.psi
+        to_host = lambda t: t.cpu().numpy().view(np.uint64)
+        idx = lambda t, ids: t[torch.as_tensor(np.asarray(ids, dtype=np.int64), device=t.device)]
+
+        def compact(plan, outs):
+            sub = plan.subset(outs)
+            ct_ids, ct_inv = np.unique(sub.term_ct, return_inverse=True)
+            pt_ids, pt_inv = np.unique(sub.term_pt, return_inverse=True)
+            return sub.off, ct_inv.astype(np.uint32), pt_inv.astype(np.uint32), ct_ids, pt_ids
+
+        s4 = list(range(0, p4.n_out, max(1, p4.n_out // args.cpu_sample_cfg4)))[: args.cpu_sample_cfg4]
+        off, tc, tp, ct_ids, pt_ids = compact(p4, s4)
+        h_ct, h_w, h_b = to_host(idx(ct4, ct_ids)), w4.cpu().numpy(), b4.cpu().numpy()
+        t = time.perf_counter()
+        wenc = oracle.encode_scalars(h_w, scale, q)
+        benc = oracle.encode_scalars(h_b, scale, q)
+        want4, _ = oracle.layer(h_ct, q, psi, off, tc, tp, wenc[pt_ids], oracle.PT_SCALAR, benc[s4])
+        t4 = time.perf_counter() - t
+        s5 = list(range(args.cpu_sample_cfg5))
+        off, tc, tp, ct_ids, pt_ids = compact(p5, s5)
+        h_ct, h_pt = to_host(idx(ct5, ct_ids)), to_host(idx(pt5, pt_ids))
+        t = time.perf_counter()
+        want5, _ = oracle.layer(h_ct, q, psi, off, tc, tp, h_pt, oracle.PT_POLY, None)
+        t5 = time.perf_counter() - t
+        # the timed GPU outputs must be the oracle's, bit for bit
+        ok = np.array_equal(to_host(idx(out4, s4)), want4) and np.array_equal(to_host(idx(out5, s5)), want5)
+        cpu_step_s = t4 * p4.n_out / len(s4) + t5 * p5.n_out / len(s5)
+        result["cpu_baseline"] = {
+            "value": total_bytes / cpu_step_s / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of %d cfg4 outputs (%.1f s) + %d of %d cfg5 outputs (%.1f s), extrapolated linearly to "
+                      "the whole step" % (len(s4), p4.n_out, t4, len(s5), p5.n_out, t5),
+            "rescaled_ct_per_s": n_rescaled / cpu_step_s, "gpu_outputs_match_oracle": bool(ok)}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -28,6 +28,11 @@ def host(t) -> np.ndarray:
     return t.cpu().numpy().view(np.uint64)
 
 
+def rows(t, ids):
+    """t[ids] for a NumPy index array of any integer type."""
+    return t[torch.as_tensor(np.asarray(ids, dtype=np.int64), device=t.device)]
+
+
 def compact(plan: wl.Plan, outputs):
     """Sub-problem for the listed outputs with ct/pt indices renumbered densely."""
     sub = plan.subset(outputs)
@@ -234,7 +239,7 @@ def check_outputs(c, ctx, plan, outputs, out_dev, ct_rows, pt_rows, pt_kind, bia
     b = None if bias is None else bias[list(outputs)]
     want, n_rescales = oracle.layer(ct, c.q, ctx.psi, sub.off, sub.term_ct, sub.term_pt, pt, pt_kind, b)
     assert n_rescales == len(outputs)
-    got = host(out_dev[torch.as_tensor(list(outputs), device="cuda")])
+    got = host(rows(out_dev, list(outputs)))
     assert np.array_equal(got, want)
 
 
@@ -248,7 +253,7 @@ def test_config1_dense_layer_full_parity(he):
     wenc = ctx.encode_scalar(w, 2.0**c.log2_scale)
     benc = ctx.encode_scalar(b, 2.0**c.log2_scale)
     out = run_layer(he, c, ctx, plan, ct, wenc, he.PT_SCALAR, benc)
-    check_outputs(c, ctx, plan, range(plan.n_out), out, lambda i: ct[i], lambda i: wenc[i], oracle.PT_SCALAR, host(benc))
+    check_outputs(c, ctx, plan, range(plan.n_out), out, lambda i: rows(ct, i), lambda i: rows(wenc, i), oracle.PT_SCALAR, host(benc))
 
 
 @pytest.mark.parametrize("cfg,sample", [(2, 12), (3, 5), (4, 6)])
@@ -269,8 +274,8 @@ def test_scalar_layers_at_full_size_sampled_outputs(he, cfg, sample):
     for k in np.unique(lens):                                   # every window size (padding rows/cols) is sampled
         outputs.append(int(np.flatnonzero(lens == k)[-1]))
     outputs = sorted(set(outputs))
-    check_outputs(c, ctx, plan, outputs, out, lambda i: ct[torch.as_tensor(i, device="cuda")],
-                  lambda i: wenc[torch.as_tensor(i, device="cuda")], oracle.PT_SCALAR, host(benc))
+    check_outputs(c, ctx, plan, outputs, out, lambda i: rows(ct, i),
+                  lambda i: rows(wenc, i), oracle.PT_SCALAR, host(benc))
     # properties that hold for every output at any size: canonical residues
     for l in range(c.L - 1):
         assert int(out[:, :, l].max()) < c.q[l] and int(out[:, :, l].min()) >= 0
@@ -285,8 +290,8 @@ def test_config5_full_poly_layer_sampled_outputs(he):
     out = run_layer(he, c, ctx, plan, ct, pt, he.PT_POLY, None)
     outputs = [0, 37, plan.n_out - 1]
     for o in outputs:
-        check_outputs(c, ctx, plan, [o], out, lambda i: ct[torch.as_tensor(i, device="cuda")],
-                      lambda i: pt[torch.as_tensor(i, device="cuda")], oracle.PT_POLY, None)
+        check_outputs(c, ctx, plan, [o], out, lambda i: rows(ct, i),
+                      lambda i: rows(pt, i), oracle.PT_POLY, None)
     for l in range(c.L - 1):
         assert int(out[:, :, l].max()) < c.q[l] and int(out[:, :, l].min()) >= 0
     # the unfused route gives the same residues as the fused call
