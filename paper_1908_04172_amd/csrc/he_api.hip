@@ -88,14 +88,29 @@ void fill_limb_const(LimbConst& c, u64 q, u64 psi, u32 N) {
     const u64 w1_inv = h_powmod(psi_inv, N / 2, q);  // psi^-bitrev(1)
     c.w1n_inv = h_mulmod(w1_inv, c.n_inv, q);
     c.w1n_inv_shoup = h_shoup(c.w1n_inv, q);
-    // accumulator bounds (see MacAcc): a term adds at most 2*(2^32-1)*qh to `mid`, qh = floor((q-1)/2^32)
-    const u64 qh = (q - 1) >> 32;
-    u64 fold = qh ? ((~0ull - 0xFFFFFFFFull) / (2 * 0xFFFFFFFFull * qh)) : 0x7FFFFFFFull;
-    c.fold_every = (u32)std::min<u64>(std::max<u64>(fold, 1), 0x7FFFFFFFull);
-    // q + R*(q-1)^2 must stay below 2^128
+    // Accumulator periods (see MacAcc).  Pieces: xa, wa <= A = 2^s - 1; xb, wb <= B = (q-1) >> s.
+    u32 bits = 0;
+    while (bits < 64 && ((q - 1) >> bits)) ++bits;
+    const u32 s = (bits + 1) / 2;
+    c.split_bits = s;
+    c.split_mask = (1ull << s) - 1;
+    const u128 A = c.split_mask, B = (q - 1) >> s, top = (u128)1 << 64;
+    // after a fold (or a restart) lo <= A and mid <= A; F more terms must keep
+    //   lo <= A + F*A*A  and  mid + (lo >> s) <= A + 2*F*A*B + (lo >> s)  below 2^64
+    u64 fold = 0;
+    for (u64 f = 1; f <= 0x7FFFFFFFull; f = (f < 64 ? f + 1 : f * 2)) {
+        const u128 lo_max = A + (u128)f * A * A;
+        const u128 mid_max = A + 2 * (u128)f * A * B + (lo_max >> s);
+        if (lo_max >= top || mid_max >= top) break;
+        fold = f;
+    }
+    c.fold_every = (u32)std::max<u64>(fold, 1);
+    // hi <= value >> 2s must stay below 2^64 and the value below 2^128: q + R*(q-1)^2 < 2^min(128, 64+2s)
+    const u128 cap = (64 + 2 * s >= 128) ? all_ones : (((u128)1 << (64 + 2 * s)) - 1);
     const u128 sq = (u128)(q - 1) * (q - 1);
-    u128 red = (all_ones - q) / sq;
+    u128 red = (cap - q) / sq;
     c.reduce_every = (u32)std::min<u128>(std::max<u128>(red, 1), 0x7FFFFFFFull);
+    c.pad = 0;
 }
 
 int check_level(const he_ctx* ctx, u32 limbs, u32 min_limbs) {
@@ -391,7 +406,7 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
     for (int cls = 0; cls < 3; ++cls)
         for (u32 i = p->class_begin_s[cls]; i < p->class_begin_s[cls + 1]; ++i) {
             wbase[i] = elems;
-            elems += (u64)ts[i].n_terms * CAPS_S[cls];
+            elems += (u64)((ts[i].n_terms + 3) / 4 * 4) * CAPS_S[cls];  // terms padded to whole blocks of 4
         }
     p->wtab_elems = elems;
     if (upload(&p->tiles_s_dev, ts.data(), ts.size()) != HE_OK || upload(&p->tiles_p_dev, tp.data(), tp.size()) != HE_OK ||
@@ -523,9 +538,14 @@ uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, 
     acc_clear(a);
     u32 f = 0, r = 0;
     for (size_t t = 0; t < n; ++t) {
-        acc_mac_s(a, x[t], w[t]);
-        if (++r == c.reduce_every) { acc_restart(a, c); r = 0; f = 0; }
-        else if (++f == c.fold_every) { acc_fold(a); f = 0; }
+        u32 xa, xb, wa, wb;
+        split_operand(x[t], c, xa, xb);
+        split_operand(w[t], c, wa, wb);
+        acc_mac(a, xa, xb, wa, wb);
+        ++f;
+        ++r;
+        if (r + 1 > c.reduce_every) { acc_restart(a, c); r = 0; f = 0; }
+        else if (f + 1 > c.fold_every) { acc_fold(a, c); f = 0; }
     }
     return acc_reduce(a, c);
 }

@@ -18,8 +18,11 @@ struct LimbConst {
     u64 two_q;
     u64 n_inv, n_inv_shoup;        // N^-1 mod q and its Shoup companion
     u64 w1n_inv, w1n_inv_shoup;    // (psi^-brv(1)) * N^-1: last inverse butterfly merged with N^-1
-    u32 fold_every;   // MAC terms the middle accumulator word takes before it must be folded
-    u32 reduce_every; // MAC terms the whole accumulator takes before it must be reduced mod q
+    u64 split_mask;   // 2^split_bits - 1
+    u32 split_bits;   // where MAC operands are cut in two (see MacAcc)
+    u32 fold_every;   // MAC terms the partial sums take between two acc_fold calls
+    u32 reduce_every; // MAC terms the accumulator takes between two reductions mod q
+    u32 pad;
 };
 
 HE_HD u64 mul_hi64(u64 a, u64 b) {
@@ -71,67 +74,49 @@ HE_HD u64 shoup_mul(u64 y, u64 w, u64 w_shoup, u64 q) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// MAC accumulator: sum of 64x64-bit products kept as three partial sums so that a term costs four
-// 32x32+64 multiply-adds and one carry add, with no carry chain between the partial sums:
-//   value = lo + carry*2^64 + mid*2^32 + hi*2^64
-//   lo  += x0*w0 (may wrap: the wrap is counted in `carry`)
-//   mid += x0*w1 + x1*w0      hi += x1*w1
-// `mid` must be folded into `hi` every LimbConst::fold_every terms and the whole accumulator
-// reduced every LimbConst::reduce_every terms; both bounds are derived from q on the host.
+// MAC accumulator.  Both operands of a product are cut at bit s = LimbConst::split_bits (about half
+// the modulus width): x = xa + xb*2^s, w = wa + wb*2^s with all four pieces below 2^32, and
+//   value = lo + mid*2^s + hi*2^(2s),   lo += xa*wa,  mid += xa*wb + xb*wa,  hi += xb*wb.
+// Each piece product is below 2^(2s) <= 2^62, so a term is four 32x32+64-bit multiply-adds with no
+// carries between the three sums.  Every LimbConst::fold_every terms the sums are renormalised
+// (acc_fold), every LimbConst::reduce_every terms the value is reduced mod q (acc_restart); both
+// periods are derived from q on the host so that no 64-bit sum can wrap.
 struct MacAcc {
     u64 lo, mid, hi;
-    u32 carry;
 };
 
-HE_HD void acc_clear(MacAcc& a) { a.lo = a.mid = a.hi = 0; a.carry = 0; }
+HE_HD void acc_clear(MacAcc& a) { a.lo = a.mid = a.hi = 0; }
 
-// w lives in scalar registers on the device (one plaintext residue for the whole wave).
-HE_HD void acc_mac_s(MacAcc& a, u64 x, u64 w) {
-    u32 x0 = (u32)x, x1 = (u32)(x >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
-#if defined(__HIP_DEVICE_COMPILE__)
-    u64 c;
-    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(a.lo), "=s"(c) : "v"(x0), "s"(w0));
-    asm("v_addc_co_u32_e64 %0, %1, 0, %0, %1" : "+v"(a.carry), "+s"(c));
-    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(a.mid), "=s"(c) : "v"(x0), "s"(w1));
-    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(a.mid), "=s"(c) : "v"(x1), "s"(w0));
-    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(a.hi), "=s"(c) : "v"(x1), "s"(w1));
-#else
-    u64 p = (u64)x0 * w0, s = a.lo + p;
-    a.carry += s < p;
-    a.lo = s;
-    a.mid += (u64)x0 * w1;
-    a.mid += (u64)x1 * w0;
-    a.hi += (u64)x1 * w1;
-#endif
+HE_HD void split_operand(u64 v, const LimbConst& c, u32& va, u32& vb) {
+    va = (u32)(v & c.split_mask);
+    vb = (u32)(v >> c.split_bits);
 }
 
-// w in vector registers (a full-polynomial plaintext: one residue per lane).
-HE_HD void acc_mac_v(MacAcc& a, u64 x, u64 w) {
+HE_HD void acc_mac(MacAcc& a, u32 xa, u32 xb, u32 wa, u32 wb) {
+    a.lo += (u64)xa * wa;
+    a.mid += (u64)xa * wb;
 #if defined(__HIP_DEVICE_COMPILE__)
-    u32 x0 = (u32)x, x1 = (u32)(x >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
-    u64 c;
-    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(a.lo), "=s"(c) : "v"(x0), "v"(w0));
-    asm("v_addc_co_u32_e64 %0, %1, 0, %0, %1" : "+v"(a.carry), "+s"(c));
-    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(a.mid), "=s"(c) : "v"(x0), "v"(w1));
-    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(a.mid), "=s"(c) : "v"(x1), "v"(w0));
-    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(a.hi), "=s"(c) : "v"(x1), "v"(w1));
-#else
-    acc_mac_s(a, x, w);
+    asm("" : "+v"(a.mid));  // keep the two products as two multiply-adds into `mid`
 #endif
+    a.mid += (u64)xb * wa;
+    a.hi += (u64)xb * wb;
 }
 
-HE_HD void acc_fold(MacAcc& a) {  // move the upper half of `mid` into `hi`
-    a.hi += a.mid >> 32;
-    a.mid &= 0xFFFFFFFFull;
+HE_HD void acc_fold(MacAcc& a, const LimbConst& c) {  // push the high parts of lo and mid upwards
+    a.mid += a.lo >> c.split_bits;
+    a.lo &= c.split_mask;
+    a.hi += a.mid >> c.split_bits;
+    a.mid &= c.split_mask;
 }
 
 HE_HD u64 acc_reduce(const MacAcc& a, const LimbConst& c) {  // the accumulated value mod q
-    u128 v = (u128)a.lo + ((u128)a.mid << 32) + ((u128)(a.hi + a.carry) << 64);
+    u128 v = (u128)a.lo + ((u128)a.mid << c.split_bits) + ((u128)a.hi << (2 * c.split_bits));
     return reduce128((u64)(v >> 64), (u64)v, c);
 }
 
 HE_HD void acc_restart(MacAcc& a, const LimbConst& c) {  // reduce in place and keep accumulating
     u64 r = acc_reduce(a, c);
-    acc_clear(a);
-    a.lo = r;
+    a.lo = r & c.split_mask;
+    a.mid = r >> c.split_bits;
+    a.hi = 0;
 }

@@ -10,42 +10,78 @@ namespace {
 
 constexpr int MAC_THREADS = 256;
 constexpr int GATHER_BLOCKS = 8;
-constexpr int PREFETCH = 4;  // terms whose inputs are in flight while the previous ones are used
+constexpr u32 BLOCK_TERMS = 4;  // terms per unrolled block; an input is loaded one block before its use
 
-template <int A>
-__device__ __forceinline__ void housekeeping(MacAcc (&acc)[A], u32& f, u32& r, const LimbConst& c) {
-    if (++r == c.reduce_every) {
-#pragma unroll
-        for (int g = 0; g < A; g++) acc_restart(acc[g], c);
-        r = 0;
-        f = 0;
-    } else if (++f == c.fold_every) {
-#pragma unroll
-        for (int g = 0; g < A; g++) acc_fold(acc[g]);
-        f = 0;
-    }
-}
+__host__ __device__ inline u32 padded_terms(u32 n_terms) { return (n_terms + BLOCK_TERMS - 1) / BLOCK_TERMS * BLOCK_TERMS; }
 
-// Weight table for scalar plaintexts: wtab[(tile.wbase*limbs) + (limb*n_terms + t)*G + g] =
-// pt[term_pt[off[out0+g] + t]][limb], zero for g >= tile.count, so the MAC loop reads G
-// consecutive residues per term with scalar loads and needs no per-output branch.
+// Weight table for scalar plaintexts: wtab[(wbase*limbs) + (limb*Kp + t)*G + g], Kp = n_terms rounded
+// up to a multiple of BLOCK_TERMS, holds the two pieces (wa | wb << 32, see MacAcc) of
+// pt[term_pt[off[out0+g] + t]][limb], and zero for g >= tile.count or t >= n_terms.  The MAC loop
+// then reads G consecutive entries per term with scalar loads, runs whole blocks of terms, and needs
+// neither a per-output branch nor a split of the plaintext operand.
 template <int G>
-__global__ void __launch_bounds__(256) gather_weights_kernel(const Tile* tiles, const u64* wbase, u32 n_tiles, u32 limbs,
-                                                             const u32* off, const u32* term_pt, const u64* pt, u64* wtab) {
+__global__ void __launch_bounds__(256) gather_weights_kernel(LimbTable lt, const Tile* tiles, const u64* wbase, u32 n_tiles,
+                                                             u32 limbs, const u32* off, const u32* term_pt, const u64* pt,
+                                                             u64* wtab) {
     const u32 tile_i = blockIdx.x / GATHER_BLOCKS;
     const u32 sub = blockIdx.x % GATHER_BLOCKS;
     if (tile_i >= n_tiles) return;
     const Tile tile = tiles[tile_i];
-    const u64 per_limb = (u64)tile.n_terms * G;
+    const u64 per_limb = (u64)padded_terms(tile.n_terms) * G;
     const u64 total = per_limb * limbs;
     u64* dst = wtab + wbase[tile_i] * limbs;
     for (u64 i = (u64)sub * blockDim.x + threadIdx.x; i < total; i += (u64)GATHER_BLOCKS * blockDim.x) {
         const u32 limb = (u32)(i / per_limb);
         const u64 rem = i % per_limb;
         const u32 t = (u32)(rem / G), g = (u32)(rem % G);
-        u64 w = 0;
-        if (g < tile.count) w = pt[(size_t)term_pt[off[tile.out0 + g] + t] * limbs + limb];
-        dst[i] = w;
+        u64 packed = 0;
+        if (g < tile.count && t < tile.n_terms) {
+            u32 wa, wb;
+            split_operand(pt[(size_t)term_pt[off[tile.out0 + g] + t] * limbs + limb], lt.c[limb], wa, wb);
+            packed = (u64)wa | ((u64)wb << 32);
+        }
+        dst[i] = packed;
+    }
+}
+
+template <int A>
+__device__ __forceinline__ void fold_all(MacAcc (&acc)[A], const LimbConst& c) {
+#pragma unroll
+    for (int g = 0; g < A; g++) acc_fold(acc[g], c);
+}
+
+template <int A>
+__device__ __forceinline__ void restart_all(MacAcc (&acc)[A], const LimbConst& c) {
+#pragma unroll
+    for (int g = 0; g < A; g++) {
+        acc_restart(acc[g], c);
+        __builtin_amdgcn_sched_barrier(0);  // one reduction at a time: keeps its temporaries few
+    }
+}
+
+// Called between runs of terms: reduce when `reduce_period` terms have gone by since the last
+// reduction, else fold when `fold_period` terms have gone by since the last fold.
+template <int A>
+__device__ __forceinline__ void housekeeping(MacAcc (&acc)[A], u32& f, u32& r, u32 fold_period, u32 reduce_period,
+                                             const LimbConst& c) {
+    if (r >= reduce_period) {
+        restart_all<A>(acc, c);
+        r = 0;
+        f = 0;
+    } else if (f >= fold_period) {
+        fold_all<A>(acc, c);
+        f = 0;
+    }
+}
+
+template <int G>
+__device__ __forceinline__ void scalar_term(MacAcc (&acc)[G], u64 x, const u64* wt, const LimbConst& c) {
+    u32 xa, xb;
+    split_operand(x, c, xa, xb);
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        const u64 w = wt[g];
+        acc_mac(acc[g], xa, xb, (u32)w, (u32)(w >> 32));
     }
 }
 
@@ -64,35 +100,50 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u64* 
     const u32 n = chunk * MAC_THREADS + threadIdx.x;
     const size_t ct_stride = (size_t)2 * limbs * N;
     const u64* x_base = ct_in + ((size_t)comp * limbs + limb) * N + n;
-    const u64* w = wtab + wbase[tile_i] * limbs + (u64)limb * tile.n_terms * G;
+    const u32 K = tile.n_terms, Kp = padded_terms(K);
+    const u64* w = wtab + wbase[tile_i] * limbs + (u64)limb * Kp * G;
     const u32* tc = term_ct + tile.term0;
-    const u32 K = tile.n_terms;
 
     MacAcc acc[G];
 #pragma unroll
     for (int g = 0; g < G; g++) acc_clear(acc[g]);
-    u32 f = 0, r = 0;
 
-    u64 x_next[PREFETCH];
+    if (K > 0 && c.fold_every >= BLOCK_TERMS) {
+        // Terms run in blocks of four (terms K..Kp-1 are padding: zero weights, input K-1 again).
+        // Ring of inputs: xq[j] holds the residue of term t+j and is refilled for term t+j+4 as soon
+        // as it has been consumed, so a load has a whole block of MACs (256 multiply-adds per lane)
+        // to complete.  Folds and reductions happen between runs of whole blocks only, so inside a
+        // run the partial sums are plain loop-carried registers.
+        const u32 fold_blocks = c.fold_every / BLOCK_TERMS * BLOCK_TERMS;
+        const u32 reduce_blocks = c.reduce_every / BLOCK_TERMS * BLOCK_TERMS;
+        u32 f = 0, r = 0, t = 0;
+        u64 xq[BLOCK_TERMS];
 #pragma unroll
-    for (int j = 0; j < PREFETCH; j++) x_next[j] = (u32)j < K ? x_base[(size_t)tc[j] * ct_stride] : 0;
-    for (u32 t0 = 0; t0 < K; t0 += PREFETCH) {
-        u64 x_cur[PREFETCH];
+        for (int j = 0; j < BLOCK_TERMS; j++) xq[j] = x_base[(size_t)tc[min((u32)j, K - 1)] * ct_stride];
+        while (t < Kp) {
+            const u32 run = min(Kp - t, min(fold_blocks - f, reduce_blocks - r));
+            const u32 t_end = t + run;
+#pragma unroll 1
+            for (; t < t_end; t += BLOCK_TERMS) {
 #pragma unroll
-        for (int j = 0; j < PREFETCH; j++) {
-            x_cur[j] = x_next[j];
-            const u32 tn = t0 + PREFETCH + j;
-            x_next[j] = tn < K ? x_base[(size_t)tc[tn] * ct_stride] : 0;
-        }
-#pragma unroll
-        for (int j = 0; j < PREFETCH; j++) {
-            const u32 t = t0 + j;
-            if (t < K) {
-                const u64* wt = w + (size_t)t * G;
-#pragma unroll
-                for (int g = 0; g < G; g++) acc_mac_s(acc[g], x_cur[j], wt[g]);
-                housekeeping<G>(acc, f, r, c);
+                for (int j = 0; j < BLOCK_TERMS; j++) {
+                    const u64 x = xq[j];
+                    xq[j] = x_base[(size_t)tc[min(t + BLOCK_TERMS + j, K - 1)] * ct_stride];
+                    scalar_term<G>(acc, x, w + (size_t)(t + j) * G, c);
+                }
             }
+            f += run;
+            r += run;
+            if (t < Kp) housekeeping<G>(acc, f, r, fold_blocks, reduce_blocks, c);
+        }
+    } else if (K > 0) {
+        // moduli above 2^60 fold more often than once per block: plain loop, one term at a time
+        u32 f = 0, r = 0;
+        for (u32 t = 0; t < K; ++t) {
+            scalar_term<G>(acc, x_base[(size_t)tc[t] * ct_stride], w + (size_t)t * G, c);
+            ++f;
+            ++r;
+            if (t + 1 < K) housekeeping<G>(acc, f, r, c.fold_every, c.reduce_every, c);
         }
     }
 #pragma unroll
@@ -102,6 +153,7 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u64* 
             u64 v = acc_reduce(acc[g], c);
             if (bias != nullptr && comp == 0) v = add_mod(v, bias[(size_t)o * limbs + limb], c.q);
             out[(((size_t)o * 2 + comp) * limbs + limb) * N + n] = v;
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -135,19 +187,25 @@ mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u32* of
 #pragma unroll
     for (int g = 0; g < 2 * G; g++) acc_clear(acc[g]);
     u32 f = 0, r = 0;
-#pragma unroll 2
     for (u32 t = 0; t < K; t++) {
         const u64* xp = x_base + (size_t)tc[t] * ct_stride;
         const u64 x0 = xp[0], x1 = xp[comp_stride];
         u64 p[G];
 #pragma unroll
         for (int g = 0; g < G; g++) p[g] = (u32)g < tile.count ? p_base[(size_t)tp[g][t] * pt_stride] : 0;
+        u32 x0a, x0b, x1a, x1b;
+        split_operand(x0, c, x0a, x0b);
+        split_operand(x1, c, x1a, x1b);
 #pragma unroll
         for (int g = 0; g < G; g++) {
-            acc_mac_v(acc[2 * g], x0, p[g]);
-            acc_mac_v(acc[2 * g + 1], x1, p[g]);
+            u32 pa, pb;
+            split_operand(p[g], c, pa, pb);
+            acc_mac(acc[2 * g], x0a, x0b, pa, pb);
+            acc_mac(acc[2 * g + 1], x1a, x1b, pa, pb);
         }
-        housekeeping<2 * G>(acc, f, r, c);
+        ++f;
+        ++r;
+        if (t + 1 < K) housekeeping<2 * G>(acc, f, r, c.fold_every, c.reduce_every, c);
     }
 #pragma unroll
     for (int g = 0; g < G; g++) {
@@ -158,6 +216,7 @@ mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u32* of
             u64* dst = out + ((size_t)o * 2 * limbs + limb) * N + n;
             dst[0] = v0;
             dst[comp_stride] = v1;
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -172,7 +231,7 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
     if (count == 0) return HE_OK;
     const Tile* tiles = plan->tiles_s_dev + begin;
     const u64* wbase = plan->wbase_s_dev + begin;
-    hipLaunchKernelGGL((gather_weights_kernel<G>), dim3(count * GATHER_BLOCKS), dim3(256), 0, s, tiles, wbase, count, limbs, plan->off_dev,
+    hipLaunchKernelGGL((gather_weights_kernel<G>), dim3(count * GATHER_BLOCKS), dim3(256), 0, s, ctx->limbs, tiles, wbase, count, limbs, plan->off_dev,
                        plan->term_pt_dev, pt, wtab);
     HE_HIP(hipGetLastError());
     const u64 blocks = (u64)count * limbs * 2 * (ctx->N / MAC_THREADS);
