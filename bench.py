@@ -33,6 +33,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", help="comma-separated phases to run (profiling aid; the JSON is then partial)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain device copies of 512 MiB (counter calibration for rocprofv3 --pmc)")
     ap.add_argument("--cpu-sample-cfg4", type=int, default=64, help="cfg4 outputs the oracle is timed on")
     ap.add_argument("--cpu-sample-cfg5", type=int, default=2, help="cfg5 outputs the oracle is timed on")
     args = ap.parse_args()
@@ -74,23 +77,43 @@ def main() -> int:
 
     phases = ["encode_cfg4", "mac_scalar_cfg4", "rescale_cfg4", "mac_poly_cfg5", "rescale_cfg5"]
 
+    only = set(filter(None, args.only.split(",")))
+    assert only <= set(phases), phases
+    on = lambda name: not only or name in only
+
     def step(ev=None):
         def mark(i):
             if ev is not None:
                 ev[i].record()
         mark(0)
-        ctx.encode_scalar(w4, scale, out=wenc4)
-        ctx.encode_scalar(b4, scale, out=benc4)
+        if on("encode_cfg4"):
+            ctx.encode_scalar(w4, scale, out=wenc4)
+            ctx.encode_scalar(b4, scale, out=benc4)
         mark(1)
-        ctx.ct_pt_mac(hp4, ct4, wenc4, he.PT_SCALAR, bias=benc4, out=acc4, workspace=ws4)
+        if on("mac_scalar_cfg4"):
+            ctx.ct_pt_mac(hp4, ct4, wenc4, he.PT_SCALAR, bias=benc4, out=acc4, workspace=ws4)
         mark(2)
-        ctx.rescale(acc4, out=out4)
+        if on("rescale_cfg4"):
+            ctx.rescale(acc4, out=out4)
         mark(3)
-        ctx.ct_pt_mac(hp5, ct5, pt5, he.PT_POLY, out=acc5)
+        if on("mac_poly_cfg5"):
+            ctx.ct_pt_mac(hp5, ct5, pt5, he.PT_POLY, out=acc5)
         mark(4)
-        ctx.rescale(acc5, out=out5)
+        if on("rescale_cfg5"):
+            ctx.rescale(acc5, out=out5)
         mark(5)
 
+    if only:                       # buffers the skipped phases would have produced
+        ctx.encode_scalar(w4, scale, out=wenc4)
+        ctx.encode_scalar(b4, scale, out=benc4)
+        acc4.zero_()
+        acc5.zero_()
+
+    if args.calibrate_copy:        # reads 512 MiB and writes 512 MiB per launch
+        dst = torch.empty_like(ct5)
+        for _ in range(3):
+            dst.copy_(ct5)
+        del dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -158,7 +181,9 @@ def main() -> int:
     }
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
-    if not args.no_cpu_baseline:
+    if only:
+        result["partial"] = sorted(only)
+    if not args.no_cpu_baseline and not only:
         import oracle
         threads = oracle.set_threads(0)
         psi = ctx.psi

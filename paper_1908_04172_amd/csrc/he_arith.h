@@ -42,15 +42,16 @@ HE_HD u64 sub_mod(u64 a, u64 b, u64 q) {  // a, b < q
     return a >= b ? a - b : a + q - b;
 }
 
-// Barrett reduction of a 128-bit value z = hi:lo by a modulus below 2^64 (Alg. 5).  With
-// r = floor(2^128/q), Qe = floor(z*r / 2^128) is the true quotient or one less, so z - Qe*q lies in
-// [0, 2q); only the low 64 bits of Qe are needed because that difference fits in 64 bits.
+// Barrett reduction of a 128-bit value z = hi:lo by a modulus below 2^62 (Alg. 5).  With
+// r = floor(2^128/q) = rh:rl, floor(z*r / 2^128) is the true quotient or one less.  The estimate
+// used here, hi*rh + floor(lo*rh / 2^64) + floor(hi*rl / 2^64), leaves out the product lo*rl and the
+// carry between the two middle products, each worth at most one more, so it is short of the true
+// quotient by at most 3 and z - estimate*q lies in [0, 4q), which fits 64 bits; only the low 64 bits
+// of the estimate matter for that difference.
 HE_HD u64 reduce128(u64 hi, u64 lo, const LimbConst& c) {
-    u64 carry = mul_hi64(lo, c.ratio_lo);
-    u128 p1 = (u128)lo * c.ratio_hi + carry;                 // < 2^128: no overflow
-    u128 p2 = (u128)hi * c.ratio_lo + (u64)p1;
-    u64 qe = hi * c.ratio_hi + (u64)(p1 >> 64) + (u64)(p2 >> 64);
+    u64 qe = hi * c.ratio_hi + mul_hi64(lo, c.ratio_hi) + mul_hi64(hi, c.ratio_lo);
     u64 r = lo - qe * c.q;
+    r = r >= c.two_q ? r - c.two_q : r;
     return r >= c.q ? r - c.q : r;
 }
 

@@ -74,19 +74,44 @@ __device__ __forceinline__ void housekeeping(MacAcc (&acc)[A], u32& f, u32& r, u
     }
 }
 
-template <int G>
-__device__ __forceinline__ void scalar_term(MacAcc (&acc)[G], u64 x, const u64* wt, const LimbConst& c) {
+// Sixteen plaintext residues (as 32-bit pieces) in 32 scalar registers.  The loads are issued by
+// hand so that they are in flight during the previous term's multiply-adds: request() starts them,
+// arrived() waits for them; between the two calls the registers must not be read.
+typedef u32 u32x16 __attribute__((ext_vector_type(16)));
+struct ScalarWeights16 {
+    u32x16 a, b;  // residues 0..7 and 8..15 as (wa, wb) pairs
+    __device__ __forceinline__ void request(const u64* wt) {
+        asm volatile("s_load_dwordx16 %0, %2, 0x0\n\ts_load_dwordx16 %1, %2, 0x40" : "=&s"(a), "=&s"(b) : "s"(wt) : "memory");
+    }
+    __device__ __forceinline__ void arrived() { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(a), "+s"(b)); }
+};
+
+__device__ __forceinline__ void scalar_term16(MacAcc (&acc)[16], u64 x, const ScalarWeights16& w, const LimbConst& c) {
     u32 xa, xb;
     split_operand(x, c, xa, xb);
 #pragma unroll
-    for (int g = 0; g < G; g++) {
-        const u64 w = wt[g];
-        acc_mac(acc[g], xa, xb, (u32)w, (u32)(w >> 32));
+    for (int g = 0; g < 8; g++) {
+        acc_mac(acc[g], xa, xb, w.a[2 * g], w.a[2 * g + 1]);
+        acc_mac(acc[g + 8], xa, xb, w.b[2 * g], w.b[2 * g + 1]);
     }
 }
 
 template <int G>
-__global__ void __launch_bounds__(MAC_THREADS)
+__device__ __forceinline__ void load_weights(u64 (&dst)[G], const u64* wt) {
+#pragma unroll
+    for (int g = 0; g < G; g++) dst[g] = wt[g];
+}
+
+template <int G>
+__device__ __forceinline__ void scalar_term(MacAcc (&acc)[G], u64 x, const u64 (&wt)[G], const LimbConst& c) {
+    u32 xa, xb;
+    split_operand(x, c, xa, xb);
+#pragma unroll
+    for (int g = 0; g < G; g++) acc_mac(acc[g], xa, xb, (u32)wt[g], (u32)(wt[g] >> 32));
+}
+
+template <int G>
+__global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8)))
 mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u64* wbase, const u32* term_ct,
                   const u64* wtab, const u64* ct_in, const u64* bias, u64* out) {
     const u32 chunks = N / MAC_THREADS;
@@ -118,8 +143,19 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u64* 
         const u32 reduce_blocks = c.reduce_every / BLOCK_TERMS * BLOCK_TERMS;
         u32 f = 0, r = 0, t = 0;
         u64 xq[BLOCK_TERMS];
+        u32 cq[BLOCK_TERMS];  // ciphertext indices of terms t+4 .. t+7, fetched a block before they are needed
 #pragma unroll
-        for (int j = 0; j < BLOCK_TERMS; j++) xq[j] = x_base[(size_t)tc[min((u32)j, K - 1)] * ct_stride];
+        for (int j = 0; j < BLOCK_TERMS; j++) {
+            xq[j] = x_base[(size_t)tc[min((u32)j, K - 1)] * ct_stride];
+            cq[j] = tc[min((u32)(BLOCK_TERMS + j), K - 1)];
+        }
+        // The plaintext residues of a term sit in scalar registers; the next term's are requested
+        // while this term's multiply-adds run (two register sets, used alternately).
+        ScalarWeights16 w_even, w_odd;
+        if constexpr (G == 16) {
+            w_even.request(w);
+            w_even.arrived();
+        }
         while (t < Kp) {
             const u32 run = min(Kp - t, min(fold_blocks - f, reduce_blocks - r));
             const u32 t_end = t + run;
@@ -128,8 +164,24 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u64* 
 #pragma unroll
                 for (int j = 0; j < BLOCK_TERMS; j++) {
                     const u64 x = xq[j];
-                    xq[j] = x_base[(size_t)tc[min(t + BLOCK_TERMS + j, K - 1)] * ct_stride];
-                    scalar_term<G>(acc, x, w + (size_t)(t + j) * G, c);
+                    xq[j] = x_base[(size_t)cq[j] * ct_stride];
+                    cq[j] = tc[min(t + 2 * BLOCK_TERMS + j, K - 1)];
+                    if constexpr (G == 16) {
+                        const u64* w_next = w + (size_t)min(t + j + 1, Kp - 1) * G;
+                        if (j % 2 == 0) {
+                            w_odd.request(w_next);
+                            scalar_term16(acc, x, w_even, c);
+                            w_odd.arrived();
+                        } else {
+                            w_even.request(w_next);
+                            scalar_term16(acc, x, w_odd, c);
+                            w_even.arrived();
+                        }
+                    } else {
+                        u64 wt[G];
+                        load_weights<G>(wt, w + (size_t)(t + j) * G);
+                        scalar_term<G>(acc, x, wt, c);
+                    }
                 }
             }
             f += run;
@@ -140,7 +192,9 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u64* 
         // moduli above 2^60 fold more often than once per block: plain loop, one term at a time
         u32 f = 0, r = 0;
         for (u32 t = 0; t < K; ++t) {
-            scalar_term<G>(acc, x_base[(size_t)tc[t] * ct_stride], w + (size_t)t * G, c);
+            u64 wt[G];
+            load_weights<G>(wt, w + (size_t)t * G);
+            scalar_term<G>(acc, x_base[(size_t)tc[t] * ct_stride], wt, c);
             ++f;
             ++r;
             if (t + 1 < K) housekeeping<G>(acc, f, r, c.fold_every, c.reduce_every, c);
