@@ -42,12 +42,17 @@ __device__ __forceinline__ u32 lds_slot(u32 idx) {
     return idx ^ (((idx >> 6) & 0xFu) << 2) ^ ((idx >> 5) & 3u);
 }
 
+// Workgroup barrier that orders LDS traffic only: waits for this wave's LDS operations, then for the
+// other waves.  (A full __syncthreads() would also wait for outstanding global loads, and the
+// twiddles of the next pass are deliberately in flight across the regrouping.)
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int LOGN, int PFROM, int PTO>
 __device__ __forceinline__ void regroup(u64 (&a)[16], u64* lds, u32 tid) {
-    __syncthreads();  // earlier readers of the buffer are done
+    lds_barrier();  // earlier readers of the buffer are done
 #pragma unroll
     for (u32 e = 0; e < 16; e++) lds[lds_slot(reg_index<LOGN, PFROM>(tid, e))] = a[e];
-    __syncthreads();
+    lds_barrier();
 #pragma unroll
     for (u32 e = 0; e < 16; e++) a[e] = lds[lds_slot(reg_index<LOGN, PTO>(tid, e))];
 }
@@ -79,25 +84,61 @@ __device__ __forceinline__ void bfly_inv(u64& x, u64& y, Twiddle t, u64 q, u64 t
     y = shoup_mul_lazy(d, t.w, t.w_shoup, q);
 }
 
-// The stages of pass P on the 16 registers of one thread.
-template <int LOGN, int P, bool INVERSE>
-__device__ __forceinline__ void run_pass(u64 (&a)[16], const u64* tw, u32 tid, const LimbConst& c) {
+// Shape of pass P: its stages, and where the twiddle of (stage k, register e) sits among the
+// pass's twiddles.  A thread's twiddles of stage k are 2^k consecutive table entries (per group of
+// registers in the last pass), 15 entries per pass at most.
+template <int LOGN, int P>
+struct PassShape {
     using G = Geo<LOGN>;
-    constexpr bool LAST = (P == G::NPASS - 1);
-    constexpr int NST = LAST ? G::REM : 4;
+    static constexpr bool LAST = (P == G::NPASS - 1);
+    static constexpr int NST = LAST ? G::REM : 4;
+    static constexpr int GROUPS = 16 >> NST;                 // independent register groups (last pass only > 1)
+    static constexpr int PER_GROUP = (1 << NST) - 1;
+    static constexpr int COUNT = GROUPS * PER_GROUP;
     // twiddles are the same for the whole wave when the thread-dependent part of the group index
     // is constant over 64 consecutive threads
-    constexpr bool UNIFORM = (P == 0) || (!LAST && (LOGN - 4 * (P + 1)) >= 6);
+    static constexpr bool UNIFORM = (P == 0) || (!LAST && (LOGN - 4 * (P + 1)) >= 6);
+    __device__ static constexpr int slot(int k, u32 e) {
+        return (int)(e >> NST) * PER_GROUP + ((1 << k) - 1) + (int)((e & ((1u << NST) - 1)) >> (NST - k));
+    }
+};
+
+template <int LOGN, int P>
+struct PassTwiddles {
+    Twiddle t[PassShape<LOGN, P>::COUNT];
+};
+
+// All twiddles of pass P for this thread, requested in one go (the caller does this before the
+// regrouping that precedes the pass, so the loads overlap the LDS traffic).
+template <int LOGN, int P>
+__device__ __forceinline__ void load_pass_twiddles(PassTwiddles<LOGN, P>& pt, const u64* tw, u32 tid) {
+    using S = PassShape<LOGN, P>;
 #pragma unroll
-    for (int kk = 0; kk < NST; kk++) {
-        const int k = INVERSE ? NST - 1 - kk : kk;
-        const int s = 4 * P + k;       // stage
-        const int bit = NST - 1 - k;   // register-index bit that the stage pairs
+    for (int k = 0; k < S::NST; k++) {
+        const int s = 4 * P + k;
+        const int bit = S::NST - 1 - k;
 #pragma unroll
         for (u32 e = 0; e < 16; e++) {
             if (e & (1u << bit)) continue;
+            if ((e & ((1u << S::NST) - 1)) & ((1u << bit) - 1)) continue;  // one load per distinct twiddle
             const u32 j = reg_index<LOGN, P>(tid, e);
-            const u32 k_tw = (1u << s) + (j >> (LOGN - s));
+            pt.t[S::slot(k, e)] = load_twiddle<S::UNIFORM>(tw, (1u << s) + (j >> (LOGN - s)));
+        }
+    }
+}
+
+// The stages of pass P on the 16 registers of one thread.
+template <int LOGN, int P, bool INVERSE>
+__device__ __forceinline__ void run_pass(u64 (&a)[16], const PassTwiddles<LOGN, P>& pt, const LimbConst& c) {
+    using S = PassShape<LOGN, P>;
+#pragma unroll
+    for (int kk = 0; kk < S::NST; kk++) {
+        const int k = INVERSE ? S::NST - 1 - kk : kk;
+        const int s = 4 * P + k;       // stage
+        const int bit = S::NST - 1 - k;   // register-index bit that the stage pairs
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) {
+            if (e & (1u << bit)) continue;
             if constexpr (INVERSE) {
                 if (s == 0) {  // merged with the multiplication by N^-1
                     u64 sum = a[e] + a[e | (1u << bit)];
@@ -105,10 +146,10 @@ __device__ __forceinline__ void run_pass(u64 (&a)[16], const u64* tw, u32 tid, c
                     a[e] = shoup_mul_lazy(sum, c.n_inv, c.n_inv_shoup, c.q);
                     a[e | (1u << bit)] = shoup_mul_lazy(dif, c.w1n_inv, c.w1n_inv_shoup, c.q);
                 } else {
-                    bfly_inv(a[e], a[e | (1u << bit)], load_twiddle<UNIFORM>(tw, k_tw), c.q, c.two_q);
+                    bfly_inv(a[e], a[e | (1u << bit)], pt.t[S::slot(k, e)], c.q, c.two_q);
                 }
             } else {
-                bfly_fwd(a[e], a[e | (1u << bit)], load_twiddle<UNIFORM>(tw, k_tw), c.q, c.two_q);
+                bfly_fwd(a[e], a[e | (1u << bit)], pt.t[S::slot(k, e)], c.q, c.two_q);
             }
         }
     }
@@ -118,20 +159,58 @@ __device__ __forceinline__ void run_pass(u64 (&a)[16], const u64* tw, u32 tid, c
 template <int LOGN>
 __device__ __forceinline__ void ntt_forward(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
     using G = Geo<LOGN>;
-    run_pass<LOGN, 0, false>(a, tw, tid, c);
-    if constexpr (G::NPASS > 1) { regroup<LOGN, 0, 1>(a, lds, tid); run_pass<LOGN, 1, false>(a, tw, tid, c); }
-    if constexpr (G::NPASS > 2) { regroup<LOGN, 1, 2>(a, lds, tid); run_pass<LOGN, 2, false>(a, tw, tid, c); }
-    if constexpr (G::NPASS > 3) { regroup<LOGN, 2, 3>(a, lds, tid); run_pass<LOGN, 3, false>(a, tw, tid, c); }
+    {
+        PassTwiddles<LOGN, 0> t0;
+        load_pass_twiddles<LOGN, 0>(t0, tw, tid);
+        run_pass<LOGN, 0, false>(a, t0, c);
+    }
+    if constexpr (G::NPASS > 1) {
+        PassTwiddles<LOGN, 1> t1;
+        load_pass_twiddles<LOGN, 1>(t1, tw, tid);
+        regroup<LOGN, 0, 1>(a, lds, tid);
+        run_pass<LOGN, 1, false>(a, t1, c);
+    }
+    if constexpr (G::NPASS > 2) {
+        PassTwiddles<LOGN, 2> t2;
+        load_pass_twiddles<LOGN, 2>(t2, tw, tid);
+        regroup<LOGN, 1, 2>(a, lds, tid);
+        run_pass<LOGN, 2, false>(a, t2, c);
+    }
+    if constexpr (G::NPASS > 3) {
+        PassTwiddles<LOGN, 3> t3;
+        load_pass_twiddles<LOGN, 3>(t3, tw, tid);
+        regroup<LOGN, 2, 3>(a, lds, tid);
+        run_pass<LOGN, 3, false>(a, t3, c);
+    }
 }
 
 // Registers in last-pass order, < 2q -> registers in pass-0 order, < 2q, multiplied by N^-1.
 template <int LOGN>
 __device__ __forceinline__ void ntt_inverse(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
     using G = Geo<LOGN>;
-    if constexpr (G::NPASS > 3) { run_pass<LOGN, 3, true>(a, tw, tid, c); regroup<LOGN, 3, 2>(a, lds, tid); }
-    if constexpr (G::NPASS > 2) { run_pass<LOGN, 2, true>(a, tw, tid, c); regroup<LOGN, 2, 1>(a, lds, tid); }
-    if constexpr (G::NPASS > 1) { run_pass<LOGN, 1, true>(a, tw, tid, c); regroup<LOGN, 1, 0>(a, lds, tid); }
-    run_pass<LOGN, 0, true>(a, tw, tid, c);
+    if constexpr (G::NPASS > 3) {
+        PassTwiddles<LOGN, 3> t3;
+        load_pass_twiddles<LOGN, 3>(t3, tw, tid);
+        run_pass<LOGN, 3, true>(a, t3, c);
+    }
+    if constexpr (G::NPASS > 2) {
+        PassTwiddles<LOGN, 2> t2;
+        load_pass_twiddles<LOGN, 2>(t2, tw, tid);
+        if constexpr (G::NPASS > 3) regroup<LOGN, 3, 2>(a, lds, tid);
+        run_pass<LOGN, 2, true>(a, t2, c);
+    }
+    if constexpr (G::NPASS > 1) {
+        PassTwiddles<LOGN, 1> t1;
+        load_pass_twiddles<LOGN, 1>(t1, tw, tid);
+        if constexpr (G::NPASS > 2) regroup<LOGN, 2, 1>(a, lds, tid);
+        run_pass<LOGN, 1, true>(a, t1, c);
+    }
+    {
+        PassTwiddles<LOGN, 0> t0;
+        load_pass_twiddles<LOGN, 0>(t0, tw, tid);
+        if constexpr (G::NPASS > 1) regroup<LOGN, 1, 0>(a, lds, tid);
+        run_pass<LOGN, 0, true>(a, t0, c);
+    }
 }
 
 __device__ __forceinline__ u64 canon4(u64 v, u64 q, u64 two_q) {  // [0,4q) -> [0,q)
@@ -185,8 +264,12 @@ rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_f
     const u32 last = limbs - 1;
     const u64* src = in + poly * limbs * G::N;
     u64* dst = out + poly * (limbs - 1) * G::N;
-    u64 t[16];
+    // t = (INTT(last limb) + h) mod p is parked in the output row of the last kept limb: every
+    // thread re-reads only what it wrote itself, and that row is overwritten only at the very end,
+    // after all its threads have taken their t back (the regrouping barriers lie in between).
+    u64* park = dst + (size_t)(last - 1) * G::N;
     {
+        u64 t[16];
         const LimbConst& c = lt.c[last];
         const u64* row = src + (size_t)last * G::N;
 #pragma unroll
@@ -197,15 +280,22 @@ rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_f
         for (u32 e = 0; e < 16; e++) {
             u64 v = t[e];
             v = v >= c.q ? v - c.q : v;
-            t[e] = add_mod(v, half, c.q);
+            park[reg_index<LOGN, 0>(tid, e)] = add_mod(v, half, c.q);
         }
     }
     for (u32 i = 0; i < last; i++) {
+        // the thread index is made opaque per iteration so that the many addresses derived from it
+        // are recomputed (a few integer operations) instead of being kept live across the loop
+        u32 tid_i = threadIdx.x;
+        asm volatile("" : "+v"(tid_i));
+        const u32 tid = tid_i;
         const LimbConst& c = lt.c[i];
         const DropConst d = drop[last * HE_MAX_LIMBS + i];
         u64 a[16];
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) a[e] = sub_mod(reduce64(t[e], c), d.half_mod, c.q);
+        for (u32 e = 0; e < 16; e++) a[e] = park[reg_index<LOGN, 0>(tid, e)];
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = sub_mod(reduce64(a[e], c), d.half_mod, c.q);
         ntt_forward<LOGN>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
         const u64* xrow = src + (size_t)i * G::N;
         u64* orow = dst + (size_t)i * G::N;
