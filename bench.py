@@ -35,9 +35,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", help="comma-separated phases to run (profiling aid; the JSON is then partial)")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run three plain device copies of 512 MiB (counter calibration for rocprofv3 --pmc)")
-    ap.add_argument("--cpu-sample-cfg4", type=int, default=64, help="cfg4 outputs the oracle is timed on")
-    ap.add_argument("--cpu-sample-cfg5", type=int, default=2, help="cfg5 outputs the oracle is timed on")
+                    help="also run three plain elementwise kernels over 2 GiB (counter calibration for rocprofv3 --pmc)")
+    ap.add_argument("--cpu-sample-cfg4", type=int, default=512, help="cfg4 outputs the oracle is timed on")
+    ap.add_argument("--cpu-sample-cfg5", type=int, default=16, help="cfg5 outputs the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU figure exists", file=sys.stderr)
@@ -109,10 +109,11 @@ def main() -> int:
         acc4.zero_()
         acc5.zero_()
 
-    if args.calibrate_copy:        # reads 512 MiB and writes 512 MiB per launch
-        dst = torch.empty_like(ct5)
+    if args.calibrate_copy:        # a plain elementwise kernel: reads 2 GiB and writes 2 GiB per launch
+        src = ct4[:1024]
+        dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(ct5)
+            torch.add(src, 1, out=dst)
         del dst
     for _ in range(args.warmup):
         step()

@@ -307,6 +307,7 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
             d.p_inv = h_powmod(p % qi, qi - 2, qi);
             d.p_inv_shoup = h_shoup(d.p_inv, qi);
             d.half_mod = (p >> 1) % qi;
+            d.reduce_mode = p <= qi ? 0 : (p <= 2 * qi ? 1 : 2);
         }
     if (device >= 0) {
         int rc = need_device(ctx);

@@ -16,7 +16,8 @@ struct LimbTable {
 struct DropConst {
     u64 p_inv, p_inv_shoup;  // q_j^-1 mod q_i and its Shoup companion
     u64 half_mod;            // floor(q_j / 2) mod q_i
-    u64 pad;
+    u32 reduce_mode;         // a value below q_j is below q_i already (0), after one subtraction (1), or needs a full reduction (2)
+    u32 pad;
 };
 
 struct he_ctx {

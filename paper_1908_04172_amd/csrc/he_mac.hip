@@ -112,14 +112,18 @@ __device__ __forceinline__ void scalar_term(MacAcc (&acc)[G], u64 x, const u64 (
 
 template <int G>
 __global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8)))
-mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u64* wbase, const u32* term_ct,
+mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u64* wbase, const u32* term_ct,
                   const u64* wtab, const u64* ct_in, const u64* bias, u64* out) {
     const u32 chunks = N / MAC_THREADS;
+    // Order: slice of the row fastest, then group of outputs, then (component, limb).  Workgroups go
+    // to the eight XCDs round-robin and the number of slices is a multiple of eight, so the same
+    // slice of neighbouring groups (which read overlapping inputs) runs on the same XCD, close in
+    // time, and hits in its L2, while the slices in flight at any moment cover whole rows.
     u32 b = blockIdx.x;
     const u32 chunk = b % chunks; b /= chunks;
-    const u32 comp = b & 1; b >>= 1;
-    const u32 limb = b % limbs;
-    const u32 tile_i = b / limbs;
+    const u32 tile_i = b % n_tiles; b /= n_tiles;
+    const u32 comp = b & 1;
+    const u32 limb = b >> 1;
     const Tile tile = tiles[tile_i];
     const LimbConst& c = lt.c[limb];
     const u32 n = chunk * MAC_THREADS + threadIdx.x;
@@ -216,13 +220,13 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u64* 
 // both ciphertext components.  A thread owns G outputs x 2 components.
 template <int G>
 __global__ void __launch_bounds__(MAC_THREADS)
-mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, const u32* off, const u32* term_ct, const u32* term_pt,
+mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u32* off, const u32* term_ct, const u32* term_pt,
                 const u64* pt, const u64* ct_in, const u64* bias, u64* out) {
     const u32 chunks = N / MAC_THREADS;
-    u32 b = blockIdx.x;
+    u32 b = blockIdx.x;  // same order as the scalar kernel: slice, group of outputs, limb
     const u32 chunk = b % chunks; b /= chunks;
-    const u32 limb = b % limbs;
-    const u32 tile_i = b / limbs;
+    const u32 tile_i = b % n_tiles;
+    const u32 limb = b / n_tiles;
     const Tile tile = tiles[tile_i];
     const LimbConst& c = lt.c[limb];
     const u32 n = chunk * MAC_THREADS + threadIdx.x;
@@ -291,7 +295,7 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
     const u64 blocks = (u64)count * limbs * 2 * (ctx->N / MAC_THREADS);
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     hipLaunchKernelGGL((mac_scalar_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles,
-                       wbase, plan->term_ct_dev, wtab, ct_in, bias, out);
+                       count, wbase, plan->term_ct_dev, wtab, ct_in, bias, out);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
@@ -304,7 +308,7 @@ static int launch_poly_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limb
     const u64 blocks = (u64)count * limbs * (ctx->N / MAC_THREADS);
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     hipLaunchKernelGGL((mac_poly_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
-                       plan->tiles_p_dev + begin, plan->off_dev, plan->term_ct_dev, plan->term_pt_dev, pt, ct_in, bias, out);
+                       plan->tiles_p_dev + begin, count, plan->off_dev, plan->term_ct_dev, plan->term_pt_dev, pt, ct_in, bias, out);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }

@@ -49,12 +49,15 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 
 template <int LOGN, int PFROM, int PTO>
 __device__ __forceinline__ void regroup(u64 (&a)[16], u64* lds, u32 tid) {
+    // reg_index(tid, e) = reg_index(tid, 0) ^ reg_index(0, e) (disjoint bits) and lds_slot is linear
+    // over XOR, so each address is one XOR of a per-thread base with a compile-time constant
+    const u32 from = lds_slot(reg_index<LOGN, PFROM>(tid, 0)), to = lds_slot(reg_index<LOGN, PTO>(tid, 0));
     lds_barrier();  // earlier readers of the buffer are done
 #pragma unroll
-    for (u32 e = 0; e < 16; e++) lds[lds_slot(reg_index<LOGN, PFROM>(tid, e))] = a[e];
+    for (u32 e = 0; e < 16; e++) lds[from ^ lds_slot(reg_index<LOGN, PFROM>(0, e))] = a[e];
     lds_barrier();
 #pragma unroll
-    for (u32 e = 0; e < 16; e++) a[e] = lds[lds_slot(reg_index<LOGN, PTO>(tid, e))];
+    for (u32 e = 0; e < 16; e++) a[e] = lds[to ^ lds_slot(reg_index<LOGN, PTO>(0, e))];
 }
 
 struct Twiddle {
@@ -294,16 +297,25 @@ rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_f
         u64 a[16];
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = park[reg_index<LOGN, 0>(tid, e)];
+        // t < p: bring it below q_i (nothing to do, one subtraction, or a full reduction, depending
+        // on how p compares with q_i), then subtract h mod q_i
+        if (d.reduce_mode == 2) {
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) a[e] = sub_mod(reduce64(a[e], c), d.half_mod, c.q);
+            for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
+        } else if (d.reduce_mode == 1) {
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) a[e] = a[e] >= c.q ? a[e] - c.q : a[e];
+        }
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = sub_mod(a[e], d.half_mod, c.q);
         ntt_forward<LOGN>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
         const u64* xrow = src + (size_t)i * G::N;
         u64* orow = dst + (size_t)i * G::N;
 #pragma unroll
         for (u32 e = 0; e < 16; e++) {
             const u32 j = reg_index<LOGN, G::NPASS - 1>(tid, e);
-            u64 delta = canon4(a[e], c.q, c.two_q);
-            u64 diff = sub_mod(xrow[j], delta, c.q);
+            u64 delta = a[e] >= c.two_q ? a[e] - c.two_q : a[e];  // [0, 2q)
+            u64 diff = xrow[j] + c.two_q - delta;                     // (0, 3q), congruent to x - delta
             orow[j] = shoup_mul(diff, d.p_inv, d.p_inv_shoup, c.q);
         }
     }
