@@ -95,7 +95,7 @@ void fill_limb_const(LimbConst& c, u64 q, u64 psi, u32 N) {
     u32 bits = 0;
     while (bits < 64 && ((q - 1) >> bits)) ++bits;
     double best_cost = 1e300;
-    for (u32 s = (bits + 1) / 2; s <= std::min<u32>((bits + 1) / 2 + 1, 32); ++s) {
+    for (u32 s = (bits + 1) / 2; s <= std::min<u32>((bits + 1) / 2 + 1, 31); ++s) {
         const u128 A = (1ull << s) - 1, B = (q - 1) >> s, top = (u128)1 << 64;
         // after a fold (or a restart) lo <= A and mid <= A; F more terms must keep
         //   lo <= A + F*A*A  and  mid + (lo >> s) <= A + 2*F*A*B + (lo >> s)  below 2^64
@@ -120,6 +120,15 @@ void fill_limb_const(LimbConst& c, u64 q, u64 psi, u32 N) {
             c.fold_every = (u32)fold;
             c.reduce_every = (u32)red;
         }
+    }
+    // one-word Barrett for the accumulator when every value it can hold stays below 2^(63+bits)
+    c.mu_shift = bits - 1;
+    c.mu = (u64)((((u128)1) << (63 + bits)) / q);
+    {
+        const u128 sq = (u128)(q - 1) * (q - 1);
+        const u128 lim = ((((u128)1) << (63 + bits)) - 1 - q) / sq;
+        c.narrow = lim >= 64;
+        if (c.narrow) c.reduce_every = (u32)std::min<u128>(c.reduce_every, lim);
     }
     c.pad = 0;
 }

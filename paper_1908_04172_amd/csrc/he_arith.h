@@ -22,6 +22,9 @@ struct LimbConst {
     u32 split_bits;   // where MAC operands are cut in two (see MacAcc)
     u32 fold_every;   // MAC terms the partial sums take between two acc_fold calls
     u32 reduce_every; // MAC terms the accumulator takes between two reductions mod q
+    u32 narrow;       // 1: accumulated values stay below 2^(63 + bit length of q): one-word Barrett applies
+    u64 mu;           // floor(2^(63 + bit length of q) / q), in (2^63, 2^64)
+    u32 mu_shift;     // bit length of q, minus 1
     u32 pad;
 };
 
@@ -110,9 +113,23 @@ HE_HD void acc_fold(MacAcc& a, const LimbConst& c) {  // push the high parts of 
     a.mid &= c.split_mask;
 }
 
-HE_HD u64 acc_reduce(const MacAcc& a, const LimbConst& c) {  // the accumulated value mod q
-    u128 v = (u128)a.lo + ((u128)a.mid << c.split_bits) + ((u128)a.hi << (2 * c.split_bits));
-    return reduce128((u64)(v >> 64), (u64)v, c);
+// The accumulated value mod q.  After a fold lo, mid < 2^s, so the value is
+// (lo | mid << s | hi << 2s) in its low word and hi >> (64 - 2s) in its high word (2s <= 62).
+// Narrow limbs (value < 2^(63+b), b the bit length of q) take a one-word Barrett step: with
+// x1 = floor(value / 2^(b-1)) < 2^64 and mu = floor(2^(63+b) / q), floor(x1 * mu / 2^64) is short
+// of the true quotient by at most 3, like the estimate in reduce128.
+HE_HD u64 acc_reduce(MacAcc a, const LimbConst& c) {
+    acc_fold(a, c);
+    const u32 s2 = 2 * c.split_bits;
+    const u64 lo = a.lo | (a.mid << c.split_bits) | (a.hi << s2);
+    const u64 hi = a.hi >> (64 - s2);
+    if (c.narrow) {
+        const u64 x1 = (hi << (64 - c.mu_shift)) | (lo >> c.mu_shift);
+        u64 r = lo - mul_hi64(x1, c.mu) * c.q;
+        r = r >= c.two_q ? r - c.two_q : r;
+        return r >= c.q ? r - c.q : r;
+    }
+    return reduce128(hi, lo, c);
 }
 
 HE_HD void acc_restart(MacAcc& a, const LimbConst& c) {  // reduce in place and keep accumulating
