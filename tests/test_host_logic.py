@@ -50,7 +50,7 @@ def test_barrett_and_shoup_equal_python_mod():
 def test_mac_accumulator_fold_and_reduce_schedule():
     rnd = random.Random(4)
     for q in primes():
-        for n in (0, 1, 2, 7, 8, 9, 16, 17, 255, 256, 257, 1000):
+        for n in (0, 1, 2, 3, 4, 5, 7, 8, 9, 16, 17, 63, 64, 65, 255, 256, 257, 1000, 4095, 4096, 4097, 9000):
             for mode in ("max", "rand"):
                 x = [q - 1] * n if mode == "max" else [rnd.randrange(q) for _ in range(n)]
                 w = [q - 1] * n if mode == "max" else [rnd.randrange(q) for _ in range(n)]
