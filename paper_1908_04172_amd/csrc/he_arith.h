@@ -68,8 +68,25 @@ HE_HD u64 mul_mod(u64 a, u64 b, const LimbConst& c) {
 // Shoup product with a fixed operand w < q and w' = floor(w * 2^64 / q): for ANY 64-bit y the
 // result is congruent to y*w and lies in [0, 2q) (Harvey's lazy form); needs q < 2^63.
 HE_HD u64 shoup_mul_lazy(u64 y, u64 w, u64 w_shoup, u64 q) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    // Written on 32-bit pieces so that it maps onto 32x32+64 multiply-adds: the quotient estimate
+    // qh = floor(y*w'/2^64) exactly, then y*w - qh*q as y*w + qh*(2^64 - q) modulo 2^64, whose two
+    // low products chain through one accumulator.
+    const u32 y0 = (u32)y, y1 = (u32)(y >> 32), p0 = (u32)w_shoup, p1 = (u32)(w_shoup >> 32);
+    const u64 b = (u64)y0 * p1 + __umulhi(y0, p0);
+    const u64 c = (u64)y1 * p0 + (u32)b;
+    const u64 qh = (u64)y1 * p1 + (b >> 32) + (c >> 32);
+    const u32 h0 = (u32)qh, h1 = (u32)(qh >> 32);
+    const u64 nq = 0 - q;
+    const u32 n0 = (u32)nq, n1 = (u32)(nq >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
+    u64 e = (u64)y0 * w0;
+    e = (u64)h0 * n0 + e;
+    const u32 hi = (u32)(e >> 32) + y0 * w1 + y1 * w0 + h0 * n1 + h1 * n0;
+    return ((u64)hi << 32) | (u32)e;
+#else
     u64 qh = mul_hi64(y, w_shoup);
     return y * w - qh * q;
+#endif
 }
 
 HE_HD u64 shoup_mul(u64 y, u64 w, u64 w_shoup, u64 q) {
