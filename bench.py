@@ -181,6 +181,38 @@ def main() -> int:
         "roofline_all": list(rooflines.values()),
     }
 
+    # ---- the two plainly HBM-bound calls of the path, outside the timed step: Alg. 4 (scalar add, in
+    # place on component 0) and Alg. 8 as one multiply per output (every ciphertext read once, written once)
+    if not only:
+        def timed(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            ev[0].record()
+            for i in range(reps):
+                fn()
+                ev[i + 1].record()
+            torch.cuda.synchronize()
+            return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
+        n_add = p4.n_in
+        pt_add = ctx.encode_scalar(torch.from_numpy(wl.normal_values(n_add, 0.1, 7)).to(dev), scale)
+        ms_add = timed(lambda: ctx.ct_pt_add(ct4, pt_add, he.PT_SCALAR))
+        add_bytes = n_add * L * N * 8 * 2                       # component 0 read + written
+        n_str = 1024
+        ids = np.arange(n_str, dtype=np.uint32)
+        hps = ctx.plan(n_str, n_str, n_str, np.arange(n_str + 1, dtype=np.uint32), ids, ids)
+        w_str = ctx.encode_scalar(torch.from_numpy(wl.normal_values(n_str, 0.1, 8)).to(dev), scale)
+        ws_str = torch.empty(max(hps.workspace_bytes(L, he.PT_SCALAR, 0), 256), dtype=torch.uint8, device=dev)
+        ms_str = timed(lambda: ctx.ct_pt_mac(hps, ct4[:n_str], w_str, he.PT_SCALAR, out=acc4[:n_str], workspace=ws_str))
+        str_bytes = n_str * ct_bytes * 2
+        result["hbm_bound_calls"] = {
+            "ct_pt_add_scalar": {"ms": ms_add, "GBps": add_bytes / (ms_add * 1e-3) / 1e9,
+                                 "pct_hbm_peak": 100 * add_bytes / (ms_add * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                 "bytes": add_bytes, "what": "3072 ciphertexts, component 0 read and written in place"},
+            "ct_pt_mac_one_term_per_output": {"ms": ms_str, "GBps": str_bytes / (ms_str * 1e-3) / 1e9,
+                                              "pct_hbm_peak": 100 * str_bytes / (ms_str * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                              "bytes": str_bytes, "what": "1024 ciphertexts times one scalar each: 2 GiB read, 2 GiB written"}}
+
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     if only:
         result["partial"] = sorted(only)

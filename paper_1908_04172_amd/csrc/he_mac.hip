@@ -216,6 +216,74 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
     }
 }
 
+// Outputs that share their inputs with no other output (one multiply per output is the extreme
+// case: a plain Alg. 8 call over a tensor).  There is little arithmetic per byte here, so the kernel
+// is shaped for the memory system instead: a thread handles SL pairs of adjacent residues (16-byte
+// accesses, SL independent loads in flight), a workgroup 512*SL residues of one row.
+template <int SL>
+__global__ void __launch_bounds__(MAC_THREADS)
+mac_scalar_single_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u64* wbase,
+                         const u32* term_ct, const u64* wtab, const u64* ct_in, const u64* bias, u64* out) {
+    const u32 per_block = MAC_THREADS * 2 * SL;
+    const u32 blocks_per_row = N / per_block;
+    u32 b = blockIdx.x;
+    const u32 part = b % blocks_per_row; b /= blocks_per_row;
+    const u32 tile_i = b % n_tiles; b /= n_tiles;
+    const u32 comp = b & 1;
+    const u32 limb = b >> 1;
+    const Tile tile = tiles[tile_i];
+    const LimbConst& c = lt.c[limb];
+    const size_t ct_stride = (size_t)2 * limbs * N;
+    const size_t row_off = ((size_t)comp * limbs + limb) * N + (size_t)part * per_block;
+    const u32 K = tile.n_terms;
+    const u64* w = wtab + wbase[tile_i] * limbs + (u64)limb * padded_terms(K);
+    const u32* tc = term_ct + tile.term0;
+
+    MacAcc acc[SL][2];
+#pragma unroll
+    for (int s = 0; s < SL; s++) { acc_clear(acc[s][0]); acc_clear(acc[s][1]); }
+    u32 f = 0, r = 0;
+    for (u32 t = 0; t < K; ++t) {
+        const ulonglong2* row = reinterpret_cast<const ulonglong2*>(ct_in + (size_t)tc[t] * ct_stride + row_off);
+        const u64 wv = w[t];
+        ulonglong2 x[SL];
+#pragma unroll
+        for (int s = 0; s < SL; s++) x[s] = row[s * MAC_THREADS + threadIdx.x];
+#pragma unroll
+        for (int s = 0; s < SL; s++) {
+            u32 xa, xb;
+            split_operand(x[s].x, c, xa, xb);
+            acc_mac(acc[s][0], xa, xb, (u32)wv, (u32)(wv >> 32));
+            split_operand(x[s].y, c, xa, xb);
+            acc_mac(acc[s][1], xa, xb, (u32)wv, (u32)(wv >> 32));
+        }
+        ++f;
+        ++r;
+        if (t + 1 < K) {
+            if (r >= c.reduce_every) {
+#pragma unroll
+                for (int s = 0; s < SL; s++) { acc_restart(acc[s][0], c); acc_restart(acc[s][1], c); }
+                r = 0;
+                f = 0;
+            } else if (f >= c.fold_every) {
+#pragma unroll
+                for (int s = 0; s < SL; s++) { acc_fold(acc[s][0], c); acc_fold(acc[s][1], c); }
+                f = 0;
+            }
+        }
+    }
+    const u32 o = tile.out0;
+    const u64 bv = (bias != nullptr && comp == 0) ? bias[(size_t)o * limbs + limb] : 0;
+    ulonglong2* dst = reinterpret_cast<ulonglong2*>(out + (size_t)o * ct_stride + row_off);
+#pragma unroll
+    for (int s = 0; s < SL; s++) {
+        ulonglong2 v;
+        v.x = add_mod(acc_reduce(acc[s][0], c), bv, c.q);
+        v.y = add_mod(acc_reduce(acc[s][1], c), bv, c.q);
+        dst[s * MAC_THREADS + threadIdx.x] = v;
+    }
+}
+
 // Full-polynomial plaintexts: the plaintext residue differs per slot, is loaded once and used for
 // both ciphertext components.  A thread owns G outputs x 2 components.
 template <int G>
@@ -292,6 +360,19 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
     hipLaunchKernelGGL((gather_weights_kernel<G>), dim3(count * GATHER_BLOCKS), dim3(256), 0, s, ctx->limbs, tiles, wbase, count, limbs, plan->off_dev,
                        plan->term_pt_dev, pt, wtab);
     HE_HIP(hipGetLastError());
+    if constexpr (G == 1) {
+        const u32 sl = ctx->N >= 2048 ? 4 : 2;
+        const u64 blocks = (u64)count * limbs * 2 * (ctx->N / (MAC_THREADS * 2 * sl));
+        if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
+        if (sl == 4)
+            hipLaunchKernelGGL((mac_scalar_single_kernel<4>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
+                               tiles, count, wbase, plan->term_ct_dev, wtab, ct_in, bias, out);
+        else
+            hipLaunchKernelGGL((mac_scalar_single_kernel<2>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
+                               tiles, count, wbase, plan->term_ct_dev, wtab, ct_in, bias, out);
+        HE_HIP(hipGetLastError());
+        return HE_OK;
+    }
     const u64 blocks = (u64)count * limbs * 2 * (ctx->N / MAC_THREADS);
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     hipLaunchKernelGGL((mac_scalar_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles,

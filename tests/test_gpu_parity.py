@@ -222,6 +222,44 @@ def test_rescale_matches_oracle(he, cfg):
         assert np.array_equal(host(ctx.rescale(dev(sub))), oracle.rescale(sub, c.q[:-1], ctx.psi[:-1]))
 
 
+def test_maximum_sizes_and_degenerate_calls(he):
+    # largest ring degree with the largest number of limbs, mixed widths including 61- and 62-bit moduli
+    N, L = 1 << 14, 16
+    q = wl.modulus_chain([62, 61, 60, 60] + [50] * 6 + [40] * 4 + [30] * 2, N)
+    ctx = he.Context(14, q)
+    assert ctx.psi == oracle.find_psis(q, N)
+    ct = wl.uniform_residues((2, 2), q, N, 71)
+    d = dev(ct)
+    ctx.ntt_fwd(d)
+    assert np.array_equal(host(d), oracle.ntt_fwd(ct, q, ctx.psi))
+    assert np.array_equal(host(ctx.rescale(dev(ct))), oracle.rescale(ct, q, ctx.psi))
+    plan = wl.dense_plan(20, 17)                                    # one full group of 16 and a ragged one of 1
+    hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+    cts = wl.uniform_residues((plan.n_in, 2), q, N, 72)
+    w = wl.uniform_residues((plan.n_pt,), q, 1, 73)[..., 0]
+    b = wl.uniform_residues((plan.n_out,), q, 1, 74)[..., 0]
+    got = host(ctx.ct_pt_mac(hp, dev(cts), dev(w), he.PT_SCALAR, bias=dev(b), flags=he.RESCALE))
+    want, n_rescales = oracle.layer(cts, q, ctx.psi, plan.off, plan.term_ct, plan.term_pt, w, oracle.PT_SCALAR, b)
+    assert n_rescales == plan.n_out and np.array_equal(got, want)
+    # two limbs: the smallest level a rescale accepts; one limb: MAC and add only
+    sub = np.ascontiguousarray(ct[:, :, :2])
+    assert np.array_equal(host(ctx.rescale(dev(sub))), oracle.rescale(sub, q[:2], ctx.psi[:2]))
+    one = np.ascontiguousarray(cts[:, :, :1])
+    got = host(ctx.ct_pt_mac(hp, dev(one), dev(np.ascontiguousarray(w[:, :1])), he.PT_SCALAR))
+    assert np.array_equal(got, oracle.mac(one, q[:1], plan.off, plan.term_ct, plan.term_pt, w[:, :1], oracle.PT_SCALAR))
+    # empty batches are no-ops
+    empty = torch.empty((0, 2, L, N), dtype=torch.int64, device="cuda")
+    assert ctx.rescale(empty).shape == (0, 2, L - 1, N)
+    ctx.ct_pt_add(empty, torch.empty((0, L), dtype=torch.int64, device="cuda"), he.PT_SCALAR)
+    hp0 = ctx.plan(3, 0, 2, np.zeros(1, np.uint32), np.zeros(0, np.uint32), np.zeros(0, np.uint32))
+    out0 = ctx.ct_pt_mac(hp0, dev(cts[:3]), dev(w[:2]), he.PT_SCALAR)
+    assert out0.shape == (0, 2, L, N)
+    # a plan whose outputs have no terms at all: zero plus the bias
+    hpz = ctx.plan(3, 2, 2, np.zeros(3, np.uint32), np.zeros(0, np.uint32), np.zeros(0, np.uint32))
+    z = host(ctx.ct_pt_mac(hpz, dev(cts[:3]), dev(w[:2]), he.PT_SCALAR, bias=dev(b[:2])))
+    assert np.all(z[:, 1] == 0) and np.array_equal(z[:, 0], np.broadcast_to(b[:2, :, None], (2, L, N)))
+
+
 # ----------------------------------------------------------------------------- whole layers, all five configs
 
 def run_layer(he, c, ctx, plan, ct_dev, pt_dev, pt_kind, bias_dev):
