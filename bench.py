@@ -25,6 +25,16 @@ HBM_PEAK_GBS = 8000.0
 INT_MUL32_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 MUL32_PER_MAC = 4          # a 64x64 -> 128-bit product is four 32x32 -> 64 multiply-adds
 MUL32_PER_SHOUP = 10       # hi64(y*w') 4, lo64(y*w) 3, lo64(qh*q) 3
+# HBM-side bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# benchmark, scaled by a plain kernel of known size (profiles/pmc_hbm_traffic_cfg4_cfg5.md).  Counters
+# cannot be read from inside this process, so these are the figures of the profiled build.
+GIB = 1 << 30
+PROFILED_TRAFFIC_BYTES = {
+    "mac_scalar_cfg4": int((9.38 + 8.63) * GIB),
+    "mac_poly_cfg5": int((17.92 + 0.125) * GIB),
+    "rescale_cfg4": int((15.16 + 9.06) * GIB),
+    "rescale_cfg5": None,
+}
 
 
 def main() -> int:
@@ -146,11 +156,11 @@ def main() -> int:
     def alu(name, mul32):
         a = mul32 / (phase_ms[name] * 1e-3) / 1e12
         return {"kernel": name, "bound": "alu", "achieved": a, "peak": INT_MUL32_PEAK_TOPS, "unit": "Tmul32/s",
-                "frac": a / INT_MUL32_PEAK_TOPS, "traffic": None}
+                "frac": a / INT_MUL32_PEAK_TOPS, "traffic": PROFILED_TRAFFIC_BYTES.get(name)}
     def hbm(name, nbytes):
         a = nbytes / (phase_ms[name] * 1e-3) / 1e9
         return {"kernel": name, "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": a / HBM_PEAK_GBS, "traffic": None}
+                "frac": a / HBM_PEAK_GBS, "traffic": PROFILED_TRAFFIC_BYTES.get(name)}
     rooflines["mac_scalar_cfg4"] = alu("mac_scalar_cfg4", macs4 * MUL32_PER_MAC)
     rooflines["rescale_cfg4"] = alu("rescale_cfg4", rescale_mul32(p4.n_out))
     # the full-polynomial MAC streams every plaintext residue once: HBM-bound

@@ -338,6 +338,34 @@ def test_config5_full_poly_layer_sampled_outputs(he):
     assert torch.equal(ctx.rescale(acc), out)
 
 
+def test_two_chained_layers_with_depth_aware_encoding(he):
+    # Sec. "Depth-aware Encoding": the second layer runs one level down, its weights encoded at that level
+    N = 1 << 12
+    q = wl.modulus_chain([60, 40, 40], N)
+    ctx = he.Context(12, q)
+    conv = wl.conv_plan(6, 6, 2, 3, 3, 4, 2, "same")               # 72 cts -> 3x3x4 = 36 cts
+    dense = wl.dense_plan(conv.n_out, 5)
+    ct = wl.uniform_residues((conv.n_in, 2), q, N, 81)
+    w1, b1 = wl.normal_values(conv.n_pt, 0.1, 82), wl.normal_values(conv.n_out, 0.1, 83)
+    w2, b2 = wl.normal_values(dense.n_pt, 0.1, 84), wl.normal_values(dense.n_out, 0.1, 85)
+    scale = 2.0**40
+    h1 = ctx.plan(conv.n_in, conv.n_out, conv.n_pt, conv.off, conv.term_ct, conv.term_pt)
+    h2 = ctx.plan(dense.n_in, dense.n_out, dense.n_pt, dense.off, dense.term_ct, dense.term_pt)
+    t = lambda a: torch.from_numpy(a).cuda()
+    y1 = ctx.ct_pt_mac(h1, dev(ct), ctx.encode_scalar(t(w1), scale), he.PT_SCALAR, bias=ctx.encode_scalar(t(b1), scale),
+                       flags=he.RESCALE)
+    assert y1.shape == (conv.n_out, 2, 2, N)
+    w2e, b2e = ctx.encode_scalar(t(w2), scale, limbs=2), ctx.encode_scalar(t(b2), scale, limbs=2)
+    assert w2e.shape == (dense.n_pt, 2)                                          # 8 * 2 bytes per scalar at level 2
+    y2 = ctx.ct_pt_mac(h2, y1, w2e, he.PT_SCALAR, bias=b2e, flags=he.RESCALE)
+    o1, _ = oracle.layer(ct, q, ctx.psi, conv.off, conv.term_ct, conv.term_pt, oracle.encode_scalars(w1, scale, q),
+                         oracle.PT_SCALAR, oracle.encode_scalars(b1, scale, q))
+    o2, _ = oracle.layer(o1, q[:2], ctx.psi[:2], dense.off, dense.term_ct, dense.term_pt,
+                         oracle.encode_scalars(w2, scale, q[:2]), oracle.PT_SCALAR, oracle.encode_scalars(b2, scale, q[:2]))
+    assert np.array_equal(host(y1), o1) and np.array_equal(host(y2), o2)
+    assert y2.shape == (dense.n_out, 2, 1, N)
+
+
 # ----------------------------------------------------------------------------- meaning: encrypt, compute, decrypt
 
 def test_encrypted_dense_layer_decrypts_to_float_layer(he):
