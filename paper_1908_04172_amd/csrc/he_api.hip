@@ -261,7 +261,7 @@ void classify(std::vector<Tile>& tiles, const u32 caps[3], u32 class_begin[4]) {
 }
 
 const u32 CAPS_S[3] = {1, 4, 16};
-const u32 CAPS_P[3] = {1, 2, 8};
+const u32 CAPS_P[3] = {1, 2, 4};
 
 }  // namespace
 

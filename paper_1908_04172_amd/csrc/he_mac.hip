@@ -285,19 +285,20 @@ mac_scalar_single_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 
 }
 
 // Full-polynomial plaintexts: the plaintext residue differs per slot, is loaded once and used for
-// both ciphertext components.  A thread owns G outputs x 2 components.
+// both ciphertext components.  A thread owns two adjacent slots (16-byte accesses) of one limb, for
+// G outputs x 2 components: 4*G accumulators.
 template <int G>
 __global__ void __launch_bounds__(MAC_THREADS)
 mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u32* off, const u32* term_ct, const u32* term_pt,
                 const u64* pt, const u64* ct_in, const u64* bias, u64* out) {
-    const u32 chunks = N / MAC_THREADS;
+    const u32 chunks = N / (2 * MAC_THREADS);
     u32 b = blockIdx.x;  // same order as the scalar kernel: slice, group of outputs, limb
     const u32 chunk = b % chunks; b /= chunks;
     const u32 tile_i = b % n_tiles;
     const u32 limb = b / n_tiles;
     const Tile tile = tiles[tile_i];
     const LimbConst& c = lt.c[limb];
-    const u32 n = chunk * MAC_THREADS + threadIdx.x;
+    const u32 n = 2 * (chunk * MAC_THREADS + threadIdx.x);
     const size_t ct_stride = (size_t)2 * limbs * N;
     const size_t comp_stride = (size_t)limbs * N;
     const u64* x_base = ct_in + (size_t)limb * N + n;
@@ -309,39 +310,58 @@ mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, 
 #pragma unroll
     for (int g = 0; g < G; g++) tp[g] = term_pt + off[tile.out0 + ((u32)g < tile.count ? g : 0)];
 
-    MacAcc acc[2 * G];
+    MacAcc acc[4 * G];  // [output][component][slot]
 #pragma unroll
-    for (int g = 0; g < 2 * G; g++) acc_clear(acc[g]);
+    for (int g = 0; g < 4 * G; g++) acc_clear(acc[g]);
     u32 f = 0, r = 0;
     for (u32 t = 0; t < K; t++) {
         const u64* xp = x_base + (size_t)tc[t] * ct_stride;
-        const u64 x0 = xp[0], x1 = xp[comp_stride];
-        u64 p[G];
-#pragma unroll
-        for (int g = 0; g < G; g++) p[g] = (u32)g < tile.count ? p_base[(size_t)tp[g][t] * pt_stride] : 0;
-        u32 x0a, x0b, x1a, x1b;
-        split_operand(x0, c, x0a, x0b);
-        split_operand(x1, c, x1a, x1b);
+        const ulonglong2 x0 = *reinterpret_cast<const ulonglong2*>(xp);
+        const ulonglong2 x1 = *reinterpret_cast<const ulonglong2*>(xp + comp_stride);
+        ulonglong2 p[G];
 #pragma unroll
         for (int g = 0; g < G; g++) {
-            u32 pa, pb;
-            split_operand(p[g], c, pa, pb);
-            acc_mac(acc[2 * g], x0a, x0b, pa, pb);
-            acc_mac(acc[2 * g + 1], x1a, x1b, pa, pb);
+            // read once: a non-temporal load keeps it from displacing the reused ciphertext rows in L2
+            if ((u32)g < tile.count) {
+                const u64* src = p_base + (size_t)tp[g][t] * pt_stride;
+                p[g].x = __builtin_nontemporal_load(src);
+                p[g].y = __builtin_nontemporal_load(src + 1);
+            } else {
+                p[g].x = p[g].y = 0;
+            }
+        }
+        u32 xa[4], xb[4];  // [component][slot]
+        split_operand(x0.x, c, xa[0], xb[0]);
+        split_operand(x0.y, c, xa[1], xb[1]);
+        split_operand(x1.x, c, xa[2], xb[2]);
+        split_operand(x1.y, c, xa[3], xb[3]);
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            u32 pa0, pb0, pa1, pb1;
+            split_operand(p[g].x, c, pa0, pb0);
+            split_operand(p[g].y, c, pa1, pb1);
+            acc_mac(acc[4 * g + 0], xa[0], xb[0], pa0, pb0);
+            acc_mac(acc[4 * g + 1], xa[1], xb[1], pa1, pb1);
+            acc_mac(acc[4 * g + 2], xa[2], xb[2], pa0, pb0);
+            acc_mac(acc[4 * g + 3], xa[3], xb[3], pa1, pb1);
         }
         ++f;
         ++r;
-        if (t + 1 < K) housekeeping<2 * G>(acc, f, r, c.fold_every, c.reduce_every, c);
+        if (t + 1 < K) housekeeping<4 * G>(acc, f, r, c.fold_every, c.reduce_every, c);
     }
 #pragma unroll
     for (int g = 0; g < G; g++) {
         if ((u32)g < tile.count) {
             const u32 o = tile.out0 + g;
-            u64 v0 = acc_reduce(acc[2 * g], c), v1 = acc_reduce(acc[2 * g + 1], c);
-            if (bias != nullptr) v0 = add_mod(v0, bias[(size_t)o * limbs + limb], c.q);
+            const u64 bv = bias != nullptr ? bias[(size_t)o * limbs + limb] : 0;
+            ulonglong2 v0, v1;
+            v0.x = add_mod(acc_reduce(acc[4 * g + 0], c), bv, c.q);
+            v0.y = add_mod(acc_reduce(acc[4 * g + 1], c), bv, c.q);
+            v1.x = acc_reduce(acc[4 * g + 2], c);
+            v1.y = acc_reduce(acc[4 * g + 3], c);
             u64* dst = out + ((size_t)o * 2 * limbs + limb) * N + n;
-            dst[0] = v0;
-            dst[comp_stride] = v1;
+            *reinterpret_cast<ulonglong2*>(dst) = v0;
+            *reinterpret_cast<ulonglong2*>(dst + comp_stride) = v1;
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -349,7 +369,7 @@ mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, 
 
 }  // namespace
 
-// tile classes: scalar plaintexts hold up to {1,4,16} outputs per thread, polynomial ones {1,2,8}
+// tile classes: scalar plaintexts hold up to {1,4,16} outputs per thread, polynomial ones {1,2,4}
 template <int G>
 static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, const u64* ct_in, const u64* pt,
                                const u64* bias, u64* out, u64* wtab, hipStream_t s) {
@@ -386,7 +406,7 @@ static int launch_poly_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limb
                              const u64* bias, u64* out, hipStream_t s) {
     const u32 begin = plan->class_begin_p[cls], count = plan->class_begin_p[cls + 1] - begin;
     if (count == 0) return HE_OK;
-    const u64 blocks = (u64)count * limbs * (ctx->N / MAC_THREADS);
+    const u64 blocks = (u64)count * limbs * (ctx->N / (2 * MAC_THREADS));
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     hipLaunchKernelGGL((mac_poly_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
                        plan->tiles_p_dev + begin, count, plan->off_dev, plan->term_ct_dev, plan->term_pt_dev, pt, ct_in, bias, out);
@@ -404,7 +424,7 @@ int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, co
     } else {
         if ((rc = launch_poly_class<1>(ctx, plan, 0, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
         if ((rc = launch_poly_class<2>(ctx, plan, 1, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
-        if ((rc = launch_poly_class<8>(ctx, plan, 2, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
+        if ((rc = launch_poly_class<4>(ctx, plan, 2, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
     }
     return HE_OK;
 }
