@@ -146,6 +146,9 @@ int he_ntt_inv(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, vo
 uint64_t he_host_mulmod(uint64_t a, uint64_t b, uint64_t q);
 uint64_t he_host_reduce128(uint64_t hi, uint64_t lo, uint64_t q);
 uint64_t he_host_shoup_mulmod(uint64_t y, uint64_t w, uint64_t q);
+/* The unreduced Shoup product of the butterflies: congruent to y*w mod q for any 64-bit y, in [0, 2q)
+ * with the exact quotient estimate (cheap_quotient = 0), in [0, 4q) with the cheap one (= 1). */
+uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotient);
 /* The accumulator the MAC kernels use, run on the host: sum of x[t]*w[t] (n terms) mod q. */
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q);
 

@@ -11,7 +11,9 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhe_mi355x.so")
 SOURCES = ["he_api.hip", "he_mac.hip", "he_ntt.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the butterfly loops must unroll completely (register arrays are indexed by their counters)
+         "-mllvm", "-pragma-unroll-threshold=1000000"]
 
 
 def _compile(src: str, extra) -> str:

@@ -130,7 +130,10 @@ void fill_limb_const(LimbConst& c, u64 q, u64 psi, u32 N) {
         c.narrow = lim >= 64;
         if (c.narrow) c.reduce_every = (u32)std::min<u128>(c.reduce_every, lim);
     }
-    c.pad = 0;
+    c.ntt_mode = q < (1ull << 58) ? 2 : q < (1ull << 61) ? 1 : 0;
+    c.neg_two_q = 0 - 2 * q;
+    c.four_q = 4 * q;
+    c.neg_four_q = 0 - 4 * q;
 }
 
 int check_level(const he_ctx* ctx, u32 limbs, u32 min_limbs) {
@@ -552,6 +555,10 @@ uint64_t he_host_reduce128(uint64_t hi, uint64_t lo, uint64_t q) { return reduce
 uint64_t he_host_mulmod(uint64_t a, uint64_t b, uint64_t q) { return mul_mod(a, b, host_const(q)); }
 
 uint64_t he_host_shoup_mulmod(uint64_t y, uint64_t w, uint64_t q) { return shoup_mul(y, w, h_shoup(w, q), q); }
+
+uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotient) {
+    return cheap_quotient ? shoup_mul_lazy4(y, w, h_shoup(w, q), q) : shoup_mul_lazy(y, w, h_shoup(w, q), q);
+}
 
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q) {
     const LimbConst c = host_const(q);

@@ -25,7 +25,8 @@ struct LimbConst {
     u32 narrow;       // 1: accumulated values stay below 2^(63 + bit length of q): one-word Barrett applies
     u64 mu;           // floor(2^(63 + bit length of q) / q), in (2^63, 2^64)
     u32 mu_shift;     // bit length of q, minus 1
-    u32 pad;
+    u32 ntt_mode;     // how lazily the butterflies reduce: 0 for q >= 2^61, 1 for q >= 2^58, else 2 (see he_ntt.hip)
+    u64 neg_two_q, four_q, neg_four_q;  // 2^64 - 2q, 4q mod 2^64, 2^64 - 4q (4q is used only when it fits)
 };
 
 HE_HD u64 mul_hi64(u64 a, u64 b) {
@@ -65,28 +66,57 @@ HE_HD u64 mul_mod(u64 a, u64 b, const LimbConst& c) {
     return reduce128((u64)(p >> 64), (u64)p, c);
 }
 
-// Shoup product with a fixed operand w < q and w' = floor(w * 2^64 / q): for ANY 64-bit y the
-// result is congruent to y*w and lies in [0, 2q) (Harvey's lazy form); needs q < 2^63.
-HE_HD u64 shoup_mul_lazy(u64 y, u64 w, u64 w_shoup, u64 q) {
+// a*b + c as one 32x32+64-bit multiply-add.  On the device the result is pinned to a 64-bit register
+// pair, so that a chain of these whose upper halves are never used still compiles to one instruction
+// per link instead of a separate multiply and add.
+HE_HD u64 mad_wide(u32 a, u32 b, u64 c) {
+    u64 r = (u64)a * b + c;
 #if defined(__HIP_DEVICE_COMPILE__)
-    // Written on 32-bit pieces so that it maps onto 32x32+64 multiply-adds: the quotient estimate
-    // qh = floor(y*w'/2^64) exactly, then y*w - qh*q as y*w + qh*(2^64 - q) modulo 2^64, whose two
-    // low products chain through one accumulator.
-    const u32 y0 = (u32)y, y1 = (u32)(y >> 32), p0 = (u32)w_shoup, p1 = (u32)(w_shoup >> 32);
-    const u64 b = (u64)y0 * p1 + __umulhi(y0, p0);
-    const u64 c = (u64)y1 * p0 + (u32)b;
-    const u64 qh = (u64)y1 * p1 + (b >> 32) + (c >> 32);
+    asm("" : "+v"(r));
+#endif
+    return r;
+}
+
+HE_HD u32 mul_hi32(u32 a, u32 b) { return (u32)(((u64)a * b) >> 32); }
+
+// y*w - qh*q modulo 2^64 on 32-bit pieces, as y*w + qh*(2^64 - q): the two products that reach the
+// low word chain through one accumulator, the four that reach only the high word through another.
+HE_HD u64 shoup_remainder(u64 y, u64 w, u64 qh, u64 q) {
+    const u32 y0 = (u32)y, y1 = (u32)(y >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
     const u32 h0 = (u32)qh, h1 = (u32)(qh >> 32);
     const u64 nq = 0 - q;
-    const u32 n0 = (u32)nq, n1 = (u32)(nq >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
+    const u32 n0 = (u32)nq, n1 = (u32)(nq >> 32);
+    u64 cross = mad_wide(y0, w1, 0);
+    cross = mad_wide(y1, w0, cross);
+    cross = mad_wide(h0, n1, cross);
+    cross = mad_wide(h1, n0, cross);
     u64 e = (u64)y0 * w0;
     e = (u64)h0 * n0 + e;
-    const u32 hi = (u32)(e >> 32) + y0 * w1 + y1 * w0 + h0 * n1 + h1 * n0;
-    return ((u64)hi << 32) | (u32)e;
-#else
-    u64 qh = mul_hi64(y, w_shoup);
-    return y * w - qh * q;
+    u32 hi = (u32)(e >> 32) + (u32)cross;
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("" : "+v"(hi));  // one 32-bit add into the high word, not a 64-bit add of a shifted pair
 #endif
+    return ((u64)hi << 32) | (u32)e;
+}
+
+// Shoup product with a fixed operand w < q and w' = floor(w * 2^64 / q): for ANY 64-bit y the
+// result is congruent to y*w and lies in [0, 2q) (Harvey's lazy form); needs q < 2^63.  The
+// quotient estimate qh = floor(y*w' / 2^64) is exact here.
+HE_HD u64 shoup_mul_lazy(u64 y, u64 w, u64 w_shoup, u64 q) {
+    const u32 y0 = (u32)y, y1 = (u32)(y >> 32), p0 = (u32)w_shoup, p1 = (u32)(w_shoup >> 32);
+    const u64 b = (u64)y0 * p1 + mul_hi32(y0, p0);
+    const u64 c = (u64)y1 * p0 + (u32)b;
+    const u64 qh = (u64)y1 * p1 + (b >> 32) + (c >> 32);
+    return shoup_remainder(y, w, qh, q);
+}
+
+// The same product with a cheaper quotient estimate: y1*p1 + floor(y0*p1 / 2^32) + floor(y1*p0 / 2^32)
+// leaves out the product y0*p0 and the fractions of the two middle products, so it is short of
+// floor(y*w' / 2^64) by at most 2 and the result lies in [0, 4q).  For ANY 64-bit y; needs q < 2^62.
+HE_HD u64 shoup_mul_lazy4(u64 y, u64 w, u64 w_shoup, u64 q) {
+    const u32 y0 = (u32)y, y1 = (u32)(y >> 32), p0 = (u32)w_shoup, p1 = (u32)(w_shoup >> 32);
+    const u64 qh = (u64)y1 * p1 + mul_hi32(y0, p1) + mul_hi32(y1, p0);
+    return shoup_remainder(y, w, qh, q);
 }
 
 HE_HD u64 shoup_mul(u64 y, u64 w, u64 w_shoup, u64 q) {

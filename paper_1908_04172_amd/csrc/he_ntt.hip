@@ -51,7 +51,13 @@ template <int LOGN, int PFROM, int PTO>
 __device__ __forceinline__ void regroup(u64 (&a)[16], u64* lds, u32 tid) {
     // reg_index(tid, e) = reg_index(tid, 0) ^ reg_index(0, e) (disjoint bits) and lds_slot is linear
     // over XOR, so each address is one XOR of a per-thread base with a compile-time constant
-    const u32 from = lds_slot(reg_index<LOGN, PFROM>(tid, 0)), to = lds_slot(reg_index<LOGN, PTO>(tid, 0));
+    // The two bases are derived from copies of the thread index that the optimizer cannot relate to
+    // each other or to other passes: a regrouping writes where the previous one read, and addresses
+    // kept alive from one to the next would cost more registers than the few operations they save.
+    u32 tid_w = tid, tid_r = tid;
+    asm("; regroup %1 write" : "+v"(tid_w) : "n"(PFROM * 16 + PTO));
+    asm("; regroup %1 read" : "+v"(tid_r) : "n"(PFROM * 16 + PTO));
+    const u32 from = lds_slot(reg_index<LOGN, PFROM>(tid_w, 0)), to = lds_slot(reg_index<LOGN, PTO>(tid_r, 0));
     lds_barrier();  // earlier readers of the buffer are done
 #pragma unroll
     for (u32 e = 0; e < 16; e++) lds[from ^ lds_slot(reg_index<LOGN, PFROM>(0, e))] = a[e];
@@ -71,20 +77,57 @@ __device__ __forceinline__ Twiddle load_twiddle(const u64* tw, u32 k) {
     return Twiddle{v.x, v.y};
 }
 
-// Forward butterfly: (X, Y) -> (X + W*Y, X - W*Y), all values in [0, 4q).
-__device__ __forceinline__ void bfly_fwd(u64& x, u64& y, Twiddle t, u64 q, u64 two_q) {
-    u64 u = x >= two_q ? x - two_q : x;
-    u64 v = shoup_mul_lazy(y, t.w, t.w_shoup, q);
-    x = u + v;
-    y = u - v + two_q;
+// How lazily the butterflies reduce depends on the room the modulus leaves in 64 bits
+// (LimbConst::ntt_mode):
+//   mode 0, q < 2^62: Harvey's butterflies as published: forward values in [0, 4q), inverse in [0, 2q),
+//           Shoup products with the exact quotient estimate (result below 2q).
+//   mode 1, q < 2^61: the Shoup products take the cheap quotient estimate (result below 4q); forward
+//           values in [0, 8q), inverse in [0, 4q), one conditional subtraction of 4q per butterfly.
+//   mode 2, q < 2^58: forward butterflies without any conditional subtraction: both outputs exceed
+//           the larger input by less than 4q, so canonical inputs stay below (1 + 4*log2N)*q <= 57q
+//           through all stages.  (Inverse butterflies add their inputs, which would double the
+//           bound per stage, so the inverse transform runs as in mode 1.)
+
+// x - m if that is not negative, else x, for x < 2m <= 2^63: the difference wraps past 2^63 exactly
+// when x < m.  neg_m = 2^64 - m.
+__device__ __forceinline__ u64 sub_if_ge(u64 x, u64 neg_m) {
+    const u64 t = x + neg_m;
+    return (int32_t)(t >> 32) < 0 ? x : t;
 }
 
-// Inverse butterfly: (X, Y) -> (X + Y, (X - Y) * W), all values in [0, 2q).
-__device__ __forceinline__ void bfly_inv(u64& x, u64& y, Twiddle t, u64 q, u64 two_q) {
-    u64 s = x + y;
-    u64 d = x - y + two_q;
-    x = s >= two_q ? s - two_q : s;
-    y = shoup_mul_lazy(d, t.w, t.w_shoup, q);
+// Forward butterfly: (X, Y) -> (X + W*Y, X - W*Y).
+template <int MODE>
+__device__ __forceinline__ void bfly_fwd(u64& x, u64& y, Twiddle t, const LimbConst& c) {
+    if constexpr (MODE == 0) {
+        const u64 u = sub_if_ge(x, c.neg_two_q);
+        const u64 v = shoup_mul_lazy(y, t.w, t.w_shoup, c.q);
+        x = u + v;
+        y = u + c.two_q - v;
+    } else if constexpr (MODE == 1) {
+        const u64 u = sub_if_ge(x, c.neg_four_q);
+        const u64 v = shoup_mul_lazy4(y, t.w, t.w_shoup, c.q);
+        x = u + v;
+        y = u + c.four_q - v;
+    } else {
+        const u64 v = shoup_mul_lazy4(y, t.w, t.w_shoup, c.q);
+        y = x + c.four_q - v;
+        x = x + v;
+    }
+}
+
+// Inverse butterfly: (X, Y) -> (X + Y, (X - Y) * W).
+template <int MODE>
+__device__ __forceinline__ void bfly_inv(u64& x, u64& y, Twiddle t, const LimbConst& c) {
+    const u64 s = x + y;
+    if constexpr (MODE == 0) {
+        const u64 d = x + c.two_q - y;
+        x = sub_if_ge(s, c.neg_two_q);
+        y = shoup_mul_lazy(d, t.w, t.w_shoup, c.q);
+    } else {
+        const u64 d = x + c.four_q - y;
+        x = sub_if_ge(s, c.neg_four_q);
+        y = shoup_mul_lazy4(d, t.w, t.w_shoup, c.q);
+    }
 }
 
 // Shape of pass P: its stages, and where the twiddle of (stage k, register e) sits among the
@@ -116,6 +159,7 @@ struct PassTwiddles {
 template <int LOGN, int P>
 __device__ __forceinline__ void load_pass_twiddles(PassTwiddles<LOGN, P>& pt, const u64* tw, u32 tid) {
     using S = PassShape<LOGN, P>;
+    asm("; twiddles of pass %1" : "+v"(tid) : "n"(P));  // addresses are derived here, not ahead of earlier passes
 #pragma unroll
     for (int k = 0; k < S::NST; k++) {
         const int s = 4 * P + k;
@@ -131,9 +175,10 @@ __device__ __forceinline__ void load_pass_twiddles(PassTwiddles<LOGN, P>& pt, co
 }
 
 // The stages of pass P on the 16 registers of one thread.
-template <int LOGN, int P, bool INVERSE>
+template <int LOGN, int P, bool INVERSE, int MODE>
 __device__ __forceinline__ void run_pass(u64 (&a)[16], const PassTwiddles<LOGN, P>& pt, const LimbConst& c) {
     using S = PassShape<LOGN, P>;
+    static_assert(!(INVERSE && MODE == 2), "the inverse transform has modes 0 and 1 only");
 #pragma unroll
     for (int kk = 0; kk < S::NST; kk++) {
         const int k = INVERSE ? S::NST - 1 - kk : kk;
@@ -143,82 +188,116 @@ __device__ __forceinline__ void run_pass(u64 (&a)[16], const PassTwiddles<LOGN, 
         for (u32 e = 0; e < 16; e++) {
             if (e & (1u << bit)) continue;
             if constexpr (INVERSE) {
-                if (s == 0) {  // merged with the multiplication by N^-1
+                if (s == 0) {  // merged with the multiplication by N^-1; the exact products end below 2q
                     u64 sum = a[e] + a[e | (1u << bit)];
-                    u64 dif = a[e] - a[e | (1u << bit)] + c.two_q;
+                    u64 dif = a[e] + (MODE == 0 ? c.two_q : c.four_q) - a[e | (1u << bit)];
                     a[e] = shoup_mul_lazy(sum, c.n_inv, c.n_inv_shoup, c.q);
                     a[e | (1u << bit)] = shoup_mul_lazy(dif, c.w1n_inv, c.w1n_inv_shoup, c.q);
                 } else {
-                    bfly_inv(a[e], a[e | (1u << bit)], pt.t[S::slot(k, e)], c.q, c.two_q);
+                    bfly_inv<MODE>(a[e], a[e | (1u << bit)], pt.t[S::slot(k, e)], c);
                 }
             } else {
-                bfly_fwd(a[e], a[e | (1u << bit)], pt.t[S::slot(k, e)], c.q, c.two_q);
+                bfly_fwd<MODE>(a[e], a[e | (1u << bit)], pt.t[S::slot(k, e)], c);
             }
         }
     }
 }
 
-// Registers in pass-0 order, canonical or lazy (< 4q) -> registers in last-pass order, < 4q.
-template <int LOGN>
+// Registers in pass-0 order, canonical -> registers in last-pass order, below 4q (mode 0), 8q
+// (mode 1) or (1 + 4*log2N)*q (mode 2).
+template <int LOGN, int MODE>
 __device__ __forceinline__ void ntt_forward(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
     using G = Geo<LOGN>;
     {
         PassTwiddles<LOGN, 0> t0;
         load_pass_twiddles<LOGN, 0>(t0, tw, tid);
-        run_pass<LOGN, 0, false>(a, t0, c);
+        run_pass<LOGN, 0, false, MODE>(a, t0, c);
     }
     if constexpr (G::NPASS > 1) {
         PassTwiddles<LOGN, 1> t1;
         load_pass_twiddles<LOGN, 1>(t1, tw, tid);
         regroup<LOGN, 0, 1>(a, lds, tid);
-        run_pass<LOGN, 1, false>(a, t1, c);
+        run_pass<LOGN, 1, false, MODE>(a, t1, c);
     }
     if constexpr (G::NPASS > 2) {
         PassTwiddles<LOGN, 2> t2;
         load_pass_twiddles<LOGN, 2>(t2, tw, tid);
         regroup<LOGN, 1, 2>(a, lds, tid);
-        run_pass<LOGN, 2, false>(a, t2, c);
+        run_pass<LOGN, 2, false, MODE>(a, t2, c);
     }
     if constexpr (G::NPASS > 3) {
         PassTwiddles<LOGN, 3> t3;
         load_pass_twiddles<LOGN, 3>(t3, tw, tid);
         regroup<LOGN, 2, 3>(a, lds, tid);
-        run_pass<LOGN, 3, false>(a, t3, c);
+        run_pass<LOGN, 3, false, MODE>(a, t3, c);
     }
 }
 
-// Registers in last-pass order, < 2q -> registers in pass-0 order, < 2q, multiplied by N^-1.
+// The forward transform in the limb's mode, ending below `cap` (returned): 4q, 4q or (1+4*log2N)*q.
+// In mode 1 the values are brought from below 8q to below 4q, so that x + cap - value fits 64 bits
+// for any canonical x.
 template <int LOGN>
+__device__ __forceinline__ u64 ntt_forward_any(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
+    if (c.ntt_mode == 2) {
+        ntt_forward<LOGN, 2>(a, tw, lds, tid, c);
+        return c.q * (4 * LOGN + 1);
+    }
+    if (c.ntt_mode == 1) {
+        ntt_forward<LOGN, 1>(a, tw, lds, tid, c);
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = sub_if_ge(a[e], c.neg_four_q);
+        return c.four_q;
+    }
+    ntt_forward<LOGN, 0>(a, tw, lds, tid, c);
+    return 2 * c.two_q;
+}
+
+// Registers in last-pass order, canonical -> registers in pass-0 order, below 2q, multiplied by N^-1.
+template <int LOGN, int MODE>
 __device__ __forceinline__ void ntt_inverse(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
     using G = Geo<LOGN>;
     if constexpr (G::NPASS > 3) {
         PassTwiddles<LOGN, 3> t3;
         load_pass_twiddles<LOGN, 3>(t3, tw, tid);
-        run_pass<LOGN, 3, true>(a, t3, c);
+        run_pass<LOGN, 3, true, MODE>(a, t3, c);
     }
     if constexpr (G::NPASS > 2) {
         PassTwiddles<LOGN, 2> t2;
         load_pass_twiddles<LOGN, 2>(t2, tw, tid);
         if constexpr (G::NPASS > 3) regroup<LOGN, 3, 2>(a, lds, tid);
-        run_pass<LOGN, 2, true>(a, t2, c);
+        run_pass<LOGN, 2, true, MODE>(a, t2, c);
     }
     if constexpr (G::NPASS > 1) {
         PassTwiddles<LOGN, 1> t1;
         load_pass_twiddles<LOGN, 1>(t1, tw, tid);
         if constexpr (G::NPASS > 2) regroup<LOGN, 2, 1>(a, lds, tid);
-        run_pass<LOGN, 1, true>(a, t1, c);
+        run_pass<LOGN, 1, true, MODE>(a, t1, c);
     }
     {
         PassTwiddles<LOGN, 0> t0;
         load_pass_twiddles<LOGN, 0>(t0, tw, tid);
         if constexpr (G::NPASS > 1) regroup<LOGN, 1, 0>(a, lds, tid);
-        run_pass<LOGN, 0, true>(a, t0, c);
+        run_pass<LOGN, 0, true, MODE>(a, t0, c);
     }
+}
+
+template <int LOGN>
+__device__ __forceinline__ void ntt_inverse_any(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
+    if (c.ntt_mode != 0) ntt_inverse<LOGN, 1>(a, tw, lds, tid, c);
+    else ntt_inverse<LOGN, 0>(a, tw, lds, tid, c);
 }
 
 __device__ __forceinline__ u64 canon4(u64 v, u64 q, u64 two_q) {  // [0,4q) -> [0,q)
     v = v >= two_q ? v - two_q : v;
     return v >= q ? v - q : v;
+}
+
+// A copy of the thread index that the optimizer treats as a new value: addresses derived from it
+// are computed where they are used instead of being carried (in registers the transform needs)
+// from the top of the kernel.
+__device__ __forceinline__ u32 fresh(u32 tid) {
+    asm("; fresh thread index" : "+v"(tid));
+    return tid;
 }
 
 template <int LOGN, bool INVERSE>
@@ -235,17 +314,25 @@ __global__ void __launch_bounds__(Geo<LOGN>::T) ntt_rows_kernel(LimbTable lt, u3
     if constexpr (!INVERSE) {
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, 0>(tid, e)];
-        ntt_forward<LOGN>(a, tw, lds, tid, c);
+        const u64 cap = ntt_forward_any<LOGN>(a, tw, lds, tid, c);
+        (void)cap;
+        if (c.ntt_mode == 2) {
+            // below 57q: a Shoup product by 1 (whose companion is floor(2^64/q)) brings it below 4q
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) p[reg_index<LOGN, G::NPASS - 1>(tid, e)] = canon4(a[e], c.q, c.two_q);
+            for (u32 e = 0; e < 16; e++) a[e] = shoup_mul_lazy4(a[e], 1, c.ratio_hi, c.q);
+        }
+        const u32 tid_s = fresh(tid);
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) p[reg_index<LOGN, G::NPASS - 1>(tid_s, e)] = canon4(a[e], c.q, c.two_q);
     } else {
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, G::NPASS - 1>(tid, e)];
-        ntt_inverse<LOGN>(a, tw, lds, tid, c);
+        ntt_inverse_any<LOGN>(a, tw, lds, tid, c);
+        const u32 tid_s = fresh(tid);
 #pragma unroll
         for (u32 e = 0; e < 16; e++) {
             u64 v = a[e];
-            p[reg_index<LOGN, 0>(tid, e)] = v >= c.q ? v - c.q : v;
+            p[reg_index<LOGN, 0>(tid_s, e)] = v >= c.q ? v - c.q : v;
         }
     }
 }
@@ -254,36 +341,45 @@ __global__ void __launch_bounds__(Geo<LOGN>::T) ntt_rows_kernel(LimbTable lt, u3
 // p the dropped modulus, h = floor(p/2), r the last limb's coefficients and t = (r + h) mod p:
 //   out_i = (x_i - NTT_i((t mod q_i) - (h mod q_i))) * p^-1  mod q_i      for every kept limb i,
 // which equals round(X / p) mod q_i for the integer X the residues stand for.  The inverse
-// transform of the last limb ends in the register order in which a forward transform starts, so t
-// never leaves the registers.
+// transform of the last limb ends in the register order in which a forward transform starts, so
+// the first kept limb takes t straight from the registers; for the others t is parked in memory.
+//
+// Compute and memory phases would otherwise alternate in step on every compute unit (one workgroup
+// each, all waiting on HBM at the same moments), so the memory side is spread out:
+//  - the x_i row is touched once per 64 bytes at the top of an iteration (two 4-byte loads per
+//    thread), which brings it into the L2 / memory-side cache while the transform runs;
+//  - the parked t for limb i+1 is requested before the outputs of limb i are stored, so that the
+//    next iteration does not queue behind those stores.
 template <int LOGN>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
 rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_fwd, const u64* tw_inv,
                const DropConst* drop) {
     using G = Geo<LOGN>;
     extern __shared__ u64 lds[];
-    const u32 tid = threadIdx.x;
     const size_t poly = blockIdx.x;  // ct*2 + component
     const u32 last = limbs - 1;
     const u64* src = in + poly * limbs * G::N;
     u64* dst = out + poly * (limbs - 1) * G::N;
-    // t = (INTT(last limb) + h) mod p is parked in the output row of the last kept limb: every
-    // thread re-reads only what it wrote itself, and that row is overwritten only at the very end,
-    // after all its threads have taken their t back (the regrouping barriers lie in between).
+    // t is parked in the output row of the last kept limb: every thread re-reads only what it wrote
+    // itself, and that row is overwritten only in the last iteration, after all its threads have
+    // taken their t back (they use it before the first regrouping barrier of that iteration).
     u64* park = dst + (size_t)(last - 1) * G::N;
+    u64 a[16];
     {
-        u64 t[16];
+        const u32 tid = threadIdx.x;
         const LimbConst& c = lt.c[last];
         const u64* row = src + (size_t)last * G::N;
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) t[e] = row[reg_index<LOGN, G::NPASS - 1>(tid, e)];
-        ntt_inverse<LOGN>(t, tw_inv + (size_t)last * G::N * 2, lds, tid, c);
+        for (u32 e = 0; e < 16; e++) a[e] = row[reg_index<LOGN, G::NPASS - 1>(tid, e)];
+        ntt_inverse_any<LOGN>(a, tw_inv + (size_t)last * G::N * 2, lds, tid, c);
         const u64 half = c.q >> 1;
+        const u32 tid_s = fresh(tid);
 #pragma unroll
         for (u32 e = 0; e < 16; e++) {
-            u64 v = t[e];
+            u64 v = a[e];
             v = v >= c.q ? v - c.q : v;
-            park[reg_index<LOGN, 0>(tid, e)] = add_mod(v, half, c.q);
+            a[e] = add_mod(v, half, c.q);
+            if (last > 1) park[reg_index<LOGN, 0>(tid_s, e)] = a[e];
         }
     }
     for (u32 i = 0; i < last; i++) {
@@ -294,9 +390,11 @@ rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_f
         const u32 tid = tid_i;
         const LimbConst& c = lt.c[i];
         const DropConst d = drop[last * HE_MAX_LIMBS + i];
-        u64 a[16];
-#pragma unroll
-        for (u32 e = 0; e < 16; e++) a[e] = park[reg_index<LOGN, 0>(tid, e)];
+        const u64* xrow = src + (size_t)i * G::N;
+        u64* orow = dst + (size_t)i * G::N;
+        // each thread touches its own 128 bytes of the x row (N*8 bytes = T*128)
+        const u32* touch = reinterpret_cast<const u32*>(xrow) + (size_t)tid * 32;
+        const u32 touched0 = touch[0], touched1 = touch[16];
         // t < p: bring it below q_i (nothing to do, one subtraction, or a full reduction, depending
         // on how p compares with q_i), then subtract h mod q_i
         if (d.reduce_mode == 2) {
@@ -308,16 +406,30 @@ rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_f
         }
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = sub_mod(a[e], d.half_mod, c.q);
-        ntt_forward<LOGN>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
-        const u64* xrow = src + (size_t)i * G::N;
-        u64* orow = dst + (size_t)i * G::N;
+        // the transformed correction stays below `cap` (a multiple of q), so x + cap - correction is
+        // positive, congruent to x - correction and fits 64 bits; the Shoup product takes it as it is
+        u64 cap = ntt_forward_any<LOGN>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
+        if (c.ntt_mode == 0) {  // 5q need not fit 64 bits, 3q does
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) {
-            const u32 j = reg_index<LOGN, G::NPASS - 1>(tid, e);
-            u64 delta = a[e] >= c.two_q ? a[e] - c.two_q : a[e];  // [0, 2q)
-            u64 diff = xrow[j] + c.two_q - delta;                     // (0, 3q), congruent to x - delta
-            orow[j] = shoup_mul(diff, d.p_inv, d.p_inv_shoup, c.q);
+            for (u32 e = 0; e < 16; e++) a[e] = sub_if_ge(a[e], c.neg_two_q);
+            cap = c.two_q;
         }
+        asm("; the touching loads end here" : "+v"(a[0]) : "v"(touched0), "v"(touched1));
+        const u32 tid_s = fresh(tid);
+        u64 x[16], next[16];
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) x[e] = xrow[reg_index<LOGN, G::NPASS - 1>(tid_s, e)];
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) next[e] = 0;
+        if (i + 1 < last) {
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) next[e] = park[reg_index<LOGN, 0>(tid_s, e)];
+        }
+#pragma unroll
+        for (u32 e = 0; e < 16; e++)
+            orow[reg_index<LOGN, G::NPASS - 1>(tid_s, e)] = shoup_mul(x[e] + cap - a[e], d.p_inv, d.p_inv_shoup, c.q);
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = next[e];
     }
 }
 

@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(_HERE, "libhe_mi355x.so")
 EXPORTS = [
     "he_strerror", "he_ctx_create", "he_ctx_destroy", "he_ctx_info", "he_encode_scalar", "he_encode_scalar_host",
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
-    "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod",
+    "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate",
 ]
 
@@ -64,6 +64,7 @@ def lib():
         "he_host_mulmod": (u64, [u64, u64, u64]),
         "he_host_reduce128": (u64, [u64, u64, u64]),
         "he_host_shoup_mulmod": (u64, [u64, u64, u64]),
+        "he_host_shoup_lazy": (u64, [u64, u64, u64, ctypes.c_int]),
         "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
     }
     for name, (res, args) in sigs.items():
@@ -252,6 +253,10 @@ def host_reduce128(hi: int, lo: int, q: int) -> int:
 
 def host_shoup_mulmod(y: int, w: int, q: int) -> int:
     return int(lib().he_host_shoup_mulmod(y, w, q))
+
+
+def host_shoup_lazy(y: int, w: int, q: int, cheap_quotient: bool) -> int:
+    return int(lib().he_host_shoup_lazy(y, w, q, int(cheap_quotient)))
 
 
 def host_mac_accumulate(x, w, q: int) -> int:

@@ -47,6 +47,22 @@ def test_barrett_and_shoup_equal_python_mod():
             assert he.host_reduce128(z >> 64, z & (2**64 - 1), q) == z % q
 
 
+def test_lazy_shoup_products_stay_in_their_ranges():
+    """The butterflies' unreduced products: congruent to y*w for any 64-bit y, below 2q with the exact
+    quotient estimate and below 4q with the cheap one."""
+    rnd = random.Random(5)
+    for q in primes() + [wl.ntt_primes(b, 1 << 14, 1)[0] for b in (58, 61)]:
+        ys = [0, 1, q - 1, q, 2 * q, 4 * q - 1, 2**32 - 1, 2**32, 2**64 - 1, 2**63, 57 * q if 57 * q < 2**64 else 2**64 - 2]
+        ys += [rnd.randrange(2**64) for _ in range(300)] + [rnd.randrange(min(8 * q, 2**64)) for _ in range(300)]
+        ws = [0, 1, q - 1, q // 2] + [rnd.randrange(q) for _ in range(4)]
+        for w in ws:
+            for y in ys:
+                exact = he.host_shoup_lazy(y, w, q, False)
+                cheap = he.host_shoup_lazy(y, w, q, True)
+                assert exact % q == y * w % q and exact < 2 * q, (q, y, w)
+                assert cheap % q == y * w % q and cheap < 4 * q and cheap >= exact, (q, y, w)
+
+
 def test_mac_accumulator_fold_and_reduce_schedule():
     rnd = random.Random(4)
     for q in primes():
