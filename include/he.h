@@ -92,6 +92,8 @@ int he_encode_scalar_host(const he_ctx* ctx, const double* values, size_t n, dou
  */
 int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, const uint32_t* off,
                    const uint32_t* term_ct, const uint32_t* term_pt, he_plan** out);
+/* Frees the plan's device arrays.  Valid also after the plan's context was destroyed; every other
+ * call on a plan needs its context alive. */
 int he_plan_destroy(he_plan* plan);
 /* Device bytes he_ct_pt_mac needs in `workspace` for this plan, level and flags. */
 int he_plan_workspace_bytes(const he_plan* plan, uint32_t limbs, int pt_kind, uint32_t flags,

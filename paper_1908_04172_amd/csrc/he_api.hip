@@ -338,8 +338,7 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
                 pwi = h_mulmod(pwi, psi_inv, q);
             }
         }
-        if (upload(&ctx->tw_fwd, fwd.data(), fwd.size()) != HE_OK || upload(&ctx->tw_inv, inv.data(), inv.size()) != HE_OK ||
-            upload(&ctx->drop_dev, &ctx->drop[0][0], (size_t)HE_MAX_LIMBS * HE_MAX_LIMBS) != HE_OK) {
+        if (upload(&ctx->tw_fwd, fwd.data(), fwd.size()) != HE_OK || upload(&ctx->tw_inv, inv.data(), inv.size()) != HE_OK) {
             he_ctx_destroy(ctx);
             return HE_ERR_DEVICE;
         }
@@ -353,8 +352,8 @@ int he_ctx_destroy(he_ctx* ctx) {
     if (ctx->device >= 0 && hipSetDevice(ctx->device) == hipSuccess) {
         if (ctx->tw_fwd) (void)hipFree(ctx->tw_fwd);
         if (ctx->tw_inv) (void)hipFree(ctx->tw_inv);
-        if (ctx->drop_dev) (void)hipFree(ctx->drop_dev);
     }
+    if (ctx->device >= 0) (void)hipGetLastError();  // a failure here must not surface in the caller's next HIP call
     delete ctx;
     return HE_OK;
 }
@@ -413,6 +412,7 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
     he_plan* p = new (std::nothrow) he_plan();
     if (!p) return HE_ERR_ARG;
     p->ctx = ctx;
+    p->device = ctx->device;
     p->n_in = n_in; p->n_out = n_out; p->n_pt = n_pt; p->n_terms = n_terms;
     p->off.assign(off, off + n_out + 1);
     p->tiles_s_dev = p->tiles_p_dev = nullptr;
@@ -445,11 +445,12 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
 
 int he_plan_destroy(he_plan* p) {
     if (!p) return HE_ERR_ARG;
-    if (p->ctx && p->ctx->device >= 0 && hipSetDevice(p->ctx->device) == hipSuccess) {
+    if (p->device >= 0 && hipSetDevice(p->device) == hipSuccess) {
         void* bufs[] = {p->tiles_s_dev, p->tiles_p_dev, p->wbase_s_dev, p->off_dev, p->term_ct_dev, p->term_pt_dev};
         for (void* b : bufs)
             if (b) (void)hipFree(b);
     }
+    (void)hipGetLastError();  // a failure here must not surface in the caller's next HIP call
     delete p;
     return HE_OK;
 }

@@ -20,6 +20,12 @@ struct DropConst {
     u32 pad;
 };
 
+// The constants of one dropped limb against every kept limb, passed to the rescale kernel by value
+// (kernel arguments are read with scalar loads, whatever else the kernel does to memory).
+struct DropRow {
+    DropConst d[HE_MAX_LIMBS];
+};
+
 struct he_ctx {
     int device;  // -1: host-only
     u32 log2N, N, L;
@@ -29,7 +35,6 @@ struct he_ctx {
     // device tables
     u64* tw_fwd;      // [L][N][2]: (psi^brv(k), Shoup companion), k in [0, N)
     u64* tw_inv;      // [L][N][2]: (psi^-brv(k), Shoup companion)
-    DropConst* drop_dev;  // [L][L]
 };
 
 // One group of outputs that read the same ciphertexts in the same order.
@@ -42,6 +47,7 @@ struct Tile {
 
 struct he_plan {
     he_ctx* ctx;
+    int device;            // the context's device, kept so that the plan can be destroyed after its context
     u32 n_in, n_out, n_pt, n_terms;
     std::vector<u32> off;  // host copy, for argument checks
     // tiles sorted by class; a class-k tile is run by the kernel instance with capacity cap[k]

@@ -344,16 +344,11 @@ __global__ void __launch_bounds__(Geo<LOGN>::T) ntt_rows_kernel(LimbTable lt, u3
 // transform of the last limb ends in the register order in which a forward transform starts, so
 // the first kept limb takes t straight from the registers; for the others t is parked in memory.
 //
-// Compute and memory phases would otherwise alternate in step on every compute unit (one workgroup
-// each, all waiting on HBM at the same moments), so the memory side is spread out:
-//  - the x_i row is touched once per 64 bytes at the top of an iteration (two 4-byte loads per
-//    thread), which brings it into the L2 / memory-side cache while the transform runs;
-//  - the parked t for limb i+1 is requested before the outputs of limb i are stored, so that the
-//    next iteration does not queue behind those stores.
+// The parked t for limb i+1 is requested before the outputs of limb i are stored, so that the next
+// iteration does not queue behind those stores.
 template <int LOGN>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
-rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_fwd, const u64* tw_inv,
-               const DropConst* drop) {
+rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, const u64* in, u64* out, const u64* tw_fwd, const u64* tw_inv) {
     using G = Geo<LOGN>;
     extern __shared__ u64 lds[];
     const size_t poly = blockIdx.x;  // ct*2 + component
@@ -389,12 +384,9 @@ rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_f
         asm volatile("" : "+v"(tid_i));
         const u32 tid = tid_i;
         const LimbConst& c = lt.c[i];
-        const DropConst d = drop[last * HE_MAX_LIMBS + i];
+        const DropConst& d = drop.d[i];
         const u64* xrow = src + (size_t)i * G::N;
         u64* orow = dst + (size_t)i * G::N;
-        // each thread touches its own 128 bytes of the x row (N*8 bytes = T*128)
-        const u32* touch = reinterpret_cast<const u32*>(xrow) + (size_t)tid * 32;
-        const u32 touched0 = touch[0], touched1 = touch[16];
         // t < p: bring it below q_i (nothing to do, one subtraction, or a full reduction, depending
         // on how p compares with q_i), then subtract h mod q_i
         if (d.reduce_mode == 2) {
@@ -414,7 +406,6 @@ rescale_kernel(LimbTable lt, u32 limbs, const u64* in, u64* out, const u64* tw_f
             for (u32 e = 0; e < 16; e++) a[e] = sub_if_ge(a[e], c.neg_two_q);
             cap = c.two_q;
         }
-        asm("; the touching loads end here" : "+v"(a[0]) : "v"(touched0), "v"(touched1));
         const u32 tid_s = fresh(tid);
         u64 x[16], next[16];
 #pragma unroll
@@ -453,8 +444,10 @@ int launch_rescale_t(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hip
     using G = Geo<LOGN>;
     const size_t lds = (size_t)G::N * sizeof(u64);
     HE_HIP(hipFuncSetAttribute((const void*)rescale_kernel<LOGN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL((rescale_kernel<LOGN>), dim3(2 * n), dim3(G::T), lds, s, ctx->limbs, limbs, in, out, ctx->tw_fwd,
-                       ctx->tw_inv, ctx->drop_dev);
+    DropRow row;
+    for (u32 i = 0; i < HE_MAX_LIMBS; i++) row.d[i] = ctx->drop[limbs - 1][i];
+    hipLaunchKernelGGL((rescale_kernel<LOGN>), dim3(2 * n), dim3(G::T), lds, s, ctx->limbs, row, limbs, in, out, ctx->tw_fwd,
+                       ctx->tw_inv);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
