@@ -8,6 +8,8 @@
 // bits again, so that consecutive threads hold consecutive short runs and global stores stay dense.
 // Butterflies are Harvey's lazy ones (values in [0,4q) forward, [0,2q) inverse) with Shoup
 // multiplication by precomputed twiddles psi^bitrev(k); moduli are below 2^62, so 4q fits 64 bits.
+#include <algorithm>
+
 #include "he_internal.h"
 
 namespace {
@@ -300,40 +302,56 @@ __device__ __forceinline__ u32 fresh(u32 tid) {
     return tid;
 }
 
+// In-place transforms of `rows` rows of N residues, row r under limb r % limbs.  A workgroup takes
+// rows blockIdx.x, blockIdx.x + gridDim.x, ... and requests its next row before it stores the
+// current one, so that the loads do not queue behind the stores and arrive while those drain.
 template <int LOGN, bool INVERSE>
-__global__ void __launch_bounds__(Geo<LOGN>::T) ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all) {
+__global__ void __launch_bounds__(Geo<LOGN>::T)
+ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows) {
     using G = Geo<LOGN>;
+    constexpr int PIN = INVERSE ? G::NPASS - 1 : 0, POUT = INVERSE ? 0 : G::NPASS - 1;
     extern __shared__ u64 lds[];
-    const u32 tid = threadIdx.x;
-    const u32 row = blockIdx.x;
-    const u32 limb = row % limbs;
-    const LimbConst& c = lt.c[limb];
-    const u64* tw = tw_all + (size_t)limb * G::N * 2;
-    u64* p = data + (size_t)row * G::N;
     u64 a[16];
-    if constexpr (!INVERSE) {
+    {
+        const u64* p = data + (size_t)blockIdx.x * G::N;
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, 0>(tid, e)];
-        const u64 cap = ntt_forward_any<LOGN>(a, tw, lds, tid, c);
-        (void)cap;
-        if (c.ntt_mode == 2) {
-            // below 57q: a Shoup product by 1 (whose companion is floor(2^64/q)) brings it below 4q
+        for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, PIN>(threadIdx.x, e)];
+    }
+    for (u32 row = blockIdx.x; row < rows; row += gridDim.x) {
+        u32 tid_i = threadIdx.x;  // opaque per iteration: addresses are recomputed, not kept live
+        asm volatile("" : "+v"(tid_i));
+        const u32 tid = tid_i;
+        const u32 limb = row % limbs;
+        const LimbConst& c = lt.c[limb];
+        const u64* tw = tw_all + (size_t)limb * G::N * 2;
+        if constexpr (!INVERSE) {
+            ntt_forward_any<LOGN>(a, tw, lds, tid, c);
+            if (c.ntt_mode == 2) {
+                // below 57q: a Shoup product by 1 (whose companion is floor(2^64/q)) brings it below 4q
 #pragma unroll
-            for (u32 e = 0; e < 16; e++) a[e] = shoup_mul_lazy4(a[e], 1, c.ratio_hi, c.q);
+                for (u32 e = 0; e < 16; e++) a[e] = shoup_mul_lazy4(a[e], 1, c.ratio_hi, c.q);
+            }
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) a[e] = canon4(a[e], c.q, c.two_q);
+        } else {
+            ntt_inverse_any<LOGN>(a, tw, lds, tid, c);
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) a[e] = a[e] >= c.q ? a[e] - c.q : a[e];
         }
         const u32 tid_s = fresh(tid);
+        u64 next[16];
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) p[reg_index<LOGN, G::NPASS - 1>(tid_s, e)] = canon4(a[e], c.q, c.two_q);
-    } else {
+        for (u32 e = 0; e < 16; e++) next[e] = 0;
+        if (row + gridDim.x < rows) {
+            const u64* p = data + (size_t)(row + gridDim.x) * G::N;
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, G::NPASS - 1>(tid, e)];
-        ntt_inverse_any<LOGN>(a, tw, lds, tid, c);
-        const u32 tid_s = fresh(tid);
-#pragma unroll
-        for (u32 e = 0; e < 16; e++) {
-            u64 v = a[e];
-            p[reg_index<LOGN, 0>(tid_s, e)] = v >= c.q ? v - c.q : v;
+            for (u32 e = 0; e < 16; e++) next[e] = p[reg_index<LOGN, PIN>(tid_s, e)];
         }
+        u64* p = data + (size_t)row * G::N;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) p[reg_index<LOGN, POUT>(tid_s, e)] = a[e];
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = next[e];
     }
 }
 
@@ -428,12 +446,16 @@ template <int LOGN>
 int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipStream_t s) {
     using G = Geo<LOGN>;
     const size_t lds = (size_t)G::N * sizeof(u64);
+    // as many workgroups as stay resident at once (LDS and the 2048 threads of a compute unit bound
+    // that), each looping over its share of the rows
+    const u32 per_cu = (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
+    const u32 grid = std::min<u32>(rows, 256 * per_cu);
     if (inverse) {
         HE_HIP(hipFuncSetAttribute((const void*)ntt_rows_kernel<LOGN, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(rows), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv);
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, rows);
     } else {
         HE_HIP(hipFuncSetAttribute((const void*)ntt_rows_kernel<LOGN, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(rows), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd);
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd, rows);
     }
     HE_HIP(hipGetLastError());
     return HE_OK;

@@ -74,6 +74,23 @@ def test_ntt_fwd_inv_match_oracle(he, log2N):
     ctx.ntt_fwd(de[:0])                                         # zero polys: a no-op
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("log2N,polys", [(14, 111), (12, 437)])
+def test_ntt_with_several_rows_per_workgroup(he, log2N, polys):
+    """More rows than resident workgroups (256 at N = 2^14, 1280 at N = 2^12), and not a multiple of
+    them: every workgroup loops, some once more than others.  All rows against the oracle."""
+    N = 1 << log2N
+    q = wl.modulus_chain(MIXED[log2N], N)
+    ctx = he.Context(log2N, q)
+    a = wl.uniform_residues((polys,), q, N, 3000 + log2N)
+    assert polys * len(q) > (256 if log2N == 14 else 1280)
+    d = dev(a)
+    ctx.ntt_fwd(d)
+    assert np.array_equal(host(d), oracle.ntt_fwd(a, q, ctx.psi))
+    ctx.ntt_inv(d)
+    assert np.array_equal(host(d), a)
+
+
 # ----------------------------------------------------------------------------- Alg. 2
 
 def test_encode_scalar_kernel_matches_oracle(he):
