@@ -46,8 +46,10 @@ def main() -> int:
     ap.add_argument("--only", default="", help="comma-separated phases to run (profiling aid; the JSON is then partial)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain elementwise kernels over 2 GiB (counter calibration for rocprofv3 --pmc)")
-    ap.add_argument("--cpu-sample-cfg4", type=int, default=512, help="cfg4 outputs the oracle is timed on")
-    ap.add_argument("--cpu-sample-cfg5", type=int, default=16, help="cfg5 outputs the oracle is timed on")
+    ap.add_argument("--no-all-configs", dest="all_configs", action="store_false",
+                    help="skip the per-config report of the five layers")
+    ap.add_argument("--cpu-sample-cfg4", type=int, default=1024, help="cfg4 outputs the oracle is timed on")
+    ap.add_argument("--cpu-sample-cfg5", type=int, default=32, help="cfg5 outputs the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU figure exists", file=sys.stderr)
@@ -169,6 +171,36 @@ def main() -> int:
     rooflines["rescale_cfg5"] = alu("rescale_cfg5", rescale_mul32(p5.n_out))
     dominant = max(rooflines, key=lambda k: phase_ms[k])
 
+    # ---- the same kernels against MEASURED register-resident rates of their own primitives
+    # (he_measure_rate): time the arithmetic alone would take at that rate / time the kernel took
+    rate_cache = {}
+    def rate(kind, limb):
+        if (kind, limb) not in rate_cache:
+            rate_cache[(kind, limb)] = ctx.measure_rate(kind, limb)
+        return rate_cache[(kind, limb)]
+    mode = [2 if qi < (1 << 58) else 1 if qi < (1 << 61) else 0 for qi in q]
+    fwd_kind = {0: he.RATE_BUTTERFLY_MODE0, 1: he.RATE_BUTTERFLY_MODE1, 2: he.RATE_BUTTERFLY_MODE2}
+    bf = (N // 2) * c4.log2N
+    def rescale_ideal_s(n_ct):
+        last = L - 1
+        inv = he.RATE_BUTTERFLY_INV if mode[last] else he.RATE_BUTTERFLY_MODE0
+        per_poly = bf / rate(inv, last)
+        for i in range(last):
+            per_poly += bf / rate(fwd_kind[mode[i]], i) + N / rate(he.RATE_SHOUP_EXACT, i)
+        return 2 * n_ct * per_poly
+    def mac_ideal_s(plan):
+        return sum(plan.n_terms * 2 * N / rate(he.RATE_MAC_TERM, i) for i in range(L))
+    ideal = {"mac_scalar_cfg4": mac_ideal_s(p4), "rescale_cfg4": rescale_ideal_s(p4.n_out),
+             "mac_poly_cfg5": mac_ideal_s(p5), "rescale_cfg5": rescale_ideal_s(p5.n_out)}
+    for name, r in rooflines.items():
+        r["arithmetic_ms_at_measured_rate"] = ideal[name] * 1e3
+        r["frac_of_measured_rate"] = ideal[name] * 1e3 / phase_ms[name]
+    names = ["mad32", "mac_term", "shoup_exact", "shoup_cheap", "butterfly_mode0", "butterfly_mode1",
+             "butterfly_mode2", "butterfly_inverse"]
+    measured_rates = {"unit": "G operations/s, register-resident, whole GPU",
+                      "rates": {"%s@%dbit" % (names[k], q[limb].bit_length()): v / 1e9
+                                for (k, limb), v in sorted(rate_cache.items(), reverse=True)}}
+
     result = {
         "metric": "ct-pt MAC GB/s (% HBM peak) + rescaled ciphertexts/sec at N=2^14, L=8",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -189,41 +221,11 @@ def main() -> int:
         "phase_ms": phase_ms,
         "roofline": {k: v for k, v in rooflines[dominant].items()},
         "roofline_all": list(rooflines.values()),
+        "measured_rates": measured_rates,
     }
 
-    # ---- the two plainly HBM-bound calls of the path, outside the timed step: Alg. 4 (scalar add, in
-    # place on component 0) and Alg. 8 as one multiply per output (every ciphertext read once, written once)
-    if not only:
-        def timed(fn, reps=5):
-            fn()
-            torch.cuda.synchronize()
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-            ev[0].record()
-            for i in range(reps):
-                fn()
-                ev[i + 1].record()
-            torch.cuda.synchronize()
-            return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
-        n_add = p4.n_in
-        pt_add = ctx.encode_scalar(torch.from_numpy(wl.normal_values(n_add, 0.1, 7)).to(dev), scale)
-        ms_add = timed(lambda: ctx.ct_pt_add(ct4, pt_add, he.PT_SCALAR))
-        add_bytes = n_add * L * N * 8 * 2                       # component 0 read + written
-        n_str = 1024
-        ids = np.arange(n_str, dtype=np.uint32)
-        hps = ctx.plan(n_str, n_str, n_str, np.arange(n_str + 1, dtype=np.uint32), ids, ids)
-        w_str = ctx.encode_scalar(torch.from_numpy(wl.normal_values(n_str, 0.1, 8)).to(dev), scale)
-        ws_str = torch.empty(max(hps.workspace_bytes(L, he.PT_SCALAR, 0), 256), dtype=torch.uint8, device=dev)
-        ms_str = timed(lambda: ctx.ct_pt_mac(hps, ct4[:n_str], w_str, he.PT_SCALAR, out=acc4[:n_str], workspace=ws_str))
-        str_bytes = n_str * ct_bytes * 2
-        result["hbm_bound_calls"] = {
-            "ct_pt_add_scalar": {"ms": ms_add, "GBps": add_bytes / (ms_add * 1e-3) / 1e9,
-                                 "pct_hbm_peak": 100 * add_bytes / (ms_add * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                 "bytes": add_bytes, "what": "3072 ciphertexts, component 0 read and written in place"},
-            "ct_pt_mac_one_term_per_output": {"ms": ms_str, "GBps": str_bytes / (ms_str * 1e-3) / 1e9,
-                                              "pct_hbm_peak": 100 * str_bytes / (ms_str * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                              "bytes": str_bytes, "what": "1024 ciphertexts times one scalar each: 2 GiB read, 2 GiB written"}}
-
-    # ---- the oracle on the host cores, on a bounded sample of the same workload
+    # ---- the oracle on the host cores, on a bounded sample of the same workload (before anything
+    # below touches the inputs of the timed step)
     if only:
         result["partial"] = sorted(only)
     if not args.no_cpu_baseline and not only:
@@ -261,6 +263,92 @@ def main() -> int:
             "sample": "%d of %d cfg4 outputs (%.1f s) + %d of %d cfg5 outputs (%.1f s), extrapolated linearly to "
                       "the whole step" % (len(s4), p4.n_out, t4, len(s5), p5.n_out, t5),
             "rescaled_ct_per_s": n_rescaled / cpu_step_s, "gpu_outputs_match_oracle": bool(ok)}
+    # ---- the two plainly HBM-bound calls of the path, outside the timed step: Alg. 4 (scalar add, in
+    # place on component 0) and Alg. 8 as one multiply per output (every ciphertext read once, written once)
+    if not only:
+        def timed(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            ev[0].record()
+            for i in range(reps):
+                fn()
+                ev[i + 1].record()
+            torch.cuda.synchronize()
+            return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
+        n_add = p4.n_in
+        pt_add = ctx.encode_scalar(torch.from_numpy(wl.normal_values(n_add, 0.1, 7)).to(dev), scale)
+        ms_add = timed(lambda: ctx.ct_pt_add(ct4, pt_add, he.PT_SCALAR))
+        add_bytes = n_add * L * N * 8 * 2                       # component 0 read + written
+        n_str = 1024
+        ids = np.arange(n_str, dtype=np.uint32)
+        hps = ctx.plan(n_str, n_str, n_str, np.arange(n_str + 1, dtype=np.uint32), ids, ids)
+        w_str = ctx.encode_scalar(torch.from_numpy(wl.normal_values(n_str, 0.1, 8)).to(dev), scale)
+        ws_str = torch.empty(max(hps.workspace_bytes(L, he.PT_SCALAR, 0), 256), dtype=torch.uint8, device=dev)
+        ms_str = timed(lambda: ctx.ct_pt_mac(hps, ct4[:n_str], w_str, he.PT_SCALAR, out=acc4[:n_str], workspace=ws_str))
+        str_bytes = n_str * ct_bytes * 2
+        result["hbm_bound_calls"] = {
+            "ct_pt_add_scalar": {"ms": ms_add, "GBps": add_bytes / (ms_add * 1e-3) / 1e9,
+                                 "pct_hbm_peak": 100 * add_bytes / (ms_add * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                 "bytes": add_bytes, "what": "3072 ciphertexts, component 0 read and written in place"},
+            "ct_pt_mac_one_term_per_output": {"ms": ms_str, "GBps": str_bytes / (ms_str * 1e-3) / 1e9,
+                                              "pct_hbm_peak": 100 * str_bytes / (ms_str * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                              "bytes": str_bytes, "what": "1024 ciphertexts times one scalar each: 2 GiB read, 2 GiB written"}}
+
+    # ---- every config as one fused layer call (encode, MAC + bias, one rescale per output): median of
+    # 20 after 5 warm-ups.  cfg1-3 inputs are small enough to stay in the caches between repetitions.
+    if not only and args.all_configs:
+        per = []
+        for k in (1, 2, 3, 4, 5):
+            ck = wl.config(k)
+            pk = ck.plan
+            if k in (4, 5):
+                cx, ctk = ctx, (ct4 if k == 4 else ct5)
+            else:
+                cx = he.Context(ck.log2N, ck.q, device=0)
+                ctk = wl.uniform_residues_torch((pk.n_in, 2), ck.q, ck.N, ck.seed, dev)
+            hp = hp4 if k == 4 else hp5 if k == 5 else cx.plan(pk.n_in, pk.n_out, pk.n_pt, pk.off, pk.term_ct, pk.term_pt)
+            poly = ck.pt_kind == "poly"
+            if poly:
+                ptk, wk, bk = pt5, None, None
+            else:
+                wk = w4 if k == 4 else torch.from_numpy(wl.normal_values(pk.n_pt, ck.sigma, ck.seed + 100)).to(dev)
+                bk = b4 if k == 4 else torch.from_numpy(wl.normal_values(pk.n_out, ck.sigma, ck.seed + 200)).to(dev)
+            kind = he.PT_POLY if poly else he.PT_SCALAR
+            outk = torch.empty((pk.n_out, 2, ck.L - 1, ck.N), dtype=torch.int64, device=dev)
+            wsk = torch.empty(max(hp.workspace_bytes(ck.L, kind, he.RESCALE), 256), dtype=torch.uint8, device=dev)
+            sc = 2.0 ** ck.log2_scale
+            def layer():
+                if poly:
+                    cx.ct_pt_mac(hp, ctk, ptk, kind, flags=he.RESCALE, out=outk, workspace=wsk)
+                else:
+                    cx.ct_pt_mac(hp, ctk, cx.encode_scalar(wk, sc), kind, bias=cx.encode_scalar(bk, sc), flags=he.RESCALE,
+                                 out=outk, workspace=wsk)
+            for _ in range(5):
+                layer()
+            torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(21)]
+            ev[0].record()
+            for i in range(20):
+                layer()
+                ev[i + 1].record()
+            torch.cuda.synchronize()
+            ms = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(20)]))
+            ctb = 2 * ck.L * ck.N * 8
+            outb = 2 * (ck.L - 1) * ck.N * 8
+            ptb = pk.n_pt * ck.L * ck.N * 8 if poly else (pk.n_pt + pk.n_out) * 8 * ck.L
+            b_min = pk.n_in * ctb + pk.n_out * outb + ptb
+            per.append({"config": k, "N": ck.N, "L": ck.L, "outputs": pk.n_out, "mac_terms": pk.n_terms,
+                        "ms": ms, "G_mac_residue_terms_per_s": pk.n_terms * 2 * ck.L * ck.N / (ms * 1e-3) / 1e9,
+                        "rescaled_ct_per_s": pk.n_out / (ms * 1e-3),
+                        "min_bytes_GBps": b_min / (ms * 1e-3) / 1e9,
+                        "per_mac_streamed_GBps": pk.n_terms * ctb / (ms * 1e-3) / 1e9})
+            del outk, wsk
+        result["per_config"] = {"what": "encode + MAC + bias + rescale as one he_ct_pt_mac(HE_RESCALE) call per layer; "
+                                        "min_bytes = inputs once + outputs once + plaintexts; per_mac_streamed = what one "
+                                        "ciphertext read per multiply (the per-call formulation of Alg. 7/8) would move, "
+                                        "which reuse lets exceed the HBM peak", "configs": per}
+
     print(json.dumps(result))
     return 0
 

@@ -154,6 +154,26 @@ uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotie
 /* The accumulator the MAC kernels use, run on the host: sum of x[t]*w[t] (n terms) mod q. */
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q);
 
+/*
+ * Measurement aid, not part of the compute path: the rate (operations per second, whole GPU) at
+ * which this device runs one of the library's arithmetic primitives on register-resident data, with
+ * the constants of limb `limb` of the context.  These are the integer-ALU ceilings against which
+ * the MAC and NTT kernels' throughputs are quoted.  Allocates a small device buffer, runs on the
+ * default stream and synchronises.  iters in [1, 2^20] loop iterations per thread (4096 gives a
+ * run of a few milliseconds).
+ */
+enum {
+    HE_RATE_MAD32 = 0,           /* one 32x32+64-bit multiply-add */
+    HE_RATE_MAC_TERM = 1,        /* the four multiply-adds of one MAC term (folds and reduction excluded) */
+    HE_RATE_SHOUP_EXACT = 2,     /* Shoup product, exact quotient estimate (result below 2q) */
+    HE_RATE_SHOUP_CHEAP = 3,     /* Shoup product, cheap quotient estimate (result below 4q) */
+    HE_RATE_BUTTERFLY_MODE0 = 4, /* forward butterfly for moduli up to 2^62 */
+    HE_RATE_BUTTERFLY_MODE1 = 5, /* forward butterfly for moduli below 2^61 */
+    HE_RATE_BUTTERFLY_MODE2 = 6, /* forward butterfly for moduli below 2^58 */
+    HE_RATE_BUTTERFLY_INV = 7    /* inverse butterfly for moduli below 2^61 */
+};
+int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s);
+
 #ifdef __cplusplus
 }
 #endif

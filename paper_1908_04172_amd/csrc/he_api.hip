@@ -561,6 +561,18 @@ uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotie
     return cheap_quotient ? shoup_mul_lazy4(y, w, h_shoup(w, q), q) : shoup_mul_lazy(y, w, h_shoup(w, q), q);
 }
 
+int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s) {
+    if (!ctx || !ops_per_s || limb >= ctx->L || iters == 0 || iters > (1u << 20)) return HE_ERR_ARG;
+    if (kind < HE_RATE_MAD32 || kind > HE_RATE_BUTTERFLY_INV) return HE_ERR_ARG;
+    // the lazier butterflies assume the room their modes are chosen by
+    const u32 mode = ctx->limbs.c[limb].ntt_mode;
+    if ((kind == HE_RATE_BUTTERFLY_MODE2 && mode < 2) || ((kind == HE_RATE_BUTTERFLY_MODE1 || kind == HE_RATE_BUTTERFLY_INV) && mode < 1))
+        return HE_ERR_MODULUS;
+    int rc = need_device(ctx);
+    if (rc != HE_OK) return rc;
+    return launch_rate(ctx, kind, limb, iters, ops_per_s);
+}
+
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q) {
     const LimbConst c = host_const(q);
     MacAcc a;

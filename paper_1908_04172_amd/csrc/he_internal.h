@@ -76,3 +76,4 @@ int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, co
                const u64* bias, u64* out, u64* wtab, hipStream_t s);
 int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s);
 int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s);
+int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s);

@@ -68,68 +68,11 @@ __device__ __forceinline__ void regroup(u64 (&a)[16], u64* lds, u32 tid) {
     for (u32 e = 0; e < 16; e++) a[e] = lds[to ^ lds_slot(reg_index<LOGN, PTO>(0, e))];
 }
 
-struct Twiddle {
-    u64 w, w_shoup;
-};
-
 template <bool UNIFORM>
 __device__ __forceinline__ Twiddle load_twiddle(const u64* tw, u32 k) {
     if constexpr (UNIFORM) k = __builtin_amdgcn_readfirstlane(k);
     const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(tw + 2 * (size_t)k);
     return Twiddle{v.x, v.y};
-}
-
-// How lazily the butterflies reduce depends on the room the modulus leaves in 64 bits
-// (LimbConst::ntt_mode):
-//   mode 0, q < 2^62: Harvey's butterflies as published: forward values in [0, 4q), inverse in [0, 2q),
-//           Shoup products with the exact quotient estimate (result below 2q).
-//   mode 1, q < 2^61: the Shoup products take the cheap quotient estimate (result below 4q); forward
-//           values in [0, 8q), inverse in [0, 4q), one conditional subtraction of 4q per butterfly.
-//   mode 2, q < 2^58: forward butterflies without any conditional subtraction: both outputs exceed
-//           the larger input by less than 4q, so canonical inputs stay below (1 + 4*log2N)*q <= 57q
-//           through all stages.  (Inverse butterflies add their inputs, which would double the
-//           bound per stage, so the inverse transform runs as in mode 1.)
-
-// x - m if that is not negative, else x, for x < 2m <= 2^63: the difference wraps past 2^63 exactly
-// when x < m.  neg_m = 2^64 - m.
-__device__ __forceinline__ u64 sub_if_ge(u64 x, u64 neg_m) {
-    const u64 t = x + neg_m;
-    return (int32_t)(t >> 32) < 0 ? x : t;
-}
-
-// Forward butterfly: (X, Y) -> (X + W*Y, X - W*Y).
-template <int MODE>
-__device__ __forceinline__ void bfly_fwd(u64& x, u64& y, Twiddle t, const LimbConst& c) {
-    if constexpr (MODE == 0) {
-        const u64 u = sub_if_ge(x, c.neg_two_q);
-        const u64 v = shoup_mul_lazy(y, t.w, t.w_shoup, c.q);
-        x = u + v;
-        y = u + c.two_q - v;
-    } else if constexpr (MODE == 1) {
-        const u64 u = sub_if_ge(x, c.neg_four_q);
-        const u64 v = shoup_mul_lazy4(y, t.w, t.w_shoup, c.q);
-        x = u + v;
-        y = u + c.four_q - v;
-    } else {
-        const u64 v = shoup_mul_lazy4(y, t.w, t.w_shoup, c.q);
-        y = x + c.four_q - v;
-        x = x + v;
-    }
-}
-
-// Inverse butterfly: (X, Y) -> (X + Y, (X - Y) * W).
-template <int MODE>
-__device__ __forceinline__ void bfly_inv(u64& x, u64& y, Twiddle t, const LimbConst& c) {
-    const u64 s = x + y;
-    if constexpr (MODE == 0) {
-        const u64 d = x + c.two_q - y;
-        x = sub_if_ge(s, c.neg_two_q);
-        y = shoup_mul_lazy(d, t.w, t.w_shoup, c.q);
-    } else {
-        const u64 d = x + c.four_q - y;
-        x = sub_if_ge(s, c.neg_four_q);
-        y = shoup_mul_lazy4(d, t.w, t.w_shoup, c.q);
-    }
 }
 
 // Shape of pass P: its stages, and where the twiddle of (stage k, register e) sits among the

@@ -13,6 +13,8 @@ from typing import Optional, Sequence
 
 import numpy as np
 
+RATE_MAD32, RATE_MAC_TERM, RATE_SHOUP_EXACT, RATE_SHOUP_CHEAP = 0, 1, 2, 3
+RATE_BUTTERFLY_MODE0, RATE_BUTTERFLY_MODE1, RATE_BUTTERFLY_MODE2, RATE_BUTTERFLY_INV = 4, 5, 6, 7
 PT_SCALAR = 0
 PT_POLY = 1
 RESCALE = 1
@@ -24,7 +26,7 @@ EXPORTS = [
     "he_strerror", "he_ctx_create", "he_ctx_destroy", "he_ctx_info", "he_encode_scalar", "he_encode_scalar_host",
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
-    "he_host_mac_accumulate",
+    "he_host_mac_accumulate", "he_measure_rate",
 ]
 
 _lib = None
@@ -65,6 +67,7 @@ def lib():
         "he_host_reduce128": (u64, [u64, u64, u64]),
         "he_host_shoup_mulmod": (u64, [u64, u64, u64]),
         "he_host_shoup_lazy": (u64, [u64, u64, u64, ctypes.c_int]),
+        "he_measure_rate": (i32, [vp, i32, u32, u32, ctypes.POINTER(ctypes.c_double)]),
         "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
     }
     for name, (res, args) in sigs.items():
@@ -130,6 +133,12 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def measure_rate(self, kind: int, limb: int = 0, iters: int = 4096) -> float:
+        """Operations per second of one arithmetic primitive on register-resident data (he_measure_rate)."""
+        r = ctypes.c_double()
+        _check(lib().he_measure_rate(self._h, kind, limb, iters, ctypes.byref(r)), "he_measure_rate")
+        return float(r.value)
 
     # -- Alg. 2
     def encode_scalar_host(self, values, scale: float, limbs: Optional[int] = None) -> np.ndarray:

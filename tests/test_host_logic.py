@@ -133,3 +133,10 @@ def test_device_calls_fail_loudly_on_a_host_only_context():
     assert he.lib().he_rescale(ctx._h, 2, dummy.ctypes.data, dummy.ctypes.data, 1, None) == -5
     assert he.lib().he_rescale(ctx._h, 1, dummy.ctypes.data, dummy.ctypes.data, 1, None) == -3
     assert he.lib().he_ntt_fwd(ctx._h, 3, dummy.ctypes.data, 1, None) == -3
+    with pytest.raises(he.HeError) as e:
+        ctx.measure_rate(he.RATE_MAD32)
+    assert e.value.status == -5
+    for bad in (dict(kind=99), dict(kind=0, limb=c.L), dict(kind=0, iters=0), dict(kind=0, iters=(1 << 20) + 1)):
+        with pytest.raises(he.HeError) as e:
+            ctx.measure_rate(**bad)
+        assert e.value.status == -1
