@@ -22,9 +22,11 @@ struct Geo {
     static constexpr int REM = LOGN - 4 * (NPASS - 1);  // stages of the last pass, 1..4
 };
 
-// Index of register e of thread tid while pass P is being computed.
+// Index of register e of thread tid while pass P is being computed.  In the last pass the registers
+// own the lowest REM index bits (the stages left) and, to fill 16 registers, the 4-REM bits just above
+// the six bits that the lane number owns, so that a wavefront holds one aligned block of 1024.
 template <int LOGN, int P>
-__device__ __forceinline__ u32 reg_index(u32 tid, u32 e) {
+__host__ __device__ constexpr u32 reg_index(u32 tid, u32 e) {
     using G = Geo<LOGN>;
     if constexpr (P < G::NPASS - 1) {
         constexpr int low = LOGN - 4 * (P + 1);
@@ -34,13 +36,25 @@ __device__ __forceinline__ u32 reg_index(u32 tid, u32 e) {
         return (tid << 4) | e;
     } else {
         u32 e_hi = e >> G::REM, e_lo = e & ((1u << G::REM) - 1);
-        return (e_hi << (LOGN - (4 - G::REM))) | (tid << G::REM) | e_lo;
+        u32 wave = tid >> 6, lane = tid & 63u;
+        return (wave << 10) | (e_hi << (G::REM + 6)) | (lane << G::REM) | e_lo;
     }
 }
 
+// True when, in pass P, every wavefront (64 consecutive threads) holds exactly the aligned block of
+// 1024 indices with its own number: a regrouping between two such passes moves data only within
+// wavefronts.  Checked over all threads and registers at compile time.
+template <int LOGN, int P>
+constexpr bool wave_holds_own_block() {
+    for (u32 tid = 0; tid < (u32)Geo<LOGN>::T; tid++)
+        for (u32 e = 0; e < 16; e++)
+            if ((reg_index<LOGN, P>(tid, e) >> 10) != (tid >> 6)) return false;
+    return true;
+}
+
 // LDS placement: XOR the low index bits with higher ones so that the strided access patterns of
-// the regrouping steps spread over the banks.  A bijection on [0, N) for N >= 1024.
-__device__ __forceinline__ u32 lds_slot(u32 idx) {
+// the regrouping steps spread over the banks.  A bijection on every aligned block of 1024 indices.
+__host__ __device__ constexpr u32 lds_slot(u32 idx) {
     return idx ^ (((idx >> 6) & 0xFu) << 2) ^ ((idx >> 5) & 3u);
 }
 
@@ -49,8 +63,14 @@ __device__ __forceinline__ u32 lds_slot(u32 idx) {
 // twiddles of the next pass are deliberately in flight across the regrouping.)
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// The same for data that stays within one wavefront: the LDS serves a wave's operations in the order
+// they were issued, so the wave only has to keep that order (and nothing may be moved across by the
+// compiler); other waves are not waited for and run ahead or behind freely.
+__device__ __forceinline__ void lds_wave_order() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 template <int LOGN, int PFROM, int PTO>
 __device__ __forceinline__ void regroup(u64 (&a)[16], u64* lds, u32 tid) {
+    constexpr bool WAVE_LOCAL = wave_holds_own_block<LOGN, PFROM>() && wave_holds_own_block<LOGN, PTO>();
     // reg_index(tid, e) = reg_index(tid, 0) ^ reg_index(0, e) (disjoint bits) and lds_slot is linear
     // over XOR, so each address is one XOR of a per-thread base with a compile-time constant
     // The two bases are derived from copies of the thread index that the optimizer cannot relate to
@@ -60,10 +80,12 @@ __device__ __forceinline__ void regroup(u64 (&a)[16], u64* lds, u32 tid) {
     asm("; regroup %1 write" : "+v"(tid_w) : "n"(PFROM * 16 + PTO));
     asm("; regroup %1 read" : "+v"(tid_r) : "n"(PFROM * 16 + PTO));
     const u32 from = lds_slot(reg_index<LOGN, PFROM>(tid_w, 0)), to = lds_slot(reg_index<LOGN, PTO>(tid_r, 0));
-    lds_barrier();  // earlier readers of the buffer are done
+    // earlier readers of the slots written here are done: all waves, or (wave-local) this wave only,
+    // since its block of slots is then touched by no other wave until the next workgroup-wide regrouping
+    if constexpr (WAVE_LOCAL) lds_wave_order(); else lds_barrier();
 #pragma unroll
     for (u32 e = 0; e < 16; e++) lds[from ^ lds_slot(reg_index<LOGN, PFROM>(0, e))] = a[e];
-    lds_barrier();
+    if constexpr (WAVE_LOCAL) lds_wave_order(); else lds_barrier();
 #pragma unroll
     for (u32 e = 0; e < 16; e++) a[e] = lds[to ^ lds_slot(reg_index<LOGN, PTO>(0, e))];
 }
