@@ -26,6 +26,8 @@ _lib = None
 
 _u64p = ctypes.POINTER(ctypes.c_uint64)
 _u32p = ctypes.POINTER(ctypes.c_uint32)
+_dblp = ctypes.POINTER(ctypes.c_double)
+_i64p = ctypes.POINTER(ctypes.c_int64)
 
 
 def build(force: bool = False) -> str:
@@ -55,6 +57,9 @@ def _load():
         "orc_ntt_fwd_rows": (None, [_u64p, u64, u32, u64, _u64p, _u64p]),
         "orc_ntt_inv_rows": (None, [_u64p, u64, u32, u64, _u64p, _u64p]),
         "orc_encode_scalar": (i32, [dbl, dbl, _u64p, u32, _u64p]),
+        "orc_encode_vector_coeffs": (i32, [_dblp, u64, u64, dbl, _i64p]),
+        "orc_encode_vector": (i32, [_dblp, u64, u64, dbl, _u64p, _u64p, u32, _u64p]),
+        "orc_decode_vector": (None, [_dblp, u64, u64, dbl, _dblp]),
         "orc_add": (None, [_u64p, u64, u32, u64, _u64p, _u64p, i32]),
         "orc_mac": (None, [u64, u32, _u64p, _u64p, _u32p, _u32p, _u32p, u32, _u64p, i32, _u64p, _u64p]),
         "orc_divide_round": (None, [_u64p, _u64p, u64, u32, u64, _u64p]),
@@ -177,6 +182,48 @@ def encode_scalars(values, scale: float, q) -> np.ndarray:
     values = np.asarray(values, dtype=np.float64).ravel()
     return np.stack([encode_scalar(v, scale, q) for v in values]) if values.size else \
         np.empty((0, len(q)), dtype=np.uint64)
+
+
+# ----------------------------------------------------------------------------- Alg. 1
+
+def _slots(z, N: int) -> np.ndarray:
+    z = np.ascontiguousarray(np.atleast_2d(np.asarray(z, dtype=np.complex128)))
+    assert z.shape[1] == N // 2, "N/2 complex slots per vector"
+    return z
+
+
+def encode_vector_coeffs(z, scale: float, N: int) -> np.ndarray:
+    """Alg. 1 before the modular reduction: int64 [n][N] coefficients round(scale * sigma^-1(z))."""
+    z = _slots(z, N)
+    out = np.empty((z.shape[0], N), dtype=np.int64)
+    rc = _load().orc_encode_vector_coeffs(z.view(np.float64).ctypes.data_as(_dblp), z.shape[0], N, float(scale),
+                                          out.ctypes.data_as(_i64p))
+    if rc != 0:
+        raise ValueError("a coefficient is not finite or not below 2^62")
+    return out
+
+
+def encode_vector(z, scale: float, q, psi, N: int) -> np.ndarray:
+    """Alg. 1: [n][N/2] complex slots -> uint64 [n][limbs][N] residues in NTT form."""
+    z = _slots(z, N)
+    q, psi = _a64(q), _a64(psi)
+    out = np.empty((z.shape[0], q.size, N), dtype=np.uint64)
+    rc = _load().orc_encode_vector(z.view(np.float64).ctypes.data_as(_dblp), z.shape[0], N, float(scale), _p64(q),
+                                   _p64(psi), q.size, _p64(out))
+    if rc != 0:
+        raise ValueError("a coefficient is not finite or not below 2^62")
+    return out
+
+
+def decode_vector(coeffs, scale: float, N: int) -> np.ndarray:
+    """Values of the polynomials with the given signed coefficients ([n][N], any numeric type whose
+    entries are exactly representable as doubles) at the slot roots, over the scale: complex [n][N/2]."""
+    m = np.ascontiguousarray(np.atleast_2d(np.asarray(coeffs, dtype=np.float64)))
+    assert m.shape[1] == N
+    out = np.empty((m.shape[0], N // 2), dtype=np.complex128)
+    _load().orc_decode_vector(m.ctypes.data_as(_dblp), m.shape[0], N, float(scale),
+                              out.view(np.float64).ctypes.data_as(_dblp))
+    return out
 
 
 # ----------------------------------------------------------------------------- Alg. 3/4, 7/8

@@ -10,6 +10,11 @@
  *
  * What each function follows:
  *   orc_encode_scalar  Alg. 2 (scalar encoding), Sec. "Scalar Encoding"
+ *   orc_encode_vector  Alg. 1 (general encoding), read as the canonical embedding: the integer
+ *                      polynomial whose values at the roots exp(i*pi*(2k+1)/N), k < N/2, are the
+ *                      scaled slots (and their conjugates at the conjugate roots), then the
+ *                      residues and the NTT.  Complex slots are the paper's complex packing.
+ *   orc_decode_vector  the inverse map: values of the polynomial at those roots, over the scale
  *   orc_add            Alg. 3 (vector plaintext) / Alg. 4 (scalar plaintext)
  *   orc_mac            Alg. 7 (64-bit multiply) / Alg. 8 (scalar multiply), summed over the
  *                      inner dimension of a Dot/Convolution (Sec. "Lazy Rescaling")
@@ -248,6 +253,97 @@ int orc_encode_scalar(double value, double scale, const u64* q, uint32_t limbs, 
         out[i] = (negative && r != 0) ? q[i] - r : r;
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------ Alg. 1: general encoding */
+
+/* cos and sin of pi*r/N for r = 0 .. 2N-1, in long double: every angle the embedding needs is
+ * one of these after reducing an integer product mod 2N. */
+static void root_table(u64 N, long double* c, long double* s) {
+    const long double pi = 3.14159265358979323846264338327950288L;
+    for (u64 r = 0; r < 2 * N; r++) {
+        c[r] = cosl(pi * (long double)r / (long double)N);
+        s[r] = sinl(pi * (long double)r / (long double)N);
+    }
+}
+
+/* Coefficients of Alg. 1 before the modular reduction, for n_vec vectors of N/2 complex slots
+ * (slots[v][k][0] real part, [1] imaginary part):
+ *     m_j = round( scale * (2/N) * sum_{k < N/2} Re( z_k * r_k^-j ) ),   r_k = exp(i*pi*(2k+1)/N),
+ * i.e. the real polynomial with m(r_k) = scale*z_k and m(conj r_k) = scale*conj(z_k), rounded
+ * coefficient-wise (halves away from zero).  The sum is taken term by term in long double; the
+ * result must stay below 2^62 in magnitude (returns -1 otherwise, or for a non-finite input). */
+int orc_encode_vector_coeffs(const double* slots, u64 n_vec, u64 N, double scale, int64_t* coeffs) {
+    long double* c = (long double*)malloc(2 * N * sizeof(long double));
+    long double* s = (long double*)malloc(2 * N * sizeof(long double));
+    root_table(N, c, s);
+    int bad = 0;
+    for (u64 v = 0; v < n_vec; v++) {
+        const double* z = slots + v * N;  /* N/2 complex numbers */
+#pragma omp parallel for schedule(static)
+        for (u64 j = 0; j < N; j++) {
+            long double acc = 0.0L;
+            for (u64 k = 0; k < N / 2; k++) {
+                u64 r = ((2 * k + 1) * j) % (2 * N);            /* r_k^-j = cos(pi r/N) - i sin(pi r/N) */
+                acc += (long double)z[2 * k] * c[r] + (long double)z[2 * k + 1] * s[r];
+            }
+            long double m = (long double)scale * (2.0L * acc / (long double)N);
+            if (!(fabsl(m) < 4611686018427387904.0L)) { /* 2^62; also catches NaN */
+#pragma omp atomic write
+                bad = 1;
+                coeffs[v * N + j] = 0;
+            } else {
+                coeffs[v * N + j] = (int64_t)roundl(m);         /* halves away from zero */
+            }
+        }
+    }
+    free(c);
+    free(s);
+    return bad ? -1 : 0;
+}
+
+/* Alg. 1 complete: coefficients as above, residues [m_j]_{q_i}, forward NTT of every limb.
+ * out: [n_vec][limbs][N]. */
+int orc_encode_vector(const double* slots, u64 n_vec, u64 N, double scale, const u64* q, const u64* psi,
+                      uint32_t limbs, u64* out) {
+    int64_t* m = (int64_t*)malloc(n_vec * N * sizeof(int64_t));
+    int rc = orc_encode_vector_coeffs(slots, n_vec, N, scale, m);
+    if (rc == 0) {
+        for (u64 v = 0; v < n_vec; v++)
+            for (uint32_t i = 0; i < limbs; i++)
+                for (u64 j = 0; j < N; j++) {
+                    int64_t x = m[v * N + j];
+                    u64 r = (u64)(x < 0 ? -x : x) % q[i];
+                    out[(v * limbs + i) * N + j] = (x < 0 && r != 0) ? q[i] - r : r;
+                }
+        orc_ntt_fwd_rows(out, n_vec, limbs, N, q, psi);
+    }
+    free(m);
+    return rc;
+}
+
+/* The inverse map on signed integer coefficients (given as doubles: the caller lifts residues to
+ * the centred representative first): z_k = m(r_k) / scale for k < N/2, term by term in long double.
+ * out[v][k][0..1] = real and imaginary part. */
+void orc_decode_vector(const double* coeffs, u64 n_vec, u64 N, double scale, double* out) {
+    long double* c = (long double*)malloc(2 * N * sizeof(long double));
+    long double* s = (long double*)malloc(2 * N * sizeof(long double));
+    root_table(N, c, s);
+    for (u64 v = 0; v < n_vec; v++) {
+#pragma omp parallel for schedule(static)
+        for (u64 k = 0; k < N / 2; k++) {
+            long double re = 0.0L, im = 0.0L;
+            for (u64 j = 0; j < N; j++) {
+                u64 r = ((2 * k + 1) * j) % (2 * N);
+                re += (long double)coeffs[v * N + j] * c[r];
+                im += (long double)coeffs[v * N + j] * s[r];
+            }
+            out[(v * N / 2 + k) * 2] = (double)(re / (long double)scale);
+            out[(v * N / 2 + k) * 2 + 1] = (double)(im / (long double)scale);
+        }
+    }
+    free(c);
+    free(s);
 }
 
 /* ------------------------------------------------------------------ Alg. 3 / 4: ct + pt */
