@@ -82,6 +82,24 @@ int he_encode_scalar_host(const he_ctx* ctx, const double* values, size_t n, dou
                           uint32_t limbs, uint64_t* out);
 
 /*
+ * General encoding, Alg. 1 (Sec. "Scalar Encoding", "General CKKS Encoding"), read as the canonical
+ * embedding: vector v of N/2 complex slots -> the polynomial with real integer coefficients
+ *     m_j = round( scale * (2/N) * sum_{k < N/2} Re( z_k * r_k^-j ) ),   r_k = exp(i*pi*(2k+1)/N),
+ * i.e. m(r_k) = scale*z_k and m(conj r_k) = scale*conj(z_k) up to the rounding (halves away from
+ * zero), then the residues [m_j]_{q_i} and the forward NTT of each limb: a plaintext for
+ * HE_PT_POLY.  Slots with a non-zero imaginary part are the paper's complex packing
+ * (Sec. "Complex packing"); N/2 equal real slots give N equal residues per limb, the value Alg. 2
+ * stores once.
+ *   slots: dev [n][N/2][2] double (real, imaginary), 16-byte aligned   ->   out: dev [n][limbs][N].
+ * The interpolation runs in IEEE double arithmetic (an FFT of N/2 points), so a coefficient of
+ * magnitude M carries an error of up to about M * 2^-53 * 4 * log2(N) before the rounding: the
+ * integers agree with an exact evaluation to within 1 + that bound.  scale must be positive and
+ * finite; non-finite slots give unspecified residues.  Two kernels on `stream`.
+ */
+int he_encode_vector(he_ctx* ctx, const double* slots, size_t n, double scale, uint32_t limbs,
+                     uint64_t* out, void* stream);
+
+/*
  * A MAC plan (Sec. "Lazy Rescaling": an FC or Convolution output is a sum over the inner
  * dimension / window):  out[o] = sum over t in [off[o], off[o+1]) of
  * ct_in[term_ct[t]] * pt[term_pt[t]].  All three arrays are host memory and are copied;

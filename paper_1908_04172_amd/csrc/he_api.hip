@@ -159,43 +159,6 @@ int upload(T** dst, const T* src, size_t n) {
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
-// ------------------------------------------------------------------------------------------------
-// Alg. 2 on one value (shared by the kernel and the host entry point)
-
-HE_HD bool encode_one(double value, double scale, const LimbConst* lc, u32 limbs, u64* out) {
-    const double v = value * scale;
-    const double mag = v < 0 ? -v : v;
-    if (!(mag <= 1.7976931348623157e308)) {  // NaN or infinity
-        for (u32 i = 0; i < limbs; ++i) out[i] = ~0ull;
-        return false;
-    }
-    const bool negative = v < 0;
-    for (u32 i = 0; i < limbs; ++i) {
-        const LimbConst& c = lc[i];
-        u64 r;
-        if (mag < 9223372036854775808.0) {
-            const double whole = trunc(mag);
-            u64 z = (u64)whole;
-            if (mag - whole >= 0.5) z += 1;  // mag - whole is exact; halves go away from zero
-            r = reduce64(z, c);
-        } else {
-            // mag = m * 2^e exactly, m a 53-bit integer, e >= 11
-            u64 bits;
-            __builtin_memcpy(&bits, &mag, sizeof bits);
-            const u64 m = (bits & 0xFFFFFFFFFFFFFull) | (1ull << 52);
-            u32 e = (u32)(bits >> 52) - 1075u;
-            u64 pow2 = 1, base = 2;
-            for (; e; e >>= 1) {
-                if (e & 1) pow2 = mul_mod(pow2, base, c);
-                base = mul_mod(base, base, c);
-            }
-            r = mul_mod(reduce64(m, c), pow2, c);
-        }
-        out[i] = (negative && r) ? c.q - r : r;
-    }
-    return true;
-}
-
 __global__ void __launch_bounds__(256) encode_kernel(LimbTable lt, const double* values, size_t n, double scale, u32 limbs,
                                                      u64* out) {
     const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -338,7 +301,19 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
                 pwi = h_mulmod(pwi, psi_inv, q);
             }
         }
-        if (upload(&ctx->tw_fwd, fwd.data(), fwd.size()) != HE_OK || upload(&ctx->tw_inv, inv.data(), inv.size()) != HE_OK) {
+        // tables of the general encoder: e^(-2 pi i k / (N/2)) for k < N/4, and e^(-i pi j / N) for j < N/2
+        std::vector<double> fft_tw((size_t)N / 2), twist((size_t)N);
+        const long double pi = 3.14159265358979323846264338327950288L;
+        for (u32 k = 0; k < N / 4; ++k) {
+            fft_tw[2 * k] = (double)cosl(4.0L * pi * k / N);
+            fft_tw[2 * k + 1] = (double)-sinl(4.0L * pi * k / N);
+        }
+        for (u32 j = 0; j < N / 2; ++j) {
+            twist[2 * j] = (double)cosl(pi * j / N);
+            twist[2 * j + 1] = (double)-sinl(pi * j / N);
+        }
+        if (upload(&ctx->tw_fwd, fwd.data(), fwd.size()) != HE_OK || upload(&ctx->tw_inv, inv.data(), inv.size()) != HE_OK ||
+            upload(&ctx->fft_tw, fft_tw.data(), fft_tw.size()) != HE_OK || upload(&ctx->twist, twist.data(), twist.size()) != HE_OK) {
             he_ctx_destroy(ctx);
             return HE_ERR_DEVICE;
         }
@@ -352,6 +327,8 @@ int he_ctx_destroy(he_ctx* ctx) {
     if (ctx->device >= 0 && hipSetDevice(ctx->device) == hipSuccess) {
         if (ctx->tw_fwd) (void)hipFree(ctx->tw_fwd);
         if (ctx->tw_inv) (void)hipFree(ctx->tw_inv);
+        if (ctx->fft_tw) (void)hipFree(ctx->fft_tw);
+        if (ctx->twist) (void)hipFree(ctx->twist);
     }
     if (ctx->device >= 0) (void)hipGetLastError();  // a failure here must not surface in the caller's next HIP call
     delete ctx;
@@ -382,6 +359,19 @@ int he_encode_scalar(he_ctx* ctx, const double* values, size_t n, double scale, 
                        limbs, out);
     HE_HIP(hipGetLastError());
     return HE_OK;
+}
+
+int he_encode_vector(he_ctx* ctx, const double* slots, size_t n, double scale, uint32_t limbs, uint64_t* out,
+                     void* stream) {
+    int rc = check_level(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (!(scale > 0.0) || !(scale <= 1.7976931348623157e308)) return HE_ERR_ARG;
+    if (n == 0) return HE_OK;
+    if (!slots || !out) return HE_ERR_ARG;
+    if (n > 0x7FFFFFFFull / limbs) return HE_ERR_RANGE;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    if ((rc = launch_encode_vector(ctx, limbs, slots, (u32)n, scale, out, (hipStream_t)stream)) != HE_OK) return rc;
+    return launch_ntt(ctx, limbs, out, (u32)n, false, (hipStream_t)stream);
 }
 
 int he_encode_scalar_host(const he_ctx* ctx, const double* values, size_t n, double scale, uint32_t limbs,

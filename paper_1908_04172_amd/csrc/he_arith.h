@@ -125,6 +125,45 @@ HE_HD u64 shoup_mul(u64 y, u64 w, u64 w_shoup, u64 q) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Alg. 2 on one value: [round(value * scale)]_{q_i} for the first `limbs` limbs (shared by the
+// scalar encoder's kernel and host entry point and by the general encoder, which passes its
+// already scaled coefficients with scale 1).  False (and all-ones residues) for a non-finite product.
+
+HE_HD bool encode_one(double value, double scale, const LimbConst* lc, u32 limbs, u64* out) {
+    const double v = value * scale;
+    const double mag = v < 0 ? -v : v;
+    if (!(mag <= 1.7976931348623157e308)) {  // NaN or infinity
+        for (u32 i = 0; i < limbs; ++i) out[i] = ~0ull;
+        return false;
+    }
+    const bool negative = v < 0;
+    for (u32 i = 0; i < limbs; ++i) {
+        const LimbConst& c = lc[i];
+        u64 r;
+        if (mag < 9223372036854775808.0) {
+            const double whole = trunc(mag);
+            u64 z = (u64)whole;
+            if (mag - whole >= 0.5) z += 1;  // mag - whole is exact; halves go away from zero
+            r = reduce64(z, c);
+        } else {
+            // mag = m * 2^e exactly, m a 53-bit integer, e >= 11
+            u64 bits;
+            __builtin_memcpy(&bits, &mag, sizeof bits);
+            const u64 m = (bits & 0xFFFFFFFFFFFFFull) | (1ull << 52);
+            u32 e = (u32)(bits >> 52) - 1075u;
+            u64 pow2 = 1, base = 2;
+            for (; e; e >>= 1) {
+                if (e & 1) pow2 = mul_mod(pow2, base, c);
+                base = mul_mod(base, base, c);
+            }
+            r = mul_mod(reduce64(m, c), pow2, c);
+        }
+        out[i] = (negative && r) ? c.q - r : r;
+    }
+    return true;
+}
+
+// ---------------------------------------------------------------------------------------------
 // MAC accumulator.  Both operands of a product are cut at bit s = LimbConst::split_bits (about half
 // the modulus width): x = xa + xb*2^s, w = wa + wb*2^s with all four pieces below 2^32, and
 //   value = lo + mid*2^s + hi*2^(2s),   lo += xa*wa,  mid += xa*wb + xb*wa,  hi += xb*wb.

@@ -35,6 +35,8 @@ struct he_ctx {
     // device tables
     u64* tw_fwd;      // [L][N][2]: (psi^brv(k), Shoup companion), k in [0, N)
     u64* tw_inv;      // [L][N][2]: (psi^-brv(k), Shoup companion)
+    double* fft_tw;   // [N/4][2]: e^(-2 pi i k / (N/2)), the twiddles of the encoder's complex FFT
+    double* twist;    // [N/2][2]: e^(-i pi j / N), the twist that follows it
 };
 
 // One group of outputs that read the same ciphertexts in the same order.
@@ -77,3 +79,4 @@ int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, co
 int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s);
 int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s);
 int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s);
+int launch_encode_vector(he_ctx* ctx, u32 limbs, const double* slots, u32 n, double scale, u64* out, hipStream_t s);

@@ -24,6 +24,7 @@ LIB_PATH = os.path.join(_HERE, "libhe_mi355x.so")
 
 EXPORTS = [
     "he_strerror", "he_ctx_create", "he_ctx_destroy", "he_ctx_info", "he_encode_scalar", "he_encode_scalar_host",
+    "he_encode_vector",
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_measure_rate",
@@ -55,6 +56,7 @@ def lib():
         "he_ctx_info": (i32, [vp, vp, vp, vp, vp]),
         "he_encode_scalar": (i32, [vp, vp, sz, dbl, u32, vp, vp]),
         "he_encode_scalar_host": (i32, [vp, vp, sz, dbl, u32, vp]),
+        "he_encode_vector": (i32, [vp, vp, sz, dbl, u32, vp, vp]),
         "he_plan_create": (i32, [vp, u32, u32, u32, vp, vp, vp, pp]),
         "he_plan_destroy": (i32, [vp]),
         "he_plan_workspace_bytes": (i32, [vp, u32, i32, u32, ctypes.POINTER(sz)]),
@@ -102,7 +104,7 @@ def _dev_ptr(t, name: str) -> Optional[int]:
     import torch
     if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
         raise TypeError(f"{name} must be a contiguous CUDA tensor")
-    if t.dtype not in (torch.int64, torch.float64, torch.uint8):
+    if t.dtype not in (torch.int64, torch.float64, torch.uint8, torch.complex128):
         raise TypeError(f"{name}: unexpected dtype {t.dtype}")
     return t.data_ptr()
 
@@ -158,6 +160,20 @@ class Context:
             out = torch.empty((n, limbs), dtype=torch.int64, device=values.device)
         _check(lib().he_encode_scalar(self._h, _dev_ptr(values, "values"), n, float(scale), limbs, _dev_ptr(out, "out"),
                                       _stream()), "he_encode_scalar")
+        return out
+
+    # -- Alg. 1
+    def encode_vector(self, slots, scale: float, limbs: Optional[int] = None, out=None):
+        """slots: CUDA complex128 tensor [n][N/2] -> CUDA int64 tensor [n][limbs][N], NTT form (he_encode_vector)."""
+        import torch
+        limbs = self.L if limbs is None else limbs
+        assert slots.dtype == torch.complex128 and slots.dim() == 2 and slots.shape[1] == self.N // 2
+        n = slots.shape[0]
+        if out is None:
+            out = torch.empty((n, limbs, self.N), dtype=torch.int64, device=slots.device)
+        assert tuple(out.shape) == (n, limbs, self.N)
+        _check(lib().he_encode_vector(self._h, _dev_ptr(slots, "slots"), n, float(scale), limbs, _dev_ptr(out, "out"),
+                                      _stream()), "he_encode_vector")
         return out
 
     # -- Alg. 3 / 4

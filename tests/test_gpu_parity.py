@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 import oracle
+from oracle import ckks_scaffold as sc
 from paper_1908_04172_amd import workloads as wl
 
 torch = pytest.importorskip("torch")
@@ -89,6 +90,94 @@ def test_ntt_with_several_rows_per_workgroup(he, log2N, polys):
     assert np.array_equal(host(d), oracle.ntt_fwd(a, q, ctx.psi))
     ctx.ntt_inv(d)
     assert np.array_equal(host(d), a)
+
+
+# ----------------------------------------------------------------------------- Alg. 1
+
+def crt_centered_rows(coef, q):
+    """[n][limbs][N] residues -> [n][N] integers in (-Q/2, Q/2] (Python ints in an object array)."""
+    q = [int(x) for x in q]
+    Q = 1
+    for qi in q:
+        Q *= qi
+    x = np.zeros((coef.shape[0], coef.shape[2]), dtype=object)
+    for i, qi in enumerate(q):
+        Qi = Q // qi
+        x = (x + coef[:, i, :].astype(object) * (Qi * pow(Qi % qi, -1, qi))) % Q
+    return np.where(x > Q // 2, x - Q, x)
+
+
+def gpu_encode_coeffs(ctx, z, scale, q, limbs=None):
+    """he_encode_vector, then back to signed coefficients: the oracle's INTT and a centred lift."""
+    d = ctx.encode_vector(torch.from_numpy(z).cuda(), scale, limbs=limbs)
+    ntt_form = host(d)
+    ql = q[: ntt_form.shape[1]]
+    coef = oracle.ntt_inv(ntt_form, ql, ctx.psi[: len(ql)])
+    return crt_centered_rows(coef, ql).astype(np.int64), ntt_form
+
+
+@pytest.mark.parametrize("log2N", [10, 11, 12, 13, 14])
+def test_encode_vector_matches_oracle(he, log2N):
+    """Alg. 1 on the GPU against the oracle's term-by-term long-double evaluation.  The GPU interpolates
+    with a double-precision FFT: a coefficient of magnitude M may differ by 1 + M * 2^-53 * 4 * log2(N)
+    (the bound the header states); at a small scale that is at most 1, and only where the exact value
+    falls within the FFT's error of a half-integer."""
+    N = 1 << log2N
+    q = wl.modulus_chain(MIXED[log2N], N)
+    ctx = he.Context(log2N, q)
+    rng = np.random.default_rng(400 + log2N)
+    z = rng.normal(size=(3, N // 2)) + 1j * rng.normal(size=(3, N // 2))
+    z[1] = z[1].real                                       # a real vector (real packing)
+    z[2] = 0.37                                            # equal real slots: the scalar-encoding Lemma
+    for scale in (2.0 ** 20, 2.0 ** 45):
+        want = oracle.encode_vector_coeffs(z, scale, N)
+        got, ntt_form = gpu_encode_coeffs(ctx, z, scale, q)
+        M = float(np.abs(want).max())
+        bound = 1 + M * 2.0 ** -53 * 4 * log2N
+        diff = np.abs(got - want)
+        assert diff.max() <= bound, (log2N, scale, diff.max(), bound)
+        if scale == 2.0 ** 20:
+            assert (diff != 0).mean() < 1e-3               # off by one only at near-ties
+            # the Lemma, through the GPU: N equal residues per limb, the ones Alg. 2 gives
+            assert np.array_equal(ntt_form[2], np.repeat(oracle.encode_scalar(0.37, scale, q)[:, None], N, axis=1))
+        # decoding what the GPU encoded returns the slots
+        back = oracle.decode_vector(got, scale, N)
+        assert np.abs(back - z).max() <= (0.5 + bound) * N / scale
+    # a lower level writes the first limbs only; no vectors is a no-op
+    got2, _ = gpu_encode_coeffs(ctx, z[:1], 2.0 ** 16, q, limbs=1)
+    assert np.abs(got2 - oracle.encode_vector_coeffs(z[:1], 2.0 ** 16, N)).max() <= 1
+    ctx.encode_vector(torch.zeros((0, N // 2), dtype=torch.complex128, device="cuda"), 2.0 ** 20)
+    with pytest.raises(he.HeError):
+        ctx.encode_vector(torch.zeros((1, N // 2), dtype=torch.complex128, device="cuda"), float("inf"))
+
+
+def test_complex_packed_layer_through_encrypt_compute_decrypt(he):
+    """Complex packing end to end: two real batches ride in the real and imaginary parts of the slots;
+    a dense layer with scalar weights and a complex-packed bias vector (encoded on the GPU by Alg. 1),
+    one lazy rescale, decrypt: both parts carry the float layer's result."""
+    c = wl.config(2)
+    N, q = c.N, c.q
+    ctx = he.Context(c.log2N, q)
+    scf = sc.Scaffold(N, q, ctx.psi, seed=77)
+    rng = np.random.default_rng(78)
+    K, M = 6, 3
+    xa, xb = rng.uniform(-1, 1, size=(K, N // 2)), rng.uniform(-1, 1, size=(K, N // 2))
+    w = rng.normal(0, 0.5, size=(K, M))
+    bias = rng.normal(0, 0.5, size=(M, N // 2)) + 1j * rng.normal(0, 0.5, size=(M, N // 2))
+    scale = 2.0 ** 40
+    ct = np.stack([scf.encrypt(xa[k] + 1j * xb[k], scale) for k in range(K)])
+    plan = wl.dense_plan(K, M)
+    hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+    wenc = ctx.encode_scalar(torch.from_numpy(w.reshape(-1).copy()).cuda(), scale)        # plaintext index k*M + o
+    acc = ctx.ct_pt_mac(hp, dev(ct), wenc, he.PT_SCALAR)
+    benc = ctx.encode_vector(torch.from_numpy(bias).cuda(), scale * scale)                # bias at scale^2
+    ctx.ct_pt_add(acc, benc, he.PT_POLY)
+    out = host(ctx.rescale(acc))
+    new_scale = scale * scale / q[-1]
+    for o in range(M):
+        got = scf.decrypt(out[o], new_scale)
+        want = (xa.T @ w[:, o] + bias[o].real) + 1j * (xb.T @ w[:, o] + bias[o].imag)
+        assert np.abs(got - want).max() <= 2.0 ** -10 * max(1.0, np.abs(want).max())
 
 
 # ----------------------------------------------------------------------------- Alg. 2
