@@ -298,6 +298,20 @@ def main() -> int:
                                               "pct_hbm_peak": 100 * str_bytes / (ms_str * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                               "bytes": str_bytes, "what": "1024 ciphertexts times one scalar each: 2 GiB read, 2 GiB written"}}
 
+    # ---- Alg. 1 on the GPU: the plaintext polynomials a layer like cfg5 consumes, encoded from slots
+    if not only:
+        n_vec = 1024
+        zs = torch.randn((n_vec, N // 2), dtype=torch.complex128, device=dev, generator=torch.Generator(device=dev).manual_seed(9))
+        enc_out = torch.empty((n_vec, L, N), dtype=torch.int64, device=dev)
+        ms_enc = timed(lambda: ctx.encode_vector(zs, scale, out=enc_out))
+        enc_bytes = n_vec * (N * 8 + L * N * 8)              # slots read once, residues written once
+        result["encode_vector"] = {"ms": ms_enc, "vectors_per_s": n_vec / (ms_enc * 1e-3),
+                                   "GBps": enc_bytes / (ms_enc * 1e-3) / 1e9,
+                                   "pct_hbm_peak": 100 * enc_bytes / (ms_enc * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                   "what": "%d vectors of N/2 complex slots -> [L][N] residues in NTT form (FFT kernel + "
+                                           "NTT kernel); bytes = slots once + residues once" % n_vec}
+        del zs, enc_out
+
     # ---- every config as one fused layer call (encode, MAC + bias, one rescale per output): median of
     # 20 after 5 warm-ups.  cfg1-3 inputs are small enough to stay in the caches between repetitions.
     if not only and args.all_configs:
