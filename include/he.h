@@ -171,6 +171,8 @@ uint64_t he_host_shoup_mulmod(uint64_t y, uint64_t w, uint64_t q);
 uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotient);
 /* The accumulator the MAC kernels use, run on the host: sum of x[t]*w[t] (n terms) mod q. */
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q);
+/* The same with the kernels' final step: (sum + addend) mod q for an addend below q (the bias of Alg. 4). */
+uint64_t he_host_mac_accumulate_add(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
 
 /*
  * Measurement aid, not part of the compute path: the rate (operations per second, whole GPU) at

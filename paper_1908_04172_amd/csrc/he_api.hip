@@ -564,6 +564,10 @@ int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double
 }
 
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q) {
+    return he_host_mac_accumulate_add(x, w, n, q, 0);
+}
+
+uint64_t he_host_mac_accumulate_add(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend) {
     const LimbConst c = host_const(q);
     MacAcc a;
     acc_clear(a);
@@ -578,7 +582,9 @@ uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, 
         if (r + 1 > c.reduce_every) { acc_restart(a, c); r = 0; f = 0; }
         else if (f + 1 > c.fold_every) { acc_fold(a, c); f = 0; }
     }
-    return acc_reduce(a, c);
+    // the final step as the kernels take it
+    if (c.narrow && c.ntt_mode >= 1) return acc_reduce_add(a, addend, c);
+    return add_mod(acc_reduce(a, c), addend, c.q);
 }
 
 }  // extern "C"

@@ -46,6 +46,13 @@ HE_HD u64 sub_mod(u64 a, u64 b, u64 q) {  // a, b < q
     return a >= b ? a - b : a + q - b;
 }
 
+// x - m if that is not negative, else x, for x < 2m <= 2^63: the difference wraps past 2^63 exactly
+// when x < m.  neg_m = 2^64 - m.
+HE_HD u64 sub_if_ge(u64 x, u64 neg_m) {
+    const u64 t = x + neg_m;
+    return (int32_t)(t >> 32) < 0 ? x : t;
+}
+
 // Barrett reduction of a 128-bit value z = hi:lo by a modulus below 2^62 (Alg. 5).  With
 // r = floor(2^128/q) = rh:rl, floor(z*r / 2^128) is the true quotient or one less.  The estimate
 // used here, hi*rh + floor(lo*rh / 2^64) + floor(hi*rl / 2^64), leaves out the product lo*rl and the
@@ -218,6 +225,36 @@ HE_HD u64 acc_reduce(MacAcc a, const LimbConst& c) {
     return reduce128(hi, lo, c);
 }
 
+// (accumulated value + addend) mod q for an addend below q (the bias of Alg. 4, or 0), for limbs with
+// LimbConst::narrow set and q < 2^61.  The one-word Barrett step of acc_reduce with the high product
+// x1*mu / 2^64 taken from three 32-bit products only (x1h*muh + hi32(x1l*muh) + hi32(x1h*mul)), which
+// is short of the full product by at most 2 more: the remainder lies in [0, 6q), the addend brings it
+// below 7q, and three conditional subtractions (4q, 2q, q) finish.  8q fits 64 bits and 4q is below
+// 2^63, as sub_if_ge needs.
+HE_HD u64 acc_reduce_add(MacAcc a, u64 addend, const LimbConst& c) {
+    acc_fold(a, c);
+    const u32 s2 = 2 * c.split_bits;
+    const u64 lo = a.lo | (a.mid << c.split_bits) | (a.hi << s2);
+    const u64 hi = a.hi >> (64 - s2);
+    const u64 x1 = (hi << (64 - c.mu_shift)) | (lo >> c.mu_shift);
+    const u32 xl = (u32)x1, xh = (u32)(x1 >> 32), ml = (u32)c.mu, mh = (u32)(c.mu >> 32);
+    const u64 qe = (u64)xh * mh + mul_hi32(xl, mh) + mul_hi32(xh, ml);
+    // lo - qe*q modulo 2^64, as lo + qe*(2^64 - q) on 32-bit pieces
+    const u64 nq = 0 - c.q;
+    const u32 n0 = (u32)nq, n1 = (u32)(nq >> 32), e0 = (u32)qe, e1 = (u32)(qe >> 32);
+    u64 cross = mad_wide(e0, n1, 0);
+    cross = mad_wide(e1, n0, cross);
+    const u64 low = (u64)e0 * n0 + lo;
+    u32 top = (u32)(low >> 32) + (u32)cross;
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("" : "+v"(top));
+#endif
+    u64 r = (((u64)top << 32) | (u32)low) + addend;
+    r = sub_if_ge(r, c.neg_four_q);
+    r = sub_if_ge(r, c.neg_two_q);
+    return sub_if_ge(r, 0 - c.q);
+}
+
 HE_HD void acc_restart(MacAcc& a, const LimbConst& c) {  // reduce in place and keep accumulating
     u64 r = acc_reduce(a, c);
     a.lo = r & c.split_mask;
@@ -241,13 +278,6 @@ struct Twiddle {
 //           the larger input by less than 4q, so canonical inputs stay below (1 + 4*log2N)*q <= 57q
 //           through all stages.  (Inverse butterflies add their inputs, which would double the
 //           bound per stage, so the inverse transform runs as in mode 1.)
-
-// x - m if that is not negative, else x, for x < 2m <= 2^63: the difference wraps past 2^63 exactly
-// when x < m.  neg_m = 2^64 - m.
-__device__ __forceinline__ u64 sub_if_ge(u64 x, u64 neg_m) {
-    const u64 t = x + neg_m;
-    return (int32_t)(t >> 32) < 0 ? x : t;
-}
 
 // Forward butterfly: (X, Y) -> (X + W*Y, X - W*Y).
 template <int MODE>

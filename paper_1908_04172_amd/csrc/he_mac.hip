@@ -204,14 +204,29 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
             if (t + 1 < K) housekeeping<G>(acc, f, r, c.fold_every, c.reduce_every, c);
         }
     }
+    // final reduction, bias (Alg. 4, component 0 only) and store; the cheaper reduction where it applies,
+    // chosen once per workgroup so that the per-output code has no branch
+    const bool with_bias = bias != nullptr && comp == 0;
+    if (c.narrow && c.ntt_mode >= 1) {
 #pragma unroll
-    for (int g = 0; g < G; g++) {
-        if ((u32)g < tile.count) {
-            const u32 o = tile.out0 + g;
-            u64 v = acc_reduce(acc[g], c);
-            if (bias != nullptr && comp == 0) v = add_mod(v, bias[(size_t)o * limbs + limb], c.q);
-            out[(((size_t)o * 2 + comp) * limbs + limb) * N + n] = v;
-            __builtin_amdgcn_sched_barrier(0);
+        for (int g = 0; g < G; g++) {
+            if ((u32)g < tile.count) {
+                const u32 o = tile.out0 + g;
+                const u64 b = with_bias ? bias[(size_t)o * limbs + limb] : 0;
+                out[(((size_t)o * 2 + comp) * limbs + limb) * N + n] = acc_reduce_add(acc[g], b, c);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            if ((u32)g < tile.count) {
+                const u32 o = tile.out0 + g;
+                u64 v = acc_reduce(acc[g], c);
+                if (with_bias) v = add_mod(v, bias[(size_t)o * limbs + limb], c.q);
+                out[(((size_t)o * 2 + comp) * limbs + limb) * N + n] = v;
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
 }

@@ -27,7 +27,7 @@ EXPORTS = [
     "he_encode_vector",
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
-    "he_host_mac_accumulate", "he_measure_rate",
+    "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_measure_rate",
 ]
 
 _lib = None
@@ -69,6 +69,7 @@ def lib():
         "he_host_reduce128": (u64, [u64, u64, u64]),
         "he_host_shoup_mulmod": (u64, [u64, u64, u64]),
         "he_host_shoup_lazy": (u64, [u64, u64, u64, ctypes.c_int]),
+        "he_host_mac_accumulate_add": (u64, [vp, vp, sz, u64, u64]),
         "he_measure_rate": (i32, [vp, i32, u32, u32, ctypes.POINTER(ctypes.c_double)]),
         "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
     }
@@ -284,7 +285,9 @@ def host_shoup_lazy(y: int, w: int, q: int, cheap_quotient: bool) -> int:
     return int(lib().he_host_shoup_lazy(y, w, q, int(cheap_quotient)))
 
 
-def host_mac_accumulate(x, w, q: int) -> int:
+def host_mac_accumulate(x, w, q: int, addend: int = 0) -> int:
     x, w = _np64(x), _np64(w)
     assert x.size == w.size
+    if addend:
+        return int(lib().he_host_mac_accumulate_add(x.ctypes.data, w.ctypes.data, x.size, q, addend))
     return int(lib().he_host_mac_accumulate(x.ctypes.data, w.ctypes.data, x.size, q))

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def primes():
-    return [wl.ntt_primes(b, 1 << 14, 1)[0] for b in (30, 40, 50, 60, 62)]
+    return [wl.ntt_primes(b, 1 << 14, 1)[0] for b in (30, 40, 50, 58, 60, 61, 62)]
 
 
 def test_barrett_and_shoup_equal_python_mod():
@@ -72,6 +72,9 @@ def test_mac_accumulator_fold_and_reduce_schedule():
                 w = [q - 1] * n if mode == "max" else [rnd.randrange(q) for _ in range(n)]
                 want = sum(a * b for a, b in zip(x, w)) % q
                 assert he.host_mac_accumulate(x, w, q) == want, (q, n, mode)
+                # the final step with an addend (the bias of Alg. 4), extreme and random
+                for b in (q - 1, 1, rnd.randrange(q)):
+                    assert he.host_mac_accumulate(x, w, q, b) == (want + b) % q, (q, n, mode, b)
 
 
 def test_context_validates_moduli():
