@@ -126,7 +126,7 @@ int he_plan_workspace_bytes(const he_plan* plan, uint32_t limbs, int pt_kind, ui
  *   flags = 0:          ct_out dev [n_out][2][limbs][N]
  *   flags = HE_RESCALE: ct_out dev [n_out][2][limbs-1][N]; each output is rescaled exactly once,
  *                       after its MACs and bias (lazy rescaling); needs limbs >= 2.
- * ct_in dev [n_in][2][limbs][N].  ct_out must not overlap ct_in, pt or workspace.
+ * ct_in dev [n_in][2][limbs][N].  ct_out must not overlap ct_in, pt, bias or workspace (checked on the host: HE_ERR_ARG).
  * workspace: dev, at least he_plan_workspace_bytes() bytes (may be NULL if that is 0).
  */
 int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_t* ct_in,
@@ -144,7 +144,7 @@ int he_ct_pt_add(he_ctx* ctx, uint32_t limbs, uint64_t* ct, uint32_t n, const ui
 /*
  * Rescaling, Eq. (2), read as ct' = round(ct / q_{limbs-1}) on the integer coefficients:
  * in dev [n][2][limbs][N] (NTT form) -> out dev [n][2][limbs-1][N] (NTT form), limbs >= 2.
- * out must not overlap in.
+ * out must not overlap in (checked on the host: HE_ERR_ARG).
  */
 int he_rescale(he_ctx* ctx, uint32_t limbs, const uint64_t* in, uint64_t* out, uint32_t n,
                void* stream);

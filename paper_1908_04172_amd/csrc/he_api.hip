@@ -142,6 +142,14 @@ int check_level(const he_ctx* ctx, u32 limbs, u32 min_limbs) {
     return HE_OK;
 }
 
+// Do the byte ranges [a, a + na) and [b, b + nb) share a byte?  (Plain address arithmetic on device
+// pointers: nothing is dereferenced.)
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    if (!a || !b || !na || !nb) return false;
+    const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+    return x < y + nb && y < x + na;
+}
+
 int need_device(const he_ctx* ctx) {
     if (ctx->device < 0) return HE_ERR_DEVICE;
     if (hipSetDevice(ctx->device) != hipSuccess) { (void)hipGetLastError(); return HE_ERR_DEVICE; }
@@ -468,6 +476,14 @@ int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_
     if (plan->n_out == 0) return HE_OK;
     if (!ct_out || (plan->n_terms && (!ct_in || !pt))) return HE_ERR_ARG;
     if (need && (!workspace || workspace_bytes < need)) return HE_ERR_WORKSPACE;
+    {   // the output is written while the inputs are still being read: it must not share memory with them
+        const size_t row = (size_t)ctx->N * sizeof(u64);
+        const size_t out_bytes = (size_t)plan->n_out * 2 * ((flags & HE_RESCALE) ? limbs - 1 : limbs) * row;
+        const size_t pt_bytes = (size_t)plan->n_pt * limbs * (pt_kind == HE_PT_POLY ? row : sizeof(u64));
+        if (overlaps(ct_out, out_bytes, ct_in, (size_t)plan->n_in * 2 * limbs * row) || overlaps(ct_out, out_bytes, pt, pt_bytes) ||
+            overlaps(ct_out, out_bytes, bias, (size_t)plan->n_out * limbs * sizeof(u64)) || overlaps(ct_out, out_bytes, workspace, need))
+            return HE_ERR_ARG;
+    }
     if ((rc = need_device(ctx)) != HE_OK) return rc;
     char* ws = (char*)workspace;
     u64* wtab = nullptr;
@@ -510,6 +526,8 @@ int he_rescale(he_ctx* ctx, uint32_t limbs, const uint64_t* in, uint64_t* out, u
     if (rc != HE_OK) return rc;
     if (n == 0) return HE_OK;
     if (!in || !out) return HE_ERR_ARG;
+    if (overlaps(in, (size_t)n * 2 * limbs * ctx->N * sizeof(u64), out, (size_t)n * 2 * (limbs - 1) * ctx->N * sizeof(u64)))
+        return HE_ERR_ARG;
     if ((rc = need_device(ctx)) != HE_OK) return rc;
     return launch_rescale(ctx, limbs, in, out, n, (hipStream_t)stream);
 }

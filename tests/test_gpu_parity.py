@@ -310,6 +310,32 @@ def test_mac_argument_errors(he):
     with pytest.raises(he.HeError) as e:                                            # rescale needs 2 limbs
         ctx.ct_pt_mac(hp, ct[:, :, :1].contiguous(), w[:, :1].contiguous(), he.PT_SCALAR, flags=he.RESCALE)
     assert e.value.status == -3
+    with pytest.raises(he.HeError) as e:                                            # output over the input
+        ctx.ct_pt_mac(hp, ct, w, he.PT_SCALAR, out=ct)
+    assert e.value.status == -1
+    with pytest.raises(he.HeError) as e:
+        ctx.rescale(ct, out=ct.view(-1)[c.N: 5 * c.N].view(2, 2, 1, c.N))
+    assert e.value.status == -1
+    # a plan outlives its context without harm: its device arrays are freed on their own
+    ctx2 = he.Context(c.log2N, c.q)
+    hp2 = ctx2.plan(p.n_in, p.n_out, p.n_pt, p.off, p.term_ct, p.term_pt)
+    ctx2.close()
+    hp2.close()
+    assert torch.zeros(4, device="cuda").sum().item() == 0                          # no error left behind
+
+
+def test_measured_rates_are_plausible(he):
+    """he_measure_rate: register-resident ceilings; the butterfly modes get faster as they get lazier."""
+    c = wl.config(4)
+    ctx = he.Context(c.log2N, c.q)
+    mad = ctx.measure_rate(he.RATE_MAD32, 0, 512)
+    assert 5e12 < mad < 45e12                                                       # nominal 39.3e12 on 256 CUs
+    b0, b1, b2 = (ctx.measure_rate(k, 2, 512) for k in (he.RATE_BUTTERFLY_MODE0, he.RATE_BUTTERFLY_MODE1,
+                                                         he.RATE_BUTTERFLY_MODE2))
+    assert b0 < b1 < b2 < mad / 4
+    with pytest.raises(he.HeError) as e:                                            # a 60-bit limb has no mode 2
+        ctx.measure_rate(he.RATE_BUTTERFLY_MODE2, 0, 512)
+    assert e.value.status == -2
 
 
 # ----------------------------------------------------------------------------- Eq. (2)

@@ -133,7 +133,10 @@ def test_device_calls_fail_loudly_on_a_host_only_context():
         ctx.plan(p.n_in, p.n_out, p.n_pt, p.off, p.term_ct, p.term_pt)
     assert e.value.status == -5
     dummy = np.zeros(4, dtype=np.uint64)
-    assert he.lib().he_rescale(ctx._h, 2, dummy.ctypes.data, dummy.ctypes.data, 1, None) == -5
+    other = np.zeros(2 * 2 * c.N, dtype=np.uint64)
+    assert he.lib().he_rescale(ctx._h, 2, other.ctypes.data, dummy.ctypes.data, 1, None) == -5
+    # output sharing memory with the input is refused before anything is launched
+    assert he.lib().he_rescale(ctx._h, 2, other.ctypes.data, other.ctypes.data + 8 * c.N, 1, None) == -1
     assert he.lib().he_rescale(ctx._h, 1, dummy.ctypes.data, dummy.ctypes.data, 1, None) == -3
     assert he.lib().he_ntt_fwd(ctx._h, 3, dummy.ctypes.data, 1, None) == -3
     with pytest.raises(he.HeError) as e:
