@@ -83,7 +83,8 @@ template <int LOGN>
 int launch_t(he_ctx* ctx, u32 limbs, const double* slots, u32 n, double scale, u64* out, hipStream_t s) {
     constexpr u32 N = 1u << LOGN;
     const size_t lds = (size_t)N * 8;
-    HE_HIP(hipFuncSetAttribute((const void*)encode_vector_kernel<LOGN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    static std::atomic<uint32_t> lds_allowed{0};
+    if (int rc = allow_dynamic_lds((const void*)encode_vector_kernel<LOGN>, lds, ctx->device, lds_allowed)) return rc;
     hipLaunchKernelGGL((encode_vector_kernel<LOGN>), dim3(n), dim3(N / 16), lds, s, ctx->limbs, limbs,
                        reinterpret_cast<const cplx*>(slots), scale, reinterpret_cast<const cplx*>(ctx->fft_tw),
                        reinterpret_cast<const cplx*>(ctx->twist), out);

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <vector>
 
 #include "../../include/he.h"
@@ -74,6 +75,20 @@ struct he_plan {
     } while (0)
 
 // kernels' launchers (defined in he_mac.hip / he_ntt.hip); all return a he_status
+// hipFuncSetAttribute(MaxDynamicSharedMemorySize) for a kernel that needs more than the default
+// 64 KiB of LDS: once per kernel and device (`done` is a bit mask over device numbers, one static
+// per call site), not on every launch.
+inline int allow_dynamic_lds(const void* kernel, size_t bytes, int device, std::atomic<uint32_t>& done) {
+    const uint32_t bit = 1u << (device & 31);
+    if (device < 32 && (done.load(std::memory_order_acquire) & bit)) return HE_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return HE_ERR_DEVICE;
+    }
+    if (device < 32) done.fetch_or(bit, std::memory_order_release);
+    return HE_OK;
+}
+
 int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, const u64* pt, int pt_kind,
                const u64* bias, u64* out, u64* wtab, hipStream_t s);
 int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s);

@@ -416,10 +416,12 @@ int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipS
     const u32 per_cu = (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
     const u32 grid = std::min<u32>(rows, 256 * per_cu);
     if (inverse) {
-        HE_HIP(hipFuncSetAttribute((const void*)ntt_rows_kernel<LOGN, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        static std::atomic<uint32_t> lds_allowed{0};
+        if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true>, lds, ctx->device, lds_allowed)) return rc;
         hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, rows);
     } else {
-        HE_HIP(hipFuncSetAttribute((const void*)ntt_rows_kernel<LOGN, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        static std::atomic<uint32_t> lds_allowed{0};
+        if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false>, lds, ctx->device, lds_allowed)) return rc;
         hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd, rows);
     }
     HE_HIP(hipGetLastError());
@@ -430,7 +432,8 @@ template <int LOGN>
 int launch_rescale_t(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s) {
     using G = Geo<LOGN>;
     const size_t lds = (size_t)G::N * sizeof(u64);
-    HE_HIP(hipFuncSetAttribute((const void*)rescale_kernel<LOGN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    static std::atomic<uint32_t> lds_allowed{0};
+    if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN>, lds, ctx->device, lds_allowed)) return rc;
     DropRow row;
     for (u32 i = 0; i < HE_MAX_LIMBS; i++) row.d[i] = ctx->drop[limbs - 1][i];
     hipLaunchKernelGGL((rescale_kernel<LOGN>), dim3(2 * n), dim3(G::T), lds, s, ctx->limbs, row, limbs, in, out, ctx->tw_fwd,
