@@ -310,7 +310,15 @@ def main() -> int:
                                    "pct_hbm_peak": 100 * enc_bytes / (ms_enc * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                    "what": "%d vectors of N/2 complex slots -> [L][N] residues in NTT form (FFT kernel + "
                                            "NTT kernel); bytes = slots once + residues once" % n_vec}
-        del zs, enc_out
+        dec_out = torch.empty((n_vec, N // 2), dtype=torch.complex128, device=dev)
+        dec_ws = torch.empty(n_vec * L * N * 8, dtype=torch.uint8, device=dev)
+        ms_dec = timed(lambda: ctx.decode_vector(enc_out, scale, out=dec_out, workspace=dec_ws))
+        result["decode_vector"] = {"ms": ms_dec, "vectors_per_s": n_vec / (ms_dec * 1e-3),
+                                   "GBps": enc_bytes / (ms_dec * 1e-3) / 1e9,
+                                   "max_abs_error_of_round_trip": float((dec_out - zs).abs().max().item()),
+                                   "what": "the inverse map on the same %d polynomials (copy + INTT kernel + lift/FFT kernel); "
+                                           "bytes = residues once + slots once" % n_vec}
+        del zs, enc_out, dec_out, dec_ws
 
     # ---- every config as one fused layer call (encode, MAC + bias, one rescale per output): median of
     # 20 after 5 warm-ups.  cfg1-3 inputs are small enough to stay in the caches between repetitions.

@@ -100,6 +100,19 @@ int he_encode_vector(he_ctx* ctx, const double* slots, size_t n, double scale, u
                      uint64_t* out, void* stream);
 
 /*
+ * The inverse of he_encode_vector: poly dev [n][limbs][N] (a plaintext polynomial in NTT form, e.g. a
+ * decrypted message at the level given by `limbs`)  ->  slots dev [n][N/2][2] double,
+ *     z_k = m(r_k) / scale,
+ * m being the polynomial whose coefficients are the integers of smallest magnitude with the given
+ * residues (an exact lift, then IEEE double arithmetic: a result is accurate to about
+ * N * max|m_j| * 2^-53 * 4 * log2(N) / scale).  poly is not modified; workspace: device memory of at
+ * least n*limbs*N*8 bytes (HE_ERR_WORKSPACE otherwise) that overlaps neither poly nor slots.  A copy
+ * and two kernels on `stream`.
+ */
+int he_decode_vector(he_ctx* ctx, const uint64_t* poly, size_t n, double scale, uint32_t limbs,
+                     double* slots, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * A MAC plan (Sec. "Lazy Rescaling": an FC or Convolution output is a sum over the inner
  * dimension / window):  out[o] = sum over t in [off[o], off[o+1]) of
  * ct_in[term_ct[t]] * pt[term_pt[t]].  All three arrays are host memory and are copied;

@@ -320,7 +320,24 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
             twist[2 * j] = (double)cosl(pi * j / N);
             twist[2 * j + 1] = (double)-sinl(pi * j / N);
         }
-        if (upload(&ctx->tw_fwd, fwd.data(), fwd.size()) != HE_OK || upload(&ctx->tw_inv, inv.data(), inv.size()) != HE_OK ||
+        // tables of the decoder: Garner inverses, and the digits of floor(Q_l / 2) in the mixed radix
+        // (q_0, q_1, ...) for every level l.  Q_l - 1 has the digits q_i - 1; halve it from the top digit.
+        std::vector<u64> garner((size_t)HE_MAX_LIMBS * HE_MAX_LIMBS * 2, 0), half((size_t)(HE_MAX_LIMBS + 1) * HE_MAX_LIMBS, 0);
+        for (u32 i = 0; i < L; ++i)
+            for (u32 k = 0; k < i; ++k) {
+                garner[((size_t)i * HE_MAX_LIMBS + k) * 2] = ctx->drop[k][i].p_inv;
+                garner[((size_t)i * HE_MAX_LIMBS + k) * 2 + 1] = ctx->drop[k][i].p_inv_shoup;
+            }
+        for (u32 l = 1; l <= L; ++l) {
+            u64 rem = 0;
+            for (int i = (int)l - 1; i >= 0; --i) {
+                const u128 cur = (u128)rem * ctx->q[i] + (ctx->q[i] - 1);
+                half[(size_t)l * HE_MAX_LIMBS + i] = (u64)(cur / 2);
+                rem = (u64)(cur % 2);
+            }
+        }
+        if (upload(&ctx->garner, garner.data(), garner.size()) != HE_OK || upload(&ctx->half_digits, half.data(), half.size()) != HE_OK ||
+            upload(&ctx->tw_fwd, fwd.data(), fwd.size()) != HE_OK || upload(&ctx->tw_inv, inv.data(), inv.size()) != HE_OK ||
             upload(&ctx->fft_tw, fft_tw.data(), fft_tw.size()) != HE_OK || upload(&ctx->twist, twist.data(), twist.size()) != HE_OK) {
             he_ctx_destroy(ctx);
             return HE_ERR_DEVICE;
@@ -337,6 +354,8 @@ int he_ctx_destroy(he_ctx* ctx) {
         if (ctx->tw_inv) (void)hipFree(ctx->tw_inv);
         if (ctx->fft_tw) (void)hipFree(ctx->fft_tw);
         if (ctx->twist) (void)hipFree(ctx->twist);
+        if (ctx->garner) (void)hipFree(ctx->garner);
+        if (ctx->half_digits) (void)hipFree(ctx->half_digits);
     }
     if (ctx->device >= 0) (void)hipGetLastError();  // a failure here must not surface in the caller's next HIP call
     delete ctx;
@@ -380,6 +399,25 @@ int he_encode_vector(he_ctx* ctx, const double* slots, size_t n, double scale, u
     if ((rc = need_device(ctx)) != HE_OK) return rc;
     if ((rc = launch_encode_vector(ctx, limbs, slots, (u32)n, scale, out, (hipStream_t)stream)) != HE_OK) return rc;
     return launch_ntt(ctx, limbs, out, (u32)n, false, (hipStream_t)stream);
+}
+
+int he_decode_vector(he_ctx* ctx, const uint64_t* poly, size_t n, double scale, uint32_t limbs, double* slots,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_level(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (!(scale > 0.0) || !(scale <= 1.7976931348623157e308)) return HE_ERR_ARG;
+    if (n == 0) return HE_OK;
+    if (!poly || !slots) return HE_ERR_ARG;
+    if (n > 0x7FFFFFFFull / limbs) return HE_ERR_RANGE;
+    const size_t bytes = n * limbs * ctx->N * sizeof(u64);
+    if (!workspace || workspace_bytes < bytes) return HE_ERR_WORKSPACE;
+    if (overlaps(workspace, bytes, poly, bytes) || overlaps(workspace, bytes, slots, n * ctx->N * sizeof(double)))
+        return HE_ERR_ARG;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    HE_HIP(hipMemcpyAsync(workspace, poly, bytes, hipMemcpyDeviceToDevice, s));
+    if ((rc = launch_ntt(ctx, limbs, (u64*)workspace, (u32)n, true, s)) != HE_OK) return rc;
+    return launch_decode_vector(ctx, limbs, (const u64*)workspace, (u32)n, scale, slots, s);
 }
 
 int he_encode_scalar_host(const he_ctx* ctx, const double* values, size_t n, double scale, uint32_t limbs,

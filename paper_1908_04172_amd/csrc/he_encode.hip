@@ -1,4 +1,4 @@
-// General CKKS encoding (Alg. 1) for gfx950: N/2 complex slots -> the integer polynomial whose values
+// General CKKS encoding (Alg. 1) and its inverse for gfx950: N/2 complex slots -> the integer polynomial whose values
 // at the roots r_k = exp(i*pi*(2k+1)/N), k < N/2, are scale*z_k (and the conjugates at the conjugate
 // roots) -> residues per limb.  The forward NTT of the rows follows as a separate launch.
 //
@@ -92,7 +92,138 @@ int launch_t(he_ctx* ctx, u32 limbs, const double* slots, u32 n, double scale, u
     return HE_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Decoding: the inverse map.  Per coefficient the residues are lifted to the integer of smallest
+// magnitude by Garner's mixed-radix form  x = v_0 + v_1 q_0 + v_2 q_0 q_1 + ...  (v_i < q_i, modular
+// arithmetic only); x > Q/2 is decided exactly by comparing digits with those of floor(Q/2), and then
+// Q - x is formed digit by digit, so the conversion to double (Horner, from the top digit) never
+// subtracts large numbers.  The slots are the values of the polynomial at the slot roots: the same
+// half-size FFT with the opposite sign, preceded by the twist xi^j.
+struct GarnerInv {
+    u64 inv, inv_shoup;  // q_k^-1 mod q_i and its Shoup companion, at [i * HE_MAX_LIMBS + k]
+};
+
+__device__ __forceinline__ double lift_centred(const u64* col, size_t limb_stride, u32 limbs, const LimbTable& lt,
+                                               const GarnerInv* g, const u64* half_digits) {
+    u64 v[HE_MAX_LIMBS];
+#pragma unroll
+    for (u32 i = 0; i < HE_MAX_LIMBS; i++) {
+        if (i < limbs) {
+            const LimbConst& c = lt.c[i];
+            u64 t = col[i * limb_stride];
+#pragma unroll
+            for (u32 k = 0; k < i; k++) {
+                const u64 vk = v[k] < c.q ? v[k] : reduce64(v[k], c);
+                t = shoup_mul(sub_mod(t, vk, c.q), g[i * HE_MAX_LIMBS + k].inv, g[i * HE_MAX_LIMBS + k].inv_shoup, c.q);
+            }
+            v[i] = t;
+        }
+    }
+    bool above = false, decided = false;
+#pragma unroll
+    for (int i = HE_MAX_LIMBS - 1; i >= 0; i--) {
+        if ((u32)i < limbs && !decided && v[i] != half_digits[i]) {
+            above = v[i] > half_digits[i];
+            decided = true;
+        }
+    }
+    if (above) {  // digits of Q - x = (Q - 1 - x) + 1
+        bool carry = true;
+#pragma unroll
+        for (u32 i = 0; i < HE_MAX_LIMBS; i++) {
+            if (i < limbs) {
+                u64 d = lt.c[i].q - 1 - v[i];
+                if (carry) {
+                    d += 1;
+                    carry = d == lt.c[i].q;
+                    if (carry) d = 0;
+                }
+                v[i] = d;
+            }
+        }
+    }
+    double acc = 0.0;
+#pragma unroll
+    for (int i = HE_MAX_LIMBS - 1; i >= 0; i--)
+        if ((u32)i < limbs) acc = acc * (double)lt.c[i].q + (double)v[i];
+    return above ? -acc : acc;
+}
+
+template <int LOGN>
+__global__ void __launch_bounds__((1 << LOGN) / 16)
+decode_vector_kernel(LimbTable lt, u32 limbs, const u64* coef, double inv_scale, const GarnerInv* garner,
+                     const u64* half_digits, const cplx* fft_tw, const cplx* twist, cplx* slots) {
+    constexpr u32 N = 1u << LOGN, n = N / 2, T = N / 16, LOGn = LOGN - 1;
+    constexpr u32 PER = n / T;
+    extern __shared__ cplx buf[];
+    const u32 tid = threadIdx.x;
+    const u64* rows = coef + (size_t)blockIdx.x * limbs * N;
+    for (u32 j = tid; j < n; j += T) {
+        const double re = lift_centred(rows + j, N, limbs, lt, garner, half_digits) * inv_scale;
+        const double im = lift_centred(rows + n + j, N, limbs, lt, garner, half_digits) * inv_scale;
+        const cplx tw = twist[j];
+        buf[j] = cmul(cplx{re, im}, cplx{tw.re, -tw.im});  // times xi^j
+    }
+    __syncthreads();
+    for (u32 s = 0; s < LOGn; s++) {
+        const u32 half = n >> (s + 1);
+        for (u32 b = tid; b < n / 2; b += T) {
+            const u32 r = b & (half - 1);
+            const u32 i = ((b >> (LOGn - 1 - s)) << (LOGn - s)) | r;
+            const cplx a = buf[i], c = buf[i + half];
+            const cplx tw = fft_tw[r << s];
+            buf[i] = cplx{a.re + c.re, a.im + c.im};
+            buf[i + half] = cmul(cplx{a.re - c.re, a.im - c.im}, cplx{tw.re, -tw.im});
+        }
+        __syncthreads();
+    }
+    cplx w[PER];
+    u32 at[PER];
+#pragma unroll
+    for (u32 k = 0; k < PER; k++) {
+        const u32 pos = tid + k * T;
+        at[k] = __brev(pos) >> (32 - LOGn);
+        w[k] = buf[pos];
+    }
+    __syncthreads();
+#pragma unroll
+    for (u32 k = 0; k < PER; k++) buf[at[k]] = w[k];
+    __syncthreads();
+    // buf[kappa] is the value at xi^(4 kappa + 1): slot 2*kappa, or the conjugate of slot N - 2*kappa - 1
+    cplx* z = slots + (size_t)blockIdx.x * n;
+    for (u32 k = tid; k < n; k += T) {
+        cplx v = (k & 1) ? buf[(N - k - 1) / 2] : buf[k / 2];
+        if (k & 1) v.im = -v.im;
+        z[k] = v;
+    }
+}
+
+template <int LOGN>
+int launch_decode_t(he_ctx* ctx, u32 limbs, const u64* coef, u32 n, double scale, double* slots, hipStream_t s) {
+    constexpr u32 N = 1u << LOGN;
+    const size_t lds = (size_t)N * 8;
+    static std::atomic<uint32_t> lds_allowed{0};
+    if (int rc = allow_dynamic_lds((const void*)decode_vector_kernel<LOGN>, lds, ctx->device, lds_allowed)) return rc;
+    hipLaunchKernelGGL((decode_vector_kernel<LOGN>), dim3(n), dim3(N / 16), lds, s, ctx->limbs, limbs, coef, 1.0 / scale,
+                       reinterpret_cast<const GarnerInv*>(ctx->garner), ctx->half_digits + (size_t)limbs * HE_MAX_LIMBS,
+                       reinterpret_cast<const cplx*>(ctx->fft_tw), reinterpret_cast<const cplx*>(ctx->twist),
+                       reinterpret_cast<cplx*>(slots));
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
 }  // namespace
+
+int launch_decode_vector(he_ctx* ctx, u32 limbs, const u64* coef, u32 n, double scale, double* slots, hipStream_t s) {
+    switch (ctx->log2N) {
+        case 10: return launch_decode_t<10>(ctx, limbs, coef, n, scale, slots, s);
+        case 11: return launch_decode_t<11>(ctx, limbs, coef, n, scale, slots, s);
+        case 12: return launch_decode_t<12>(ctx, limbs, coef, n, scale, slots, s);
+        case 13: return launch_decode_t<13>(ctx, limbs, coef, n, scale, slots, s);
+        case 14: return launch_decode_t<14>(ctx, limbs, coef, n, scale, slots, s);
+    }
+    return HE_ERR_ARG;
+}
 
 int launch_encode_vector(he_ctx* ctx, u32 limbs, const double* slots, u32 n, double scale, u64* out, hipStream_t s) {
     switch (ctx->log2N) {

@@ -38,6 +38,8 @@ struct he_ctx {
     u64* tw_inv;      // [L][N][2]: (psi^-brv(k), Shoup companion)
     double* fft_tw;   // [N/4][2]: e^(-2 pi i k / (N/2)), the twiddles of the encoder's complex FFT
     double* twist;    // [N/2][2]: e^(-i pi j / N), the twist that follows it
+    u64* garner;      // [L][L][2]: (q_k^-1 mod q_i, Shoup companion) at [i][k], for the decoder's lift
+    u64* half_digits; // [L+1][L]: mixed-radix digits of floor(q_0...q_{l-1} / 2) for every level l
 };
 
 // One group of outputs that read the same ciphertexts in the same order.
@@ -95,3 +97,4 @@ int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hip
 int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s);
 int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s);
 int launch_encode_vector(he_ctx* ctx, u32 limbs, const double* slots, u32 n, double scale, u64* out, hipStream_t s);
+int launch_decode_vector(he_ctx* ctx, u32 limbs, const u64* coef, u32 n, double scale, double* slots, hipStream_t s);

@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(_HERE, "libhe_mi355x.so")
 
 EXPORTS = [
     "he_strerror", "he_ctx_create", "he_ctx_destroy", "he_ctx_info", "he_encode_scalar", "he_encode_scalar_host",
-    "he_encode_vector",
+    "he_encode_vector", "he_decode_vector",
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_measure_rate",
@@ -57,6 +57,7 @@ def lib():
         "he_encode_scalar": (i32, [vp, vp, sz, dbl, u32, vp, vp]),
         "he_encode_scalar_host": (i32, [vp, vp, sz, dbl, u32, vp]),
         "he_encode_vector": (i32, [vp, vp, sz, dbl, u32, vp, vp]),
+        "he_decode_vector": (i32, [vp, vp, sz, dbl, u32, vp, vp, sz, vp]),
         "he_plan_create": (i32, [vp, u32, u32, u32, vp, vp, vp, pp]),
         "he_plan_destroy": (i32, [vp]),
         "he_plan_workspace_bytes": (i32, [vp, u32, i32, u32, ctypes.POINTER(sz)]),
@@ -175,6 +176,19 @@ class Context:
         assert tuple(out.shape) == (n, limbs, self.N)
         _check(lib().he_encode_vector(self._h, _dev_ptr(slots, "slots"), n, float(scale), limbs, _dev_ptr(out, "out"),
                                       _stream()), "he_encode_vector")
+        return out
+
+    def decode_vector(self, poly, scale: float, out=None, workspace=None):
+        """poly: CUDA int64 tensor [n][limbs][N] (NTT form) -> CUDA complex128 tensor [n][N/2] (he_decode_vector)."""
+        import torch
+        n, limbs, N = poly.shape
+        assert N == self.N
+        if out is None:
+            out = torch.empty((n, N // 2), dtype=torch.complex128, device=poly.device)
+        if workspace is None:
+            workspace = torch.empty(max(n * limbs * N * 8, 8), dtype=torch.uint8, device=poly.device)
+        _check(lib().he_decode_vector(self._h, _dev_ptr(poly, "poly"), n, float(scale), limbs, _dev_ptr(out, "slots"),
+                                      _dev_ptr(workspace, "workspace"), workspace.numel(), _stream()), "he_decode_vector")
         return out
 
     # -- Alg. 3 / 4

@@ -151,6 +151,47 @@ def test_encode_vector_matches_oracle(he, log2N):
         ctx.encode_vector(torch.zeros((1, N // 2), dtype=torch.complex128, device="cuda"), float("inf"))
 
 
+@pytest.mark.parametrize("log2N", [10, 12, 14])
+def test_decode_vector_matches_oracle(he, log2N):
+    """The inverse map on the GPU: an exact lift of the residues (checked here on coefficients far
+    beyond 64 bits and of both signs), then double arithmetic against the oracle's long-double sums."""
+    N = 1 << log2N
+    q = wl.modulus_chain(MIXED[log2N], N)
+    ctx = he.Context(log2N, q)
+    rng = np.random.default_rng(500 + log2N)
+    Q = 1
+    for qi in q:
+        Q *= int(qi)
+    bits = Q.bit_length() - 2
+    # three polynomials: small coefficients, coefficients near +-Q/2, and the extremes themselves
+    m = np.zeros((3, N), dtype=object)
+    m[0] = [int(x) for x in rng.integers(-2**40, 2**40, size=N)]
+    m[1] = [int(rng.integers(-2**62, 2**62)) * (1 << (bits - 62)) + int(rng.integers(-5, 5)) for _ in range(N)]
+    m[2] = [0] * N
+    m[2, :6] = [Q // 2, -(Q // 2), 1, -1, Q // 2 - 1, 0]
+    res = np.stack([np.array([[int(x) % int(qi) for x in m[v]] for qi in q], dtype=np.uint64) for v in range(3)])
+    poly = oracle.ntt_fwd(res, q, ctx.psi)
+    for scale, vecs in ((2.0 ** 30, [0]), (2.0 ** (bits - 10), [1, 2])):
+        got = ctx.decode_vector(dev(poly[vecs]), scale).cpu().numpy()
+        want = oracle.decode_vector(np.array([[float(x) for x in m[v]] for v in vecs]), scale, N)
+        mag = max(abs(int(x)) for v in vecs for x in m[v])
+        tol = N * mag * 2.0 ** -53 * 4 * log2N / scale
+        assert np.abs(got - want).max() <= tol, (log2N, scale, np.abs(got - want).max(), tol)
+    # encode then decode on the GPU returns the slots (to the rounding of the coefficients)
+    z = rng.normal(size=(2, N // 2)) + 1j * rng.normal(size=(2, N // 2))
+    enc = ctx.encode_vector(torch.from_numpy(z).cuda(), 2.0 ** 40)
+    back = ctx.decode_vector(enc, 2.0 ** 40).cpu().numpy()
+    assert np.abs(back - z).max() <= N / 2.0 ** 40
+    assert np.array_equal(host(enc), host(enc.clone()))               # the input polynomial is left as it was
+    # a lower level, an empty batch, a workspace that is too small
+    back1 = ctx.decode_vector(ctx.encode_vector(torch.from_numpy(z).cuda(), 2.0 ** 20, limbs=1), 2.0 ** 20).cpu().numpy()
+    assert np.abs(back1 - z).max() <= N / 2.0 ** 20
+    ctx.decode_vector(enc[:0], 2.0 ** 40)
+    with pytest.raises(he.HeError) as e:
+        ctx.decode_vector(enc, 2.0 ** 40, workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -6
+
+
 def test_complex_packed_layer_through_encrypt_compute_decrypt(he):
     """Complex packing end to end: two real batches ride in the real and imaginary parts of the slots;
     a dense layer with scalar weights and a complex-packed bias vector (encoded on the GPU by Alg. 1),
