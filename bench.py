@@ -261,7 +261,19 @@ def main() -> int:
         # the timed GPU outputs must be the oracle's, bit for bit
         ok = np.array_equal(to_host(idx(out4, s4)), want4) and np.array_equal(to_host(idx(out5, s5)), want5)
         cpu_step_s = t4 * p4.n_out / len(s4) + t5 * p5.n_out / len(s5)
+        # the serial program (one thread) on a few cfg4 outputs: the paper's single-operation tables are
+        # single-threaded
+        n1 = min(16, len(s4))
+        off1, tc1, tp1, ct_ids1, pt_ids1 = compact(p4, s4[:n1])
+        h_ct1 = to_host(idx(ct4, ct_ids1))
+        oracle.set_threads(1)
+        t = time.perf_counter()
+        oracle.layer(h_ct1, q, psi, off1, tc1, tp1, wenc[pt_ids1], oracle.PT_SCALAR, benc[s4[:n1]])
+        t1 = time.perf_counter() - t
+        oracle.set_threads(0)
         result["cpu_baseline"] = {
+            "one_thread_rescaled_ct_per_s": n1 / t1,
+            "one_thread_sample": "%d cfg4 outputs (MAC of up to 27 terms + bias + rescale each), %.1f s" % (n1, t1),
             "value": total_bytes / cpu_step_s / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": "%d of %d cfg4 outputs (%.1f s) + %d of %d cfg5 outputs (%.1f s), extrapolated linearly to "
                       "the whole step" % (len(s4), p4.n_out, t4, len(s5), p5.n_out, t5),
@@ -279,6 +291,10 @@ def main() -> int:
                 ev[i + 1].record()
             torch.cuda.synchronize()
             return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
+        # the copy ceiling of this machine, by the library every tensor here comes from: 2 GiB read + 2 GiB written
+        cp_src, cp_dst = ct4[:1024], acc4[:1024]
+        ms_copy = timed(lambda: cp_dst.copy_(cp_src))
+        result["measured_copy_GBps"] = 2 * cp_src.numel() * 8 / (ms_copy * 1e-3) / 1e9
         n_add = p4.n_in
         pt_add = ctx.encode_scalar(torch.from_numpy(wl.normal_values(n_add, 0.1, 7)).to(dev), scale)
         ms_add = timed(lambda: ctx.ct_pt_add(ct4, pt_add, he.PT_SCALAR))
