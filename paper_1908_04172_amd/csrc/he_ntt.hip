@@ -329,19 +329,26 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows)
 //
 // The parked t for limb i+1 is requested before the outputs of limb i are stored, so that the next
 // iteration does not queue behind those stores.
-template <int LOGN>
+template <int LOGN, bool SPLIT>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
-rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, const u64* in, u64* out, const u64* tw_fwd, const u64* tw_inv) {
+rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, u64* out, const u64* tw_fwd,
+               const u64* tw_inv) {
     using G = Geo<LOGN>;
     extern __shared__ u64 lds[];
-    const size_t poly = blockIdx.x;  // ct*2 + component
+    // A polynomial is handled by `parts` workgroups when there are too few polynomials to fill the
+    // chip: each repeats the inverse transform of the dropped limb and takes a contiguous share
+    // [first, end) of the kept limbs.
+    // (SPLIT = false is the plain case, one workgroup per polynomial, with nothing of this computed.)
+    const size_t poly = SPLIT ? blockIdx.x / parts : blockIdx.x;  // ct*2 + component
+    const u32 part = SPLIT ? blockIdx.x % parts : 0;
     const u32 last = limbs - 1;
+    const u32 first = SPLIT ? part * last / parts : 0, end = SPLIT ? (part + 1) * last / parts : last;
     const u64* src = in + poly * limbs * G::N;
     u64* dst = out + poly * (limbs - 1) * G::N;
-    // t is parked in the output row of the last kept limb: every thread re-reads only what it wrote
-    // itself, and that row is overwritten only in the last iteration, after all its threads have
+    // t is parked in the output row of this workgroup's last limb: every thread re-reads only what it
+    // wrote itself, and that row is overwritten only in the last iteration, after all its threads have
     // taken their t back (they use it before the first regrouping barrier of that iteration).
-    u64* park = dst + (size_t)(last - 1) * G::N;
+    u64* park = dst + (size_t)(end - 1) * G::N;
     u64 a[16];
     {
         const u32 tid = threadIdx.x;
@@ -357,10 +364,10 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, const u64* in, u64* out, c
             u64 v = a[e];
             v = v >= c.q ? v - c.q : v;
             a[e] = add_mod(v, half, c.q);
-            if (last > 1) park[reg_index<LOGN, 0>(tid_s, e)] = a[e];
+            if (end - first > 1) park[reg_index<LOGN, 0>(tid_s, e)] = a[e];
         }
     }
-    for (u32 i = 0; i < last; i++) {
+    for (u32 i = first; i < end; i++) {
         // the thread index is made opaque per iteration so that the many addresses derived from it
         // are recomputed (a few integer operations) instead of being kept live across the loop
         u32 tid_i = threadIdx.x;
@@ -395,7 +402,7 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, const u64* in, u64* out, c
         for (u32 e = 0; e < 16; e++) x[e] = xrow[reg_index<LOGN, G::NPASS - 1>(tid_s, e)];
 #pragma unroll
         for (u32 e = 0; e < 16; e++) next[e] = 0;
-        if (i + 1 < last) {
+        if (i + 1 < end) {
 #pragma unroll
             for (u32 e = 0; e < 16; e++) next[e] = park[reg_index<LOGN, 0>(tid_s, e)];
         }
@@ -432,12 +439,21 @@ template <int LOGN>
 int launch_rescale_t(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s) {
     using G = Geo<LOGN>;
     const size_t lds = (size_t)G::N * sizeof(u64);
-    static std::atomic<uint32_t> lds_allowed{0};
-    if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN>, lds, ctx->device, lds_allowed)) return rc;
+    static std::atomic<uint32_t> lds_allowed{0}, lds_allowed_split{0};
+    if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN, false>, lds, ctx->device, lds_allowed)) return rc;
+    if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN, true>, lds, ctx->device, lds_allowed_split)) return rc;
     DropRow row;
     for (u32 i = 0; i < HE_MAX_LIMBS; i++) row.d[i] = ctx->drop[limbs - 1][i];
-    hipLaunchKernelGGL((rescale_kernel<LOGN>), dim3(2 * n), dim3(G::T), lds, s, ctx->limbs, row, limbs, in, out, ctx->tw_fwd,
-                       ctx->tw_inv);
+    // with fewer polynomials than workgroups the chip holds at once, split each over several workgroups
+    // (at most one per kept limb), as far as they still all run at the same time
+    const u32 resident = 256 * (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
+    const u32 parts = std::max(1u, std::min(limbs - 1, resident / (2 * n)));
+    if (parts > 1)
+        hipLaunchKernelGGL((rescale_kernel<LOGN, true>), dim3(2 * n * parts), dim3(G::T), lds, s, ctx->limbs, row, limbs, parts,
+                           in, out, ctx->tw_fwd, ctx->tw_inv);
+    else
+        hipLaunchKernelGGL((rescale_kernel<LOGN, false>), dim3(2 * n), dim3(G::T), lds, s, ctx->limbs, row, limbs, 1u, in, out,
+                           ctx->tw_fwd, ctx->tw_inv);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
