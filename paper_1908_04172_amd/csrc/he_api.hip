@@ -463,12 +463,15 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
     p->n_tiles_p = (u32)tp.size();
     std::vector<u64> wbase(ts.size() + 1, 0);
     u64 elems = 0;
-    for (int cls = 0; cls < 3; ++cls)
+    for (int cls = 0; cls < 3; ++cls) {
+        p->min_terms_s[cls] = p->class_begin_s[cls] < p->class_begin_s[cls + 1] ? ~0u : 0;
         for (u32 i = p->class_begin_s[cls]; i < p->class_begin_s[cls + 1]; ++i) {
+            p->min_terms_s[cls] = std::min(p->min_terms_s[cls], ts[i].n_terms);
             wbase[i] = elems;
             elems += (u64)((ts[i].n_terms + 3) / 4 * 4) * CAPS_S[cls];  // terms padded to whole blocks of 4
         }
-    p->wtab_elems = elems;
+    }
+    p->wtab_elems = elems + 16;  // padding: the 16-output kernel requests one term's weights past its last
     if (upload(&p->tiles_s_dev, ts.data(), ts.size()) != HE_OK || upload(&p->tiles_p_dev, tp.data(), tp.size()) != HE_OK ||
         upload(&p->wbase_s_dev, wbase.data(), ts.size()) != HE_OK || upload(&p->off_dev, off, (size_t)n_out + 1) != HE_OK ||
         upload(&p->term_ct_dev, term_ct, n_terms) != HE_OK || upload(&p->term_pt_dev, term_pt, n_terms) != HE_OK) {

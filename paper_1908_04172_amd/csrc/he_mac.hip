@@ -11,25 +11,28 @@ namespace {
 constexpr int MAC_THREADS = 256;
 constexpr int GATHER_BLOCKS = 8;
 constexpr u32 BLOCK_TERMS = 4;  // terms per unrolled block; an input is loaded one block before its use
+constexpr u32 GROUPS_PER_WG = 8;  // groups of outputs a workgroup of the scalar kernel runs through, at most
+constexpr u64 MIN_WORKGROUPS = 256 * 32;  // ... while the launch keeps at least this many workgroups
 
 __host__ __device__ inline u32 padded_terms(u32 n_terms) { return (n_terms + BLOCK_TERMS - 1) / BLOCK_TERMS * BLOCK_TERMS; }
 
-// Weight table for scalar plaintexts: wtab[(wbase*limbs) + (limb*Kp + t)*G + g], Kp = n_terms rounded
-// up to a multiple of BLOCK_TERMS, holds the two pieces (wa | wb << 32, see MacAcc) of
+// Weight table for scalar plaintexts: wtab[limb*wtab_elems + wbase + t*G + g], 0 <= t < Kp = n_terms
+// rounded up to a multiple of BLOCK_TERMS (so the groups of a class follow each other within a limb,
+// and every limb's part ends with 16 entries of padding that are read ahead but never used), holds the two pieces (wa | wb << 32, see MacAcc) of
 // pt[term_pt[off[out0+g] + t]][limb], and zero for g >= tile.count or t >= n_terms.  The MAC loop
 // then reads G consecutive entries per term with scalar loads, runs whole blocks of terms, and needs
 // neither a per-output branch nor a split of the plaintext operand.
 template <int G>
 __global__ void __launch_bounds__(256) gather_weights_kernel(LimbTable lt, const Tile* tiles, const u64* wbase, u32 n_tiles,
                                                              u32 limbs, const u32* off, const u32* term_pt, const u64* pt,
-                                                             u64* wtab) {
+                                                             u64* wtab, u64 wtab_elems) {
     const u32 tile_i = blockIdx.x / GATHER_BLOCKS;
     const u32 sub = blockIdx.x % GATHER_BLOCKS;
     if (tile_i >= n_tiles) return;
     const Tile tile = tiles[tile_i];
     const u64 per_limb = (u64)padded_terms(tile.n_terms) * G;
     const u64 total = per_limb * limbs;
-    u64* dst = wtab + wbase[tile_i] * limbs;
+    u64* dst = wtab + wbase[tile_i];
     for (u64 i = (u64)sub * blockDim.x + threadIdx.x; i < total; i += (u64)GATHER_BLOCKS * blockDim.x) {
         const u32 limb = (u32)(i / per_limb);
         const u64 rem = i % per_limb;
@@ -40,7 +43,7 @@ __global__ void __launch_bounds__(256) gather_weights_kernel(LimbTable lt, const
             split_operand(pt[(size_t)term_pt[off[tile.out0 + g] + t] * limbs + limb], lt.c[limb], wa, wb);
             packed = (u64)wa | ((u64)wb << 32);
         }
-        dst[i] = packed;
+        dst[(u64)limb * wtab_elems + rem] = packed;
     }
 }
 
@@ -74,26 +77,33 @@ __device__ __forceinline__ void housekeeping(MacAcc (&acc)[A], u32& f, u32& r, u
     }
 }
 
-// Sixteen plaintext residues (as 32-bit pieces) in 32 scalar registers.  The loads are issued by
-// hand so that they are in flight during the previous term's multiply-adds: request() starts them,
-// arrived() waits for them; between the two calls the registers must not be read.
+// A load of read-only, workgroup-uniform data (the plan's tables) through the constant address space:
+// it becomes a scalar load wherever it sits, also after hand-issued loads that clobber "memory".
+template <typename T>
+__device__ __forceinline__ T uniform_load(const T* p) {
+    return *(const __attribute__((address_space(4))) T*)(p);
+}
+__device__ __forceinline__ Tile uniform_load(const Tile* p) {
+    return Tile{uniform_load(&p->out0), uniform_load(&p->count), uniform_load(&p->term0), uniform_load(&p->n_terms)};
+}
+
+// Eight plaintext residues (as 32-bit pieces) in 16 scalar registers.  The loads are issued by hand
+// so that they are in flight during multiply-adds that do not need them: request() starts one,
+// arrived() waits for it; between the two calls the registers must not be read.
 typedef u32 u32x16 __attribute__((ext_vector_type(16)));
-struct ScalarWeights16 {
-    u32x16 a, b;  // residues 0..7 and 8..15 as (wa, wb) pairs
+struct ScalarWeights8 {
+    u32x16 v;  // (wa, wb) pairs
     __device__ __forceinline__ void request(const u64* wt) {
-        asm volatile("s_load_dwordx16 %0, %2, 0x0\n\ts_load_dwordx16 %1, %2, 0x40" : "=&s"(a), "=&s"(b) : "s"(wt) : "memory");
+        asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=&s"(v) : "s"(wt) : "memory");
     }
-    __device__ __forceinline__ void arrived() { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(a), "+s"(b)); }
+    __device__ __forceinline__ void arrived() { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(v)); }
 };
 
-__device__ __forceinline__ void scalar_term16(MacAcc (&acc)[16], u64 x, const ScalarWeights16& w, const LimbConst& c) {
-    u32 xa, xb;
-    split_operand(x, c, xa, xb);
+// one term's multiply-adds into eight of the sixteen outputs
+template <int FIRST>
+__device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[16], u32 xa, u32 xb, const ScalarWeights8& w) {
 #pragma unroll
-    for (int g = 0; g < 8; g++) {
-        acc_mac(acc[g], xa, xb, w.a[2 * g], w.a[2 * g + 1]);
-        acc_mac(acc[g + 8], xa, xb, w.b[2 * g], w.b[2 * g + 1]);
-    }
+    for (int g = 0; g < 8; g++) acc_mac(acc[FIRST + g], xa, xb, w.v[2 * g], w.v[2 * g + 1]);
 }
 
 template <int G>
@@ -110,90 +120,187 @@ __device__ __forceinline__ void scalar_term(MacAcc (&acc)[G], u64 x, const u64 (
     for (int g = 0; g < G; g++) acc_mac(acc[g], xa, xb, (u32)wt[g], (u32)(wt[g] >> 32));
 }
 
+// Final reduction, bias (Alg. 4, component 0 only) and store of one group of outputs; the cheaper
+// reduction where it applies, chosen once so that the per-output code has no branch.  The group's
+// bias residues come in with one load (lane g of every wave fetches output g's) and are handed out
+// with lane reads, so the outputs do not each wait for a load of their own.
+template <int G>
+__device__ __forceinline__ void store_group(MacAcc (&acc)[G], u32 out0, u32 count, const LimbConst& c, const u64* bias, u32 comp,
+                                            u32 limb, u32 limbs, u32 N, u32 n, u64* out) {
+    const u32 lane = threadIdx.x % 64;
+    u64 bias_lane = 0;
+    if (bias != nullptr && comp == 0 && lane < count) bias_lane = bias[(size_t)(out0 + lane) * limbs + limb];
+    u64* dst = out + (((size_t)out0 * 2 + comp) * limbs + limb) * N + n;
+    const size_t out_stride = (size_t)2 * limbs * N;
+    if (c.narrow && c.ntt_mode >= 1) {
+        // the constants of the reduction, fetched once and held in registers for all the outputs (left
+        // to itself the compiler fetches them again for every output, and waits each time)
+        LimbConst k = c;
+        asm volatile("" : "+s"(k.q), "+s"(k.mu), "+s"(k.neg_four_q), "+s"(k.neg_two_q), "+s"(k.split_mask), "+s"(k.split_bits), "+s"(k.mu_shift));
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            if ((u32)g < count) {
+                const u64 b = (u64)(u32)__builtin_amdgcn_readlane((int)(u32)bias_lane, g) |
+                              ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(bias_lane >> 32), g) << 32);
+                dst[g * out_stride] = acc_reduce_add(acc[g], b, k);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            if ((u32)g < count) {
+                const u64 b = (u64)(u32)__builtin_amdgcn_readlane((int)(u32)bias_lane, g) |
+                              ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(bias_lane >> 32), g) << 32);
+                dst[g * out_stride] = add_mod(acc_reduce(acc[g], c), b, c.q);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+}
+
+// A workgroup owns one 256-residue slice of one (component, limb) row and `per_wg` consecutive groups
+// of outputs, which it handles one after the other.  In the main path the input ring and the scalar
+// weights run on into the next group while the current one is still being reduced and stored, so the
+// chain of dependent loads that opens a group (descriptor -> term list -> inputs) and the stores that
+// close it are paid once per workgroup instead of once per group.
 template <int G>
 __global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8)))
-mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u64* wbase, const u32* term_ct,
-                  const u64* wtab, const u64* ct_in, const u64* bias, u64* out) {
+mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg, const u64* wbase,
+                  const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
     const u32 chunks = N / MAC_THREADS;
-    // Order: slice of the row fastest, then group of outputs, then (component, limb).  Workgroups go
+    const u32 n_wg_tiles = (n_tiles + per_wg - 1) / per_wg;
+    // Order: slice of the row fastest, then run of groups, then (component, limb).  Workgroups go
     // to the eight XCDs round-robin and the number of slices is a multiple of eight, so the same
     // slice of neighbouring groups (which read overlapping inputs) runs on the same XCD, close in
     // time, and hits in its L2, while the slices in flight at any moment cover whole rows.
     u32 b = blockIdx.x;
     const u32 chunk = b % chunks; b /= chunks;
-    const u32 tile_i = b % n_tiles; b /= n_tiles;
+    const u32 tile_first = (b % n_wg_tiles) * per_wg; b /= n_wg_tiles;
+    const u32 tile_end = min(tile_first + per_wg, n_tiles);
     const u32 comp = b & 1;
     const u32 limb = b >> 1;
-    const Tile tile = tiles[tile_i];
     const LimbConst& c = lt.c[limb];
     const u32 n = chunk * MAC_THREADS + threadIdx.x;
     const size_t ct_stride = (size_t)2 * limbs * N;
     const u64* x_base = ct_in + ((size_t)comp * limbs + limb) * N + n;
-    const u32 K = tile.n_terms, Kp = padded_terms(K);
-    const u64* w = wtab + wbase[tile_i] * limbs + (u64)limb * Kp * G;
-    const u32* tc = term_ct + tile.term0;
-
     MacAcc acc[G];
-#pragma unroll
-    for (int g = 0; g < G; g++) acc_clear(acc[g]);
 
-    if (K > 0 && c.fold_every >= BLOCK_TERMS) {
+    if (c.fold_every >= BLOCK_TERMS && uniform_load(&tiles[tile_first].n_terms) > 0) {
         // Terms run in blocks of four (terms K..Kp-1 are padding: zero weights, input K-1 again).
         // Ring of inputs: xq[j] holds the residue of term t+j and is refilled for term t+j+4 as soon
         // as it has been consumed, so a load has a whole block of MACs (256 multiply-adds per lane)
-        // to complete.  Folds and reductions happen between runs of whole blocks only, so inside a
-        // run the partial sums are plain loop-carried registers.
+        // to complete.  The ring looks 8 terms ahead; two blocks before the end of a group it moves
+        // on to the next group's list (the host runs several groups per workgroup only if every
+        // group has at least 8 padded terms, so the ring is never more than one group ahead).
+        // Folds and reductions happen between runs of whole blocks only, so inside a run the partial
+        // sums are plain loop-carried registers.
         const u32 fold_blocks = c.fold_every / BLOCK_TERMS * BLOCK_TERMS;
         const u32 reduce_blocks = c.reduce_every / BLOCK_TERMS * BLOCK_TERMS;
-        u32 f = 0, r = 0, t = 0;
+        const Tile first = uniform_load(tiles + tile_first);
+        u32 Kp = padded_terms(first.n_terms);
+        // the list the ring is filled from: term u of the current group (u may run past Kp, into the
+        // next group) is term_ct[list0 + min(u, u_last)], the sum taken modulo 2^32 (list0 is the
+        // next list's start minus Kp, which may be "negative")
+        u32 list0 = first.term0;
+        u32 u_last = first.n_terms - 1;
+        // weights of the term being multiplied; within a limb the groups of a class follow each other
+        // in the table, so this pointer simply runs on
+        const u64* wp = wtab + (u64)limb * wtab_elems + uniform_load(wbase + tile_first);
         u64 xq[BLOCK_TERMS];
         u32 cq[BLOCK_TERMS];  // ciphertext indices of terms t+4 .. t+7, fetched a block before they are needed
 #pragma unroll
         for (int j = 0; j < BLOCK_TERMS; j++) {
-            xq[j] = x_base[(size_t)tc[min((u32)j, K - 1)] * ct_stride];
-            cq[j] = tc[min((u32)(BLOCK_TERMS + j), K - 1)];
+            xq[j] = x_base[(size_t)term_ct[(u32)(list0 + min((u32)j, u_last))] * ct_stride];
+            cq[j] = term_ct[(u32)(list0 + min((u32)(BLOCK_TERMS + j), u_last))];
         }
-        // The plaintext residues of a term sit in scalar registers; the next term's are requested
-        // while this term's multiply-adds run (two register sets, used alternately).
-        ScalarWeights16 w_even, w_odd;
+        // The plaintext residues of a term sit in scalar registers, eight outputs' worth in each of
+        // two sets.  While one set's multiply-adds run, the other set's next load is in flight: at
+        // the start of a term w_lo holds this term's residues for outputs 0..7 and the load of w_hi
+        // (outputs 8..15) has been issued.  After the last term of the last group the requests reach
+        // the next group's weights or the table's padding.
+        ScalarWeights8 w_lo, w_hi;
+        // where the operands are cut, held in registers for the whole loop (left to itself the
+        // compiler fetches the two words again in every block, and waits for them)
+        u32 split_mask = (u32)c.split_mask, split_bits = c.split_bits;
+        asm volatile("" : "+s"(split_mask), "+s"(split_bits));
         if constexpr (G == 16) {
-            w_even.request(w);
-            w_even.arrived();
+            w_lo.request(wp);
+            w_lo.arrived();
+            w_hi.request(wp + 8);
         }
-        while (t < Kp) {
-            const u32 run = min(Kp - t, min(fold_blocks - f, reduce_blocks - r));
-            const u32 t_end = t + run;
-#pragma unroll 1
-            for (; t < t_end; t += BLOCK_TERMS) {
-#pragma unroll
-                for (int j = 0; j < BLOCK_TERMS; j++) {
-                    const u64 x = xq[j];
-                    xq[j] = x_base[(size_t)cq[j] * ct_stride];
-                    cq[j] = tc[min(t + 2 * BLOCK_TERMS + j, K - 1)];
-                    if constexpr (G == 16) {
-                        const u64* w_next = w + (size_t)min(t + j + 1, Kp - 1) * G;
-                        if (j % 2 == 0) {
-                            w_odd.request(w_next);
-                            scalar_term16(acc, x, w_even, c);
-                            w_odd.arrived();
-                        } else {
-                            w_even.request(w_next);
-                            scalar_term16(acc, x, w_odd, c);
-                            w_even.arrived();
-                        }
-                    } else {
-                        u64 wt[G];
-                        load_weights<G>(wt, w + (size_t)(t + j) * G);
-                        scalar_term<G>(acc, x, wt, c);
-                    }
-                }
+        for (u32 tile_i = tile_first; tile_i < tile_end; tile_i++) {
+            // the group after this one; after the last one the ring stays on this group's last term
+            // (loads that hit in the cache and are never used)
+            u32 next_list0 = list0 + u_last, next_K = 1;
+            if (tile_i + 1 < tile_end) {
+                const Tile next = uniform_load(tiles + tile_i + 1);
+                next_list0 = next.term0;
+                next_K = next.n_terms;
             }
-            f += run;
-            r += run;
-            if (t < Kp) housekeeping<G>(acc, f, r, fold_blocks, reduce_blocks, c);
+            const Tile cur = uniform_load(tiles + tile_i);
+            const u32 out0 = cur.out0, count = cur.count;
+#pragma unroll
+            for (int g = 0; g < G; g++) acc_clear(acc[g]);
+            u32 f = 0, r = 0, t = 0;
+            while (t < Kp) {
+                const u32 run = min(Kp - t, min(fold_blocks - f, reduce_blocks - r));
+                const u32 t_end = t + run;
+#pragma unroll 1
+                for (; t < t_end; t += BLOCK_TERMS) {
+                    if (t + 2 * BLOCK_TERMS == Kp) {  // from here on the look-ahead is in the next group
+                        list0 = next_list0 - Kp;
+                        u_last = Kp + next_K - 1;
+                    }
+#pragma unroll
+                    for (int j = 0; j < BLOCK_TERMS; j++) {
+                        const u64 x = xq[j];
+                        xq[j] = x_base[(size_t)cq[j] * ct_stride];
+                        cq[j] = term_ct[(u32)(list0 + min(t + 2 * BLOCK_TERMS + j, u_last))];
+                        if constexpr (G == 16) {
+                            // (the scheduling barriers keep each half's multiply-adds between a
+                            // request and the wait for it, where they hide the load's latency)
+                            const u32 xa = (u32)x & split_mask, xb = (u32)(x >> split_bits);  // split_operand
+                            __builtin_amdgcn_sched_barrier(0);
+                            scalar_half_term<0>(acc, xa, xb, w_lo);
+                            __builtin_amdgcn_sched_barrier(0);
+                            w_hi.arrived();
+                            w_lo.request(wp + (j + 1) * G);
+                            __builtin_amdgcn_sched_barrier(0);
+                            scalar_half_term<8>(acc, xa, xb, w_hi);
+                            __builtin_amdgcn_sched_barrier(0);
+                            w_lo.arrived();
+                            w_hi.request(wp + (j + 1) * G + 8);
+                        } else {
+                            u64 wt[G];
+                            load_weights<G>(wt, wp + j * G);
+                            scalar_term<G>(acc, x, wt, c);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);  // one term at a time: keeps the live values few
+                    }
+                    wp += BLOCK_TERMS * G;
+                }
+                if constexpr (G == 16) w_hi.arrived();  // no load in flight outside the block loop
+                f += run;
+                r += run;
+                if (t < Kp) housekeeping<G>(acc, f, r, fold_blocks, reduce_blocks, c);
+            }
+            store_group<G>(acc, out0, count, c, bias, comp, limb, limbs, N, n, out);
+            list0 += Kp;
+            u_last -= Kp;
+            Kp = padded_terms(next_K);
         }
-    } else if (K > 0) {
-        // moduli above 2^60 fold more often than once per block: plain loop, one term at a time
+        return;
+    }
+    // Every other case, one group at a time: moduli above 2^60 (they fold more often than once per
+    // block), groups without terms.
+    for (u32 tile_i = tile_first; tile_i < tile_end; tile_i++) {
+        const Tile tile = tiles[tile_i];
+        const u32 K = tile.n_terms;
+        const u64* w = wtab + (u64)limb * wtab_elems + wbase[tile_i];
+        const u32* tc = term_ct + tile.term0;
+#pragma unroll
+        for (int g = 0; g < G; g++) acc_clear(acc[g]);
         u32 f = 0, r = 0;
         for (u32 t = 0; t < K; ++t) {
             u64 wt[G];
@@ -203,31 +310,7 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
             ++r;
             if (t + 1 < K) housekeeping<G>(acc, f, r, c.fold_every, c.reduce_every, c);
         }
-    }
-    // final reduction, bias (Alg. 4, component 0 only) and store; the cheaper reduction where it applies,
-    // chosen once per workgroup so that the per-output code has no branch
-    const bool with_bias = bias != nullptr && comp == 0;
-    if (c.narrow && c.ntt_mode >= 1) {
-#pragma unroll
-        for (int g = 0; g < G; g++) {
-            if ((u32)g < tile.count) {
-                const u32 o = tile.out0 + g;
-                const u64 b = with_bias ? bias[(size_t)o * limbs + limb] : 0;
-                out[(((size_t)o * 2 + comp) * limbs + limb) * N + n] = acc_reduce_add(acc[g], b, c);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    } else {
-#pragma unroll
-        for (int g = 0; g < G; g++) {
-            if ((u32)g < tile.count) {
-                const u32 o = tile.out0 + g;
-                u64 v = acc_reduce(acc[g], c);
-                if (with_bias) v = add_mod(v, bias[(size_t)o * limbs + limb], c.q);
-                out[(((size_t)o * 2 + comp) * limbs + limb) * N + n] = v;
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
+        store_group<G>(acc, tile.out0, tile.count, c, bias, comp, limb, limbs, N, n, out);
     }
 }
 
@@ -238,7 +321,7 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
 template <int SL>
 __global__ void __launch_bounds__(MAC_THREADS)
 mac_scalar_single_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u64* wbase,
-                         const u32* term_ct, const u64* wtab, const u64* ct_in, const u64* bias, u64* out) {
+                         const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
     const u32 per_block = MAC_THREADS * 2 * SL;
     const u32 blocks_per_row = N / per_block;
     u32 b = blockIdx.x;
@@ -251,7 +334,7 @@ mac_scalar_single_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 
     const size_t ct_stride = (size_t)2 * limbs * N;
     const size_t row_off = ((size_t)comp * limbs + limb) * N + (size_t)part * per_block;
     const u32 K = tile.n_terms;
-    const u64* w = wtab + wbase[tile_i] * limbs + (u64)limb * padded_terms(K);
+    const u64* w = wtab + (u64)limb * wtab_elems + wbase[tile_i];
     const u32* tc = term_ct + tile.term0;
 
     MacAcc acc[SL][2];
@@ -393,7 +476,7 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
     const Tile* tiles = plan->tiles_s_dev + begin;
     const u64* wbase = plan->wbase_s_dev + begin;
     hipLaunchKernelGGL((gather_weights_kernel<G>), dim3(count * GATHER_BLOCKS), dim3(256), 0, s, ctx->limbs, tiles, wbase, count, limbs, plan->off_dev,
-                       plan->term_pt_dev, pt, wtab);
+                       plan->term_pt_dev, pt, wtab, plan->wtab_elems);
     HE_HIP(hipGetLastError());
     if constexpr (G == 1) {
         const u32 sl = ctx->N >= 2048 ? 4 : 2;
@@ -401,17 +484,22 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
         if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
         if (sl == 4)
             hipLaunchKernelGGL((mac_scalar_single_kernel<4>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
-                               tiles, count, wbase, plan->term_ct_dev, wtab, ct_in, bias, out);
+                               tiles, count, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
         else
             hipLaunchKernelGGL((mac_scalar_single_kernel<2>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
-                               tiles, count, wbase, plan->term_ct_dev, wtab, ct_in, bias, out);
+                               tiles, count, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
         HE_HIP(hipGetLastError());
         return HE_OK;
     }
-    const u64 blocks = (u64)count * limbs * 2 * (ctx->N / MAC_THREADS);
+    // several groups per workgroup where the kernel can run from one into the next (see mac_scalar_kernel)
+    // and where enough workgroups remain to keep every compute unit's wave slots full several times over
+    const u64 per_group = (u64)limbs * 2 * (ctx->N / MAC_THREADS);
+    u32 per_wg = plan->min_terms_s[cls] > BLOCK_TERMS ? GROUPS_PER_WG : 1;
+    while (per_wg > 1 && (u64)((count + per_wg - 1) / per_wg) * per_group < MIN_WORKGROUPS) per_wg /= 2;
+    const u64 blocks = (u64)((count + per_wg - 1) / per_wg) * per_group;
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     hipLaunchKernelGGL((mac_scalar_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles,
-                       count, wbase, plan->term_ct_dev, wtab, ct_in, bias, out);
+                       count, per_wg, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
