@@ -311,6 +311,55 @@ def test_mac_scalar_and_poly_match_oracle_on_irregular_plan(he, log2N, bits):
                           host(ctx.ct_pt_mac(hp, dev(ct), dev(w), he.PT_SCALAR)))
 
 
+def chained_groups_plan(n_in, seed):
+    """Enough groups of every size class for the kernel to chain several per workgroup, every group
+    with more than 4 terms, term counts changing from group to group."""
+    rng = np.random.default_rng(seed)
+    off, tc, tp, first_of_group = [0], [], [], []
+    n_pt = 0
+    for n_groups, lo, hi in ((2100, 5, 16), (1200, 2, 4), (40, 1, 1)):
+        for _ in range(n_groups):
+            k = int(rng.integers(5, 41))
+            cts = rng.integers(0, n_in, k).tolist()
+            first_of_group.append(len(off) - 1)
+            for _ in range(int(rng.integers(lo, hi + 1))):
+                tc.extend(cts)
+                tp.extend(range(n_pt, n_pt + k))
+                n_pt += k
+                off.append(len(tc))
+    plan = wl.Plan(n_in, len(off) - 1, n_pt, np.asarray(off, np.uint32), np.asarray(tc, np.uint32), np.asarray(tp, np.uint32))
+    return plan, first_of_group
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("bits", [[50, 58], [59, 61, 30]])
+def test_mac_scalar_chains_groups_with_changing_term_counts(he, bits):
+    """Several groups per workgroup (the input ring and the weight pointer run on from one group
+    into the next): whole runs of consecutive groups at both ends of every size class, and random
+    groups in between, against the oracle on a sub-plan."""
+    log2N, N = 11, 1 << 11
+    q = wl.modulus_chain(bits, N)
+    ctx = he.Context(log2N, q)
+    plan, first = chained_groups_plan(37, 77)
+    hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+    ct = wl.uniform_residues((plan.n_in, 2), q, N, 78)
+    w = dev(wl.uniform_residues((plan.n_pt,), q, 1, 79)[..., 0])
+    bias = wl.uniform_residues((plan.n_out,), q, 1, 80)[..., 0]
+    out = ctx.ct_pt_mac(hp, dev(ct), w, he.PT_SCALAR, bias=dev(bias))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(81)
+    groups = set(rng.integers(0, len(first), 40).tolist())
+    for lo, hi in ((0, 2100), (2100, 3300), (3300, 3340)):
+        groups |= set(range(lo, min(lo + 20, hi))) | set(range(max(hi - 20, lo), hi))
+    bounds = first + [plan.n_out]
+    outputs = [o for g in sorted(groups) for o in range(bounds[g], bounds[g + 1])]
+    sub, ct_ids, pt_ids = compact(plan, outputs)
+    want = oracle.mac(ct[ct_ids], q, sub.off, sub.term_ct, sub.term_pt, host(rows(w, pt_ids)), oracle.PT_SCALAR, bias[outputs])
+    assert np.array_equal(host(rows(out, outputs)), want)
+    for l in range(len(q)):                                     # every output, any size: canonical residues
+        assert int(out[:, :, l].max()) < q[l] and int(out[:, :, l].min()) >= 0
+
+
 def test_mac_long_sums_of_extreme_operands(he):
     # (q-1)*(q-1) summed 700 times: crosses every fold and reduce boundary of the accumulator
     N = 1 << 10
