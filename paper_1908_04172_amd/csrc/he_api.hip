@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <map>
 #include <new>
 
 #include "he_internal.h"
@@ -453,6 +454,7 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
     p->off.assign(off, off + n_out + 1);
     p->tiles_s_dev = p->tiles_p_dev = nullptr;
     p->wbase_s_dev = nullptr;
+    p->wowner_s_dev = nullptr;
     p->off_dev = p->term_ct_dev = p->term_pt_dev = nullptr;
     std::vector<Tile> ts, tp;
     build_tiles(off, term_ct, n_out, CAPS_S[2], ts);
@@ -461,19 +463,36 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
     classify(tp, CAPS_P, p->class_begin_p);
     p->n_tiles_s = (u32)ts.size();
     p->n_tiles_p = (u32)tp.size();
+    // Groups of one class that multiply by the same plaintexts in the same arrangement (all windows of a
+    // convolution that have the same shape) share one table of gathered weights: the table then stays
+    // in the scalar cache instead of being fetched anew by every group.  wowner[i] = 1 for the group
+    // that fills the table.
     std::vector<u64> wbase(ts.size() + 1, 0);
+    std::vector<u32> wowner(ts.size() + 1, 0);
     u64 elems = 0;
     for (int cls = 0; cls < 3; ++cls) {
         p->min_terms_s[cls] = p->class_begin_s[cls] < p->class_begin_s[cls + 1] ? ~0u : 0;
+        std::map<std::vector<u32>, u64> tables;
+        std::vector<u32> key;
         for (u32 i = p->class_begin_s[cls]; i < p->class_begin_s[cls + 1]; ++i) {
             p->min_terms_s[cls] = std::min(p->min_terms_s[cls], ts[i].n_terms);
+            key.assign(1, ts[i].n_terms);
+            for (u32 g = 0; g < ts[i].count; ++g)
+                key.insert(key.end(), term_pt + off[ts[i].out0 + g], term_pt + off[ts[i].out0 + g] + ts[i].n_terms);
+            const auto found = tables.find(key);
+            if (found != tables.end()) {
+                wbase[i] = found->second;
+                continue;
+            }
+            tables.emplace(key, elems);
             wbase[i] = elems;
+            wowner[i] = 1;
             elems += (u64)((ts[i].n_terms + 3) / 4 * 4) * CAPS_S[cls];  // terms padded to whole blocks of 4
         }
     }
     p->wtab_elems = elems + 16;  // padding: the 16-output kernel requests one term's weights past its last
     if (upload(&p->tiles_s_dev, ts.data(), ts.size()) != HE_OK || upload(&p->tiles_p_dev, tp.data(), tp.size()) != HE_OK ||
-        upload(&p->wbase_s_dev, wbase.data(), ts.size()) != HE_OK || upload(&p->off_dev, off, (size_t)n_out + 1) != HE_OK ||
+        upload(&p->wbase_s_dev, wbase.data(), ts.size()) != HE_OK || upload(&p->wowner_s_dev, wowner.data(), ts.size()) != HE_OK || upload(&p->off_dev, off, (size_t)n_out + 1) != HE_OK ||
         upload(&p->term_ct_dev, term_ct, n_terms) != HE_OK || upload(&p->term_pt_dev, term_pt, n_terms) != HE_OK) {
         he_plan_destroy(p);
         return HE_ERR_DEVICE;
@@ -485,7 +504,7 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
 int he_plan_destroy(he_plan* p) {
     if (!p) return HE_ERR_ARG;
     if (p->device >= 0 && hipSetDevice(p->device) == hipSuccess) {
-        void* bufs[] = {p->tiles_s_dev, p->tiles_p_dev, p->wbase_s_dev, p->off_dev, p->term_ct_dev, p->term_pt_dev};
+        void* bufs[] = {p->tiles_s_dev, p->tiles_p_dev, p->wbase_s_dev, p->wowner_s_dev, p->off_dev, p->term_ct_dev, p->term_pt_dev};
         for (void* b : bufs)
             if (b) (void)hipFree(b);
     }

@@ -62,6 +62,7 @@ struct he_plan {
     Tile* tiles_s_dev;
     Tile* tiles_p_dev;
     u64* wbase_s_dev;      // per scalar tile: start of its weights in the gathered table, per limb
+    u32* wowner_s_dev;     // per scalar tile: 1 if it fills the table at wbase (tiles with equal plaintexts share one)
     u64 wtab_elems;        // residues per limb in the gathered weight table
     u32 n_tiles_s, n_tiles_p;
     u32* off_dev;

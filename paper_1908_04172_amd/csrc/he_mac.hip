@@ -17,18 +17,19 @@ constexpr u64 MIN_WORKGROUPS = 256 * 32;  // ... while the launch keeps at least
 __host__ __device__ inline u32 padded_terms(u32 n_terms) { return (n_terms + BLOCK_TERMS - 1) / BLOCK_TERMS * BLOCK_TERMS; }
 
 // Weight table for scalar plaintexts: wtab[limb*wtab_elems + wbase + t*G + g], 0 <= t < Kp = n_terms
-// rounded up to a multiple of BLOCK_TERMS (so the groups of a class follow each other within a limb,
-// and every limb's part ends with 16 entries of padding that are read ahead but never used), holds the two pieces (wa | wb << 32, see MacAcc) of
+// rounded up to a multiple of BLOCK_TERMS, holds the two pieces (wa | wb << 32, see MacAcc) of
 // pt[term_pt[off[out0+g] + t]][limb], and zero for g >= tile.count or t >= n_terms.  The MAC loop
 // then reads G consecutive entries per term with scalar loads, runs whole blocks of terms, and needs
-// neither a per-output branch nor a split of the plaintext operand.
+// neither a per-output branch nor a split of the plaintext operand.  Groups with the same plaintext
+// indices share one table (same wbase; the group with wowner set fills it), and every limb's part
+// ends with 16 entries of padding that are read ahead but never used.
 template <int G>
-__global__ void __launch_bounds__(256) gather_weights_kernel(LimbTable lt, const Tile* tiles, const u64* wbase, u32 n_tiles,
+__global__ void __launch_bounds__(256) gather_weights_kernel(LimbTable lt, const Tile* tiles, const u64* wbase, const u32* wowner, u32 n_tiles,
                                                              u32 limbs, const u32* off, const u32* term_pt, const u64* pt,
                                                              u64* wtab, u64 wtab_elems) {
     const u32 tile_i = blockIdx.x / GATHER_BLOCKS;
     const u32 sub = blockIdx.x % GATHER_BLOCKS;
-    if (tile_i >= n_tiles) return;
+    if (tile_i >= n_tiles || !wowner[tile_i]) return;  // a shared table is filled by one of its groups
     const Tile tile = tiles[tile_i];
     const u64 per_limb = (u64)padded_terms(tile.n_terms) * G;
     const u64 total = per_limb * limbs;
@@ -99,11 +100,23 @@ struct ScalarWeights8 {
     __device__ __forceinline__ void arrived() { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(v)); }
 };
 
-// one term's multiply-adds into eight of the sixteen outputs
+// One term's multiply-adds into eight of the sixteen outputs (acc_mac, spelt out).  A multiply-add
+// that reads the sum its predecessor wrote waits for it (the result takes far longer than the issue
+// of one instruction), so the two that go into `mid` are kept 16 instructions apart: four passes over
+// the eight outputs, pinned in this order.
 template <int FIRST>
 __device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[16], u32 xa, u32 xb, const ScalarWeights8& w) {
 #pragma unroll
-    for (int g = 0; g < 8; g++) acc_mac(acc[FIRST + g], xa, xb, w.v[2 * g], w.v[2 * g + 1]);
+    for (int g = 0; g < 8; g++) acc[FIRST + g].lo += (u64)xa * w.v[2 * g];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g < 8; g++) acc[FIRST + g].mid += (u64)xa * w.v[2 * g + 1];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g < 8; g++) acc[FIRST + g].hi += (u64)xb * w.v[2 * g + 1];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g < 8; g++) acc[FIRST + g].mid += (u64)xb * w.v[2 * g];
 }
 
 template <int G>
@@ -204,9 +217,9 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
         // next list's start minus Kp, which may be "negative")
         u32 list0 = first.term0;
         u32 u_last = first.n_terms - 1;
-        // weights of the term being multiplied; within a limb the groups of a class follow each other
-        // in the table, so this pointer simply runs on
-        const u64* wp = wtab + (u64)limb * wtab_elems + uniform_load(wbase + tile_first);
+        // weights of the term being multiplied
+        const u64* w_limb = wtab + (u64)limb * wtab_elems;
+        const u64* wp = w_limb + uniform_load(wbase + tile_first);
         u64 xq[BLOCK_TERMS];
         u32 cq[BLOCK_TERMS];  // ciphertext indices of terms t+4 .. t+7, fetched a block before they are needed
 #pragma unroll
@@ -218,7 +231,7 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
         // two sets.  While one set's multiply-adds run, the other set's next load is in flight: at
         // the start of a term w_lo holds this term's residues for outputs 0..7 and the load of w_hi
         // (outputs 8..15) has been issued.  After the last term of the last group the requests reach
-        // the next group's weights or the table's padding.
+        // whatever follows its table (another table or the padding).
         ScalarWeights8 w_lo, w_hi;
         // where the operands are cut, held in registers for the whole loop (left to itself the
         // compiler fetches the two words again in every block, and waits for them)
@@ -233,10 +246,12 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
             // the group after this one; after the last one the ring stays on this group's last term
             // (loads that hit in the cache and are never used)
             u32 next_list0 = list0 + u_last, next_K = 1;
+            const u64* wp_next_group = wp + (size_t)Kp * G;  // after the last group: whatever follows its table
             if (tile_i + 1 < tile_end) {
                 const Tile next = uniform_load(tiles + tile_i + 1);
                 next_list0 = next.term0;
                 next_K = next.n_terms;
+                wp_next_group = w_limb + uniform_load(wbase + tile_i + 1);
             }
             const Tile cur = uniform_load(tiles + tile_i);
             const u32 out0 = cur.out0, count = cur.count;
@@ -252,6 +267,8 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
                         list0 = next_list0 - Kp;
                         u_last = Kp + next_K - 1;
                     }
+                    // where the weights of the term after this block are
+                    const u64* wp_after = t + BLOCK_TERMS == Kp ? wp_next_group : wp + BLOCK_TERMS * G;
 #pragma unroll
                     for (int j = 0; j < BLOCK_TERMS; j++) {
                         const u64 x = xq[j];
@@ -265,12 +282,12 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
                             scalar_half_term<0>(acc, xa, xb, w_lo);
                             __builtin_amdgcn_sched_barrier(0);
                             w_hi.arrived();
-                            w_lo.request(wp + (j + 1) * G);
+                            w_lo.request(j + 1 < (int)BLOCK_TERMS ? wp + (j + 1) * G : wp_after);
                             __builtin_amdgcn_sched_barrier(0);
                             scalar_half_term<8>(acc, xa, xb, w_hi);
                             __builtin_amdgcn_sched_barrier(0);
                             w_lo.arrived();
-                            w_hi.request(wp + (j + 1) * G + 8);
+                            w_hi.request((j + 1 < (int)BLOCK_TERMS ? wp + (j + 1) * G : wp_after) + 8);
                         } else {
                             u64 wt[G];
                             load_weights<G>(wt, wp + j * G);
@@ -278,7 +295,7 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
                         }
                         __builtin_amdgcn_sched_barrier(0);  // one term at a time: keeps the live values few
                     }
-                    wp += BLOCK_TERMS * G;
+                    wp = wp_after;
                 }
                 if constexpr (G == 16) w_hi.arrived();  // no load in flight outside the block loop
                 f += run;
@@ -475,7 +492,7 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
     if (count == 0) return HE_OK;
     const Tile* tiles = plan->tiles_s_dev + begin;
     const u64* wbase = plan->wbase_s_dev + begin;
-    hipLaunchKernelGGL((gather_weights_kernel<G>), dim3(count * GATHER_BLOCKS), dim3(256), 0, s, ctx->limbs, tiles, wbase, count, limbs, plan->off_dev,
+    hipLaunchKernelGGL((gather_weights_kernel<G>), dim3(count * GATHER_BLOCKS), dim3(256), 0, s, ctx->limbs, tiles, wbase, plan->wowner_s_dev + begin, count, limbs, plan->off_dev,
                        plan->term_pt_dev, pt, wtab, plan->wtab_elems);
     HE_HIP(hipGetLastError());
     if constexpr (G == 1) {
