@@ -172,6 +172,31 @@ int he_ntt_fwd(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, vo
 int he_ntt_inv(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, void* stream);
 
 /*
+ * Packed 32-bit storage: the paper's optimisation for moduli of at most 32 bits (Sec.
+ * "Ciphertext-plaintext Multiplication": BarrettReduction64, Alg. 6, and Alg. 8) with the residues
+ * stored as uint32, half the bytes of the 64-bit form.  The calls below mirror he_ct_pt_mac,
+ * he_ct_pt_add, he_rescale, he_ntt_fwd and he_ntt_inv on tensors dev uint32 [ct][2][limbs][N] and
+ * compute the same residues.  Every limb of the level must be below 2^30 (the lazy 32-bit butterflies
+ * need 4q < 2^32), else HE_ERR_MODULUS.  Scalar plaintexts and biases stay uint64 [n][limbs], as
+ * he_encode_scalar writes them; full-polynomial plaintexts are dev uint32 [n_pt][limbs][N].
+ *
+ * he_pack32 / he_unpack32 convert `count` residues between the two forms (dev pointers, which must
+ * not overlap; values of at least 2^32 lose their high word in he_pack32).
+ * he_ct_pt_mac32 takes the same plan and the same workspace size (he_plan_workspace_bytes) as
+ * he_ct_pt_mac, and the same flags; the no-overlap rule of he_ct_pt_mac applies.
+ */
+int he_pack32(he_ctx* ctx, const uint64_t* in, uint32_t* out, size_t count, void* stream);
+int he_unpack32(he_ctx* ctx, const uint32_t* in, uint64_t* out, size_t count, void* stream);
+int he_ct_pt_mac32(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint32_t* ct_in, const void* pt,
+                   int pt_kind, const uint64_t* bias, uint32_t* ct_out, uint32_t flags, void* workspace,
+                   size_t workspace_bytes, void* stream);
+int he_ct_pt_add32(he_ctx* ctx, uint32_t limbs, uint32_t* ct, uint32_t n, const void* pt, int pt_kind,
+                   void* stream);
+int he_rescale32(he_ctx* ctx, uint32_t limbs, const uint32_t* in, uint32_t* out, uint32_t n, void* stream);
+int he_ntt_fwd32(he_ctx* ctx, uint32_t limbs, uint32_t* data, uint32_t n_polys, void* stream);
+int he_ntt_inv32(he_ctx* ctx, uint32_t limbs, uint32_t* data, uint32_t n_polys, void* stream);
+
+/*
  * Host-side checks of the device arithmetic (the same inline functions the kernels use, compiled
  * for the host): a*b mod q by 128-bit Barrett reduction (Alg. 5), and the lazy Shoup product used
  * in the NTT butterflies.  For tests; no device needed.

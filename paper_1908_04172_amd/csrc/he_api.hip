@@ -282,6 +282,16 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
         ctx->psi[i] = h_min_psi(moduli[i], N);
         if (!ctx->psi[i]) { delete ctx; return HE_ERR_MODULUS; }
         fill_limb_const(ctx->limbs.c[i], ctx->q[i], ctx->psi[i], N);
+        if (ctx->q[i] < (1ull << 30)) {  // the limb has a packed 32-bit form
+            Limb32& c = ctx->limbs32.c[i];
+            const u64 q = ctx->q[i], n_inv = ctx->limbs.c[i].n_inv;
+            c.q = (u32)q;
+            c.two_q = (u32)(2 * q);
+            c.n_inv = (u32)n_inv;
+            c.n_inv_shoup = (u32)((n_inv << 32) / q);
+            c.ratio = (u64)((((u128)1) << 64) / q);
+            c.ok = 1;
+        }
     }
     for (u32 j = 0; j < L; ++j)
         for (u32 i = 0; i < L; ++i) {
@@ -309,6 +319,23 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
                 pw = h_mulmod(pw, psi, q);
                 pwi = h_mulmod(pwi, psi_inv, q);
             }
+        }
+        // 32-bit tables for the limbs that have a packed form (moduli below 2^30), zeros for the others
+        std::vector<u32> fwd32((size_t)L * N * 2, 0), inv32((size_t)L * N * 2, 0);
+        for (u32 i = 0; i < L; ++i) {
+            if (!ctx->limbs32.c[i].ok) continue;
+            const u64 q = ctx->q[i];
+            for (size_t k = 0; k < N; ++k) {
+                const size_t slot = ((size_t)i * N + k) * 2;
+                fwd32[slot] = (u32)fwd[slot];
+                fwd32[slot + 1] = (u32)((fwd[slot] << 32) / q);
+                inv32[slot] = (u32)inv[slot];
+                inv32[slot + 1] = (u32)((inv[slot] << 32) / q);
+            }
+        }
+        if (upload(&ctx->tw32_fwd, fwd32.data(), fwd32.size()) != HE_OK || upload(&ctx->tw32_inv, inv32.data(), inv32.size()) != HE_OK) {
+            he_ctx_destroy(ctx);
+            return HE_ERR_DEVICE;
         }
         // tables of the general encoder: e^(-2 pi i k / (N/2)) for k < N/4, and e^(-i pi j / N) for j < N/2
         std::vector<double> fft_tw((size_t)N / 2), twist((size_t)N);
@@ -357,6 +384,8 @@ int he_ctx_destroy(he_ctx* ctx) {
         if (ctx->twist) (void)hipFree(ctx->twist);
         if (ctx->garner) (void)hipFree(ctx->garner);
         if (ctx->half_digits) (void)hipFree(ctx->half_digits);
+        if (ctx->tw32_fwd) (void)hipFree(ctx->tw32_fwd);
+        if (ctx->tw32_inv) (void)hipFree(ctx->tw32_inv);
     }
     if (ctx->device >= 0) (void)hipGetLastError();  // a failure here must not surface in the caller's next HIP call
     delete ctx;
@@ -608,6 +637,109 @@ int he_ntt_inv(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, vo
     if (!data) return HE_ERR_ARG;
     if ((rc = need_device(ctx)) != HE_OK) return rc;
     return launch_ntt(ctx, limbs, data, n_polys, true, (hipStream_t)stream);
+}
+
+// ---- packed 32-bit storage
+
+// every limb of the level must have a 32-bit form
+static int check_level32(const he_ctx* ctx, u32 limbs, u32 min_limbs) {
+    int rc = check_level(ctx, limbs, min_limbs);
+    if (rc != HE_OK) return rc;
+    for (u32 i = 0; i < limbs; ++i)
+        if (!ctx->limbs32.c[i].ok) return HE_ERR_MODULUS;
+    return HE_OK;
+}
+
+int he_pack32(he_ctx* ctx, const uint64_t* in, uint32_t* out, size_t count, void* stream) {
+    if (!ctx) return HE_ERR_ARG;
+    if (count == 0) return HE_OK;
+    if (!in || !out) return HE_ERR_ARG;
+    if (overlaps(in, count * sizeof(u64), out, count * sizeof(u32))) return HE_ERR_ARG;
+    int rc = need_device(ctx);
+    if (rc != HE_OK) return rc;
+    return launch_pack32(ctx, in, out, count, (hipStream_t)stream);
+}
+
+int he_unpack32(he_ctx* ctx, const uint32_t* in, uint64_t* out, size_t count, void* stream) {
+    if (!ctx) return HE_ERR_ARG;
+    if (count == 0) return HE_OK;
+    if (!in || !out) return HE_ERR_ARG;
+    if (overlaps(in, count * sizeof(u32), out, count * sizeof(u64))) return HE_ERR_ARG;
+    int rc = need_device(ctx);
+    if (rc != HE_OK) return rc;
+    return launch_unpack32(ctx, in, out, count, (hipStream_t)stream);
+}
+
+int he_ct_pt_mac32(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint32_t* ct_in, const void* pt, int pt_kind,
+                   const uint64_t* bias, uint32_t* ct_out, uint32_t flags, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+    if (!ctx || !plan || plan->ctx != ctx) return HE_ERR_ARG;
+    size_t need = 0;
+    int rc = he_plan_workspace_bytes(plan, limbs, pt_kind, flags, &need);
+    if (rc != HE_OK) return rc;
+    if ((rc = check_level32(ctx, limbs, (flags & HE_RESCALE) ? 2 : 1)) != HE_OK) return rc;
+    if (plan->n_out == 0) return HE_OK;
+    if (!ct_out || (plan->n_terms && (!ct_in || !pt))) return HE_ERR_ARG;
+    if (need && (!workspace || workspace_bytes < need)) return HE_ERR_WORKSPACE;
+    {
+        const size_t row = (size_t)ctx->N * sizeof(u32);
+        const size_t out_bytes = (size_t)plan->n_out * 2 * ((flags & HE_RESCALE) ? limbs - 1 : limbs) * row;
+        const size_t pt_bytes = (size_t)plan->n_pt * limbs * (pt_kind == HE_PT_POLY ? row : sizeof(u64));
+        if (overlaps(ct_out, out_bytes, ct_in, (size_t)plan->n_in * 2 * limbs * row) || overlaps(ct_out, out_bytes, pt, pt_bytes) ||
+            overlaps(ct_out, out_bytes, bias, (size_t)plan->n_out * limbs * sizeof(u64)) || overlaps(ct_out, out_bytes, workspace, need))
+            return HE_ERR_ARG;
+    }
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if (flags & HE_RESCALE) {
+        // the workspace is sized for the 64-bit form: the weight table first, the accumulators after it
+        char* ws = (char*)workspace;
+        if (pt_kind == HE_PT_SCALAR) ws += align256((size_t)plan->wtab_elems * limbs * sizeof(u64));
+        u32* acc = (u32*)ws;
+        if ((rc = launch_mac32(ctx, plan, limbs, ct_in, pt, pt_kind, bias, acc, workspace, s)) != HE_OK) return rc;
+        return launch_rescale32(ctx, limbs, acc, ct_out, plan->n_out, s);
+    }
+    return launch_mac32(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, workspace, s);
+}
+
+int he_ct_pt_add32(he_ctx* ctx, uint32_t limbs, uint32_t* ct, uint32_t n, const void* pt, int pt_kind, void* stream) {
+    int rc = check_level32(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (pt_kind != HE_PT_SCALAR && pt_kind != HE_PT_POLY) return HE_ERR_ARG;
+    if (n == 0) return HE_OK;
+    if (!ct || !pt) return HE_ERR_ARG;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    return launch_add32(ctx, limbs, ct, n, pt, pt_kind, (hipStream_t)stream);
+}
+
+int he_rescale32(he_ctx* ctx, uint32_t limbs, const uint32_t* in, uint32_t* out, uint32_t n, void* stream) {
+    int rc = check_level32(ctx, limbs, 2);
+    if (rc != HE_OK) return rc;
+    if (n == 0) return HE_OK;
+    if (!in || !out) return HE_ERR_ARG;
+    if (n > 0x3FFFFFFFu) return HE_ERR_RANGE;
+    if (overlaps(in, (size_t)n * 2 * limbs * ctx->N * sizeof(u32), out, (size_t)n * 2 * (limbs - 1) * ctx->N * sizeof(u32)))
+        return HE_ERR_ARG;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    return launch_rescale32(ctx, limbs, in, out, n, (hipStream_t)stream);
+}
+
+static int ntt32_entry(he_ctx* ctx, uint32_t limbs, uint32_t* data, uint32_t n_polys, bool inverse, void* stream) {
+    int rc = check_level32(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (n_polys == 0) return HE_OK;
+    if (!data) return HE_ERR_ARG;
+    if ((u64)n_polys * limbs > 0x7FFFFFFFull) return HE_ERR_RANGE;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    return launch_ntt32(ctx, limbs, data, n_polys * limbs, inverse, (hipStream_t)stream);
+}
+
+int he_ntt_fwd32(he_ctx* ctx, uint32_t limbs, uint32_t* data, uint32_t n_polys, void* stream) {
+    return ntt32_entry(ctx, limbs, data, n_polys, false, stream);
+}
+
+int he_ntt_inv32(he_ctx* ctx, uint32_t limbs, uint32_t* data, uint32_t n_polys, void* stream) {
+    return ntt32_entry(ctx, limbs, data, n_polys, true, stream);
 }
 
 // ---- host-side checks of the device arithmetic

@@ -27,6 +27,28 @@ struct DropRow {
     DropConst d[HE_MAX_LIMBS];
 };
 
+// ---- packed 32-bit storage (moduli below 2^30: Sec. "Ciphertext-plaintext Multiplication", Alg. 6 / Alg. 8)
+// Per-limb constants of the 32-bit arithmetic.
+struct Limb32 {
+    u32 q, two_q;
+    u32 n_inv, n_inv_shoup;  // N^-1 mod q and floor(N^-1 * 2^32 / q)
+    u64 ratio;               // floor(2^64 / q): the Barrett ratio of Alg. 6
+    u32 ok;                  // 1 if this limb's modulus is below 2^30 (else the limb has no 32-bit form)
+    u32 pad;
+};
+struct Limb32Table {
+    Limb32 c[HE_MAX_LIMBS];
+};
+// Dropping limb j while keeping limb i < j, 32-bit constants.
+struct Drop32 {
+    u32 p_inv, p_inv_shoup;  // q_j^-1 mod q_i and floor(that * 2^32 / q_i)
+    u32 half_mod;            // floor(q_j / 2) mod q_i
+    u32 pad;
+};
+struct Drop32Row {
+    Drop32 d[HE_MAX_LIMBS];
+};
+
 struct he_ctx {
     int device;  // -1: host-only
     u32 log2N, N, L;
@@ -40,6 +62,9 @@ struct he_ctx {
     double* twist;    // [N/2][2]: e^(-i pi j / N), the twist that follows it
     u64* garner;      // [L][L][2]: (q_k^-1 mod q_i, Shoup companion) at [i][k], for the decoder's lift
     u64* half_digits; // [L+1][L]: mixed-radix digits of floor(q_0...q_{l-1} / 2) for every level l
+    Limb32Table limbs32;
+    u32* tw32_fwd;    // [L][N][2]: (psi^brv(k), floor(that * 2^32 / q)) for limbs below 2^30, else zeros
+    u32* tw32_inv;    // [L][N][2]: the same for psi^-brv(k)
 };
 
 // One group of outputs that read the same ciphertexts in the same order.
@@ -98,5 +123,13 @@ int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, co
 int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s);
 int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s);
 int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s);
+// packed 32-bit storage (he_packed32.hip)
+int launch_pack32(he_ctx* ctx, const u64* in, u32* out, size_t count, hipStream_t s);
+int launch_unpack32(he_ctx* ctx, const u32* in, u64* out, size_t count, hipStream_t s);
+int launch_mac32(he_ctx* ctx, const he_plan* plan, u32 limbs, const u32* ct_in, const void* pt, int pt_kind, const u64* bias,
+                 u32* out, void* workspace, hipStream_t s);
+int launch_add32(he_ctx* ctx, u32 limbs, u32* ct, u32 n, const void* pt, int pt_kind, hipStream_t s);
+int launch_ntt32(he_ctx* ctx, u32 limbs, u32* data, u32 rows, bool inverse, hipStream_t s);
+int launch_rescale32(he_ctx* ctx, u32 limbs, const u32* in, u32* out, u32 n, hipStream_t s);
 int launch_encode_vector(he_ctx* ctx, u32 limbs, const double* slots, u32 n, double scale, u64* out, hipStream_t s);
 int launch_decode_vector(he_ctx* ctx, u32 limbs, const u64* coef, u32 n, double scale, double* slots, hipStream_t s);

@@ -28,6 +28,7 @@ EXPORTS = [
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_measure_rate",
+    "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
 ]
 
 _lib = None
@@ -73,6 +74,13 @@ def lib():
         "he_host_mac_accumulate_add": (u64, [vp, vp, sz, u64, u64]),
         "he_measure_rate": (i32, [vp, i32, u32, u32, ctypes.POINTER(ctypes.c_double)]),
         "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
+        "he_pack32": (i32, [vp, vp, vp, sz, vp]),
+        "he_unpack32": (i32, [vp, vp, vp, sz, vp]),
+        "he_ct_pt_mac32": (i32, [vp, vp, u32, vp, vp, i32, vp, vp, u32, vp, sz, vp]),
+        "he_ct_pt_add32": (i32, [vp, u32, vp, u32, vp, i32, vp]),
+        "he_rescale32": (i32, [vp, u32, vp, vp, u32, vp]),
+        "he_ntt_fwd32": (i32, [vp, u32, vp, u32, vp]),
+        "he_ntt_inv32": (i32, [vp, u32, vp, u32, vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(L, name)
@@ -106,7 +114,7 @@ def _dev_ptr(t, name: str) -> Optional[int]:
     import torch
     if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
         raise TypeError(f"{name} must be a contiguous CUDA tensor")
-    if t.dtype not in (torch.int64, torch.float64, torch.uint8, torch.complex128):
+    if t.dtype not in (torch.int64, torch.int32, torch.float64, torch.uint8, torch.complex128):
         raise TypeError(f"{name}: unexpected dtype {t.dtype}")
     return t.data_ptr()
 
@@ -250,6 +258,82 @@ class Context:
                                   _dev_ptr(bias, "bias"), _dev_ptr(out, "ct_out"), flags, _dev_ptr(workspace, "workspace"),
                                   ws_bytes, _stream()), "he_ct_pt_mac")
         return out
+
+
+    # -- packed 32-bit storage (moduli below 2^30): int32 tensors whose bit patterns are the uint32 residues
+    def pack32(self, t):
+        import torch
+        assert t.dtype == torch.int64
+        out = torch.empty(t.shape, dtype=torch.int32, device=t.device)
+        _check(lib().he_pack32(self._h, _dev_ptr(t, "in"), _dev_ptr(out, "out"), t.numel(), _stream()), "he_pack32")
+        return out
+
+    def unpack32(self, t):
+        import torch
+        assert t.dtype == torch.int32
+        out = torch.empty(t.shape, dtype=torch.int64, device=t.device)
+        _check(lib().he_unpack32(self._h, _dev_ptr(t, "in"), _dev_ptr(out, "out"), t.numel(), _stream()), "he_unpack32")
+        return out
+
+    def ct_pt_mac32(self, plan: "Plan", ct_in, pt, pt_kind: int, bias=None, flags: int = 0, out=None, workspace=None):
+        import torch
+        limbs = ct_in.shape[2]
+        assert ct_in.dtype == torch.int32 and tuple(ct_in.shape) == (plan.n_in, 2, limbs, self.N)
+        if pt_kind == PT_SCALAR:
+            assert pt.dtype == torch.int64 and tuple(pt.shape) == (plan.n_pt, limbs)
+        else:
+            assert pt.dtype == torch.int32 and tuple(pt.shape) == (plan.n_pt, limbs, self.N)
+        if bias is not None:
+            assert bias.dtype == torch.int64 and tuple(bias.shape) == (plan.n_out, limbs)
+        out_limbs = limbs - 1 if flags & RESCALE else limbs
+        if out is None:
+            out = torch.empty((plan.n_out, 2, out_limbs, self.N), dtype=torch.int32, device=ct_in.device)
+        assert out.dtype == torch.int32 and tuple(out.shape) == (plan.n_out, 2, out_limbs, self.N)
+        need = plan.workspace_bytes(limbs, pt_kind, flags)
+        if workspace is None and need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=ct_in.device)
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        _check(lib().he_ct_pt_mac32(self._h, plan._h, limbs, _dev_ptr(ct_in, "ct_in"), _dev_ptr(pt, "pt"), pt_kind,
+                                    _dev_ptr(bias, "bias"), _dev_ptr(out, "ct_out"), flags, _dev_ptr(workspace, "workspace"),
+                                    ws_bytes, _stream()), "he_ct_pt_mac32")
+        return out
+
+    def ct_pt_add32(self, ct, pt, pt_kind: int):
+        import torch
+        n, two, limbs, N = ct.shape
+        assert ct.dtype == torch.int32 and two == 2 and N == self.N
+        if pt_kind == PT_SCALAR:
+            assert pt.dtype == torch.int64 and tuple(pt.shape) == (n, limbs)
+        else:
+            assert pt.dtype == torch.int32 and tuple(pt.shape) == (n, limbs, self.N)
+        _check(lib().he_ct_pt_add32(self._h, limbs, _dev_ptr(ct, "ct"), n, _dev_ptr(pt, "pt"), pt_kind, _stream()),
+               "he_ct_pt_add32")
+        return ct
+
+    def rescale32(self, ct, out=None):
+        import torch
+        n, two, limbs, N = ct.shape
+        assert ct.dtype == torch.int32 and two == 2 and N == self.N
+        if out is None:
+            out = torch.empty((n, 2, limbs - 1, N), dtype=torch.int32, device=ct.device)
+        _check(lib().he_rescale32(self._h, limbs, _dev_ptr(ct, "in"), _dev_ptr(out, "out"), n, _stream()), "he_rescale32")
+        return out
+
+    def ntt_fwd32(self, data):
+        import torch
+        limbs, N = data.shape[-2:]
+        assert data.dtype == torch.int32 and N == self.N
+        _check(lib().he_ntt_fwd32(self._h, limbs, _dev_ptr(data, "data"), data.numel() // (limbs * N), _stream()),
+               "he_ntt_fwd32")
+        return data
+
+    def ntt_inv32(self, data):
+        import torch
+        limbs, N = data.shape[-2:]
+        assert data.dtype == torch.int32 and N == self.N
+        _check(lib().he_ntt_inv32(self._h, limbs, _dev_ptr(data, "data"), data.numel() // (limbs * N), _stream()),
+               "he_ntt_inv32")
+        return data
 
 
 class Plan:
