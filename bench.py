@@ -390,6 +390,50 @@ def main() -> int:
                                         "ciphertext read per multiply (the per-call formulation of Alg. 7/8) would move, "
                                         "which reuse lets exceed the HBM peak", "configs": per}
 
+    # ---- packed 32-bit storage (moduli below 2^30, cfg1's parameter set: N = 2^12, two 30-bit limbs) next
+    # to the 64-bit path on the same residues: a dense layer large enough to time, the streaming add, and
+    # the rescale on its own
+    if not only and args.all_configs:
+        c1 = wl.config(1)
+        cx = he.Context(c1.log2N, c1.q, device=0)
+        K1, M1, n_big = 1024, 256, 8192
+        pl = wl.dense_plan(K1, M1)
+        hp1 = cx.plan(pl.n_in, pl.n_out, pl.n_pt, pl.off, pl.term_ct, pl.term_pt)
+        sc1 = 2.0 ** c1.log2_scale
+        big64 = wl.uniform_residues_torch((n_big, 2), c1.q, c1.N, 11, dev)
+        big32 = cx.pack32(big64)
+        w1 = cx.encode_scalar(torch.from_numpy(wl.normal_values(pl.n_pt, 0.1, 12)).to(dev), sc1)
+        b1 = cx.encode_scalar(torch.from_numpy(wl.normal_values(pl.n_out, 0.1, 13)).to(dev), sc1)
+        ws1 = torch.empty(max(hp1.workspace_bytes(c1.L, he.PT_SCALAR, he.RESCALE), 256), dtype=torch.uint8, device=dev)
+        o64 = torch.empty((M1, 2, c1.L - 1, c1.N), dtype=torch.int64, device=dev)
+        o32 = torch.empty((M1, 2, c1.L - 1, c1.N), dtype=torch.int32, device=dev)
+        ms_l64 = timed(lambda: cx.ct_pt_mac(hp1, big64[:K1], w1, he.PT_SCALAR, bias=b1, flags=he.RESCALE, out=o64, workspace=ws1), 20)
+        ms_l32 = timed(lambda: cx.ct_pt_mac32(hp1, big32[:K1], w1, he.PT_SCALAR, bias=b1, flags=he.RESCALE, out=o32, workspace=ws1), 20)
+        same = bool(torch.equal(cx.unpack32(o32), o64))
+        pa = cx.encode_scalar(torch.from_numpy(wl.normal_values(n_big, 0.1, 14)).to(dev), sc1)
+        ms_a64 = timed(lambda: cx.ct_pt_add(big64, pa, he.PT_SCALAR), 20)
+        ms_a32 = timed(lambda: cx.ct_pt_add32(big32, pa, he.PT_SCALAR), 20)
+        r64 = torch.empty((n_big, 2, c1.L - 1, c1.N), dtype=torch.int64, device=dev)
+        r32 = torch.empty((n_big, 2, c1.L - 1, c1.N), dtype=torch.int32, device=dev)
+        ms_r64 = timed(lambda: cx.rescale(big64, out=r64), 10)
+        ms_r32 = timed(lambda: cx.rescale32(big32, out=r32), 10)
+        resid = n_big * c1.L * c1.N                              # residues of component 0 (read and written)
+        res_b = lambda width, ms: n_big * 2 * (2 * c1.L - 1) * c1.N * width / (ms * 1e-3) / 1e9
+        result["packed32"] = {
+            "what": "cfg1's parameter set (N=2^12, two 30-bit limbs), the same residues stored as uint64 and as uint32",
+            "dense_%dx%d_layer" % (K1, M1): {"ms_u64": ms_l64, "ms_u32": ms_l32, "speedup": ms_l64 / ms_l32,
+                                              "outputs_equal": same,
+                                              "G_mac_residue_terms_per_s_u32": K1 * M1 * 2 * c1.L * c1.N / (ms_l32 * 1e-3) / 1e9},
+            "ct_pt_add_scalar_%d_ct" % n_big: {"ms_u64": ms_a64, "ms_u32": ms_a32,
+                                                "GBps_u64": resid * 16 / (ms_a64 * 1e-3) / 1e9,
+                                                "GBps_u32": resid * 8 / (ms_a32 * 1e-3) / 1e9,
+                                                "G_residues_per_s_u64": resid / (ms_a64 * 1e-3) / 1e9,
+                                                "G_residues_per_s_u32": resid / (ms_a32 * 1e-3) / 1e9},
+            "rescale_%d_ct" % n_big: {"ms_u64": ms_r64, "ms_u32": ms_r32, "speedup": ms_r64 / ms_r32,
+                                      "GBps_u64": res_b(8, ms_r64), "GBps_u32": res_b(4, ms_r32),
+                                      "ct_per_s_u32": n_big / (ms_r32 * 1e-3)}}
+        del big64, big32, r64, r32
+
     print(json.dumps(result))
     return 0
 

@@ -231,54 +231,106 @@ __global__ void __launch_bounds__(256) add32_kernel(Limb32Table lt, u32 limbs, u
 // ---------------------------------------------------------------------------------------------
 // Negacyclic transforms of a row held in LDS (same root and output order as the 64-bit entry points:
 // slot j holds the value at psi^(2*bitrev(j)+1)).  Harvey's lazy butterflies in 32 bits: forward values
-// stay in [0, 4q), inverse values in [0, 2q); both need 4q < 2^32.  The row comes back in [0, q).
-// Every thread of the workgroup must call; the caller has synchronised after filling `a`.
+// stay in [0, 4q), inverse values in [0, 2q); both need 4q < 2^32.  Two stages are taken per trip
+// through LDS (four values per thread in registers), a single one when the number of stages is odd.
+// The "lazy" transforms leave the last reduction (and, for the inverse, the factor N^-1) to the caller,
+// who applies finish_forward / finish_inverse to each value as it consumes it.  Every thread of the
+// workgroup must call; the caller has synchronised after filling `a`, and the transforms end with a
+// barrier.
 
-__device__ void ntt32_forward(u32* a, const uint2* tw, u32 N, const Limb32& c) {
-    const u32 q = c.q, two_q = c.two_q;
-    u32 t = N >> 1, logt = 31 - __clz(t);
-    for (u32 m = 1; m < N; m <<= 1, t >>= 1, --logt) {
-        for (u32 b = threadIdx.x; b < N / 2; b += blockDim.x) {
-            const u32 i = b >> logt, j = b & (t - 1);
-            const u32 pos = (i << (logt + 1)) + j;
-            const uint2 w = tw[m + i];
-            u32 x = a[pos];
-            const u32 y = a[pos + t];
-            x = x >= two_q ? x - two_q : x;
-            const u32 v = shoup32(y, w.x, w.y, q);
-            a[pos] = x + v;
-            a[pos + t] = x - v + two_q;
-        }
-        __syncthreads();
-    }
-    for (u32 k = threadIdx.x; k < N; k += blockDim.x) {
-        u32 v = a[k];
-        v = v >= two_q ? v - two_q : v;
-        a[k] = v >= q ? v - q : v;
-    }
-    __syncthreads();
+__device__ __forceinline__ void bfly32_fwd(u32& x, u32& y, uint2 w, u32 q, u32 two_q) {  // (X, Y) -> (X + W*Y, X - W*Y)
+    const u32 u = x >= two_q ? x - two_q : x;
+    const u32 v = shoup32(y, w.x, w.y, q);
+    x = u + v;
+    y = u - v + two_q;
 }
 
-__device__ void ntt32_inverse(u32* a, const uint2* tw, u32 N, const Limb32& c) {
+__device__ __forceinline__ void bfly32_inv(u32& x, u32& y, uint2 w, u32 q, u32 two_q) {  // (X, Y) -> (X + Y, (X - Y)*W)
+    const u32 s = x + y;
+    const u32 d = x - y + two_q;
+    x = s >= two_q ? s - two_q : s;
+    y = shoup32(d, w.x, w.y, q);
+}
+
+__device__ __forceinline__ u32 finish_forward(u32 v, const Limb32& c) {  // [0, 4q) -> [0, q)
+    v = v >= c.two_q ? v - c.two_q : v;
+    return v >= c.q ? v - c.q : v;
+}
+
+__device__ __forceinline__ u32 finish_inverse(u32 v, const Limb32& c) {  // [0, 2q) -> times N^-1, in [0, q)
+    v = shoup32(v, c.n_inv, c.n_inv_shoup, c.q);
+    return v >= c.q ? v - c.q : v;
+}
+
+__device__ void ntt32_forward_lazy(u32* a, const uint2* tw, u32 N, const Limb32& c) {
     const u32 q = c.q, two_q = c.two_q;
-    u32 t = 1, logt = 0;
-    for (u32 m = N >> 1; m >= 1; m >>= 1, t <<= 1, ++logt) {
-        for (u32 b = threadIdx.x; b < N / 2; b += blockDim.x) {
-            const u32 i = b >> logt, j = b & (t - 1);
-            const u32 pos = (i << (logt + 1)) + j;
-            const uint2 w = tw[m + i];
-            const u32 u = a[pos], v = a[pos + t];
-            const u32 s = u + v;
-            a[pos] = s >= two_q ? s - two_q : s;
-            a[pos + t] = shoup32(u - v + two_q, w.x, w.y, q);
+    u32 m = 1, t = N >> 1, logt = 31 - __clz(t);
+    while (m < N) {
+        if (2 * m < N) {  // the stages with distances t and t/2
+            const u32 h = t >> 1;
+            for (u32 b = threadIdx.x; b < N / 4; b += blockDim.x) {
+                const u32 i = b >> (logt - 1), j = b & (h - 1);
+                const u32 p = (i << (logt + 1)) + j;
+                u32 x0 = a[p], x1 = a[p + h], x2 = a[p + t], x3 = a[p + t + h];
+                const uint2 w1 = tw[m + i];
+                bfly32_fwd(x0, x2, w1, q, two_q);
+                bfly32_fwd(x1, x3, w1, q, two_q);
+                bfly32_fwd(x0, x1, tw[2 * m + 2 * i], q, two_q);
+                bfly32_fwd(x2, x3, tw[2 * m + 2 * i + 1], q, two_q);
+                a[p] = x0;
+                a[p + h] = x1;
+                a[p + t] = x2;
+                a[p + t + h] = x3;
+            }
+            m <<= 2;
+            t >>= 2;
+            logt -= 2;
+        } else {  // a last single stage (distance 1)
+            for (u32 b = threadIdx.x; b < N / 2; b += blockDim.x) {
+                u32 x = a[2 * b], y = a[2 * b + 1];
+                bfly32_fwd(x, y, tw[m + b], q, two_q);
+                a[2 * b] = x;
+                a[2 * b + 1] = y;
+            }
+            m <<= 1;
         }
         __syncthreads();
     }
-    for (u32 k = threadIdx.x; k < N; k += blockDim.x) {
-        const u32 v = shoup32(a[k], c.n_inv, c.n_inv_shoup, q);
-        a[k] = v >= q ? v - q : v;
+}
+
+__device__ void ntt32_inverse_lazy(u32* a, const uint2* tw, u32 N, const Limb32& c) {
+    const u32 q = c.q, two_q = c.two_q;
+    u32 m = N >> 1, t = 1, logt = 0;  // m groups of butterflies at distance t
+    while (m >= 1) {
+        if (m >= 2) {  // the stages with distances t and 2t
+            for (u32 b = threadIdx.x; b < N / 4; b += blockDim.x) {
+                const u32 i = b >> logt, j = b & (t - 1);
+                const u32 p = (i << (logt + 2)) + j;
+                u32 x0 = a[p], x1 = a[p + t], x2 = a[p + 2 * t], x3 = a[p + 3 * t];
+                bfly32_inv(x0, x1, tw[m + 2 * i], q, two_q);
+                bfly32_inv(x2, x3, tw[m + 2 * i + 1], q, two_q);
+                const uint2 w = tw[(m >> 1) + i];
+                bfly32_inv(x0, x2, w, q, two_q);
+                bfly32_inv(x1, x3, w, q, two_q);
+                a[p] = x0;
+                a[p + t] = x1;
+                a[p + 2 * t] = x2;
+                a[p + 3 * t] = x3;
+            }
+            m >>= 2;
+            t <<= 2;
+            logt += 2;
+        } else {  // a last single stage (one group, distance N/2)
+            for (u32 b = threadIdx.x; b < N / 2; b += blockDim.x) {
+                u32 x = a[b], y = a[b + t];
+                bfly32_inv(x, y, tw[1], q, two_q);
+                a[b] = x;
+                a[b + t] = y;
+            }
+            m = 0;
+        }
+        __syncthreads();
     }
-    __syncthreads();
 }
 
 template <bool INVERSE>
@@ -286,13 +338,18 @@ __global__ void __launch_bounds__(1024) ntt32_rows_kernel(Limb32Table lt, u32 li
     extern __shared__ u32 lds32[];
     const size_t row_i = blockIdx.x;
     const u32 limb = (u32)(row_i % limbs);
+    const Limb32& c = lt.c[limb];
     u32* row = data + row_i * N;
     const uint2* tw = reinterpret_cast<const uint2*>(tw_all) + (size_t)limb * N;
     for (u32 k = threadIdx.x; k < N; k += blockDim.x) lds32[k] = row[k];
     __syncthreads();
-    if (INVERSE) ntt32_inverse(lds32, tw, N, lt.c[limb]);
-    else ntt32_forward(lds32, tw, N, lt.c[limb]);
-    for (u32 k = threadIdx.x; k < N; k += blockDim.x) row[k] = lds32[k];
+    if (INVERSE) {
+        ntt32_inverse_lazy(lds32, tw, N, c);
+        for (u32 k = threadIdx.x; k < N; k += blockDim.x) row[k] = finish_inverse(lds32[k], c);
+    } else {
+        ntt32_forward_lazy(lds32, tw, N, c);
+        for (u32 k = threadIdx.x; k < N; k += blockDim.x) row[k] = finish_forward(lds32[k], c);
+    }
 }
 
 // Rescale, Eq. (2) in RNS form, one workgroup per polynomial (ciphertext, component):
@@ -311,10 +368,10 @@ __global__ void __launch_bounds__(1024) rescale32_kernel(Limb32Table lt, Drop32R
         const Limb32& c = lt.c[last];
         for (u32 k = threadIdx.x; k < N; k += blockDim.x) trow[k] = src[(size_t)last * N + k];
         __syncthreads();
-        ntt32_inverse(trow, reinterpret_cast<const uint2*>(tw_inv) + (size_t)last * N, N, c);
+        ntt32_inverse_lazy(trow, reinterpret_cast<const uint2*>(tw_inv) + (size_t)last * N, N, c);
+        // (in the loops below every thread touches only the elements k = tid mod blockDim, as here)
         const u32 half = c.q >> 1;
-        for (u32 k = threadIdx.x; k < N; k += blockDim.x) trow[k] = add_mod32(trow[k], half, c.q);
-        __syncthreads();
+        for (u32 k = threadIdx.x; k < N; k += blockDim.x) trow[k] = add_mod32(finish_inverse(trow[k], c), half, c.q);
     }
     for (u32 i = 0; i < last; i++) {
         const Limb32& c = lt.c[i];
@@ -324,16 +381,19 @@ __global__ void __launch_bounds__(1024) rescale32_kernel(Limb32Table lt, Drop32R
             wrow[k] = r >= d.half_mod ? r - d.half_mod : r + c.q - d.half_mod;
         }
         __syncthreads();
-        ntt32_forward(wrow, reinterpret_cast<const uint2*>(tw_fwd) + (size_t)i * N, N, c);
+        ntt32_forward_lazy(wrow, reinterpret_cast<const uint2*>(tw_fwd) + (size_t)i * N, N, c);
         for (u32 k = threadIdx.x; k < N; k += blockDim.x) {
-            const u32 v = shoup32(src[(size_t)i * N + k] + c.q - wrow[k], d.p_inv, d.p_inv_shoup, c.q);
+            u32 corr = wrow[k];  // below 4q
+            corr = corr >= c.two_q ? corr - c.two_q : corr;
+            const u32 v = shoup32(src[(size_t)i * N + k] + c.two_q - corr, d.p_inv, d.p_inv_shoup, c.q);  // argument below 3q < 2^32
             dst[(size_t)i * N + k] = v >= c.q ? v - c.q : v;
         }
-        __syncthreads();  // wrow is refilled by the next limb
+        // wrow is refilled by the next limb: each thread rewrites the elements it has just read
     }
 }
 
-u32 transform_threads(u32 N) { return std::min<u32>(1024, N / 4); }
+// workgroup size of the transforms: two radix-4 groups per thread and trip (measured best of N/4, N/8, N/16)
+u32 transform_threads(u32 N) { return std::min<u32>(1024, N / 8); }
 
 }  // namespace
 
