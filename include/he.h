@@ -211,6 +211,11 @@ uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotie
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q);
 /* The same with the kernels' final step: (sum + addend) mod q for an addend below q (the bias of Alg. 4). */
 uint64_t he_host_mac_accumulate_add(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
+/* The two primitives of the packed 32-bit path, for q in [2, 2^30): BarrettReduction64 (Alg. 6), z mod q for
+ * any 64-bit z; and the lazy 32-bit Shoup product, congruent to y*w mod q and in [0, 2q), for w < q and any
+ * 32-bit y. */
+uint32_t he_host_barrett64(uint64_t z, uint32_t q);
+uint32_t he_host_shoup32(uint32_t y, uint32_t w, uint32_t q);
 
 /*
  * Measurement aid, not part of the compute path: the rate (operations per second, whole GPU) at

@@ -761,6 +761,10 @@ uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotie
     return cheap_quotient ? shoup_mul_lazy4(y, w, h_shoup(w, q), q) : shoup_mul_lazy(y, w, h_shoup(w, q), q);
 }
 
+uint32_t he_host_barrett64(uint64_t z, uint32_t q) { return barrett64(z, q, (u64)((((u128)1) << 64) / q)); }
+
+uint32_t he_host_shoup32(uint32_t y, uint32_t w, uint32_t q) { return shoup32(y, w, (u32)(((u64)w << 32) / q), q); }
+
 int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s) {
     if (!ctx || !ops_per_s || limb >= ctx->L || iters == 0 || iters > (1u << 20)) return HE_ERR_ARG;
     if (kind < HE_RATE_MAD32 || kind > HE_RATE_BUTTERFLY_INV) return HE_ERR_ARG;

@@ -263,6 +263,20 @@ HE_HD void acc_restart(MacAcc& a, const LimbConst& c) {  // reduce in place and 
 }
 
 // ---------------------------------------------------------------------------------------------
+// 32-bit moduli (below 2^30), the primitives of the packed path.
+
+// Alg. 6 (BarrettReduction64): z mod q for a 64-bit z, ratio = floor(2^64 / q).  The estimate
+// floor(z * ratio / 2^64) is the quotient or one less, so one conditional subtraction finishes.
+HE_HD u32 barrett64(u64 z, u32 q, u64 ratio) {
+    const u64 est = mul_hi64(z, ratio);
+    const u32 r = (u32)z - (u32)est * q;  // below 2q < 2^31: the low words suffice
+    return r >= q ? r - q : r;
+}
+
+// y * w mod q up to one q: w < q with ws = floor(w * 2^32 / q), any y below 2^32; the result is in [0, 2q).
+HE_HD u32 shoup32(u32 y, u32 w, u32 ws, u32 q) { return y * w - (u32)(((u64)y * ws) >> 32) * q; }
+
+// ---------------------------------------------------------------------------------------------
 // NTT butterflies (Harvey's lazy forms with Shoup multiplication by a precomputed twiddle).
 struct Twiddle {
     u64 w, w_shoup;  // W and floor(W * 2^64 / q)

@@ -14,16 +14,7 @@ namespace {
 
 constexpr u32 TERMS_PER_REDUCTION = 15;  // r + 15 * (2^30 - 1)^2 < 2^64 for r < 2^30
 
-// Alg. 6: z mod q for a 64-bit z, q < 2^30, ratio = floor(2^64 / q).  The estimate floor(z * ratio / 2^64)
-// is the quotient or one less, so one conditional subtraction finishes.
-__device__ __forceinline__ u32 barrett64(u64 z, const Limb32& c) {
-    const u64 est = __umul64hi(z, c.ratio);
-    const u32 r = (u32)z - (u32)est * c.q;  // below 2q < 2^31: the low words suffice
-    return r >= c.q ? r - c.q : r;
-}
-
-// y * w mod q up to one q: w < q with ws = floor(w * 2^32 / q), any y below 2^32; the result is in [0, 2q).
-__device__ __forceinline__ u32 shoup32(u32 y, u32 w, u32 ws, u32 q) { return y * w - __umulhi(y, ws) * q; }
+__device__ __forceinline__ u32 barrett64(u64 z, const Limb32& c) { return ::barrett64(z, c.q, c.ratio); }
 
 __device__ __forceinline__ u32 add_mod32(u32 a, u32 b, u32 q) {
     const u32 s = a + b;

@@ -28,7 +28,7 @@ EXPORTS = [
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_measure_rate",
-    "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
+    "he_host_barrett64", "he_host_shoup32", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
 ]
 
 _lib = None
@@ -74,6 +74,8 @@ def lib():
         "he_host_mac_accumulate_add": (u64, [vp, vp, sz, u64, u64]),
         "he_measure_rate": (i32, [vp, i32, u32, u32, ctypes.POINTER(ctypes.c_double)]),
         "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
+        "he_host_barrett64": (u32, [u64, u32]),
+        "he_host_shoup32": (u32, [u32, u32, u32]),
         "he_pack32": (i32, [vp, vp, vp, sz, vp]),
         "he_unpack32": (i32, [vp, vp, vp, sz, vp]),
         "he_ct_pt_mac32": (i32, [vp, vp, u32, vp, vp, i32, vp, vp, u32, vp, sz, vp]),
@@ -381,6 +383,14 @@ def host_shoup_mulmod(y: int, w: int, q: int) -> int:
 
 def host_shoup_lazy(y: int, w: int, q: int, cheap_quotient: bool) -> int:
     return int(lib().he_host_shoup_lazy(y, w, q, int(cheap_quotient)))
+
+
+def host_barrett64(z: int, q: int) -> int:
+    return int(lib().he_host_barrett64(z, q))
+
+
+def host_shoup32(y: int, w: int, q: int) -> int:
+    return int(lib().he_host_shoup32(y, w, q))
 
 
 def host_mac_accumulate(x, w, q: int, addend: int = 0) -> int:

@@ -146,3 +146,22 @@ def test_device_calls_fail_loudly_on_a_host_only_context():
         with pytest.raises(he.HeError) as e:
             ctx.measure_rate(**bad)
         assert e.value.status == -1
+
+
+def test_packed32_primitives_against_python_integers():
+    """Alg. 6 (BarrettReduction64) and the lazy 32-bit Shoup product, compiled for the host, on the
+    extremes and on random operands, for the smallest and the largest moduli the packed path takes."""
+    rng = np.random.default_rng(32)
+    for q in (3, 12289, 1073479681, 2**30 - 35, 2**29 + 11):
+        zs = [0, 1, q - 1, q, q + 1, 2**64 - 1, 2**64 - q, (q - 1) ** 2, 16 * (q - 1) ** 2 % 2**64]
+        zs += [int(z) for z in rng.integers(0, 2**64, 2000, dtype=np.uint64)]
+        for z in zs:
+            assert he.host_barrett64(z, q) == z % q
+        ws = [0, 1, q - 1] + [int(w) for w in rng.integers(0, q, 40)]
+        ys = [0, 1, q - 1, 2 * q - 1, 2**32 - 1] + [int(y) for y in rng.integers(0, 2**32, 60, dtype=np.uint64)]
+        for w in ws:
+            for y in ys:
+                if y >= 2**32:
+                    continue
+                r = he.host_shoup32(y, w, q)
+                assert r < 2 * q and r % q == y * w % q
