@@ -308,3 +308,77 @@ def layer(ct_in, q, psi, off, term_ct, term_pt, pt, pt_kind: int, bias=None):
     n_rescales = _load().orc_layer(N, limbs, _p64(q), _p64(psi), _p64(ct_in), _p32(off), _p32(term_ct),
                                    _p32(term_pt), n_out, _p64(pt), pt_kind, _p64(bias), _p64(out))
     return out, int(n_rescales)
+
+
+# ----------------------------------------------------------------------------- ct x ct square, relinearisation
+# The x^2 activation (Sec. "CryptoNets"; "Square" and "Relinearize" in the paper's table of operation
+# runtimes).  The paper names the method only: relinearisation (key switching) by raising the modulus
+# with a special prime (Sec. "Homomorphic Encryption").  Reading taken: the ciphertext lives on limbs
+# q_0..q_{l-1}, the special prime P is one more limb; the quadratic component d2 is cut into its l RNS
+# digits, digit j = the coefficients of [d2]_{q_j} as integers in [0, q_j), re-reduced modulo every q_i
+# and P; the digits are multiplied by the key-switching key (one pair of polynomials modulo Q*P per
+# digit) and summed; the sum is divided by P with rounding (Eq. (2) with P as the dropped limb) and added
+# to (d0, d1).  Every step below is one of the oracle's own routines or a plain big-integer product.
+
+def _mulmod_rows(a, b, q) -> np.ndarray:
+    """Slot-wise product of [..., limbs, N] arrays, limb i modulo q[i] (Python integers)."""
+    a, b = _a64(a), _a64(b)
+    out = np.empty(a.shape, dtype=np.uint64)
+    for i, qi in enumerate(q):
+        out[..., i, :] = ((a[..., i, :].astype(object) * b[..., i, :].astype(object)) % int(qi)).astype(np.uint64)
+    return out
+
+
+def square(ct, q) -> np.ndarray:
+    """(c0, c1) -> (c0^2, 2 c0 c1, c1^2), NTT form: [n][2][l][N] -> [n][3][l][N]."""
+    ct = _a64(ct)
+    n, two, l, N = ct.shape
+    assert two == 2 and l == len(q)
+    out = np.empty((n, 3, l, N), dtype=np.uint64)
+    out[:, 0] = _mulmod_rows(ct[:, 0], ct[:, 0], q)
+    cross = _mulmod_rows(ct[:, 0], ct[:, 1], q)
+    for i, qi in enumerate(q):
+        out[:, 1, i] = ((cross[:, i].astype(object) * 2) % int(qi)).astype(np.uint64)
+    out[:, 2] = _mulmod_rows(ct[:, 1], ct[:, 1], q)
+    return out
+
+
+def relin_digits(d2, q_all, psi_all) -> np.ndarray:
+    """[n][l][N] (NTT form, limbs q_0..q_{l-1}) -> [n][l digits][l+1 limbs][N] (NTT form, limbs q_0..q_{l-1}, P):
+    digit j is the polynomial whose coefficients are those of [d2]_{q_j}, taken in [0, q_j)."""
+    d2 = _a64(d2)
+    n, l, N = d2.shape
+    assert len(q_all) == l + 1
+    coef = ntt_inv(d2, q_all[:l], psi_all[:l])                  # row j: coefficients modulo q_j
+    out = np.empty((n, l, l + 1, N), dtype=np.uint64)
+    for j in range(l):
+        rows = np.stack([coef[:, j] % np.uint64(qi) for qi in q_all], axis=1)  # [n][l+1][N]
+        out[:, j] = ntt_fwd(rows, q_all, psi_all)
+    return out
+
+
+def relinearize(d, q_all, psi_all, evk) -> np.ndarray:
+    """(d0, d1, d2) on limbs q_0..q_{l-1} -> (c0', c1') on the same limbs, with the key evk [l][2][l+1][N]
+    (NTT form, limbs q_0..q_{l-1}, P)."""
+    d = _a64(d)
+    evk = _a64(evk)
+    n, three, l, N = d.shape
+    assert three == 3 and evk.shape == (l, 2, l + 1, N) and len(q_all) == len(psi_all) == l + 1
+    digits = relin_digits(d[:, 2], q_all, psi_all)
+    off = np.array([0, l], dtype=np.uint32)
+    idx = np.arange(l, dtype=np.uint32)
+    out = np.empty((n, 2, l, N), dtype=np.uint64)
+    for c in range(n):
+        # sum over the digits of digit_j * evk_j: the key's pairs play the ciphertexts, the digits the plaintexts
+        acc = mac(evk, q_all, off, idx, idx, digits[c], PT_POLY)            # [1][2][l+1][N]
+        down = rescale(acc, q_all, psi_all)[0]                               # divide by P, rounding
+        for k in range(2):
+            for i in range(l):
+                out[c, k, i] = (d[c, k, i].astype(object) + down[k, i].astype(object)) % int(q_all[i])
+    return out
+
+
+def square_relin(ct, q_all, psi_all, evk) -> np.ndarray:
+    """The x^2 activation on ciphertexts [n][2][l][N] with l = len(q_all) - 1: square, then relinearise."""
+    l = len(q_all) - 1
+    return relinearize(square(ct, q_all[:l]), q_all, psi_all, evk)

@@ -100,3 +100,35 @@ class Scaffold:
 
     def decrypt(self, ct: np.ndarray, scale: float) -> np.ndarray:
         return decode_coeffs(self.decrypt_coeffs(ct), scale, self.N)
+
+    def relin_key(self) -> np.ndarray:
+        """Key-switching key for s^2 -> s with the LAST modulus as the special prime P: for each digit
+        j < l = L-1 the pair (-a_j*s + e_j + P*g_j*s^2, a_j) modulo Q*P, where g_j = 1 mod q_j and 0 modulo
+        the other q_i; in RNS the last term is (P mod q_j)*s^2 on limb j and nothing elsewhere.
+        [l][2][L][N], NTT form."""
+        N, q = self.N, self.q
+        l, P = len(q) - 1, q[-1]
+        evk = np.empty((l, 2, len(q), N), dtype=np.uint64)
+        for j in range(l):
+            e_ntt = coeffs_to_rns_ntt([int(round(x)) for x in self.rng.normal(0.0, 3.2, size=N)], q, self.psi)
+            for i, qi in enumerate(q):
+                a = self.rng.integers(0, qi, size=N, dtype=np.uint64)
+                b = (qi - _obj(_mulmod_vec(a, self.s_ntt[i], qi))) % qi + _obj(e_ntt[i])
+                if i == j:
+                    s2 = _mulmod_vec(self.s_ntt[i], self.s_ntt[i], qi)
+                    b = b + _obj(s2) * (P % qi)
+                evk[j, 0, i] = (b % qi).astype(np.uint64)
+                evk[j, 1, i] = a
+        return evk
+
+    def decrypt3_coeffs(self, d: np.ndarray) -> List[int]:
+        """d0 + d1*s + d2*s^2 for a three-component ciphertext [3][limbs][N], centred coefficients."""
+        limbs = d.shape[1]
+        q, psi = self.q[:limbs], self.psi[:limbs]
+        v = np.empty((limbs, self.N), dtype=np.uint64)
+        for i, qi in enumerate(q):
+            s2 = _mulmod_vec(self.s_ntt[i], self.s_ntt[i], qi)
+            t = _addmod_vec(d[0, i], _mulmod_vec(d[1, i], self.s_ntt[i], qi), qi)
+            v[i] = _addmod_vec(t, _mulmod_vec(d[2, i], s2, qi), qi)
+        v = ntt_inv(v, q, psi)
+        return [crt_centered([v[i, k] for i in range(limbs)], q) for k in range(self.N)]
