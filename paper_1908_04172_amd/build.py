@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhe_mi355x.so")
-SOURCES = ["he_api.hip", "he_mac.hip", "he_ntt.hip", "he_ubench.hip", "he_encode.hip", "he_packed32.hip"]
+SOURCES = ["he_api.hip", "he_mac.hip", "he_ntt.hip", "he_ubench.hip", "he_encode.hip", "he_packed32.hip", "he_relin.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # the butterfly loops must unroll completely (register arrays are indexed by their counters)

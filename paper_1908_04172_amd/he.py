@@ -28,7 +28,7 @@ EXPORTS = [
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_measure_rate",
-    "he_host_barrett64", "he_host_shoup32", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
+    "he_host_barrett64", "he_host_shoup32", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
 ]
 
 _lib = None
@@ -74,6 +74,8 @@ def lib():
         "he_host_mac_accumulate_add": (u64, [vp, vp, sz, u64, u64]),
         "he_measure_rate": (i32, [vp, i32, u32, u32, ctypes.POINTER(ctypes.c_double)]),
         "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
+        "he_square_relin_workspace_bytes": (i32, [vp, u32, ctypes.POINTER(sz)]),
+        "he_ct_square_relin": (i32, [vp, vp, u32, vp, vp, vp, sz, vp]),
         "he_host_barrett64": (u32, [u64, u32]),
         "he_host_shoup32": (u32, [u32, u32, u32]),
         "he_pack32": (i32, [vp, vp, vp, sz, vp]),
@@ -261,6 +263,26 @@ class Context:
                                   ws_bytes, _stream()), "he_ct_pt_mac")
         return out
 
+
+    # -- the x^2 activation: square + relinearise, the context's last limb being the special prime
+    def square_relin_workspace_bytes(self, n: int) -> int:
+        b = ctypes.c_size_t()
+        _check(lib().he_square_relin_workspace_bytes(self._h, n, ctypes.byref(b)), "he_square_relin_workspace_bytes")
+        return b.value
+
+    def ct_square_relin(self, ct, evk, out=None, workspace=None):
+        import torch
+        n, two, l, N = ct.shape
+        assert two == 2 and N == self.N and l == self.L - 1
+        assert tuple(evk.shape) == (l, 2, self.L, N)
+        if out is None:
+            out = torch.empty_like(ct)
+        need = self.square_relin_workspace_bytes(n)
+        if workspace is None:
+            workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=ct.device)
+        _check(lib().he_ct_square_relin(self._h, _dev_ptr(ct, "ct_in"), n, _dev_ptr(evk, "evk"), _dev_ptr(out, "ct_out"),
+                                        _dev_ptr(workspace, "workspace"), workspace.numel(), _stream()), "he_ct_square_relin")
+        return out
 
     # -- packed 32-bit storage (moduli below 2^30): int32 tensors whose bit patterns are the uint32 residues
     def pack32(self, t):

@@ -1,0 +1,80 @@
+"""GPU parity of he_ct_square_relin (the x^2 activation: square, relinearise with the special prime) against the
+CPU oracle: bit-exact residues through the C ABI; and its meaning through the test scaffold's decryption."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import ckks_scaffold as sc
+from paper_1908_04172_amd import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def he():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1908_04172_amd import he as he_mod
+    he_mod.lib()                                                # fails loudly if the library is not built
+    return he_mod
+
+
+def dev(a: np.ndarray):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int64)).cuda()
+
+
+def host(t) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint64)
+
+
+@pytest.mark.parametrize("log2N,bits,n", [(10, [30, 62, 50], 5), (12, [40, 30, 30, 45], 3), (14, [60, 60, 50, 50, 50, 50, 50, 50], 2)])
+def test_square_relin_matches_oracle(he, log2N, bits, n):
+    """Any residues will do: the result is an exact function of the inputs (extreme values in the first ciphertext)."""
+    N = 1 << log2N
+    q = wl.modulus_chain(bits, N)
+    ctx = he.Context(log2N, q)
+    l = len(q) - 1
+    ct = wl.uniform_residues((n, 2), q[:l], N, 91)
+    ct[0, 0] = np.array(q[:l], dtype=np.uint64)[:, None] - 1
+    ct[0, 1, :, ::2] = 0
+    evk = wl.uniform_residues((l, 2), q, N, 92)
+    got = host(ctx.ct_square_relin(dev(ct), dev(evk)))
+    want = oracle.square_relin(ct, q, ctx.psi, evk)
+    assert np.array_equal(got, want)
+
+
+def test_square_relin_rescale_decrypts_to_the_square(he):
+    N = 1 << 10
+    q = wl.modulus_chain([40, 30, 30, 45], N)
+    ctx = he.Context(10, q)
+    sf = sc.Scaffold(N, q, ctx.psi, seed=11)
+    evk = sf.relin_key()
+    z = np.random.default_rng(12).uniform(-1, 1, size=(2, N // 2)) + 0j
+    ct = np.stack([sf.encrypt(z[i], 2.0**30)[:, :3] for i in range(2)])
+    sq = ctx.ct_square_relin(dev(ct), dev(evk))
+    down = host(ctx.rescale(sq))
+    for i in range(2):
+        back = sf.decrypt(down[i], 2.0**60 / q[2])
+        assert np.abs(back - z[i] * z[i]).max() <= 2.0**-10                # the decrypt-level tolerance of the path
+
+
+def test_square_relin_argument_errors(he):
+    N = 1 << 10
+    q = wl.modulus_chain([30, 30, 36], N)
+    ctx = he.Context(10, q)
+    ct = torch.zeros((2, 2, 2, N), dtype=torch.int64, device="cuda")
+    evk = torch.zeros((2, 2, 3, N), dtype=torch.int64, device="cuda")
+    need = ctx.square_relin_workspace_bytes(2)
+    small = torch.empty(need - 1, dtype=torch.uint8, device="cuda")
+    with pytest.raises(he.HeError) as e:
+        ctx.ct_square_relin(ct, evk, workspace=small)
+    assert e.value.status == -6
+    with pytest.raises(he.HeError) as e:
+        ctx.ct_square_relin(ct, evk, out=ct)                               # in place is not allowed
+    assert e.value.status == -1
+    assert torch.equal(ctx.ct_square_relin(ct[:0], evk), ct[:0])           # zero ciphertexts: a no-op
+    one = he.Context(10, q[:1])
+    with pytest.raises(he.HeError) as e:
+        one.square_relin_workspace_bytes(1)                                # no limb left beside the special prime
+    assert e.value.status == -3
