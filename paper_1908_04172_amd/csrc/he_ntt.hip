@@ -270,15 +270,21 @@ __device__ __forceinline__ u32 fresh(u32 tid) {
 // In-place transforms of `rows` rows of N residues, row r under limb r % limbs.  A workgroup takes
 // rows blockIdx.x, blockIdx.x + gridDim.x, ... and requests its next row before it stores the
 // current one, so that the loads do not queue behind the stores and arrive while those drain.
-template <int LOGN, bool INVERSE>
+// SPREAD (forward only): row r is not read from `data` but from row r / limbs of `spread_src`, a
+// table of coefficient rows [..][digits][N] whose row (.., j) holds integers below q_j; they are
+// reduced modulo the row's own limb first.  This is the digit expansion of a key switch: each
+// digit transformed under every limb, written to data [..][digits][limbs][N].
+template <int LOGN, bool INVERSE, bool SPREAD = false>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
-ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows) {
+ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows, const u64* spread_src = nullptr,
+                u32 digits = 1) {
     using G = Geo<LOGN>;
+    static_assert(!(SPREAD && INVERSE), "the digit expansion is a forward transform");
     constexpr int PIN = INVERSE ? G::NPASS - 1 : 0, POUT = INVERSE ? 0 : G::NPASS - 1;
     extern __shared__ u64 lds[];
     u64 a[16];
     {
-        const u64* p = data + (size_t)blockIdx.x * G::N;
+        const u64* p = SPREAD ? spread_src + (size_t)(blockIdx.x / limbs) * G::N : data + (size_t)blockIdx.x * G::N;
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, PIN>(threadIdx.x, e)];
     }
@@ -289,6 +295,12 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows)
         const u32 limb = row % limbs;
         const LimbConst& c = lt.c[limb];
         const u64* tw = tw_all + (size_t)limb * G::N * 2;
+        if constexpr (SPREAD) {
+            if ((row / limbs) % digits != limb) {  // a digit is already reduced modulo its own limb
+#pragma unroll
+                for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
+            }
+        }
         if constexpr (!INVERSE) {
             ntt_forward_any<LOGN>(a, tw, lds, tid, c);
             if (c.ntt_mode == 2) {
@@ -308,7 +320,8 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows)
 #pragma unroll
         for (u32 e = 0; e < 16; e++) next[e] = 0;
         if (row + gridDim.x < rows) {
-            const u64* p = data + (size_t)(row + gridDim.x) * G::N;
+            const u32 nr = row + gridDim.x;
+            const u64* p = SPREAD ? spread_src + (size_t)(nr / limbs) * G::N : data + (size_t)nr * G::N;
 #pragma unroll
             for (u32 e = 0; e < 16; e++) next[e] = p[reg_index<LOGN, PIN>(tid_s, e)];
         }
@@ -436,6 +449,20 @@ int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipS
 }
 
 template <int LOGN>
+int launch_ntt_spread_t(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 rows, u32 digits, hipStream_t s) {
+    using G = Geo<LOGN>;
+    const size_t lds = (size_t)G::N * sizeof(u64);
+    const u32 per_cu = (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
+    const u32 grid = std::min<u32>(rows, 256 * per_cu);
+    static std::atomic<uint32_t> lds_allowed{0};
+    if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false, true>, lds, ctx->device, lds_allowed)) return rc;
+    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, out, ctx->tw_fwd, rows, src,
+                       digits);
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+template <int LOGN>
 int launch_rescale_t(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s) {
     using G = Geo<LOGN>;
     const size_t lds = (size_t)G::N * sizeof(u64);
@@ -471,6 +498,23 @@ int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hip
         case 12: return launch_ntt_t<12>(ctx, limbs, data, rows, inverse, s);
         case 13: return launch_ntt_t<13>(ctx, limbs, data, rows, inverse, s);
         case 14: return launch_ntt_t<14>(ctx, limbs, data, rows, inverse, s);
+    }
+    return HE_ERR_ARG;
+}
+
+// out [n_digit_rows][limbs][N] = forward transforms, under every limb, of the coefficient rows src [n_digit_rows][N]
+// (row r holding integers below the modulus of limb r % digits)
+int launch_ntt_spread(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 n_digit_rows, u32 digits, hipStream_t s) {
+    const u64 rows64 = (u64)n_digit_rows * limbs;
+    if (rows64 == 0) return HE_OK;
+    if (rows64 > 0x7FFFFFFFull) return HE_ERR_RANGE;
+    const u32 rows = (u32)rows64;
+    switch (ctx->log2N) {
+        case 10: return launch_ntt_spread_t<10>(ctx, limbs, src, out, rows, digits, s);
+        case 11: return launch_ntt_spread_t<11>(ctx, limbs, src, out, rows, digits, s);
+        case 12: return launch_ntt_spread_t<12>(ctx, limbs, src, out, rows, digits, s);
+        case 13: return launch_ntt_spread_t<13>(ctx, limbs, src, out, rows, digits, s);
+        case 14: return launch_ntt_spread_t<14>(ctx, limbs, src, out, rows, digits, s);
     }
     return HE_ERR_ARG;
 }

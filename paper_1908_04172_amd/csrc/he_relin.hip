@@ -4,12 +4,12 @@
 // q_0..q_{l-1} with l = L-1; the context's last limb is the special prime P.  Steps, each a launch:
 //   1. (d0, d1, d2) = (c0^2, 2 c0 c1, c1^2), slot-wise; d0, d1 go to the output, d2 to the workspace;
 //   2. inverse NTT of d2: row j now holds the coefficients of [d2]_{q_j} in [0, q_j): RNS digit j;
-//   3. every digit re-reduced modulo q_0..q_{l-1} and P;
-//   4. forward NTT of the l * L rows;
+//   3+4. every digit re-reduced modulo q_0..q_{l-1} and P and transformed under that limb: one launch of the
+//      transform kernel in its digit-expansion form, l * L rows written from l rows read;
 //   5. acc_k = sum_j digit_j * evk[j][k], k = 0, 1, on all L limbs;
 //   6. division of acc by P with rounding: Eq. (2) with P as the dropped limb, the rescale kernel as it is;
 //   7. out_k = d_k + that.
-// Steps 2, 4 and 6 are the library's transforms; this file adds the three slot-wise kernels around them.
+// Steps 2, 3+4 and 6 are the library's transforms; this file adds the three slot-wise kernels around them.
 #include "he_internal.h"
 
 namespace {
@@ -27,16 +27,6 @@ __global__ void __launch_bounds__(256) square_kernel(LimbTable lt, u32 l, u32 N,
     out[((c_idx * 2) * l + limb) * N + k] = mul_mod(c0, c0, c);
     out[((c_idx * 2 + 1) * l + limb) * N + k] = add_mod(cross, cross, c.q);
     d2[row * N + k] = mul_mod(c1, c1, c);
-}
-
-// step 3: digits [n][l][N] (coefficients, row j below q_j) -> [n][l][L][N], limb i = the same integers modulo q_i
-__global__ void __launch_bounds__(256) spread_kernel(LimbTable lt, u32 l, u32 L, u32 N, const u64* digits, size_t n, u64* out) {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= n * l * N) return;
-    const size_t k = idx % N, row = idx / N;  // row = ct * l + digit
-    const u32 j = (u32)(row % l);
-    const u64 v = digits[idx];
-    for (u32 i = 0; i < L; ++i) out[(row * L + i) * N + k] = i == j ? v : reduce64(v, lt.c[i]);
 }
 
 // step 5: one thread = one slot of one limb of one ciphertext, both components
@@ -92,9 +82,7 @@ int launch_square_relin(he_ctx* ctx, const u64* ct_in, u32 n, const u64* evk, u6
     hipLaunchKernelGGL(square_kernel, dim3((u32)b1), dim3(256), 0, s, ctx->limbs, l, N, ct_in, (size_t)n, ct_out, d2);
     HE_HIP(hipGetLastError());
     if ((rc = launch_ntt(ctx, l, d2, n, true, s)) != HE_OK) return rc;
-    hipLaunchKernelGGL(spread_kernel, dim3((u32)b1), dim3(256), 0, s, ctx->limbs, l, L, N, d2, (size_t)n, digits);
-    HE_HIP(hipGetLastError());
-    if ((rc = launch_ntt(ctx, L, digits, n * l, false, s)) != HE_OK) return rc;
+    if ((rc = launch_ntt_spread(ctx, L, d2, digits, n * l, l, s)) != HE_OK) return rc;
     hipLaunchKernelGGL(key_product_kernel, dim3((u32)b5), dim3(256), 0, s, ctx->limbs, l, L, N, digits, (size_t)n, evk, acc);
     HE_HIP(hipGetLastError());
     if ((rc = launch_rescale(ctx, L, acc, down, n, s)) != HE_OK) return rc;
