@@ -38,14 +38,15 @@ __global__ void __launch_bounds__(256) key_product_kernel(LimbTable lt, u32 l, u
     const u32 limb = (u32)(row % L);
     const size_t c_idx = row / L;
     const LimbConst& c = lt.c[limb];
-    u64 a0 = 0, a1 = 0;
+    // at most 15 products below 2^124 each: the sums fit 128 bits and are reduced once (Alg. 5)
+    u128 a0 = 0, a1 = 0;
     for (u32 j = 0; j < l; ++j) {
         const u64 b = digits[((c_idx * l + j) * L + limb) * N + k];
-        a0 = add_mod(a0, mul_mod(b, evk[(((size_t)j * 2) * L + limb) * N + k], c), c.q);
-        a1 = add_mod(a1, mul_mod(b, evk[(((size_t)j * 2 + 1) * L + limb) * N + k], c), c.q);
+        a0 += (u128)b * evk[(((size_t)j * 2) * L + limb) * N + k];
+        a1 += (u128)b * evk[(((size_t)j * 2 + 1) * L + limb) * N + k];
     }
-    acc[((c_idx * 2) * L + limb) * N + k] = a0;
-    acc[((c_idx * 2 + 1) * L + limb) * N + k] = a1;
+    acc[((c_idx * 2) * L + limb) * N + k] = reduce128((u64)(a0 >> 64), (u64)a0, c);
+    acc[((c_idx * 2 + 1) * L + limb) * N + k] = reduce128((u64)(a1 >> 64), (u64)a1, c);
 }
 
 // step 7: out += down, both [n][2][l][N]
