@@ -442,7 +442,7 @@ def main() -> int:
         evk = wl.uniform_residues_torch((L - 1, 2), q, N, 22, dev)
         out_sq = torch.empty_like(ct_sq)
         down_sq = torch.empty((n_sq, 2, L - 2, N), dtype=torch.int64, device=dev)
-        ws_sq = torch.empty(ctx.square_relin_workspace_bytes(n_sq), dtype=torch.uint8, device=dev)
+        ws_sq = torch.empty(ctx.square_relin_workspace_bytes(L - 1, n_sq), dtype=torch.uint8, device=dev)
         def activation():
             ctx.ct_square_relin(ct_sq, evk, out=out_sq, workspace=ws_sq)
             ctx.rescale(out_sq, out=down_sq)

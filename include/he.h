@@ -173,20 +173,22 @@ int he_ntt_inv(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, vo
 
 /*
  * The x^2 activation (Sec. "CryptoNets"; "Square" and "Relinearize" in the paper's table of operation
- * runtimes): ct_out = relinearise(ct_in squared).  The ciphertexts live on the first L-1 limbs of the
- * context and its LAST limb is the special prime P of the key switching (Sec. "Homomorphic Encryption":
- * relinearisation by raising the modulus with a special prime).  ct_in, ct_out dev [n][2][L-1][N], NTT form.
- * evk dev [L-1][2][L][N], NTT form: for digit j the pair (-a_j s + e_j + P g_j s^2, a_j) modulo q_0...q_{L-2} P,
+ * runtimes): ct_out = relinearise(ct_in squared).  The ciphertexts live on the first `limbs` limbs of the
+ * context, 1 <= limbs <= L-1 (HE_ERR_LEVEL otherwise), and the context's LAST limb is the special prime P of
+ * the key switching (Sec. "Homomorphic Encryption": relinearisation by raising the modulus with a special
+ * prime).  ct_in, ct_out dev [n][2][limbs][N], NTT form.
+ * evk dev [L-1][2][L][N], NTT form, the key of the top level (lower levels use its first `limbs` digits and,
+ * of each, the limbs in use and P): for digit j the pair (-a_j s + e_j + P g_j s^2, a_j) modulo q_0...q_{L-2} P,
  * where g_j is 1 modulo q_j and 0 modulo the other q_i.  Computes (d0, d1, d2) = (c0^2, 2 c0 c1, c1^2); cuts d2
- * into its L-1 RNS digits (digit j = the coefficients of d2 modulo q_j, as integers in [0, q_j)); sums
- * digit_j * evk[j] over j on all L limbs; divides by P with rounding (Eq. (2), P the dropped limb); adds
- * (d0, d1).  The result is at the same level and scale^2: a he_rescale(limbs = L-1) usually follows.
+ * into its RNS digits (digit j = the coefficients of d2 modulo q_j, as integers in [0, q_j)); sums
+ * digit_j * evk[j] over j on the limbs in use and P; divides by P with rounding (Eq. (2), P the dropped limb);
+ * adds (d0, d1).  The result is at the same level and scale^2: a he_rescale(limbs) usually follows.
  * workspace: dev, at least he_square_relin_workspace_bytes bytes (HE_ERR_WORKSPACE otherwise); ct_out, ct_in,
- * evk and workspace must not overlap one another (HE_ERR_ARG).  L >= 2 (HE_ERR_LEVEL).
+ * evk and workspace must not overlap one another (HE_ERR_ARG).
  */
-int he_square_relin_workspace_bytes(const he_ctx* ctx, uint32_t n, size_t* bytes);
-int he_ct_square_relin(he_ctx* ctx, const uint64_t* ct_in, uint32_t n, const uint64_t* evk, uint64_t* ct_out,
-                       void* workspace, size_t workspace_bytes, void* stream);
+int he_square_relin_workspace_bytes(const he_ctx* ctx, uint32_t limbs, uint32_t n, size_t* bytes);
+int he_ct_square_relin(he_ctx* ctx, uint32_t limbs, const uint64_t* ct_in, uint32_t n, const uint64_t* evk,
+                       uint64_t* ct_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Packed 32-bit storage: the paper's optimisation for moduli of at most 32 bits (Sec.

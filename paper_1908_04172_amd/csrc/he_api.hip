@@ -641,30 +641,30 @@ int he_ntt_inv(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, vo
 
 // ---- ciphertext square + relinearisation
 
-int he_square_relin_workspace_bytes(const he_ctx* ctx, uint32_t n, size_t* bytes) {
+int he_square_relin_workspace_bytes(const he_ctx* ctx, uint32_t limbs, uint32_t n, size_t* bytes) {
     if (!ctx || !bytes) return HE_ERR_ARG;
-    if (ctx->L < 2) return HE_ERR_LEVEL;
-    *bytes = square_relin_workspace(ctx, n);
+    if (limbs < 1 || limbs + 1 > ctx->L) return HE_ERR_LEVEL;
+    *bytes = square_relin_workspace(ctx, limbs, n);
     return HE_OK;
 }
 
-int he_ct_square_relin(he_ctx* ctx, const uint64_t* ct_in, uint32_t n, const uint64_t* evk, uint64_t* ct_out,
-                       void* workspace, size_t workspace_bytes, void* stream) {
+int he_ct_square_relin(he_ctx* ctx, uint32_t limbs, const uint64_t* ct_in, uint32_t n, const uint64_t* evk,
+                       uint64_t* ct_out, void* workspace, size_t workspace_bytes, void* stream) {
     if (!ctx) return HE_ERR_ARG;
-    if (ctx->L < 2) return HE_ERR_LEVEL;
+    if (limbs < 1 || limbs + 1 > ctx->L) return HE_ERR_LEVEL;
     if (n == 0) return HE_OK;
     if (!ct_in || !evk || !ct_out) return HE_ERR_ARG;
-    const size_t need = square_relin_workspace(ctx, n);
+    const size_t need = square_relin_workspace(ctx, limbs, n);
     if (!workspace || workspace_bytes < need) return HE_ERR_WORKSPACE;
-    const size_t row = (size_t)ctx->N * sizeof(u64), l = ctx->L - 1;
-    const size_t ct_bytes = (size_t)n * 2 * l * row;
-    if (overlaps(ct_out, ct_bytes, ct_in, ct_bytes) || overlaps(ct_out, ct_bytes, evk, l * 2 * ctx->L * row) ||
+    const size_t row = (size_t)ctx->N * sizeof(u64);
+    const size_t ct_bytes = (size_t)n * 2 * limbs * row, key_bytes = (size_t)(ctx->L - 1) * 2 * ctx->L * row;
+    if (overlaps(ct_out, ct_bytes, ct_in, ct_bytes) || overlaps(ct_out, ct_bytes, evk, key_bytes) ||
         overlaps(ct_out, ct_bytes, workspace, need) || overlaps(ct_in, ct_bytes, workspace, need) ||
-        overlaps(evk, l * 2 * ctx->L * row, workspace, need))
+        overlaps(evk, key_bytes, workspace, need))
         return HE_ERR_ARG;
     int rc = need_device(ctx);
     if (rc != HE_OK) return rc;
-    return launch_square_relin(ctx, ct_in, n, evk, ct_out, workspace, (hipStream_t)stream);
+    return launch_square_relin(ctx, limbs, ct_in, n, evk, ct_out, workspace, (hipStream_t)stream);
 }
 
 // ---- packed 32-bit storage

@@ -123,10 +123,11 @@ int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, co
 int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s);
 int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s);
 int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s);
+int launch_rescale_drop(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* out, u32 n, hipStream_t s);
 int launch_ntt_spread(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 n_digit_rows, u32 digits, hipStream_t s);
 // square + relinearisation (he_relin.hip)
-size_t square_relin_workspace(const he_ctx* ctx, u32 n);
-int launch_square_relin(he_ctx* ctx, const u64* ct_in, u32 n, const u64* evk, u64* ct_out, void* workspace, hipStream_t s);
+size_t square_relin_workspace(const he_ctx* ctx, u32 limbs, u32 n);
+int launch_square_relin(he_ctx* ctx, u32 limbs, const u64* ct_in, u32 n, const u64* evk, u64* ct_out, void* workspace, hipStream_t s);
 // packed 32-bit storage (he_packed32.hip)
 int launch_pack32(he_ctx* ctx, const u64* in, u32* out, size_t count, hipStream_t s);
 int launch_unpack32(he_ctx* ctx, const u32* in, u64* out, size_t count, hipStream_t s);

@@ -273,11 +273,12 @@ __device__ __forceinline__ u32 fresh(u32 tid) {
 // SPREAD (forward only): row r is not read from `data` but from row r / limbs of `spread_src`, a
 // table of coefficient rows [..][digits][N] whose row (.., j) holds integers below q_j; they are
 // reduced modulo the row's own limb first.  This is the digit expansion of a key switch: each
-// digit transformed under every limb, written to data [..][digits][limbs][N].
+// digit transformed under every limb, written to data [..][digits][limbs][N]; the limbs are
+// q_0..q_{limbs-2} and, at the last position, the special prime (limb `last_id` of the context).
 template <int LOGN, bool INVERSE, bool SPREAD = false>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
 ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows, const u64* spread_src = nullptr,
-                u32 digits = 1) {
+                u32 digits = 1, u32 last_id = 0) {
     using G = Geo<LOGN>;
     static_assert(!(SPREAD && INVERSE), "the digit expansion is a forward transform");
     constexpr int PIN = INVERSE ? G::NPASS - 1 : 0, POUT = INVERSE ? 0 : G::NPASS - 1;
@@ -294,7 +295,9 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
         const u32 tid = tid_i;
         const u32 limb = row % limbs;
         const LimbConst& c = lt.c[limb];
-        const u64* tw = tw_all + (size_t)limb * G::N * 2;
+        // (digit expansion: the last position is the special prime, whose twiddles sit at its own limb's
+        // place in the table; `lt` comes with that limb's constants at the last position)
+        const u64* tw = tw_all + (size_t)(SPREAD && limb == limbs - 1 ? last_id : limb) * G::N * 2;
         if constexpr (SPREAD) {
             if ((row / limbs) % digits != limb) {  // a digit is already reduced modulo its own limb
 #pragma unroll
@@ -450,37 +453,46 @@ int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipS
 
 template <int LOGN>
 int launch_ntt_spread_t(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 rows, u32 digits, hipStream_t s) {
+    LimbTable lt = ctx->limbs;
+    lt.c[limbs - 1] = ctx->limbs.c[ctx->L - 1];
     using G = Geo<LOGN>;
     const size_t lds = (size_t)G::N * sizeof(u64);
     const u32 per_cu = (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
     const u32 grid = std::min<u32>(rows, 256 * per_cu);
     static std::atomic<uint32_t> lds_allowed{0};
     if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false, true>, lds, ctx->device, lds_allowed)) return rc;
-    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, out, ctx->tw_fwd, rows, src,
-                       digits);
+    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false, true>), dim3(grid), dim3(G::T), lds, s, lt, limbs, out, ctx->tw_fwd, rows, src,
+                       digits, ctx->L - 1);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
 
+// drop_id: the context's limb that sits at the last position of `in` and is dropped (limbs - 1 for a
+// rescale; the special prime for the division that ends a key switch).  The kernel addresses limbs by
+// position: it gets a table with drop_id's constants at the last position and the inverse twiddles
+// shifted so that the last position finds drop_id's.
 template <int LOGN>
-int launch_rescale_t(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s) {
+int launch_rescale_t(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* out, u32 n, hipStream_t s) {
     using G = Geo<LOGN>;
+    LimbTable lt = ctx->limbs;
+    lt.c[limbs - 1] = ctx->limbs.c[drop_id];
+    const u64* tw_inv = ctx->tw_inv + (size_t)(drop_id - (limbs - 1)) * G::N * 2;
     const size_t lds = (size_t)G::N * sizeof(u64);
     static std::atomic<uint32_t> lds_allowed{0}, lds_allowed_split{0};
     if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN, false>, lds, ctx->device, lds_allowed)) return rc;
     if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN, true>, lds, ctx->device, lds_allowed_split)) return rc;
     DropRow row;
-    for (u32 i = 0; i < HE_MAX_LIMBS; i++) row.d[i] = ctx->drop[limbs - 1][i];
+    for (u32 i = 0; i < HE_MAX_LIMBS; i++) row.d[i] = ctx->drop[drop_id][i];
     // with fewer polynomials than workgroups the chip holds at once, split each over several workgroups
     // (at most one per kept limb), as far as they still all run at the same time
     const u32 resident = 256 * (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
     const u32 parts = std::max(1u, std::min(limbs - 1, resident / (2 * n)));
     if (parts > 1)
-        hipLaunchKernelGGL((rescale_kernel<LOGN, true>), dim3(2 * n * parts), dim3(G::T), lds, s, ctx->limbs, row, limbs, parts,
-                           in, out, ctx->tw_fwd, ctx->tw_inv);
+        hipLaunchKernelGGL((rescale_kernel<LOGN, true>), dim3(2 * n * parts), dim3(G::T), lds, s, lt, row, limbs, parts,
+                           in, out, ctx->tw_fwd, tw_inv);
     else
-        hipLaunchKernelGGL((rescale_kernel<LOGN, false>), dim3(2 * n), dim3(G::T), lds, s, ctx->limbs, row, limbs, 1u, in, out,
-                           ctx->tw_fwd, ctx->tw_inv);
+        hipLaunchKernelGGL((rescale_kernel<LOGN, false>), dim3(2 * n), dim3(G::T), lds, s, lt, row, limbs, 1u, in, out,
+                           ctx->tw_fwd, tw_inv);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
@@ -502,8 +514,9 @@ int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hip
     return HE_ERR_ARG;
 }
 
-// out [n_digit_rows][limbs][N] = forward transforms, under every limb, of the coefficient rows src [n_digit_rows][N]
-// (row r holding integers below the modulus of limb r % digits)
+// out [n_digit_rows][limbs][N] = forward transforms, under the limbs q_0..q_{limbs-2} and the special prime (the
+// context's last limb), of the coefficient rows src [n_digit_rows][N] (row r holding integers below the modulus of
+// limb r % digits)
 int launch_ntt_spread(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 n_digit_rows, u32 digits, hipStream_t s) {
     const u64 rows64 = (u64)n_digit_rows * limbs;
     if (rows64 == 0) return HE_OK;
@@ -520,14 +533,19 @@ int launch_ntt_spread(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 n_di
 }
 
 int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s) {
+    return launch_rescale_drop(ctx, limbs, limbs - 1, in, out, n, s);
+}
+
+// `in` [n][2][limbs][N] holds the context's limbs 0..limbs-2 and, at the last position, limb drop_id >= limbs - 1
+int launch_rescale_drop(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* out, u32 n, hipStream_t s) {
     if (n == 0) return HE_OK;
     if (n > 0x3FFFFFFFu) return HE_ERR_RANGE;
     switch (ctx->log2N) {
-        case 10: return launch_rescale_t<10>(ctx, limbs, in, out, n, s);
-        case 11: return launch_rescale_t<11>(ctx, limbs, in, out, n, s);
-        case 12: return launch_rescale_t<12>(ctx, limbs, in, out, n, s);
-        case 13: return launch_rescale_t<13>(ctx, limbs, in, out, n, s);
-        case 14: return launch_rescale_t<14>(ctx, limbs, in, out, n, s);
+        case 10: return launch_rescale_t<10>(ctx, limbs, drop_id, in, out, n, s);
+        case 11: return launch_rescale_t<11>(ctx, limbs, drop_id, in, out, n, s);
+        case 12: return launch_rescale_t<12>(ctx, limbs, drop_id, in, out, n, s);
+        case 13: return launch_rescale_t<13>(ctx, limbs, drop_id, in, out, n, s);
+        case 14: return launch_rescale_t<14>(ctx, limbs, drop_id, in, out, n, s);
     }
     return HE_ERR_ARG;
 }

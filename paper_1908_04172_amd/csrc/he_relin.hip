@@ -1,7 +1,8 @@
 // The x^2 activation on ciphertexts (Sec. "CryptoNets"; "Square" and "Relinearize" in the paper's table of
 // operation runtimes): square a ciphertext and relinearise the result with a special prime (Sec.
 // "Homomorphic Encryption": key switching by raising the modulus).  The ciphertext lives on limbs
-// q_0..q_{l-1} with l = L-1; the context's last limb is the special prime P.  Steps, each a launch:
+// q_0..q_{l-1}, 1 <= l <= L-1; the context's last limb is the special prime P.  Working tensors have l+1
+// limb positions: q_0..q_{l-1}, then P.  Steps, each a launch:
 //   1. (d0, d1, d2) = (c0^2, 2 c0 c1, c1^2), slot-wise; d0, d1 go to the output, d2 to the workspace;
 //   2. inverse NTT of d2: row j now holds the coefficients of [d2]_{q_j} in [0, q_j): RNS digit j;
 //   3+4. every digit re-reduced modulo q_0..q_{l-1} and P and transformed under that limb: one launch of the
@@ -30,20 +31,23 @@ __global__ void __launch_bounds__(256) square_kernel(LimbTable lt, u32 l, u32 N,
 }
 
 // step 5: one thread = one slot of one limb of one ciphertext, both components
-__global__ void __launch_bounds__(256) key_product_kernel(LimbTable lt, u32 l, u32 L, u32 N, const u64* digits, size_t n,
-                                                          const u64* evk, u64* acc) {
+// (L = l + 1 limb positions; `lt` has the special prime's constants at position l; the key is the top-level one,
+// [..][2][key_limbs][N], in which the special prime is limb key_limbs - 1)
+__global__ void __launch_bounds__(256) key_product_kernel(LimbTable lt, u32 l, u32 L, u32 key_limbs, u32 N, const u64* digits,
+                                                          size_t n, const u64* evk, u64* acc) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= n * L * N) return;
-    const size_t k = idx % N, row = idx / N;  // row = ct * L + limb
+    const size_t k = idx % N, row = idx / N;  // row = ct * L + limb position
     const u32 limb = (u32)(row % L);
+    const u32 key_limb = limb == l ? key_limbs - 1 : limb;
     const size_t c_idx = row / L;
     const LimbConst& c = lt.c[limb];
     // at most 15 products below 2^124 each: the sums fit 128 bits and are reduced once (Alg. 5)
     u128 a0 = 0, a1 = 0;
     for (u32 j = 0; j < l; ++j) {
         const u64 b = digits[((c_idx * l + j) * L + limb) * N + k];
-        a0 += (u128)b * evk[(((size_t)j * 2) * L + limb) * N + k];
-        a1 += (u128)b * evk[(((size_t)j * 2 + 1) * L + limb) * N + k];
+        a0 += (u128)b * evk[(((size_t)j * 2) * key_limbs + key_limb) * N + k];
+        a1 += (u128)b * evk[(((size_t)j * 2 + 1) * key_limbs + key_limb) * N + k];
     }
     acc[((c_idx * 2) * L + limb) * N + k] = reduce128((u64)(a0 >> 64), (u64)a0, c);
     acc[((c_idx * 2 + 1) * L + limb) * N + k] = reduce128((u64)(a1 >> 64), (u64)a1, c);
@@ -61,13 +65,13 @@ size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 }  // namespace
 
-size_t square_relin_workspace(const he_ctx* ctx, u32 n) {
-    const size_t row = (size_t)ctx->N * sizeof(u64), l = ctx->L - 1, L = ctx->L;
+size_t square_relin_workspace(const he_ctx* ctx, u32 l, u32 n) {
+    const size_t row = (size_t)ctx->N * sizeof(u64), L = (size_t)l + 1;
     return align256(n * l * row) + align256(n * l * L * row) + align256(n * 2 * L * row);
 }
 
-int launch_square_relin(he_ctx* ctx, const u64* ct_in, u32 n, const u64* evk, u64* ct_out, void* workspace, hipStream_t s) {
-    const u32 L = ctx->L, l = L - 1, N = ctx->N;
+int launch_square_relin(he_ctx* ctx, u32 l, const u64* ct_in, u32 n, const u64* evk, u64* ct_out, void* workspace, hipStream_t s) {
+    const u32 L = l + 1, N = ctx->N;  // limb positions of the working tensors: q_0..q_{l-1}, P
     const size_t row = (size_t)N * sizeof(u64);
     char* ws = (char*)workspace;
     u64* d2 = (u64*)ws;
@@ -79,14 +83,16 @@ int launch_square_relin(he_ctx* ctx, const u64* ct_in, u32 n, const u64* evk, u6
     const size_t per_ct = (size_t)l * N;
     const size_t b1 = ((size_t)n * per_ct + 255) / 256, b5 = ((size_t)n * L * N + 255) / 256, b7 = ((size_t)n * 2 * per_ct + 255) / 256;
     if (b1 > 0x7FFFFFFFull || b5 > 0x7FFFFFFFull || b7 > 0x7FFFFFFFull || (u64)n * l > 0x0FFFFFFFull) return HE_ERR_RANGE;
+    LimbTable lt = ctx->limbs;
+    lt.c[l] = ctx->limbs.c[ctx->L - 1];  // the special prime at the last position
     int rc;
     hipLaunchKernelGGL(square_kernel, dim3((u32)b1), dim3(256), 0, s, ctx->limbs, l, N, ct_in, (size_t)n, ct_out, d2);
     HE_HIP(hipGetLastError());
     if ((rc = launch_ntt(ctx, l, d2, n, true, s)) != HE_OK) return rc;
     if ((rc = launch_ntt_spread(ctx, L, d2, digits, n * l, l, s)) != HE_OK) return rc;
-    hipLaunchKernelGGL(key_product_kernel, dim3((u32)b5), dim3(256), 0, s, ctx->limbs, l, L, N, digits, (size_t)n, evk, acc);
+    hipLaunchKernelGGL(key_product_kernel, dim3((u32)b5), dim3(256), 0, s, lt, l, L, ctx->L, N, digits, (size_t)n, evk, acc);
     HE_HIP(hipGetLastError());
-    if ((rc = launch_rescale(ctx, L, acc, down, n, s)) != HE_OK) return rc;
+    if ((rc = launch_rescale_drop(ctx, L, ctx->L - 1, acc, down, n, s)) != HE_OK) return rc;
     hipLaunchKernelGGL(add_rows_kernel, dim3((u32)b7), dim3(256), 0, s, ctx->limbs, l, N, ct_out, down, (size_t)n * 2 * l);
     HE_HIP(hipGetLastError());
     return HE_OK;

@@ -74,8 +74,8 @@ def lib():
         "he_host_mac_accumulate_add": (u64, [vp, vp, sz, u64, u64]),
         "he_measure_rate": (i32, [vp, i32, u32, u32, ctypes.POINTER(ctypes.c_double)]),
         "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
-        "he_square_relin_workspace_bytes": (i32, [vp, u32, ctypes.POINTER(sz)]),
-        "he_ct_square_relin": (i32, [vp, vp, u32, vp, vp, vp, sz, vp]),
+        "he_square_relin_workspace_bytes": (i32, [vp, u32, u32, ctypes.POINTER(sz)]),
+        "he_ct_square_relin": (i32, [vp, u32, vp, u32, vp, vp, vp, sz, vp]),
         "he_host_barrett64": (u32, [u64, u32]),
         "he_host_shoup32": (u32, [u32, u32, u32]),
         "he_pack32": (i32, [vp, vp, vp, sz, vp]),
@@ -265,22 +265,23 @@ class Context:
 
 
     # -- the x^2 activation: square + relinearise, the context's last limb being the special prime
-    def square_relin_workspace_bytes(self, n: int) -> int:
+    def square_relin_workspace_bytes(self, limbs: int, n: int) -> int:
         b = ctypes.c_size_t()
-        _check(lib().he_square_relin_workspace_bytes(self._h, n, ctypes.byref(b)), "he_square_relin_workspace_bytes")
+        _check(lib().he_square_relin_workspace_bytes(self._h, limbs, n, ctypes.byref(b)), "he_square_relin_workspace_bytes")
         return b.value
 
     def ct_square_relin(self, ct, evk, out=None, workspace=None):
+        """ct [n][2][limbs][N] at any level limbs <= L-1; evk [L-1][2][L][N], the top-level key."""
         import torch
         n, two, l, N = ct.shape
-        assert two == 2 and N == self.N and l == self.L - 1
-        assert tuple(evk.shape) == (l, 2, self.L, N)
+        assert two == 2 and N == self.N
+        assert tuple(evk.shape) == (self.L - 1, 2, self.L, N)
         if out is None:
             out = torch.empty_like(ct)
-        need = self.square_relin_workspace_bytes(n)
+        need = self.square_relin_workspace_bytes(l, n)
         if workspace is None:
             workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=ct.device)
-        _check(lib().he_ct_square_relin(self._h, _dev_ptr(ct, "ct_in"), n, _dev_ptr(evk, "evk"), _dev_ptr(out, "ct_out"),
+        _check(lib().he_ct_square_relin(self._h, l, _dev_ptr(ct, "ct_in"), n, _dev_ptr(evk, "evk"), _dev_ptr(out, "ct_out"),
                                         _dev_ptr(workspace, "workspace"), workspace.numel(), _stream()), "he_ct_square_relin")
         return out
 

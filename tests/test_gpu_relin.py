@@ -42,6 +42,14 @@ def test_square_relin_matches_oracle(he, log2N, bits, n):
     got = host(ctx.ct_square_relin(dev(ct), dev(evk)))
     want = oracle.square_relin(ct, q, ctx.psi, evk)
     assert np.array_equal(got, want)
+    # lower levels: the same key, of which the first `lv` digits and the limbs q_0..q_{lv-1}, P are used
+    for lv in range(1, l):
+        keep = list(range(lv)) + [l]
+        sub_q, sub_psi = [q[i] for i in keep], [ctx.psi[i] for i in keep]
+        sub_ct = ct[:2, :, :lv].copy()
+        got = host(ctx.ct_square_relin(dev(sub_ct), dev(evk)))
+        want = oracle.square_relin(sub_ct, sub_q, sub_psi, evk[:lv][:, :, keep])
+        assert np.array_equal(got, want), lv
 
 
 def test_square_relin_rescale_decrypts_to_the_square(he):
@@ -57,6 +65,12 @@ def test_square_relin_rescale_decrypts_to_the_square(he):
     for i in range(2):
         back = sf.decrypt(down[i], 2.0**60 / q[2])
         assert np.abs(back - z[i] * z[i]).max() <= 2.0**-10                # the decrypt-level tolerance of the path
+    # one level down, as after a rescaled layer: square the two-limb ciphertexts again (z^4 at (scale^2/q_2)^2 / q_1)
+    sq2 = ctx.ct_square_relin(dev(down), dev(evk))
+    down2 = host(ctx.rescale(sq2))
+    for i in range(2):
+        back = sf.decrypt(down2[i], (2.0**60 / q[2]) ** 2 / q[1])
+        assert np.abs(back - z[i] ** 4).max() <= 2.0**-10
 
 
 def test_square_relin_argument_errors(he):
@@ -65,7 +79,7 @@ def test_square_relin_argument_errors(he):
     ctx = he.Context(10, q)
     ct = torch.zeros((2, 2, 2, N), dtype=torch.int64, device="cuda")
     evk = torch.zeros((2, 2, 3, N), dtype=torch.int64, device="cuda")
-    need = ctx.square_relin_workspace_bytes(2)
+    need = ctx.square_relin_workspace_bytes(2, 2)
     small = torch.empty(need - 1, dtype=torch.uint8, device="cuda")
     with pytest.raises(he.HeError) as e:
         ctx.ct_square_relin(ct, evk, workspace=small)
@@ -74,7 +88,9 @@ def test_square_relin_argument_errors(he):
         ctx.ct_square_relin(ct, evk, out=ct)                               # in place is not allowed
     assert e.value.status == -1
     assert torch.equal(ctx.ct_square_relin(ct[:0], evk), ct[:0])           # zero ciphertexts: a no-op
-    one = he.Context(10, q[:1])
     with pytest.raises(he.HeError) as e:
-        one.square_relin_workspace_bytes(1)                                # no limb left beside the special prime
+        ctx.square_relin_workspace_bytes(3, 1)                             # all three limbs in use: none left as the special prime
+    assert e.value.status == -3
+    with pytest.raises(he.HeError) as e:
+        ctx.square_relin_workspace_bytes(0, 1)
     assert e.value.status == -3
