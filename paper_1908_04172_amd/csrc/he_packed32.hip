@@ -98,13 +98,30 @@ mac_scalar32_kernel(Limb32Table lt, u32 limbs, u32 N, const Tile* tiles, u32 n_t
 #pragma unroll
     for (int g = 0; g < G; g++) acc[g][0] = acc[g][1] = 0;
     u32 since = 0;
+    // the next term's input and weights are requested before this term's multiply-adds, so that the loads
+    // (the weights of a dense layer miss the scalar cache) are in flight while those run
+    uint2 x_next = make_uint2(0, 0);
+    u32 w_next[G];
+#pragma unroll
+    for (int g = 0; g < G; g++) w_next[g] = 0;
+    if (K > 0) {
+        x_next = x_base[(size_t)uniform_load(tc) * ct_pairs];
+#pragma unroll
+        for (int g = 0; g < G; g++) w_next[g] = uniform_load(w + g);
+    }
     for (u32 t = 0; t < K; ++t) {
-        const uint2 x = x_base[(size_t)uniform_load(tc + t) * ct_pairs];
+        const uint2 x = x_next;
+        u32 wv[G];
+#pragma unroll
+        for (int g = 0; g < G; g++) wv[g] = w_next[g];
+        const u32 tn = min(t + 1, K - 1);  // the last term asks for itself again: a repeat that is never used
+        x_next = x_base[(size_t)uniform_load(tc + tn) * ct_pairs];
+#pragma unroll
+        for (int g = 0; g < G; g++) w_next[g] = uniform_load(w + (size_t)tn * G + g);
 #pragma unroll
         for (int g = 0; g < G; g++) {
-            const u32 wv = uniform_load(w + (size_t)t * G + g);
-            acc[g][0] += (u64)x.x * wv;
-            acc[g][1] += (u64)x.y * wv;
+            acc[g][0] += (u64)x.x * wv[g];
+            acc[g][1] += (u64)x.y * wv[g];
         }
         if (++since == TERMS_PER_REDUCTION && t + 1 < K) {
             since = 0;
