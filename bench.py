@@ -32,7 +32,7 @@ GIB = 1 << 30
 PROFILED_TRAFFIC_BYTES = {
     "mac_scalar_cfg4": int((10.61 + 8.19) * GIB),
     "mac_poly_cfg5": int((16.58 + 0.125) * GIB),
-    "rescale_cfg4": int((15.76 + 9.59) * GIB),
+    "rescale_cfg4": int((15.66 + 9.59) * GIB),
     "rescale_cfg5": None,
 }
 
