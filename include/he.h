@@ -230,6 +230,11 @@ uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotie
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q);
 /* The same with the kernels' final step: (sum + addend) mod q for an addend below q (the bias of Alg. 4). */
 uint64_t he_host_mac_accumulate_add(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
+/* The three-product (Karatsuba) form of the MAC terms that the 16-output kernel uses on limbs that leave room
+ * for it: the number of terms such sums can take for modulus q (0: the form is not used for q), and
+ * (sum of x[t]*w[t] + addend) mod q computed that way for n terms (UINT64_MAX if n exceeds that number). */
+uint32_t he_host_mac_three_product_terms(uint64_t q);
+uint64_t he_host_mac_accumulate_three_products(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
 /* The two primitives of the packed 32-bit path, for q in [2, 2^30): BarrettReduction64 (Alg. 6), z mod q for
  * any 64-bit z; and the lazy 32-bit Shoup product, congruent to y*w mod q and in [0, 2q), for w < q and any
  * 32-bit y. */

@@ -132,6 +132,18 @@ void fill_limb_const(LimbConst& c, u64 q, u64 psi, u32 N) {
         if (c.narrow) c.reduce_every = (u32)std::min<u128>(c.reduce_every, lim);
     }
     c.ntt_mode = q < (1ull << 58) ? 2 : q < (1ull << 61) ? 1 : 0;
+    // three products per MAC term: the sum of (xa+xb)*(wa+wb) must fit 64 bits with xa+xb, wa+wb below 2^32,
+    // and the total must stay within the one-word Barrett of acc_reduce_add (narrow limbs below 2^61)
+    c.kara_terms = 0;
+    const u128 all_ones64 = (((u128)1) << 64) - 1;
+    if (c.narrow && q < (1ull << 61)) {
+        const u128 ab = (u128)c.split_mask + ((q - 1) >> c.split_bits);
+        if (ab < ((u128)1 << 32)) {
+            const u128 sq = (u128)(q - 1) * (q - 1);
+            const u128 lim = std::min<u128>(all_ones64 / (ab * ab), ((((u128)1) << (63 + bits)) - 1 - q) / sq);
+            c.kara_terms = (u32)std::min<u128>(lim, 0x7FFFFFFFull);
+        }
+    }
     c.neg_two_q = 0 - 2 * q;
     c.four_q = 4 * q;
     c.neg_four_q = 0 - 4 * q;
@@ -501,10 +513,12 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
     u64 elems = 0;
     for (int cls = 0; cls < 3; ++cls) {
         p->min_terms_s[cls] = p->class_begin_s[cls] < p->class_begin_s[cls + 1] ? ~0u : 0;
+        p->max_terms_s[cls] = 0;
         std::map<std::vector<u32>, u64> tables;
         std::vector<u32> key;
         for (u32 i = p->class_begin_s[cls]; i < p->class_begin_s[cls + 1]; ++i) {
             p->min_terms_s[cls] = std::min(p->min_terms_s[cls], ts[i].n_terms);
+            p->max_terms_s[cls] = std::max(p->max_terms_s[cls], ts[i].n_terms);
             key.assign(1, ts[i].n_terms);
             for (u32 g = 0; g < ts[i].count; ++g)
                 key.insert(key.end(), term_pt + off[ts[i].out0 + g], term_pt + off[ts[i].out0 + g] + ts[i].n_terms);
@@ -516,10 +530,10 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
             tables.emplace(key, elems);
             wbase[i] = elems;
             wowner[i] = 1;
-            elems += (u64)((ts[i].n_terms + 3) / 4 * 4) * CAPS_S[cls];  // terms padded to whole blocks of 4
+            elems += (u64)((ts[i].n_terms + 3) / 4 * 4) * (cls == 2 ? 24 : CAPS_S[cls]);  // terms padded to whole blocks of 4; 24 words per term in 16-output tables
         }
     }
-    p->wtab_elems = elems + 16;  // padding: the 16-output kernel requests one term's weights past its last
+    p->wtab_elems = elems + 24;  // padding: the 16-output kernel requests one term's entry past its last
     if (upload(&p->tiles_s_dev, ts.data(), ts.size()) != HE_OK || upload(&p->tiles_p_dev, tp.data(), tp.size()) != HE_OK ||
         upload(&p->wbase_s_dev, wbase.data(), ts.size()) != HE_OK || upload(&p->wowner_s_dev, wowner.data(), ts.size()) != HE_OK || upload(&p->off_dev, off, (size_t)n_out + 1) != HE_OK ||
         upload(&p->term_ct_dev, term_ct, n_terms) != HE_OK || upload(&p->term_pt_dev, term_pt, n_terms) != HE_OK) {
@@ -828,5 +842,27 @@ uint64_t he_host_mac_accumulate_add(const uint64_t* x, const uint64_t* w, size_t
     if (c.narrow && c.ntt_mode >= 1) return acc_reduce_add(a, addend, c);
     return add_mod(acc_reduce(a, c), addend, c.q);
 }
+
+// The three-product form of the MAC terms, as the 16-output kernel takes it where the limb allows:
+// (sum of x[t]*w[t] + addend) mod q for n <= he_host_mac_three_product_terms(q) terms.  Returns UINT64_MAX if
+// n exceeds that.
+uint64_t he_host_mac_accumulate_three_products(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend) {
+    const LimbConst c = host_const(q);
+    if (n > c.kara_terms) return ~0ull;
+    MacAcc a;
+    acc_clear(a);
+    for (size_t t = 0; t < n; ++t) {
+        u32 xa, xb, wa, wb;
+        split_operand(x[t], c, xa, xb);
+        split_operand(w[t], c, wa, wb);
+        a.lo += (u64)xa * wa;
+        a.mid += (u64)(xa + xb) * (wa + wb);
+        a.hi += (u64)xb * wb;
+    }
+    acc_uncross(a);
+    return acc_reduce_add(a, addend, c);
+}
+
+uint32_t he_host_mac_three_product_terms(uint64_t q) { return host_const(q).kara_terms; }
 
 }  // extern "C"

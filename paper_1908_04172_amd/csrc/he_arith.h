@@ -27,6 +27,8 @@ struct LimbConst {
     u32 mu_shift;     // bit length of q, minus 1
     u32 ntt_mode;     // how lazily the butterflies reduce: 0 for q >= 2^61, 1 for q >= 2^58, else 2 (see the butterflies at the end of this file)
     u64 neg_two_q, four_q, neg_four_q;  // 2^64 - 2q, 4q mod 2^64, 2^64 - 4q (4q is used only when it fits)
+    u32 kara_terms;   // MAC terms whose three-product sums (see acc_uncross) fit 64 bits and the one-word Barrett; 0: never
+    u32 pad;
 };
 
 HE_HD u64 mul_hi64(u64 a, u64 b) {
@@ -198,6 +200,10 @@ HE_HD void acc_mac(MacAcc& a, u32 xa, u32 xb, u32 wa, u32 wb) {
     a.mid += (u64)xb * wa;
     a.hi += (u64)xb * wb;
 }
+
+// The three-product form of a term (Karatsuba) adds xa*wa to lo, xb*wb to hi and (xa+xb)*(wa+wb) to mid;
+// this turns such sums into the plain ones (mid = the cross terms xa*wb + xb*wa), once, when they are read out.
+HE_HD void acc_uncross(MacAcc& a) { a.mid -= a.lo + a.hi; }
 
 HE_HD void acc_fold(MacAcc& a, const LimbConst& c) {  // push the high parts of lo and mid upwards
     a.mid += a.lo >> c.split_bits;

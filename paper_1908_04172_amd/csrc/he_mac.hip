@@ -16,17 +16,26 @@ constexpr u64 MIN_WORKGROUPS = 256 * 32;  // ... while the launch keeps at least
 
 __host__ __device__ inline u32 padded_terms(u32 n_terms) { return (n_terms + BLOCK_TERMS - 1) / BLOCK_TERMS * BLOCK_TERMS; }
 
-// Weight table for scalar plaintexts: wtab[limb*wtab_elems + wbase + t*G + g], 0 <= t < Kp = n_terms
-// rounded up to a multiple of BLOCK_TERMS, holds the two pieces (wa | wb << 32, see MacAcc) of
-// pt[term_pt[off[out0+g] + t]][limb], and zero for g >= tile.count or t >= n_terms.  The MAC loop
-// then reads G consecutive entries per term with scalar loads, runs whole blocks of terms, and needs
-// neither a per-output branch nor a split of the plaintext operand.  Groups with the same plaintext
-// indices share one table (same wbase; the group with wowner set fills it), and every limb's part
-// ends with 16 entries of padding that are read ahead but never used.
+// A term's entry in a 16-output weight table: 16 residues as (wa, wb) pairs, then the 16 sums wa + wb
+// (used by the three-product form), 24 64-bit words in all; smaller groups have G words per term.
+template <int G>
+struct TermStride {
+    static constexpr u32 WORDS = G == 16 ? 24 : G;
+};
+
+// Weight table for scalar plaintexts: the entry of term t (0 <= t < Kp = n_terms rounded up to a
+// multiple of BLOCK_TERMS) of a group starts at wtab[limb*wtab_elems + wbase + t*WORDS]; word g holds the
+// two pieces (wa | wb << 32, see MacAcc) of pt[term_pt[off[out0+g] + t]][limb], zero for g >= tile.count or
+// t >= n_terms, and in 16-output tables the 32-bit sums wa + wb follow in words 16..23.  The MAC loop then
+// reads a term's entry with scalar loads, runs whole blocks of terms, and needs neither a per-output
+// branch nor a split of the plaintext operand.  Groups with the same plaintext indices share one table
+// (same wbase; the group with wowner set fills it), and every limb's part ends with one entry of padding
+// that is read ahead but never used.
 template <int G>
 __global__ void __launch_bounds__(256) gather_weights_kernel(LimbTable lt, const Tile* tiles, const u64* wbase, const u32* wowner, u32 n_tiles,
                                                              u32 limbs, const u32* off, const u32* term_pt, const u64* pt,
                                                              u64* wtab, u64 wtab_elems) {
+    constexpr u32 WORDS = TermStride<G>::WORDS;
     const u32 tile_i = blockIdx.x / GATHER_BLOCKS;
     const u32 sub = blockIdx.x % GATHER_BLOCKS;
     if (tile_i >= n_tiles || !wowner[tile_i]) return;  // a shared table is filled by one of its groups
@@ -38,13 +47,12 @@ __global__ void __launch_bounds__(256) gather_weights_kernel(LimbTable lt, const
         const u32 limb = (u32)(i / per_limb);
         const u64 rem = i % per_limb;
         const u32 t = (u32)(rem / G), g = (u32)(rem % G);
-        u64 packed = 0;
-        if (g < tile.count && t < tile.n_terms) {
-            u32 wa, wb;
+        u32 wa = 0, wb = 0;
+        if (g < tile.count && t < tile.n_terms)
             split_operand(pt[(size_t)term_pt[off[tile.out0 + g] + t] * limbs + limb], lt.c[limb], wa, wb);
-            packed = (u64)wa | ((u64)wb << 32);
-        }
-        dst[(u64)limb * wtab_elems + rem] = packed;
+        u64* entry = dst + (u64)limb * wtab_elems + (u64)t * WORDS;
+        entry[g] = (u64)wa | ((u64)wb << 32);
+        if constexpr (G == 16) reinterpret_cast<u32*>(entry + 16)[g] = wa + wb;
     }
 }
 
@@ -88,16 +96,29 @@ __device__ __forceinline__ Tile uniform_load(const Tile* p) {
     return Tile{uniform_load(&p->out0), uniform_load(&p->count), uniform_load(&p->term0), uniform_load(&p->n_terms)};
 }
 
-// Eight plaintext residues (as 32-bit pieces) in 16 scalar registers.  The loads are issued by hand
-// so that they are in flight during multiply-adds that do not need them: request() starts one,
-// arrived() waits for it; between the two calls the registers must not be read.
+// Eight plaintext residues (as 32-bit pieces) in 16 scalar registers, and (SUMS) their eight sums
+// wa + wb in 8 more.  The loads are issued by hand so that they are in flight during multiply-adds
+// that do not need them: request<HALF>(term) starts the loads of outputs 8*HALF .. 8*HALF+7 of the
+// table entry `term`, arrived() waits for them; between the two calls the registers must not be read.
 typedef u32 u32x16 __attribute__((ext_vector_type(16)));
+typedef u32 u32x8 __attribute__((ext_vector_type(8)));
+template <bool SUMS>
 struct ScalarWeights8 {
     u32x16 v;  // (wa, wb) pairs
-    __device__ __forceinline__ void request(const u64* wt) {
-        asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=&s"(v) : "s"(wt) : "memory");
+    u32x8 s;   // wa + wb
+    template <int HALF>
+    __device__ __forceinline__ void request(const u64* term) {
+        if constexpr (HALF == 0) asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=&s"(v) : "s"(term) : "memory");
+        else asm volatile("s_load_dwordx16 %0, %1, 0x40" : "=&s"(v) : "s"(term) : "memory");
+        if constexpr (SUMS) {
+            if constexpr (HALF == 0) asm volatile("s_load_dwordx8 %0, %1, 0x80" : "=&s"(s) : "s"(term) : "memory");
+            else asm volatile("s_load_dwordx8 %0, %1, 0xa0" : "=&s"(s) : "s"(term) : "memory");
+        }
     }
-    __device__ __forceinline__ void arrived() { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(v)); }
+    __device__ __forceinline__ void arrived() {
+        if constexpr (SUMS) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(v), "+s"(s));
+        else asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(v));
+    }
 };
 
 // One term's multiply-adds into eight of the sixteen outputs (acc_mac, spelt out).  A multiply-add
@@ -105,7 +126,7 @@ struct ScalarWeights8 {
 // of one instruction), so the two that go into `mid` are kept 16 instructions apart: four passes over
 // the eight outputs, pinned in this order.
 template <int FIRST>
-__device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[16], u32 xa, u32 xb, const ScalarWeights8& w) {
+__device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[16], u32 xa, u32 xb, const ScalarWeights8<false>& w) {
 #pragma unroll
     for (int g = 0; g < 8; g++) acc[FIRST + g].lo += (u64)xa * w.v[2 * g];
     __builtin_amdgcn_sched_barrier(0);
@@ -117,6 +138,22 @@ __device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[16], u32 xa, u32 
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int g = 0; g < 8; g++) acc[FIRST + g].mid += (u64)xb * w.v[2 * g];
+}
+
+// The three-product form (Karatsuba): lo += xa*wa, hi += xb*wb, mid += (xa+xb)*(wa+wb); the cross
+// terms xa*wb + xb*wa are mid - lo - hi, formed once per output when the sums are read out
+// (acc_uncross).  Used where LimbConst::kara_terms says that a whole group's terms fit the sums.
+template <int FIRST>
+__device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[16], u32 xa, u32 xb, const ScalarWeights8<true>& w) {
+    const u32 xs = xa + xb;
+#pragma unroll
+    for (int g = 0; g < 8; g++) acc[FIRST + g].lo += (u64)xa * w.v[2 * g];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g < 8; g++) acc[FIRST + g].mid += (u64)xs * w.s[g];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g < 8; g++) acc[FIRST + g].hi += (u64)xb * w.v[2 * g + 1];
 }
 
 template <int G>
@@ -172,6 +209,128 @@ __device__ __forceinline__ void store_group(MacAcc (&acc)[G], u32 out0, u32 coun
     }
 }
 
+// The main path of the scalar MAC kernel (see mac_scalar_kernel): groups tile_first .. tile_end-1, chained.
+// KARA selects the three-product form of a term (16-output groups only).
+template <int G, bool KARA>
+__device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, u32 N, const Tile* tiles, u32 tile_first, u32 tile_end,
+                                                 const u64* wbase, const u32* term_ct, const u64* wtab, u64 wtab_elems,
+                                                 const u64* x_base, size_t ct_stride, const u64* bias, u32 comp, u32 limb, u32 n,
+                                                 u64* out) {
+    constexpr u32 WS = TermStride<G>::WORDS;
+    MacAcc acc[G];
+    // Terms run in blocks of four (terms K..Kp-1 are padding: zero weights, input K-1 again).
+    // Ring of inputs: xq[j] holds the residue of term t+j and is refilled for term t+j+4 as soon
+    // as it has been consumed, so a load has a whole block of MACs (256 multiply-adds per lane)
+    // to complete.  The ring looks 8 terms ahead; two blocks before the end of a group it moves
+    // on to the next group's list (the host runs several groups per workgroup only if every
+    // group has at least 8 padded terms, so the ring is never more than one group ahead).
+    // Folds and reductions happen between runs of whole blocks only, so inside a run the partial
+    // sums are plain loop-carried registers.
+    const u32 fold_blocks = c.fold_every / BLOCK_TERMS * BLOCK_TERMS;
+    const u32 reduce_blocks = c.reduce_every / BLOCK_TERMS * BLOCK_TERMS;
+    const Tile first = uniform_load(tiles + tile_first);
+    u32 Kp = padded_terms(first.n_terms);
+    // the list the ring is filled from: term u of the current group (u may run past Kp, into the
+    // next group) is term_ct[list0 + min(u, u_last)], the sum taken modulo 2^32 (list0 is the
+    // next list's start minus Kp, which may be "negative")
+    u32 list0 = first.term0;
+    u32 u_last = first.n_terms - 1;
+    // weights of the term being multiplied
+    const u64* w_limb = wtab + (u64)limb * wtab_elems;
+    const u64* wp = w_limb + uniform_load(wbase + tile_first);
+    u64 xq[BLOCK_TERMS];
+    u32 cq[BLOCK_TERMS];  // ciphertext indices of terms t+4 .. t+7, fetched a block before they are needed
+#pragma unroll
+    for (int j = 0; j < BLOCK_TERMS; j++) {
+        xq[j] = x_base[(size_t)term_ct[(u32)(list0 + min((u32)j, u_last))] * ct_stride];
+        cq[j] = term_ct[(u32)(list0 + min((u32)(BLOCK_TERMS + j), u_last))];
+    }
+    // The plaintext residues of a term sit in scalar registers, eight outputs' worth in each of
+    // two sets.  While one set's multiply-adds run, the other set's next load is in flight: at
+    // the start of a term w_lo holds this term's residues for outputs 0..7 and the load of w_hi
+    // (outputs 8..15) has been issued.  After the last term of the last group the requests reach
+    // whatever follows its table (another table or the padding).
+    ScalarWeights8<KARA> w_lo, w_hi;
+    // where the operands are cut, held in registers for the whole loop (left to itself the
+    // compiler fetches the two words again in every block, and waits for them)
+    u32 split_mask = (u32)c.split_mask, split_bits = c.split_bits;
+    asm volatile("" : "+s"(split_mask), "+s"(split_bits));
+    if constexpr (G == 16) {
+        w_lo.template request<0>(wp);
+        w_lo.arrived();
+        w_hi.template request<1>(wp);
+    }
+    for (u32 tile_i = tile_first; tile_i < tile_end; tile_i++) {
+        // the group after this one; after the last one the ring stays on this group's last term
+        // (loads that hit in the cache and are never used)
+        u32 next_list0 = list0 + u_last, next_K = 1;
+        const u64* wp_next_group = wp + (size_t)Kp * WS;  // after the last group: whatever follows its table
+        if (tile_i + 1 < tile_end) {
+            const Tile next = uniform_load(tiles + tile_i + 1);
+            next_list0 = next.term0;
+            next_K = next.n_terms;
+            wp_next_group = w_limb + uniform_load(wbase + tile_i + 1);
+        }
+        const Tile cur = uniform_load(tiles + tile_i);
+        const u32 out0 = cur.out0, count = cur.count;
+#pragma unroll
+        for (int g = 0; g < G; g++) acc_clear(acc[g]);
+        u32 f = 0, r = 0, t = 0;
+        while (t < Kp) {
+            const u32 run = min(Kp - t, min(fold_blocks - f, reduce_blocks - r));
+            const u32 t_end = t + run;
+#pragma unroll 1
+            for (; t < t_end; t += BLOCK_TERMS) {
+                if (t + 2 * BLOCK_TERMS == Kp) {  // from here on the look-ahead is in the next group
+                    list0 = next_list0 - Kp;
+                    u_last = Kp + next_K - 1;
+                }
+                // where the weights of the term after this block are
+                const u64* wp_after = t + BLOCK_TERMS == Kp ? wp_next_group : wp + BLOCK_TERMS * WS;
+#pragma unroll
+                for (int j = 0; j < BLOCK_TERMS; j++) {
+                    const u64 x = xq[j];
+                    xq[j] = x_base[(size_t)cq[j] * ct_stride];
+                    cq[j] = term_ct[(u32)(list0 + min(t + 2 * BLOCK_TERMS + j, u_last))];
+                    if constexpr (G == 16) {
+                        // (the scheduling barriers keep each half's multiply-adds between a
+                        // request and the wait for it, where they hide the load's latency)
+                        const u32 xa = (u32)x & split_mask, xb = (u32)(x >> split_bits);  // split_operand
+                        __builtin_amdgcn_sched_barrier(0);
+                        scalar_half_term<0>(acc, xa, xb, w_lo);
+                        __builtin_amdgcn_sched_barrier(0);
+                        w_hi.arrived();
+                        w_lo.template request<0>(j + 1 < (int)BLOCK_TERMS ? wp + (j + 1) * WS : wp_after);
+                        __builtin_amdgcn_sched_barrier(0);
+                        scalar_half_term<8>(acc, xa, xb, w_hi);
+                        __builtin_amdgcn_sched_barrier(0);
+                        w_lo.arrived();
+                        w_hi.template request<1>(j + 1 < (int)BLOCK_TERMS ? wp + (j + 1) * WS : wp_after);
+                    } else {
+                        u64 wt[G];
+                        load_weights<G>(wt, wp + j * WS);
+                        scalar_term<G>(acc, x, wt, c);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);  // one term at a time: keeps the live values few
+                }
+                wp = wp_after;
+            }
+            if constexpr (G == 16) w_hi.arrived();  // no load in flight outside the block loop
+            f += run;
+            r += run;
+            if (t < Kp) housekeeping<G>(acc, f, r, fold_blocks, reduce_blocks, c);
+        }
+        if constexpr (KARA) {
+#pragma unroll
+        for (int g = 0; g < G; g++) acc_uncross(acc[g]);
+    }
+    store_group<G>(acc, out0, count, c, bias, comp, limb, limbs, N, n, out);
+        list0 += Kp;
+        u_last -= Kp;
+        Kp = padded_terms(next_K);
+    }
+}
+
 // A workgroup owns one 256-residue slice of one (component, limb) row and `per_wg` consecutive groups
 // of outputs, which it handles one after the other.  In the main path the input ring and the scalar
 // weights run on into the next group while the current one is still being reduced and stored, so the
@@ -179,7 +338,7 @@ __device__ __forceinline__ void store_group(MacAcc (&acc)[G], u32 out0, u32 coun
 // close it are paid once per workgroup instead of once per group.
 template <int G>
 __global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8)))
-mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg, const u64* wbase,
+mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg, u32 max_terms, const u64* wbase,
                   const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
     const u32 chunks = N / MAC_THREADS;
     const u32 n_wg_tiles = (n_tiles + per_wg - 1) / per_wg;
@@ -200,113 +359,13 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
     MacAcc acc[G];
 
     if (c.fold_every >= BLOCK_TERMS && uniform_load(&tiles[tile_first].n_terms) > 0) {
-        // Terms run in blocks of four (terms K..Kp-1 are padding: zero weights, input K-1 again).
-        // Ring of inputs: xq[j] holds the residue of term t+j and is refilled for term t+j+4 as soon
-        // as it has been consumed, so a load has a whole block of MACs (256 multiply-adds per lane)
-        // to complete.  The ring looks 8 terms ahead; two blocks before the end of a group it moves
-        // on to the next group's list (the host runs several groups per workgroup only if every
-        // group has at least 8 padded terms, so the ring is never more than one group ahead).
-        // Folds and reductions happen between runs of whole blocks only, so inside a run the partial
-        // sums are plain loop-carried registers.
-        const u32 fold_blocks = c.fold_every / BLOCK_TERMS * BLOCK_TERMS;
-        const u32 reduce_blocks = c.reduce_every / BLOCK_TERMS * BLOCK_TERMS;
-        const Tile first = uniform_load(tiles + tile_first);
-        u32 Kp = padded_terms(first.n_terms);
-        // the list the ring is filled from: term u of the current group (u may run past Kp, into the
-        // next group) is term_ct[list0 + min(u, u_last)], the sum taken modulo 2^32 (list0 is the
-        // next list's start minus Kp, which may be "negative")
-        u32 list0 = first.term0;
-        u32 u_last = first.n_terms - 1;
-        // weights of the term being multiplied
-        const u64* w_limb = wtab + (u64)limb * wtab_elems;
-        const u64* wp = w_limb + uniform_load(wbase + tile_first);
-        u64 xq[BLOCK_TERMS];
-        u32 cq[BLOCK_TERMS];  // ciphertext indices of terms t+4 .. t+7, fetched a block before they are needed
-#pragma unroll
-        for (int j = 0; j < BLOCK_TERMS; j++) {
-            xq[j] = x_base[(size_t)term_ct[(u32)(list0 + min((u32)j, u_last))] * ct_stride];
-            cq[j] = term_ct[(u32)(list0 + min((u32)(BLOCK_TERMS + j), u_last))];
-        }
-        // The plaintext residues of a term sit in scalar registers, eight outputs' worth in each of
-        // two sets.  While one set's multiply-adds run, the other set's next load is in flight: at
-        // the start of a term w_lo holds this term's residues for outputs 0..7 and the load of w_hi
-        // (outputs 8..15) has been issued.  After the last term of the last group the requests reach
-        // whatever follows its table (another table or the padding).
-        ScalarWeights8 w_lo, w_hi;
-        // where the operands are cut, held in registers for the whole loop (left to itself the
-        // compiler fetches the two words again in every block, and waits for them)
-        u32 split_mask = (u32)c.split_mask, split_bits = c.split_bits;
-        asm volatile("" : "+s"(split_mask), "+s"(split_bits));
-        if constexpr (G == 16) {
-            w_lo.request(wp);
-            w_lo.arrived();
-            w_hi.request(wp + 8);
-        }
-        for (u32 tile_i = tile_first; tile_i < tile_end; tile_i++) {
-            // the group after this one; after the last one the ring stays on this group's last term
-            // (loads that hit in the cache and are never used)
-            u32 next_list0 = list0 + u_last, next_K = 1;
-            const u64* wp_next_group = wp + (size_t)Kp * G;  // after the last group: whatever follows its table
-            if (tile_i + 1 < tile_end) {
-                const Tile next = uniform_load(tiles + tile_i + 1);
-                next_list0 = next.term0;
-                next_K = next.n_terms;
-                wp_next_group = w_limb + uniform_load(wbase + tile_i + 1);
-            }
-            const Tile cur = uniform_load(tiles + tile_i);
-            const u32 out0 = cur.out0, count = cur.count;
-#pragma unroll
-            for (int g = 0; g < G; g++) acc_clear(acc[g]);
-            u32 f = 0, r = 0, t = 0;
-            while (t < Kp) {
-                const u32 run = min(Kp - t, min(fold_blocks - f, reduce_blocks - r));
-                const u32 t_end = t + run;
-#pragma unroll 1
-                for (; t < t_end; t += BLOCK_TERMS) {
-                    if (t + 2 * BLOCK_TERMS == Kp) {  // from here on the look-ahead is in the next group
-                        list0 = next_list0 - Kp;
-                        u_last = Kp + next_K - 1;
-                    }
-                    // where the weights of the term after this block are
-                    const u64* wp_after = t + BLOCK_TERMS == Kp ? wp_next_group : wp + BLOCK_TERMS * G;
-#pragma unroll
-                    for (int j = 0; j < BLOCK_TERMS; j++) {
-                        const u64 x = xq[j];
-                        xq[j] = x_base[(size_t)cq[j] * ct_stride];
-                        cq[j] = term_ct[(u32)(list0 + min(t + 2 * BLOCK_TERMS + j, u_last))];
-                        if constexpr (G == 16) {
-                            // (the scheduling barriers keep each half's multiply-adds between a
-                            // request and the wait for it, where they hide the load's latency)
-                            const u32 xa = (u32)x & split_mask, xb = (u32)(x >> split_bits);  // split_operand
-                            __builtin_amdgcn_sched_barrier(0);
-                            scalar_half_term<0>(acc, xa, xb, w_lo);
-                            __builtin_amdgcn_sched_barrier(0);
-                            w_hi.arrived();
-                            w_lo.request(j + 1 < (int)BLOCK_TERMS ? wp + (j + 1) * G : wp_after);
-                            __builtin_amdgcn_sched_barrier(0);
-                            scalar_half_term<8>(acc, xa, xb, w_hi);
-                            __builtin_amdgcn_sched_barrier(0);
-                            w_lo.arrived();
-                            w_hi.request((j + 1 < (int)BLOCK_TERMS ? wp + (j + 1) * G : wp_after) + 8);
-                        } else {
-                            u64 wt[G];
-                            load_weights<G>(wt, wp + j * G);
-                            scalar_term<G>(acc, x, wt, c);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);  // one term at a time: keeps the live values few
-                    }
-                    wp = wp_after;
-                }
-                if constexpr (G == 16) w_hi.arrived();  // no load in flight outside the block loop
-                f += run;
-                r += run;
-                if (t < Kp) housekeeping<G>(acc, f, r, fold_blocks, reduce_blocks, c);
-            }
-            store_group<G>(acc, out0, count, c, bias, comp, limb, limbs, N, n, out);
-            list0 += Kp;
-            u_last -= Kp;
-            Kp = padded_terms(next_K);
-        }
+        // three products per term where every group of the launch fits the sums (16-output groups only)
+        if (G == 16 && max_terms <= c.kara_terms)
+            scalar_main_path<G, G == 16>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base, ct_stride,
+                                         bias, comp, limb, n, out);
+        else
+            scalar_main_path<G, false>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base, ct_stride,
+                                       bias, comp, limb, n, out);
         return;
     }
     // Every other case, one group at a time: moduli above 2^60 (they fold more often than once per
@@ -321,7 +380,7 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
         u32 f = 0, r = 0;
         for (u32 t = 0; t < K; ++t) {
             u64 wt[G];
-            load_weights<G>(wt, w + (size_t)t * G);
+            load_weights<G>(wt, w + (size_t)t * TermStride<G>::WORDS);
             scalar_term<G>(acc, x_base[(size_t)tc[t] * ct_stride], wt, c);
             ++f;
             ++r;
@@ -516,7 +575,7 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
     const u64 blocks = (u64)((count + per_wg - 1) / per_wg) * per_group;
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     hipLaunchKernelGGL((mac_scalar_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles,
-                       count, per_wg, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+                       count, per_wg, plan->max_terms_s[cls], wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }

@@ -28,7 +28,7 @@ EXPORTS = [
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_measure_rate",
-    "he_host_barrett64", "he_host_shoup32", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
+    "he_host_barrett64", "he_host_shoup32", "he_host_mac_three_product_terms", "he_host_mac_accumulate_three_products", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
 ]
 
 _lib = None
@@ -76,6 +76,8 @@ def lib():
         "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
         "he_square_relin_workspace_bytes": (i32, [vp, u32, u32, ctypes.POINTER(sz)]),
         "he_ct_square_relin": (i32, [vp, u32, vp, u32, vp, vp, vp, sz, vp]),
+        "he_host_mac_three_product_terms": (u32, [u64]),
+        "he_host_mac_accumulate_three_products": (u64, [vp, vp, sz, u64, u64]),
         "he_host_barrett64": (u32, [u64, u32]),
         "he_host_shoup32": (u32, [u32, u32, u32]),
         "he_pack32": (i32, [vp, vp, vp, sz, vp]),
@@ -406,6 +408,16 @@ def host_shoup_mulmod(y: int, w: int, q: int) -> int:
 
 def host_shoup_lazy(y: int, w: int, q: int, cheap_quotient: bool) -> int:
     return int(lib().he_host_shoup_lazy(y, w, q, int(cheap_quotient)))
+
+
+def host_mac_three_product_terms(q: int) -> int:
+    return int(lib().he_host_mac_three_product_terms(q))
+
+
+def host_mac_accumulate_three_products(x, w, q: int, addend: int = 0) -> int:
+    x, w = _np64(x), _np64(w)
+    assert x.shape == w.shape and x.ndim == 1
+    return int(lib().he_host_mac_accumulate_three_products(x.ctypes.data, w.ctypes.data, x.size, q, addend))
 
 
 def host_barrett64(z: int, q: int) -> int:

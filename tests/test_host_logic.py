@@ -165,3 +165,25 @@ def test_packed32_primitives_against_python_integers():
                     continue
                 r = he.host_shoup32(y, w, q)
                 assert r < 2 * q and r % q == y * w % q
+
+
+def test_three_product_mac_terms_on_the_host():
+    """The Karatsuba form of the MAC terms (lo += xa*wa, hi += xb*wb, mid += (xa+xb)*(wa+wb), cross terms taken
+    out once at the end): exact for as many terms as the library says fit, on extreme and random operands;
+    not used for moduli whose sums leave no room."""
+    rng = np.random.default_rng(33)
+    for bits in (30, 40, 50, 58, 60):
+        q = wl.ntt_primes(bits, 1 << 14, 1)[0]
+        cap = he.host_mac_three_product_terms(q)
+        assert cap >= 64 or bits >= 58, (bits, cap)                     # wide moduli leave no room: the form is off
+        if cap == 0:
+            continue
+        n = min(cap, 5000)
+        for x, w in ((np.full(n, q - 1, dtype=np.uint64), np.full(n, q - 1, dtype=np.uint64)),
+                     (rng.integers(0, q, n, dtype=np.uint64), rng.integers(0, q, n, dtype=np.uint64)),
+                     (np.full(n, (1 << ((bits + 1) // 2)) - 1, dtype=np.uint64), np.full(n, q - 1, dtype=np.uint64))):
+            want = (sum(int(a) * int(b) for a, b in zip(x, w)) + (q - 1)) % q
+            assert he.host_mac_accumulate_three_products(x, w, q, q - 1) == want
+        too_many = np.zeros(cap + 1, dtype=np.uint64)
+        assert he.host_mac_accumulate_three_products(too_many, too_many, q) == 2**64 - 1
+    assert he.host_mac_three_product_terms(wl.ntt_primes(62, 1 << 14, 1)[0]) == 0
