@@ -140,8 +140,11 @@ void fill_limb_const(LimbConst& c, u64 q, u64 psi, u32 N) {
         const u128 ab = (u128)c.split_mask + ((q - 1) >> c.split_bits);
         if (ab < ((u128)1 << 32)) {
             const u128 sq = (u128)(q - 1) * (q - 1);
-            const u128 lim = std::min<u128>(all_ones64 / (ab * ab), ((((u128)1) << (63 + bits)) - 1 - q) / sq);
-            c.kara_terms = (u32)std::min<u128>(lim, 0x7FFFFFFFull);
+            u128 lim = std::min<u128>(all_ones64 / (ab * ab), ((((u128)1) << (63 + bits)) - 1 - q) / sq);
+            // the kernel runs such a group's padded terms (up to 3 more, zero weights) in one go, with no
+            // fold or reduction on the way: stay within those periods too
+            lim = std::min<u128>(lim, std::min(c.fold_every, c.reduce_every));
+            c.kara_terms = lim > 3 ? (u32)std::min<u128>(lim - 3, 0x7FFFFFFFull) : 0;
         }
     }
     c.neg_two_q = 0 - 2 * q;
