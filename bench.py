@@ -199,7 +199,9 @@ def main() -> int:
             r["arithmetic_ms_at_measured_rate"] = ideal[name] * 1e3
             r["frac_of_measured_rate"] = ideal[name] * 1e3 / phase_ms[name]
     names = ["mad32", "mac_term", "shoup_exact", "shoup_cheap", "butterfly_mode0", "butterfly_mode1",
-             "butterfly_mode2", "butterfly_inverse"]
+             "butterfly_mode2", "butterfly_inverse", "butterfly_fp64_probe"]
+    if args.rates and not only:
+        rate(he.RATE_BUTTERFLY_FP64, L - 1)      # what a double-precision butterfly would cost on a 50-bit limb (no kernel uses it)
     measured_rates = {"unit": "G operations/s, register-resident, whole GPU",
                       "rates": {"%s@%dbit" % (names[k], q[limb].bit_length()): v / 1e9
                                 for (k, limb), v in sorted(rate_cache.items(), reverse=True)}}

@@ -257,7 +257,9 @@ enum {
     HE_RATE_BUTTERFLY_MODE0 = 4, /* forward butterfly for moduli up to 2^62 */
     HE_RATE_BUTTERFLY_MODE1 = 5, /* forward butterfly for moduli below 2^61 */
     HE_RATE_BUTTERFLY_MODE2 = 6, /* forward butterfly for moduli below 2^58 */
-    HE_RATE_BUTTERFLY_INV = 7    /* inverse butterfly for moduli below 2^61 */
+    HE_RATE_BUTTERFLY_INV = 7,   /* inverse butterfly for moduli below 2^61 */
+    HE_RATE_BUTTERFLY_FP64 = 8   /* a forward butterfly for moduli below 2^50 on double-precision FMAs: no kernel uses
+                                    it; it is timed to say what that arithmetic would cost (HE_ERR_MODULUS above 2^50) */
 };
 int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s);
 

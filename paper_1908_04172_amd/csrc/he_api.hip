@@ -812,7 +812,8 @@ uint32_t he_host_shoup32(uint32_t y, uint32_t w, uint32_t q) { return shoup32(y,
 
 int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s) {
     if (!ctx || !ops_per_s || limb >= ctx->L || iters == 0 || iters > (1u << 20)) return HE_ERR_ARG;
-    if (kind < HE_RATE_MAD32 || kind > HE_RATE_BUTTERFLY_INV) return HE_ERR_ARG;
+    if (kind < HE_RATE_MAD32 || kind > HE_RATE_BUTTERFLY_FP64) return HE_ERR_ARG;
+    if (kind == HE_RATE_BUTTERFLY_FP64 && ctx->q[limb] >= (1ull << 50)) return HE_ERR_MODULUS;
     // the lazier butterflies assume the room their modes are chosen by
     const u32 mode = ctx->limbs.c[limb].ntt_mode;
     if ((kind == HE_RATE_BUTTERFLY_MODE2 && mode < 2) || ((kind == HE_RATE_BUTTERFLY_MODE1 || kind == HE_RATE_BUTTERFLY_INV) && mode < 1))

@@ -428,6 +428,10 @@ def test_measured_rates_are_plausible(he):
     b0, b1, b2 = (ctx.measure_rate(k, 2, 512) for k in (he.RATE_BUTTERFLY_MODE0, he.RATE_BUTTERFLY_MODE1,
                                                          he.RATE_BUTTERFLY_MODE2))
     assert b0 < b1 < b2 < mad / 4
+    assert 1e11 < ctx.measure_rate(he.RATE_BUTTERFLY_FP64, 2, 512) < 4e13            # the double-precision probe (50-bit limb)
+    with pytest.raises(he.HeError) as e:                                            # nor does a 60-bit limb fit doubles
+        ctx.measure_rate(he.RATE_BUTTERFLY_FP64, 0, 512)
+    assert e.value.status == -2
     with pytest.raises(he.HeError) as e:                                            # a 60-bit limb has no mode 2
         ctx.measure_rate(he.RATE_BUTTERFLY_MODE2, 0, 512)
     assert e.value.status == -2
