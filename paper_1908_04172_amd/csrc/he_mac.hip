@@ -220,8 +220,8 @@ __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, 
     MacAcc acc[G];
     // Terms run in blocks of four (terms K..Kp-1 are padding: zero weights, input K-1 again).
     // Ring of inputs: xq[j] holds the residue of term t+j and is refilled for term t+j+4 as soon
-    // as it has been consumed, so a load has a whole block of MACs (256 multiply-adds per lane)
-    // to complete.  The ring looks 8 terms ahead; two blocks before the end of a group it moves
+    // as it has been consumed, so a load has a whole block of MACs (256 multiply-adds per lane, 192
+    // in the three-product form) to complete.  The ring looks 8 terms ahead; two blocks before the end of a group it moves
     // on to the next group's list (the host runs several groups per workgroup only if every
     // group has at least 8 padded terms, so the ring is never more than one group ahead).
     // Folds and reductions happen between runs of whole blocks only, so inside a run the partial
