@@ -270,9 +270,9 @@ __device__ __forceinline__ u32 fresh(u32 tid) {
 // In-place transforms of `rows` rows of N residues, row r under limb r % limbs.  A workgroup takes
 // rows blockIdx.x, blockIdx.x + gridDim.x, ... and requests its next row before it stores the
 // current one, so that the loads do not queue behind the stores and arrive while those drain.
-// SPREAD (forward only): row r is not read from `data` but from row r / limbs of `spread_src`, a
-// table of coefficient rows [..][digits][N] whose row (.., j) holds integers below q_j; they are
-// reduced modulo the row's own limb first.  This is the digit expansion of a key switch: each
+// SPREAD (forward only): a row is not read from `data` but from a row of `spread_src`, a table of
+// coefficient rows [..][digits][N] whose row (.., j) holds integers below q_j; they are reduced
+// modulo the target limb first.  This is the digit expansion of a key switch: each
 // digit transformed under every limb, written to data [..][digits][limbs][N]; the limbs are
 // q_0..q_{limbs-2} and, at the last position, the special prime (limb `last_id` of the context).
 template <int LOGN, bool INVERSE, bool SPREAD = false>
@@ -284,25 +284,36 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
     constexpr int PIN = INVERSE ? G::NPASS - 1 : 0, POUT = INVERSE ? 0 : G::NPASS - 1;
     extern __shared__ u64 lds[];
     u64 a[16];
+    // SPREAD: `rows` counts the rows to transform, limbs - 1 per digit row: digit j under every limb position but
+    // j, where the result is the digit's own NTT-form row, which the caller has put there.  Work item w maps to
+    // digit row w / (limbs - 1) and limb position (w % (limbs - 1)), stepped over j.
+    auto spread_row = [&](u32 w, u32& src_row) -> u32 {
+        src_row = w / (limbs - 1);
+        u32 pos = w % (limbs - 1);
+        pos += pos >= src_row % digits;
+        return src_row * limbs + pos;
+    };
     {
-        const u64* p = SPREAD ? spread_src + (size_t)(blockIdx.x / limbs) * G::N : data + (size_t)blockIdx.x * G::N;
+        u32 src_row = 0;
+        if constexpr (SPREAD) (void)spread_row(blockIdx.x, src_row);
+        const u64* p = SPREAD ? spread_src + (size_t)src_row * G::N : data + (size_t)blockIdx.x * G::N;
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, PIN>(threadIdx.x, e)];
     }
-    for (u32 row = blockIdx.x; row < rows; row += gridDim.x) {
+    for (u32 work = blockIdx.x; work < rows; work += gridDim.x) {
         u32 tid_i = threadIdx.x;  // opaque per iteration: addresses are recomputed, not kept live
         asm volatile("" : "+v"(tid_i));
         const u32 tid = tid_i;
+        u32 src_row_unused = 0;
+        const u32 row = SPREAD ? spread_row(work, src_row_unused) : work;
         const u32 limb = row % limbs;
         const LimbConst& c = lt.c[limb];
         // (digit expansion: the last position is the special prime, whose twiddles sit at its own limb's
         // place in the table; `lt` comes with that limb's constants at the last position)
         const u64* tw = tw_all + (size_t)(SPREAD && limb == limbs - 1 ? last_id : limb) * G::N * 2;
         if constexpr (SPREAD) {
-            if ((row / limbs) % digits != limb) {  // a digit is already reduced modulo its own limb
 #pragma unroll
-                for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
-            }
+            for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
         }
         if constexpr (!INVERSE) {
             ntt_forward_any<LOGN>(a, tw, lds, tid, c);
@@ -322,9 +333,11 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
         u64 next[16];
 #pragma unroll
         for (u32 e = 0; e < 16; e++) next[e] = 0;
-        if (row + gridDim.x < rows) {
-            const u32 nr = row + gridDim.x;
-            const u64* p = SPREAD ? spread_src + (size_t)(nr / limbs) * G::N : data + (size_t)nr * G::N;
+        if (work + gridDim.x < rows) {
+            const u32 nr = work + gridDim.x;
+            u32 next_src = 0;
+            if constexpr (SPREAD) (void)spread_row(nr, next_src);
+            const u64* p = SPREAD ? spread_src + (size_t)next_src * G::N : data + (size_t)nr * G::N;
 #pragma unroll
             for (u32 e = 0; e < 16; e++) next[e] = p[reg_index<LOGN, PIN>(tid_s, e)];
         }
@@ -516,9 +529,10 @@ int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hip
 
 // out [n_digit_rows][limbs][N] = forward transforms, under the limbs q_0..q_{limbs-2} and the special prime (the
 // context's last limb), of the coefficient rows src [n_digit_rows][N] (row r holding integers below the modulus of
-// limb r % digits)
+// limb r % digits); the row of digit j under limb j itself is not written: it is the NTT-form row the coefficients
+// came from, which the caller has
 int launch_ntt_spread(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 n_digit_rows, u32 digits, hipStream_t s) {
-    const u64 rows64 = (u64)n_digit_rows * limbs;
+    const u64 rows64 = (u64)n_digit_rows * (limbs - 1);  // digit j under its own limb is left to the caller
     if (rows64 == 0) return HE_OK;
     if (rows64 > 0x7FFFFFFFull) return HE_ERR_RANGE;
     const u32 rows = (u32)rows64;

@@ -5,8 +5,9 @@
 // limb positions: q_0..q_{l-1}, then P.  Steps, each a launch:
 //   1. (d0, d1, d2) = (c0^2, 2 c0 c1, c1^2), slot-wise; d0, d1 go to the output, d2 to the workspace;
 //   2. inverse NTT of d2: row j now holds the coefficients of [d2]_{q_j} in [0, q_j): RNS digit j;
-//   3+4. every digit re-reduced modulo q_0..q_{l-1} and P and transformed under that limb: one launch of the
-//      transform kernel in its digit-expansion form, l * L rows written from l rows read;
+//   3+4. every digit re-reduced modulo the other q_i and P and transformed under that limb: one launch of the
+//      transform kernel in its digit-expansion form, l * l rows written from l rows read (digit j under limb j
+//      is d2's own row, written by step 1);
 //   5. acc_k = sum_j digit_j * evk[j][k], k = 0, 1, on all L limbs;
 //   6. division of acc by P with rounding: Eq. (2) with P as the dropped limb, the rescale kernel as it is;
 //   7. out_k = d_k + that.
@@ -16,7 +17,10 @@
 namespace {
 
 // step 1: one thread = one slot of one limb of one ciphertext
-__global__ void __launch_bounds__(256) square_kernel(LimbTable lt, u32 l, u32 N, const u64* ct, size_t n, u64* out, u64* d2) {
+// (d2 goes out twice: to d2 [n][l][N], which the inverse transform then turns into coefficients, and to its place
+// among the expanded digits, digit j under limb j, where it needs no transform)
+__global__ void __launch_bounds__(256) square_kernel(LimbTable lt, u32 l, u32 N, const u64* ct, size_t n, u64* out, u64* d2,
+                                                     u64* digits) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= n * l * N) return;
     const size_t k = idx % N, row = idx / N;  // row = ct * l + limb
@@ -27,7 +31,9 @@ __global__ void __launch_bounds__(256) square_kernel(LimbTable lt, u32 l, u32 N,
     const u64 cross = mul_mod(c0, c1, c);
     out[((c_idx * 2) * l + limb) * N + k] = mul_mod(c0, c0, c);
     out[((c_idx * 2 + 1) * l + limb) * N + k] = add_mod(cross, cross, c.q);
-    d2[row * N + k] = mul_mod(c1, c1, c);
+    const u64 sq = mul_mod(c1, c1, c);
+    d2[row * N + k] = sq;
+    digits[(row * (l + 1) + limb) * N + k] = sq;
 }
 
 // step 5: one thread = one slot of one limb of one ciphertext, both components
@@ -86,7 +92,7 @@ int launch_square_relin(he_ctx* ctx, u32 l, const u64* ct_in, u32 n, const u64* 
     LimbTable lt = ctx->limbs;
     lt.c[l] = ctx->limbs.c[ctx->L - 1];  // the special prime at the last position
     int rc;
-    hipLaunchKernelGGL(square_kernel, dim3((u32)b1), dim3(256), 0, s, ctx->limbs, l, N, ct_in, (size_t)n, ct_out, d2);
+    hipLaunchKernelGGL(square_kernel, dim3((u32)b1), dim3(256), 0, s, ctx->limbs, l, N, ct_in, (size_t)n, ct_out, d2, digits);
     HE_HIP(hipGetLastError());
     if ((rc = launch_ntt(ctx, l, d2, n, true, s)) != HE_OK) return rc;
     if ((rc = launch_ntt_spread(ctx, L, d2, digits, n * l, l, s)) != HE_OK) return rc;
