@@ -170,6 +170,13 @@ __device__ __forceinline__ void scalar_term(MacAcc (&acc)[G], u64 x, const u64 (
     for (int g = 0; g < G; g++) acc_mac(acc[g], xa, xb, (u32)wt[g], (u32)(wt[g] >> 32));
 }
 
+// Where ciphertext `ct`'s residue of this thread's (component, limb, slot) is: one 32 x 32 -> 64 bit
+// multiply-add (a ciphertext has fewer than 2^32 bytes, so the stride needs no 64-bit multiply).
+static_assert(((u64)2 * HE_MAX_LIMBS * 8) << HE_MAX_LOG2N < (1ull << 32), "a ciphertext's byte stride fits 32 bits");
+__device__ __forceinline__ const u64* input_at(const u64* x_base, u32 ct, u32 ct_stride_bytes) {
+    return reinterpret_cast<const u64*>(reinterpret_cast<const char*>(x_base) + (u64)ct * ct_stride_bytes);
+}
+
 // Final reduction, bias (Alg. 4, component 0 only) and store of one group of outputs; the cheaper
 // reduction where it applies, chosen once so that the per-output code has no branch.  The group's
 // bias residues come in with one load (lane g of every wave fetches output g's) and are handed out
@@ -214,7 +221,7 @@ __device__ __forceinline__ void store_group(MacAcc (&acc)[G], u32 out0, u32 coun
 template <int G, bool KARA>
 __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, u32 N, const Tile* tiles, u32 tile_first, u32 tile_end,
                                                  const u64* wbase, const u32* term_ct, const u64* wtab, u64 wtab_elems,
-                                                 const u64* x_base, size_t ct_stride, const u64* bias, u32 comp, u32 limb, u32 n,
+                                                 const u64* x_base, u32 ct_stride_bytes, const u64* bias, u32 comp, u32 limb, u32 n,
                                                  u64* out) {
     constexpr u32 WS = TermStride<G>::WORDS;
     MacAcc acc[G];
@@ -242,7 +249,7 @@ __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, 
     u32 cq[BLOCK_TERMS];  // ciphertext indices of terms t+4 .. t+7, fetched a block before they are needed
 #pragma unroll
     for (int j = 0; j < BLOCK_TERMS; j++) {
-        xq[j] = x_base[(size_t)term_ct[(u32)(list0 + min((u32)j, u_last))] * ct_stride];
+        xq[j] = *input_at(x_base, term_ct[(u32)(list0 + min((u32)j, u_last))], ct_stride_bytes);
         cq[j] = term_ct[(u32)(list0 + min((u32)(BLOCK_TERMS + j), u_last))];
     }
     // The plaintext residues of a term sit in scalar registers, eight outputs' worth in each of
@@ -290,7 +297,7 @@ __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, 
 #pragma unroll
                 for (int j = 0; j < BLOCK_TERMS; j++) {
                     const u64 x = xq[j];
-                    xq[j] = x_base[(size_t)cq[j] * ct_stride];
+                    xq[j] = *input_at(x_base, cq[j], ct_stride_bytes);
                     cq[j] = term_ct[(u32)(list0 + min(t + 2 * BLOCK_TERMS + j, u_last))];
                     if constexpr (G == 16) {
                         // (the scheduling barriers keep each half's multiply-adds between a
@@ -361,11 +368,11 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
     if (c.fold_every >= BLOCK_TERMS && uniform_load(&tiles[tile_first].n_terms) > 0) {
         // three products per term where every group of the launch fits the sums (16-output groups only)
         if (G == 16 && max_terms <= c.kara_terms)
-            scalar_main_path<G, G == 16>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base, ct_stride,
-                                         bias, comp, limb, n, out);
+            scalar_main_path<G, G == 16>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base,
+                                         (u32)(ct_stride * 8), bias, comp, limb, n, out);
         else
-            scalar_main_path<G, false>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base, ct_stride,
-                                       bias, comp, limb, n, out);
+            scalar_main_path<G, false>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base,
+                                       (u32)(ct_stride * 8), bias, comp, limb, n, out);
         return;
     }
     // Every other case, one group at a time: moduli above 2^60 (they fold more often than once per
