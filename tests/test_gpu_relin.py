@@ -94,3 +94,60 @@ def test_square_relin_argument_errors(he):
     with pytest.raises(he.HeError) as e:
         ctx.square_relin_workspace_bytes(0, 1)
     assert e.value.status == -3
+
+
+def test_conv_square_dense_network_end_to_end(he):
+    """The shape of the paper's CryptoNets evaluation network in miniature, all on the GPU path: convolution with the
+    scalar encoding + bias + lazy rescale, the x^2 activation (square, relinearise, rescale), a dense layer one
+    level further down.  Every stage is bit-exact against the oracle and the decrypted result matches the float
+    network within the decrypt-level tolerance."""
+    N = 1 << 10
+    q = wl.modulus_chain([45, 30, 30, 30, 50], N)                   # q_0..q_3 and the special prime
+    ctx = he.Context(10, q)
+    sf = sc.Scaffold(N, q, ctx.psi, seed=21)
+    evk = sf.relin_key()
+    conv = wl.conv_plan(4, 4, 1, 3, 3, 2, 2, "same")                # 16 cts -> 2x2x2 = 8 cts
+    dense = wl.dense_plan(conv.n_out, 3)
+    rng = np.random.default_rng(22)
+    x = rng.uniform(-1, 1, size=(conv.n_in, N // 2))
+    w1, b1 = rng.normal(0, 0.3, conv.n_pt), rng.normal(0, 0.3, conv.n_out)
+    w2, b2 = rng.normal(0, 0.3, dense.n_pt), rng.normal(0, 0.3, dense.n_out)
+    s_in = s_w = 2.0**30
+    ct = np.stack([sf.encrypt(x[i] + 0j, s_in)[:, :4] for i in range(conv.n_in)])
+    t = lambda a: torch.from_numpy(a).cuda()
+    h1 = ctx.plan(conv.n_in, conv.n_out, conv.n_pt, conv.off, conv.term_ct, conv.term_pt)
+    h2 = ctx.plan(dense.n_in, dense.n_out, dense.n_pt, dense.off, dense.term_ct, dense.term_pt)
+
+    # convolution at four limbs, rescaled to three
+    y1 = ctx.ct_pt_mac(h1, dev(ct), ctx.encode_scalar(t(w1), s_w, limbs=4), he.PT_SCALAR,
+                       bias=ctx.encode_scalar(t(b1), s_in * s_w, limbs=4), flags=he.RESCALE)
+    s1 = s_in * s_w / q[3]
+    o1, _ = oracle.layer(ct, q[:4], ctx.psi[:4], conv.off, conv.term_ct, conv.term_pt, oracle.encode_scalars(w1, s_w, q[:4]),
+                         oracle.PT_SCALAR, oracle.encode_scalars(b1, s_in * s_w, q[:4]))
+    assert np.array_equal(host(y1), o1)
+    # x^2 at three limbs, rescaled to two
+    y2 = ctx.rescale(ctx.ct_square_relin(y1, dev(evk)))
+    s2 = s1 * s1 / q[2]
+    keep = [0, 1, 2, 4]
+    o2 = oracle.rescale(oracle.square_relin(o1, [q[i] for i in keep], [ctx.psi[i] for i in keep], evk[:3][:, :, keep]), q[:3], ctx.psi[:3])
+    assert np.array_equal(host(y2), o2)
+    # dense layer at two limbs, rescaled to one
+    y3 = ctx.ct_pt_mac(h2, y2, ctx.encode_scalar(t(w2), s_w, limbs=2), he.PT_SCALAR,
+                       bias=ctx.encode_scalar(t(b2), s2 * s_w, limbs=2), flags=he.RESCALE)
+    s3 = s2 * s_w / q[1]
+    o3, _ = oracle.layer(o2, q[:2], ctx.psi[:2], dense.off, dense.term_ct, dense.term_pt, oracle.encode_scalars(w2, s_w, q[:2]),
+                         oracle.PT_SCALAR, oracle.encode_scalars(b2, s2 * s_w, q[:2]))
+    assert np.array_equal(host(y3), o3)
+    assert y3.shape == (dense.n_out, 2, 1, N)
+
+    # the float network, from the same plans
+    def apply(plan, inp, w, b):
+        out = np.zeros((plan.n_out, inp.shape[1]))
+        for o in range(plan.n_out):
+            for k in range(plan.off[o], plan.off[o + 1]):
+                out[o] += inp[plan.term_ct[k]] * w[plan.term_pt[k]]
+            out[o] += b[o]
+        return out
+    want = apply(dense, apply(conv, x, w1, b1) ** 2, w2, b2)
+    got = np.stack([sf.decrypt(host(y3)[o], s3).real for o in range(dense.n_out)])
+    assert np.max(np.abs(got - want) / np.maximum(1.0, np.abs(want))) <= 2.0**-10
