@@ -517,11 +517,13 @@ int he_plan_create(he_ctx* ctx, uint32_t n_in, uint32_t n_out, uint32_t n_pt, co
     for (int cls = 0; cls < 3; ++cls) {
         p->min_terms_s[cls] = p->class_begin_s[cls] < p->class_begin_s[cls + 1] ? ~0u : 0;
         p->max_terms_s[cls] = 0;
+        p->max_count_s[cls] = 0;
         std::map<std::vector<u32>, u64> tables;
         std::vector<u32> key;
         for (u32 i = p->class_begin_s[cls]; i < p->class_begin_s[cls + 1]; ++i) {
             p->min_terms_s[cls] = std::min(p->min_terms_s[cls], ts[i].n_terms);
             p->max_terms_s[cls] = std::max(p->max_terms_s[cls], ts[i].n_terms);
+            p->max_count_s[cls] = std::max(p->max_count_s[cls], ts[i].count);
             key.assign(1, ts[i].n_terms);
             for (u32 g = 0; g < ts[i].count; ++g)
                 key.insert(key.end(), term_pt + off[ts[i].out0 + g], term_pt + off[ts[i].out0 + g] + ts[i].n_terms);

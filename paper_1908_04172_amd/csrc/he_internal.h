@@ -85,6 +85,7 @@ struct he_plan {
     u32 class_begin_p[4];  // polynomial plaintexts: capacities 1, 2, 4 outputs per thread
     u32 min_terms_s[3];    // fewest terms of any scalar tile of the class (0 for an empty class)
     u32 max_terms_s[3];    // most terms of any scalar tile of the class
+    u32 max_count_s[3];    // most outputs of any scalar tile of the class
     Tile* tiles_s_dev;
     Tile* tiles_p_dev;
     u64* wbase_s_dev;      // per scalar tile: start of its weights in the gathered table, per limb

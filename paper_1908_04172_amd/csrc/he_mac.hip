@@ -125,8 +125,8 @@ struct ScalarWeights8 {
 // that reads the sum its predecessor wrote waits for it (the result takes far longer than the issue
 // of one instruction), so the two that go into `mid` are kept 16 instructions apart: four passes over
 // the eight outputs, pinned in this order.
-template <int FIRST>
-__device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[16], u32 xa, u32 xb, const ScalarWeights8<false>& w) {
+template <int FIRST, int A>
+__device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[A], u32 xa, u32 xb, const ScalarWeights8<false>& w) {
 #pragma unroll
     for (int g = 0; g < 8; g++) acc[FIRST + g].lo += (u64)xa * w.v[2 * g];
     __builtin_amdgcn_sched_barrier(0);
@@ -143,8 +143,8 @@ __device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[16], u32 xa, u32 
 // The three-product form (Karatsuba): lo += xa*wa, hi += xb*wb, mid += (xa+xb)*(wa+wb); the cross
 // terms xa*wb + xb*wa are mid - lo - hi, formed once per output when the sums are read out
 // (acc_uncross).  Used where LimbConst::kara_terms says that a whole group's terms fit the sums.
-template <int FIRST>
-__device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[16], u32 xa, u32 xb, const ScalarWeights8<true>& w) {
+template <int FIRST, int A>
+__device__ __forceinline__ void scalar_half_term(MacAcc (&acc)[A], u32 xa, u32 xb, const ScalarWeights8<true>& w) {
     const u32 xs = xa + xb;
 #pragma unroll
     for (int g = 0; g < 8; g++) acc[FIRST + g].lo += (u64)xa * w.v[2 * g];
@@ -397,6 +397,130 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
     }
 }
 
+// The main path for launches whose groups all have at most eight outputs (a convolution with five
+// filters, say): the tables are the 16-output ones, of which only outputs 0..7 are read and multiplied,
+// so no multiply-add goes to the empty half of a group.  Eight accumulators per thread leave room for
+// five waves per SIMD.  A term's eight residues fill one set of scalar registers; the two sets take the
+// even and the odd terms, one being loaded while the other is multiplied.
+template <bool KARA>
+__device__ __forceinline__ void scalar_eight_path(const LimbConst& c, u32 limbs, u32 N, const Tile* tiles, u32 tile_first, u32 tile_end,
+                                                  const u64* wbase, const u32* term_ct, const u64* wtab, u64 wtab_elems,
+                                                  const u64* x_base, u32 ct_stride_bytes, const u64* bias, u32 comp, u32 limb, u32 n,
+                                                  u64* out) {
+    constexpr u32 WS = TermStride<16>::WORDS;
+    static_assert(BLOCK_TERMS % 2 == 0, "the weight sets alternate term by term");
+    MacAcc acc[8];
+    // (blocks, ring of inputs, switch to the next group's list, folds: as in scalar_main_path)
+    const u32 fold_blocks = c.fold_every / BLOCK_TERMS * BLOCK_TERMS;
+    const u32 reduce_blocks = c.reduce_every / BLOCK_TERMS * BLOCK_TERMS;
+    const Tile first = uniform_load(tiles + tile_first);
+    u32 Kp = padded_terms(first.n_terms);
+    u32 list0 = first.term0;
+    u32 u_last = first.n_terms - 1;
+    const u64* w_limb = wtab + (u64)limb * wtab_elems;
+    const u64* wp = w_limb + uniform_load(wbase + tile_first);
+    u64 xq[BLOCK_TERMS];
+    u32 cq[BLOCK_TERMS];
+#pragma unroll
+    for (int j = 0; j < BLOCK_TERMS; j++) {
+        xq[j] = *input_at(x_base, term_ct[(u32)(list0 + min((u32)j, u_last))], ct_stride_bytes);
+        cq[j] = term_ct[(u32)(list0 + min((u32)(BLOCK_TERMS + j), u_last))];
+    }
+    ScalarWeights8<KARA> w_even, w_odd;
+    u32 split_mask = (u32)c.split_mask, split_bits = c.split_bits;
+    asm volatile("" : "+s"(split_mask), "+s"(split_bits));
+    w_even.template request<0>(wp);
+    w_even.arrived();
+    for (u32 tile_i = tile_first; tile_i < tile_end; tile_i++) {
+        u32 next_list0 = list0 + u_last, next_K = 1;
+        const u64* wp_next_group = wp + (size_t)Kp * WS;  // after the last group: whatever follows its table
+        if (tile_i + 1 < tile_end) {
+            const Tile next = uniform_load(tiles + tile_i + 1);
+            next_list0 = next.term0;
+            next_K = next.n_terms;
+            wp_next_group = w_limb + uniform_load(wbase + tile_i + 1);
+        }
+        const Tile cur = uniform_load(tiles + tile_i);
+        const u32 out0 = cur.out0, count = cur.count;
+#pragma unroll
+        for (int g = 0; g < 8; g++) acc_clear(acc[g]);
+        u32 f = 0, r = 0, t = 0;
+        while (t < Kp) {
+            const u32 run = min(Kp - t, min(fold_blocks - f, reduce_blocks - r));
+            const u32 t_end = t + run;
+#pragma unroll 1
+            for (; t < t_end; t += BLOCK_TERMS) {
+                if (t + 2 * BLOCK_TERMS == Kp) {
+                    list0 = next_list0 - Kp;
+                    u_last = Kp + next_K - 1;
+                }
+                const u64* wp_after = t + BLOCK_TERMS == Kp ? wp_next_group : wp + BLOCK_TERMS * WS;
+#pragma unroll
+                for (int j = 0; j < BLOCK_TERMS; j++) {
+                    const u64 x = xq[j];
+                    xq[j] = *input_at(x_base, cq[j], ct_stride_bytes);
+                    cq[j] = term_ct[(u32)(list0 + min(t + 2 * BLOCK_TERMS + j, u_last))];
+                    const u32 xa = (u32)x & split_mask, xb = (u32)(x >> split_bits);  // split_operand
+                    const u64* wp_term_after = j + 1 < (int)BLOCK_TERMS ? wp + (j + 1) * WS : wp_after;
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (j % 2 == 0) {
+                        w_odd.template request<0>(wp_term_after);
+                        __builtin_amdgcn_sched_barrier(0);
+                        scalar_half_term<0>(acc, xa, xb, w_even);
+                        __builtin_amdgcn_sched_barrier(0);
+                        w_odd.arrived();
+                    } else {
+                        w_even.template request<0>(wp_term_after);
+                        __builtin_amdgcn_sched_barrier(0);
+                        scalar_half_term<0>(acc, xa, xb, w_odd);
+                        __builtin_amdgcn_sched_barrier(0);
+                        w_even.arrived();
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                wp = wp_after;
+            }
+            f += run;
+            r += run;
+            if (t < Kp) housekeeping<8>(acc, f, r, fold_blocks, reduce_blocks, c);
+        }
+        if constexpr (KARA) {
+#pragma unroll
+            for (int g = 0; g < 8; g++) acc_uncross(acc[g]);
+        }
+        store_group<8>(acc, out0, count, c, bias, comp, limb, limbs, N, n, out);
+        list0 += Kp;
+        u_last -= Kp;
+        Kp = padded_terms(next_K);
+    }
+}
+
+// Launched instead of mac_scalar_kernel<16> where no group of the class has more than eight outputs and
+// every limb and every group can take the main path (the host checks: no modulus that folds more often
+// than once per block, no group without terms).  Same grid and block order.
+__global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(5, 8)))
+mac_scalar_eight_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg, u32 max_terms, const u64* wbase,
+                        const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
+    const u32 chunks = N / MAC_THREADS;
+    const u32 n_wg_tiles = (n_tiles + per_wg - 1) / per_wg;
+    u32 b = blockIdx.x;
+    const u32 chunk = b % chunks; b /= chunks;
+    const u32 tile_first = (b % n_wg_tiles) * per_wg; b /= n_wg_tiles;
+    const u32 tile_end = min(tile_first + per_wg, n_tiles);
+    const u32 comp = b & 1;
+    const u32 limb = b >> 1;
+    const LimbConst& c = lt.c[limb];
+    const u32 n = chunk * MAC_THREADS + threadIdx.x;
+    const u32 ct_stride_bytes = 2 * limbs * N * 8;
+    const u64* x_base = ct_in + ((size_t)comp * limbs + limb) * N + n;
+    if (max_terms <= c.kara_terms)
+        scalar_eight_path<true>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base, ct_stride_bytes, bias,
+                                comp, limb, n, out);
+    else
+        scalar_eight_path<false>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base, ct_stride_bytes, bias,
+                                 comp, limb, n, out);
+}
+
 // Outputs that share their inputs with no other output (one multiply per output is the extreme
 // case: a plain Alg. 8 call over a tensor).  There is little arithmetic per byte here, so the kernel
 // is shaped for the memory system instead: a thread handles SL pairs of adjacent residues (16-byte
@@ -581,6 +705,17 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
     while (per_wg > 1 && (u64)((count + per_wg - 1) / per_wg) * per_group < MIN_WORKGROUPS) per_wg /= 2;
     const u64 blocks = (u64)((count + per_wg - 1) / per_wg) * per_group;
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
+    if constexpr (G == 16) {
+        // groups of at most eight outputs: the kernel that multiplies only the first half of a table entry
+        bool eight = plan->max_count_s[cls] <= 8 && plan->min_terms_s[cls] > 0;
+        for (u32 i = 0; i < limbs; i++) eight = eight && ctx->limbs.c[i].fold_every >= BLOCK_TERMS;
+        if (eight) {
+            hipLaunchKernelGGL(mac_scalar_eight_kernel, dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles,
+                               count, per_wg, plan->max_terms_s[cls], wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+            HE_HIP(hipGetLastError());
+            return HE_OK;
+        }
+    }
     hipLaunchKernelGGL((mac_scalar_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles,
                        count, per_wg, plan->max_terms_s[cls], wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
     HE_HIP(hipGetLastError());

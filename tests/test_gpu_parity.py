@@ -311,15 +311,16 @@ def test_mac_scalar_and_poly_match_oracle_on_irregular_plan(he, log2N, bits):
                           host(ctx.ct_pt_mac(hp, dev(ct), dev(w), he.PT_SCALAR)))
 
 
-def chained_groups_plan(n_in, seed, shared_weights=False):
+def chained_groups_plan(n_in, seed, shared_weights=False, largest=16):
     """Enough groups of every size class for the kernel to chain several per workgroup, every group
     with more than 4 terms, term counts changing from group to group.  shared_weights: output g of a group
     multiplies by plaintexts 40*g .. 40*g + k - 1, so that groups of equal shape share their weight table (as the
-    windows of a convolution do); else every output has plaintexts of its own (as in a dense layer)."""
+    windows of a convolution do); else every output has plaintexts of its own (as in a dense layer).
+    largest: the most outputs a group has (at most 8: the launch takes the kernel for narrow groups)."""
     rng = np.random.default_rng(seed)
     off, tc, tp, first_of_group = [0], [], [], []
     n_pt = 16 * 40 if shared_weights else 0
-    for n_groups, lo, hi in ((2100, 5, 16), (1200, 2, 4), (40, 1, 1)):
+    for n_groups, lo, hi in ((2100, 5, largest), (1200, 2, 4), (40, 1, 1)):
         for _ in range(n_groups):
             k = int(rng.integers(5, 41))
             cts = rng.integers(0, n_in, k).tolist()
@@ -337,15 +338,16 @@ def chained_groups_plan(n_in, seed, shared_weights=False):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("bits,shared", [([50, 58], False), ([59, 61, 30], False), ([50, 57, 40], True)])
-def test_mac_scalar_chains_groups_with_changing_term_counts(he, bits, shared):
+@pytest.mark.parametrize("bits,shared,largest", [([50, 58], False, 16), ([59, 61, 30], False, 16), ([50, 57, 40], True, 16),
+                                                 ([50, 58], False, 8), ([59, 61, 30], False, 7), ([50, 57, 40], True, 8)])
+def test_mac_scalar_chains_groups_with_changing_term_counts(he, bits, shared, largest):
     """Several groups per workgroup (the input ring and the weight pointer run on from one group
     into the next): whole runs of consecutive groups at both ends of every size class, and random
     groups in between, against the oracle on a sub-plan."""
     log2N, N = 11, 1 << 11
     q = wl.modulus_chain(bits, N)
     ctx = he.Context(log2N, q)
-    plan, first = chained_groups_plan(37, 77, shared)                  # shared tables: the three-product form of the terms
+    plan, first = chained_groups_plan(37, 77, shared, largest)         # shared tables: the three-product form of the terms
     hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
     ct = wl.uniform_residues((plan.n_in, 2), q, N, 78)
     w = dev(wl.uniform_residues((plan.n_pt,), q, 1, 79)[..., 0])
