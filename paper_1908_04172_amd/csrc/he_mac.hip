@@ -262,10 +262,17 @@ __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, 
     // compiler fetches the two words again in every block, and waits for them)
     u32 split_mask = (u32)c.split_mask, split_bits = c.split_bits;
     asm volatile("" : "+s"(split_mask), "+s"(split_bits));
+    // Smaller groups keep their weights in vector registers, in a ring like the inputs': wq[j] holds the
+    // residues of term t+j and is refilled for term t+j+4 once they have been multiplied.
+    constexpr int WQ = G == 16 ? 1 : G;
+    u64 wq[BLOCK_TERMS][WQ];
     if constexpr (G == 16) {
         w_lo.template request<0>(wp);
         w_lo.arrived();
         w_hi.template request<1>(wp);
+    } else {
+#pragma unroll
+        for (int j = 0; j < BLOCK_TERMS; j++) load_weights<G>(wq[j], wp + j * WS);
     }
     for (u32 tile_i = tile_first; tile_i < tile_end; tile_i++) {
         // the group after this one; after the last one the ring stays on this group's last term
@@ -315,7 +322,9 @@ __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, 
                         w_hi.template request<1>(j + 1 < (int)BLOCK_TERMS ? wp + (j + 1) * WS : wp_after);
                     } else {
                         u64 wt[G];
-                        load_weights<G>(wt, wp + j * WS);
+#pragma unroll
+                        for (int g = 0; g < G; g++) wt[g] = wq[j][g];
+                        load_weights<G>(wq[j], wp_after + j * WS);
                         scalar_term<G>(acc, x, wt, c);
                     }
                     __builtin_amdgcn_sched_barrier(0);  // one term at a time: keeps the live values few
@@ -343,17 +352,17 @@ __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, 
 // weights run on into the next group while the current one is still being reduced and stored, so the
 // chain of dependent loads that opens a group (descriptor -> term list -> inputs) and the stores that
 // close it are paid once per workgroup instead of once per group.
+// (`b` is the workgroup's index within the launch of this class.)
 template <int G>
-__global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8)))
-mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg, u32 max_terms, const u64* wbase,
-                  const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
+__device__ __forceinline__ void mac_scalar_body(u32 b, const LimbTable& lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg,
+                                                u32 max_terms, const u64* wbase, const u32* term_ct, const u64* wtab, u64 wtab_elems,
+                                                const u64* ct_in, const u64* bias, u64* out) {
     const u32 chunks = N / MAC_THREADS;
     const u32 n_wg_tiles = (n_tiles + per_wg - 1) / per_wg;
     // Order: slice of the row fastest, then run of groups, then (component, limb).  Workgroups go
     // to the eight XCDs round-robin and the number of slices is a multiple of eight, so the same
     // slice of neighbouring groups (which read overlapping inputs) runs on the same XCD, close in
     // time, and hits in its L2, while the slices in flight at any moment cover whole rows.
-    u32 b = blockIdx.x;
     const u32 chunk = b % chunks; b /= chunks;
     const u32 tile_first = (b % n_wg_tiles) * per_wg; b /= n_wg_tiles;
     const u32 tile_end = min(tile_first + per_wg, n_tiles);
@@ -395,6 +404,32 @@ mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles
         }
         store_group<G>(acc, tile.out0, tile.count, c, bias, comp, limb, limbs, N, n, out);
     }
+}
+
+template <int G>
+__global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8)))
+mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg, u32 max_terms, const u64* wbase,
+                  const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
+    mac_scalar_body<G>(blockIdx.x, lt, limbs, N, tiles, n_tiles, per_wg, max_terms, wbase, term_ct, wtab, wtab_elems, ct_in, bias, out);
+}
+
+// A plan's groups of 5..16 outputs and its groups of 2..4 in one launch: the first `blocks16` workgroups
+// take the larger class, the others the smaller one (often the ragged end of a layer: too few workgroups
+// to fill the chip in a launch of their own), which so fills in while the larger class drains.
+struct ScalarClass {
+    const Tile* tiles;
+    const u64* wbase;
+    u32 n_tiles, per_wg, max_terms, blocks;
+};
+__global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8)))
+mac_scalar_two_class_kernel(LimbTable lt, u32 limbs, u32 N, ScalarClass c16, ScalarClass c4, const u32* term_ct, const u64* wtab,
+                            u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
+    if (blockIdx.x < c16.blocks)
+        mac_scalar_body<16>(blockIdx.x, lt, limbs, N, c16.tiles, c16.n_tiles, c16.per_wg, c16.max_terms, c16.wbase, term_ct, wtab,
+                            wtab_elems, ct_in, bias, out);
+    else
+        mac_scalar_body<4>(blockIdx.x - c16.blocks, lt, limbs, N, c4.tiles, c4.n_tiles, c4.per_wg, c4.max_terms, c4.wbase, term_ct, wtab,
+                           wtab_elems, ct_in, bias, out);
 }
 
 // The main path for launches whose groups all have at most eight outputs (a convolution with five
@@ -676,15 +711,44 @@ mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, 
 
 // tile classes: scalar plaintexts hold up to {1,4,16} outputs per thread, polynomial ones {1,2,4}
 template <int G>
+static int gather_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, const u64* pt, u64* wtab, hipStream_t s) {
+    const u32 begin = plan->class_begin_s[cls], count = plan->class_begin_s[cls + 1] - begin;
+    hipLaunchKernelGGL((gather_weights_kernel<G>), dim3(count * GATHER_BLOCKS), dim3(256), 0, s, ctx->limbs, plan->tiles_s_dev + begin,
+                       plan->wbase_s_dev + begin, plan->wowner_s_dev + begin, count, limbs, plan->off_dev, plan->term_pt_dev, pt, wtab,
+                       plan->wtab_elems);
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+// Grid of mac_scalar_kernel / mac_scalar_eight_kernel for a class: several groups per workgroup where the
+// kernel can run from one into the next (see mac_scalar_kernel) and where enough workgroups remain to keep
+// every compute unit's wave slots full several times over.
+static int scalar_class_grid(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, ScalarClass& g) {
+    const u32 begin = plan->class_begin_s[cls], count = plan->class_begin_s[cls + 1] - begin;
+    const u64 per_group = (u64)limbs * 2 * (ctx->N / MAC_THREADS);
+    u32 per_wg = plan->min_terms_s[cls] > BLOCK_TERMS ? GROUPS_PER_WG : 1;
+    while (per_wg > 1 && (u64)((count + per_wg - 1) / per_wg) * per_group < MIN_WORKGROUPS) per_wg /= 2;
+    const u64 blocks = (u64)((count + per_wg - 1) / per_wg) * per_group;
+    if (blocks > 0x3FFFFFFFull) return HE_ERR_RANGE;
+    g = ScalarClass{plan->tiles_s_dev + begin, plan->wbase_s_dev + begin, count, per_wg, plan->max_terms_s[cls], (u32)blocks};
+    return HE_OK;
+}
+
+// groups of at most eight outputs: the kernel that multiplies only the first half of a table entry
+static bool eight_outputs_suffice(he_ctx* ctx, const he_plan* plan, u32 limbs) {
+    bool eight = plan->max_count_s[2] <= 8 && plan->min_terms_s[2] > 0;
+    for (u32 i = 0; i < limbs; i++) eight = eight && ctx->limbs.c[i].fold_every >= BLOCK_TERMS;
+    return eight;
+}
+
+template <int G>
 static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, const u64* ct_in, const u64* pt,
                                const u64* bias, u64* out, u64* wtab, hipStream_t s) {
     const u32 begin = plan->class_begin_s[cls], count = plan->class_begin_s[cls + 1] - begin;
     if (count == 0) return HE_OK;
     const Tile* tiles = plan->tiles_s_dev + begin;
     const u64* wbase = plan->wbase_s_dev + begin;
-    hipLaunchKernelGGL((gather_weights_kernel<G>), dim3(count * GATHER_BLOCKS), dim3(256), 0, s, ctx->limbs, tiles, wbase, plan->wowner_s_dev + begin, count, limbs, plan->off_dev,
-                       plan->term_pt_dev, pt, wtab, plan->wtab_elems);
-    HE_HIP(hipGetLastError());
+    if (int rc = gather_scalar_class<G>(ctx, plan, cls, limbs, pt, wtab, s)) return rc;
     if constexpr (G == 1) {
         const u32 sl = ctx->N >= 2048 ? 4 : 2;
         const u64 blocks = (u64)count * limbs * 2 * (ctx->N / (MAC_THREADS * 2 * sl));
@@ -697,27 +761,35 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
                                tiles, count, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
         HE_HIP(hipGetLastError());
         return HE_OK;
+    } else {
+        ScalarClass g;
+        if (int rc = scalar_class_grid(ctx, plan, cls, limbs, g)) return rc;
+        if (G == 16 && eight_outputs_suffice(ctx, plan, limbs))
+            hipLaunchKernelGGL(mac_scalar_eight_kernel, dim3(g.blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles, count,
+                               g.per_wg, g.max_terms, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+        else
+            hipLaunchKernelGGL((mac_scalar_kernel<G>), dim3(g.blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles, count,
+                               g.per_wg, g.max_terms, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+        HE_HIP(hipGetLastError());
+        return HE_OK;
     }
-    // several groups per workgroup where the kernel can run from one into the next (see mac_scalar_kernel)
-    // and where enough workgroups remain to keep every compute unit's wave slots full several times over
-    const u64 per_group = (u64)limbs * 2 * (ctx->N / MAC_THREADS);
-    u32 per_wg = plan->min_terms_s[cls] > BLOCK_TERMS ? GROUPS_PER_WG : 1;
-    while (per_wg > 1 && (u64)((count + per_wg - 1) / per_wg) * per_group < MIN_WORKGROUPS) per_wg /= 2;
-    const u64 blocks = (u64)((count + per_wg - 1) / per_wg) * per_group;
-    if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
-    if constexpr (G == 16) {
-        // groups of at most eight outputs: the kernel that multiplies only the first half of a table entry
-        bool eight = plan->max_count_s[cls] <= 8 && plan->min_terms_s[cls] > 0;
-        for (u32 i = 0; i < limbs; i++) eight = eight && ctx->limbs.c[i].fold_every >= BLOCK_TERMS;
-        if (eight) {
-            hipLaunchKernelGGL(mac_scalar_eight_kernel, dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles,
-                               count, per_wg, plan->max_terms_s[cls], wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
-            HE_HIP(hipGetLastError());
-            return HE_OK;
-        }
+}
+
+// Classes 1 (2..4 outputs) and 2 (5..16 outputs) together, in one launch, when the plan has both.
+static int launch_scalar_classes_4_16(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, const u64* pt, const u64* bias,
+                                      u64* out, u64* wtab, hipStream_t s) {
+    const bool has4 = plan->class_begin_s[2] > plan->class_begin_s[1], has16 = plan->class_begin_s[3] > plan->class_begin_s[2];
+    if (!has4 || !has16 || eight_outputs_suffice(ctx, plan, limbs)) {
+        if (int rc = launch_scalar_class<4>(ctx, plan, 1, limbs, ct_in, pt, bias, out, wtab, s)) return rc;
+        return launch_scalar_class<16>(ctx, plan, 2, limbs, ct_in, pt, bias, out, wtab, s);
     }
-    hipLaunchKernelGGL((mac_scalar_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles,
-                       count, per_wg, plan->max_terms_s[cls], wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+    ScalarClass c4, c16;
+    if (int rc = scalar_class_grid(ctx, plan, 1, limbs, c4)) return rc;
+    if (int rc = scalar_class_grid(ctx, plan, 2, limbs, c16)) return rc;
+    if (int rc = gather_scalar_class<4>(ctx, plan, 1, limbs, pt, wtab, s)) return rc;
+    if (int rc = gather_scalar_class<16>(ctx, plan, 2, limbs, pt, wtab, s)) return rc;
+    hipLaunchKernelGGL(mac_scalar_two_class_kernel, dim3(c16.blocks + c4.blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, c16, c4,
+                       plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
@@ -740,8 +812,7 @@ int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, co
     int rc;
     if (pt_kind == HE_PT_SCALAR) {
         if ((rc = launch_scalar_class<1>(ctx, plan, 0, limbs, ct_in, pt, bias, out, wtab, s)) != HE_OK) return rc;
-        if ((rc = launch_scalar_class<4>(ctx, plan, 1, limbs, ct_in, pt, bias, out, wtab, s)) != HE_OK) return rc;
-        if ((rc = launch_scalar_class<16>(ctx, plan, 2, limbs, ct_in, pt, bias, out, wtab, s)) != HE_OK) return rc;
+        if ((rc = launch_scalar_classes_4_16(ctx, plan, limbs, ct_in, pt, bias, out, wtab, s)) != HE_OK) return rc;
     } else {
         if ((rc = launch_poly_class<1>(ctx, plan, 0, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
         if ((rc = launch_poly_class<2>(ctx, plan, 1, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
