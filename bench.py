@@ -459,6 +459,9 @@ def main() -> int:
         del ct_sq, evk, out_sq, down_sq, ws_sq
 
     print(json.dumps(result))
+    if "cpu_baseline" in result and not result["cpu_baseline"]["gpu_outputs_match_oracle"]:
+        print("bench.py: the timed GPU outputs differ from the oracle's", file=sys.stderr)
+        return 3
     return 0
 
 

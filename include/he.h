@@ -15,8 +15,10 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device work is
  *    enqueued on it and no call synchronises with the device, except he_ctx_create,
  *    he_plan_create and the two destroy calls.
- *  - Every call returns HE_OK (0) or a negative he_status; nothing aborts or throws.  On an error
- *    no device work has been enqueued by that call.
+ *  - Every call returns HE_OK (0) or a negative he_status; nothing aborts or throws.  Arguments,
+ *    sizes and launch shapes are all checked before the first launch: on any status other than
+ *    HE_ERR_DEVICE no device work has been enqueued by that call.  HE_ERR_DEVICE reports a failed HIP
+ *    call; launches that the same call made before it stay on the stream.
  */
 #ifndef HE_H
 #define HE_H
@@ -41,7 +43,8 @@ typedef enum he_status {
 #define HE_PT_SCALAR 0 /* plaintext = one residue per limb (Alg. 2 / 4 / 8) */
 #define HE_PT_POLY 1   /* plaintext = N residues per limb, NTT form (Alg. 3 / 7) */
 
-#define HE_RESCALE 1u  /* he_ct_pt_mac flag: finish with one lazy rescale per output */
+#define HE_RESCALE 1u     /* he_ct_pt_mac flag: finish with one lazy rescale per output */
+#define HE_ACCUMULATE 2u  /* he_ct_pt_mac flag: add the sums (and the bias) to what ct_out holds */
 
 #define HE_MAX_LIMBS 16
 #define HE_MIN_LOG2N 10
@@ -54,7 +57,7 @@ const char* he_strerror(int status);
 
 /*
  * Context for ring degree N = 2^log2N and the modulus chain moduli[0..L-1] (host).  Each
- * modulus must be a prime = 1 (mod 2N) below 2^62 ("maximum modulus of 62 bits", Sec.
+ * modulus must be a prime = 1 (mod 2N) below 2^62 (the bound on the moduli in Sec.
  * "Ciphertext-plaintext Multiplication"), all distinct.  For limb i the library fixes
  * psi_i = the smallest primitive 2N-th root of unity modulo q_i; the NTT entry points are defined
  * with respect to it.  device >= 0 selects the GPU (tables are uploaded there); device = -1 makes a
@@ -136,10 +139,17 @@ int he_plan_workspace_bytes(const he_plan* plan, uint32_t limbs, int pt_kind, ui
  * both ciphertext components are multiplied.  bias (dev [n_out][limbs] scalar residues, or NULL)
  * is added to component 0 after the sum (Alg. 4; "addition is allowed post-multiplication,
  * pre-rescaling").
- *   flags = 0:          ct_out dev [n_out][2][limbs][N]
- *   flags = HE_RESCALE: ct_out dev [n_out][2][limbs-1][N]; each output is rescaled exactly once,
- *                       after its MACs and bias (lazy rescaling); needs limbs >= 2.
- * ct_in dev [n_in][2][limbs][N].  ct_out must not overlap ct_in, pt, bias or workspace (checked on the host: HE_ERR_ARG).
+ *   flags = 0:             ct_out dev [n_out][2][limbs][N]
+ *   flags = HE_RESCALE:    ct_out dev [n_out][2][limbs-1][N]; each output is rescaled exactly once,
+ *                          after its MACs and bias (lazy rescaling); needs limbs >= 2.
+ *   flags = HE_ACCUMULATE: ct_out dev [n_out][2][limbs][N] holds canonical residues on entry and
+ *                          ct_out[o] += the sum (+ bias[o] on component 0): the accumulate-into-output
+ *                          form of Alg. 7 / Alg. 8 inside a Dot or Convolution.  A layer whose terms are
+ *                          split over several calls (several plans over the same outputs) gives the
+ *                          residues of the one-call layer.  Not together with HE_RESCALE (HE_ERR_ARG):
+ *                          the rescale belongs after the last partial sum, as a he_rescale call.
+ * ct_in dev [n_in][2][limbs][N].  ct_out and workspace must not overlap each other nor ct_in, pt or bias
+ * (checked on the host: HE_ERR_ARG).
  * workspace: dev, at least he_plan_workspace_bytes() bytes (may be NULL if that is 0).
  */
 int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_t* ct_in,
@@ -216,52 +226,14 @@ int he_ntt_fwd32(he_ctx* ctx, uint32_t limbs, uint32_t* data, uint32_t n_polys, 
 int he_ntt_inv32(he_ctx* ctx, uint32_t limbs, uint32_t* data, uint32_t n_polys, void* stream);
 
 /*
- * Host-side checks of the device arithmetic (the same inline functions the kernels use, compiled
- * for the host): a*b mod q by 128-bit Barrett reduction (Alg. 5), and the lazy Shoup product used
- * in the NTT butterflies.  For tests; no device needed.
+ * Debug aid for the precondition "every residue is canonical" (the un-reduced accumulators of the MAC
+ * kernels rely on it): counts the residues of data dev [rows][limbs][row_len] that are not below the
+ * modulus of their limb (row_len = N for ciphertext components and polynomial plaintexts, 1 for scalar
+ * plaintexts and biases; a [n][2][limbs][N] tensor is rows = 2n).  Writes the count to *n_bad (host),
+ * after waiting for `stream`.  One call at a time per context (the counter lives in the context).
  */
-uint64_t he_host_mulmod(uint64_t a, uint64_t b, uint64_t q);
-uint64_t he_host_reduce128(uint64_t hi, uint64_t lo, uint64_t q);
-uint64_t he_host_shoup_mulmod(uint64_t y, uint64_t w, uint64_t q);
-/* The unreduced Shoup product of the butterflies: congruent to y*w mod q for any 64-bit y, in [0, 2q)
- * with the exact quotient estimate (cheap_quotient = 0), in [0, 4q) with the cheap one (= 1). */
-uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotient);
-/* The accumulator the MAC kernels use, run on the host: sum of x[t]*w[t] (n terms) mod q. */
-uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q);
-/* The same with the kernels' final step: (sum + addend) mod q for an addend below q (the bias of Alg. 4). */
-uint64_t he_host_mac_accumulate_add(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
-/* The three-product (Karatsuba) form of the MAC terms that the 16-output kernel uses on limbs that leave room
- * for it: the number of terms such sums can take for modulus q (0: the form is not used for q), and
- * (sum of x[t]*w[t] + addend) mod q computed that way for n terms (UINT64_MAX if n exceeds that number). */
-uint32_t he_host_mac_three_product_terms(uint64_t q);
-uint64_t he_host_mac_accumulate_three_products(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
-/* The two primitives of the packed 32-bit path, for q in [2, 2^30): BarrettReduction64 (Alg. 6), z mod q for
- * any 64-bit z; and the lazy 32-bit Shoup product, congruent to y*w mod q and in [0, 2q), for w < q and any
- * 32-bit y. */
-uint32_t he_host_barrett64(uint64_t z, uint32_t q);
-uint32_t he_host_shoup32(uint32_t y, uint32_t w, uint32_t q);
-
-/*
- * Measurement aid, not part of the compute path: the rate (operations per second, whole GPU) at
- * which this device runs one of the library's arithmetic primitives on register-resident data, with
- * the constants of limb `limb` of the context.  These are the integer-ALU ceilings against which
- * the MAC and NTT kernels' throughputs are quoted.  Allocates a small device buffer, runs on the
- * default stream and synchronises.  iters in [1, 2^20] loop iterations per thread (4096 gives a
- * run of a few milliseconds).
- */
-enum {
-    HE_RATE_MAD32 = 0,           /* one 32x32+64-bit multiply-add */
-    HE_RATE_MAC_TERM = 1,        /* the four multiply-adds of one MAC term (folds and reduction excluded) */
-    HE_RATE_SHOUP_EXACT = 2,     /* Shoup product, exact quotient estimate (result below 2q) */
-    HE_RATE_SHOUP_CHEAP = 3,     /* Shoup product, cheap quotient estimate (result below 4q) */
-    HE_RATE_BUTTERFLY_MODE0 = 4, /* forward butterfly for moduli up to 2^62 */
-    HE_RATE_BUTTERFLY_MODE1 = 5, /* forward butterfly for moduli below 2^61 */
-    HE_RATE_BUTTERFLY_MODE2 = 6, /* forward butterfly for moduli below 2^58 */
-    HE_RATE_BUTTERFLY_INV = 7,   /* inverse butterfly for moduli below 2^61 */
-    HE_RATE_BUTTERFLY_FP64 = 8   /* a forward butterfly for moduli below 2^50 on double-precision FMAs: no kernel uses
-                                    it; it is timed to say what that arithmetic would cost (HE_ERR_MODULUS above 2^50) */
-};
-int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s);
+int he_check_reduced(he_ctx* ctx, uint32_t limbs, const uint64_t* data, size_t rows, uint32_t row_len,
+                     uint64_t* n_bad, void* stream);
 
 #ifdef __cplusplus
 }

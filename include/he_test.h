@@ -1,0 +1,66 @@
+/*
+ * he_test.h -- test and measurement hooks of the library, kept apart from the product ABI of he.h:
+ * the device arithmetic compiled for the host (for CPU-only tests of Alg. 5 / Alg. 6, the Shoup
+ * products and the MAC accumulator), and the register-resident rate probes against which the
+ * benchmark quotes the MAC and NTT kernels.  Nothing on the compute path calls these.
+ */
+#ifndef HE_TEST_H
+#define HE_TEST_H
+
+#include "he.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Host-side checks of the device arithmetic (the same inline functions the kernels use, compiled
+ * for the host): a*b mod q by 128-bit Barrett reduction (Alg. 5), and the lazy Shoup product used
+ * in the NTT butterflies.  For tests; no device needed.
+ */
+uint64_t he_host_mulmod(uint64_t a, uint64_t b, uint64_t q);
+uint64_t he_host_reduce128(uint64_t hi, uint64_t lo, uint64_t q);
+uint64_t he_host_shoup_mulmod(uint64_t y, uint64_t w, uint64_t q);
+/* The unreduced Shoup product of the butterflies: congruent to y*w mod q for any 64-bit y, in [0, 2q)
+ * with the exact quotient estimate (cheap_quotient = 0), in [0, 4q) with the cheap one (= 1). */
+uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotient);
+/* The accumulator the MAC kernels use, run on the host: sum of x[t]*w[t] (n terms) mod q. */
+uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q);
+/* The same with the kernels' final step: (sum + addend) mod q for an addend below q (the bias of Alg. 4). */
+uint64_t he_host_mac_accumulate_add(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
+/* The three-product (Karatsuba) form of the MAC terms that the 16-output kernel uses on limbs that leave room
+ * for it: the number of terms such sums can take for modulus q (0: the form is not used for q), and
+ * (sum of x[t]*w[t] + addend) mod q computed that way for n terms (UINT64_MAX if n exceeds that number). */
+uint32_t he_host_mac_three_product_terms(uint64_t q);
+uint64_t he_host_mac_accumulate_three_products(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
+/* The two primitives of the packed 32-bit path, for q in [2, 2^30): BarrettReduction64 (Alg. 6), z mod q for
+ * any 64-bit z; and the lazy 32-bit Shoup product, congruent to y*w mod q and in [0, 2q), for w < q and any
+ * 32-bit y. */
+uint32_t he_host_barrett64(uint64_t z, uint32_t q);
+uint32_t he_host_shoup32(uint32_t y, uint32_t w, uint32_t q);
+
+/*
+ * Measurement aid, not part of the compute path: the rate (operations per second, whole GPU) at
+ * which this device runs one of the library's arithmetic primitives on register-resident data, with
+ * the constants of limb `limb` of the context.  These are the integer-ALU ceilings against which
+ * the MAC and NTT kernels' throughputs are quoted.  Allocates a small device buffer, runs on the
+ * default stream and synchronises.  iters in [1, 2^20] loop iterations per thread (4096 gives a
+ * run of a few milliseconds).
+ */
+enum {
+    HE_RATE_MAD32 = 0,           /* one 32x32+64-bit multiply-add */
+    HE_RATE_MAC_TERM = 1,        /* the four multiply-adds of one MAC term (folds and reduction excluded) */
+    HE_RATE_SHOUP_EXACT = 2,     /* Shoup product, exact quotient estimate (result below 2q) */
+    HE_RATE_SHOUP_CHEAP = 3,     /* Shoup product, cheap quotient estimate (result below 4q) */
+    HE_RATE_BUTTERFLY_MODE0 = 4, /* forward butterfly for moduli up to 2^62 */
+    HE_RATE_BUTTERFLY_MODE1 = 5, /* forward butterfly for moduli below 2^61 */
+    HE_RATE_BUTTERFLY_MODE2 = 6, /* forward butterfly for moduli below 2^58 */
+    HE_RATE_BUTTERFLY_INV = 7,   /* inverse butterfly for moduli below 2^61 */
+    HE_RATE_MAC_TERM3 = 8        /* the three multiply-adds of one MAC term in the three-product form */
+};
+int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HE_TEST_H */

@@ -7,6 +7,7 @@
 #include <new>
 
 #include "he_internal.h"
+#include "../../include/he_test.h"
 
 // ------------------------------------------------------------------------------------------------
 // host number theory (context set-up only)
@@ -218,6 +219,18 @@ __global__ void __launch_bounds__(256) add_kernel(LimbTable lt, u32 limbs, u32 N
     *p = v;
 }
 
+// he_check_reduced: residues of data [rows][limbs][row_len] that are not below their limb's modulus, counted
+// into *bad (one atomic per wave that found any).
+__global__ void __launch_bounds__(256) check_reduced_kernel(LimbTable lt, u32 limbs, const u64* data, size_t total, u32 row_len,
+                                                            unsigned long long* bad) {
+    u32 mine = 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const u32 limb = (u32)((i / row_len) % limbs);
+        mine += data[i] >= lt.c[limb].q;
+    }
+    if (mine) atomicAdd(bad, (unsigned long long)mine);
+}
+
 // Group consecutive outputs whose term_ct lists are identical, at most `cap` per group.
 void build_tiles(const u32* off, const u32* term_ct, u32 n_out, u32 cap, std::vector<Tile>& tiles) {
     u32 o = 0;
@@ -379,7 +392,8 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
                 rem = (u64)(cur % 2);
             }
         }
-        if (upload(&ctx->garner, garner.data(), garner.size()) != HE_OK || upload(&ctx->half_digits, half.data(), half.size()) != HE_OK ||
+        if (upload(&ctx->bad_count, (const u64*)nullptr, 1) != HE_OK ||
+            upload(&ctx->garner, garner.data(), garner.size()) != HE_OK || upload(&ctx->half_digits, half.data(), half.size()) != HE_OK ||
             upload(&ctx->tw_fwd, fwd.data(), fwd.size()) != HE_OK || upload(&ctx->tw_inv, inv.data(), inv.size()) != HE_OK ||
             upload(&ctx->fft_tw, fft_tw.data(), fft_tw.size()) != HE_OK || upload(&ctx->twist, twist.data(), twist.size()) != HE_OK) {
             he_ctx_destroy(ctx);
@@ -401,6 +415,7 @@ int he_ctx_destroy(he_ctx* ctx) {
         if (ctx->half_digits) (void)hipFree(ctx->half_digits);
         if (ctx->tw32_fwd) (void)hipFree(ctx->tw32_fwd);
         if (ctx->tw32_inv) (void)hipFree(ctx->tw32_inv);
+        if (ctx->bad_count) (void)hipFree(ctx->bad_count);
     }
     if (ctx->device >= 0) (void)hipGetLastError();  // a failure here must not surface in the caller's next HIP call
     delete ctx;
@@ -564,7 +579,8 @@ int he_plan_destroy(he_plan* p) {
 int he_plan_workspace_bytes(const he_plan* plan, uint32_t limbs, int pt_kind, uint32_t flags, size_t* bytes) {
     if (!plan || !bytes) return HE_ERR_ARG;
     if (pt_kind != HE_PT_SCALAR && pt_kind != HE_PT_POLY) return HE_ERR_ARG;
-    if (flags & ~HE_RESCALE) return HE_ERR_ARG;
+    if (flags & ~(HE_RESCALE | HE_ACCUMULATE)) return HE_ERR_ARG;
+    if ((flags & HE_RESCALE) && (flags & HE_ACCUMULATE)) return HE_ERR_ARG;  // a rescaled output is not a partial sum
     int rc = check_level(plan->ctx, limbs, (flags & HE_RESCALE) ? 2 : 1);
     if (rc != HE_OK) return rc;
     size_t b = 0;
@@ -584,14 +600,21 @@ int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_
     if (plan->n_out == 0) return HE_OK;
     if (!ct_out || (plan->n_terms && (!ct_in || !pt))) return HE_ERR_ARG;
     if (need && (!workspace || workspace_bytes < need)) return HE_ERR_WORKSPACE;
-    {   // the output is written while the inputs are still being read: it must not share memory with them
+    {   // the output and the workspace are written while the inputs are still being read: neither may share
+        // memory with them, nor with each other
         const size_t row = (size_t)ctx->N * sizeof(u64);
         const size_t out_bytes = (size_t)plan->n_out * 2 * ((flags & HE_RESCALE) ? limbs - 1 : limbs) * row;
+        const size_t in_bytes = (size_t)plan->n_in * 2 * limbs * row;
         const size_t pt_bytes = (size_t)plan->n_pt * limbs * (pt_kind == HE_PT_POLY ? row : sizeof(u64));
-        if (overlaps(ct_out, out_bytes, ct_in, (size_t)plan->n_in * 2 * limbs * row) || overlaps(ct_out, out_bytes, pt, pt_bytes) ||
-            overlaps(ct_out, out_bytes, bias, (size_t)plan->n_out * limbs * sizeof(u64)) || overlaps(ct_out, out_bytes, workspace, need))
+        const size_t bias_bytes = (size_t)plan->n_out * limbs * sizeof(u64);
+        if (overlaps(ct_out, out_bytes, ct_in, in_bytes) || overlaps(ct_out, out_bytes, pt, pt_bytes) ||
+            overlaps(ct_out, out_bytes, bias, bias_bytes) || overlaps(ct_out, out_bytes, workspace, need) ||
+            overlaps(workspace, need, ct_in, in_bytes) || overlaps(workspace, need, pt, pt_bytes) ||
+            overlaps(workspace, need, bias, bias_bytes))
             return HE_ERR_ARG;
     }
+    if ((rc = check_mac_launch(ctx, plan, limbs, pt_kind)) != HE_OK) return rc;
+    if ((flags & HE_RESCALE) && plan->n_out > 0x3FFFFFFFu) return HE_ERR_RANGE;
     if ((rc = need_device(ctx)) != HE_OK) return rc;
     char* ws = (char*)workspace;
     u64* wtab = nullptr;
@@ -602,10 +625,10 @@ int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_
     hipStream_t s = (hipStream_t)stream;
     if (flags & HE_RESCALE) {
         u64* acc = (u64*)ws;
-        if ((rc = launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, acc, wtab, s)) != HE_OK) return rc;
+        if ((rc = launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, acc, wtab, 0, s)) != HE_OK) return rc;
         return launch_rescale(ctx, limbs, acc, ct_out, plan->n_out, s);
     }
-    return launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, wtab, s);
+    return launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, wtab, (flags & HE_ACCUMULATE) ? 1u : 0u, s);
 }
 
 int he_ct_pt_add(he_ctx* ctx, uint32_t limbs, uint64_t* ct, uint32_t n, const uint64_t* pt, int pt_kind,
@@ -638,6 +661,31 @@ int he_rescale(he_ctx* ctx, uint32_t limbs, const uint64_t* in, uint64_t* out, u
         return HE_ERR_ARG;
     if ((rc = need_device(ctx)) != HE_OK) return rc;
     return launch_rescale(ctx, limbs, in, out, n, (hipStream_t)stream);
+}
+
+int he_check_reduced(he_ctx* ctx, uint32_t limbs, const uint64_t* data, size_t rows, uint32_t row_len, uint64_t* n_bad,
+                     void* stream) {
+    int rc = check_level(ctx, limbs, 1);
+    if (rc != HE_OK) return rc;
+    if (!n_bad || row_len == 0) return HE_ERR_ARG;
+    *n_bad = 0;
+    if (rows == 0) return HE_OK;
+    if (!data) return HE_ERR_ARG;
+    if (rows > (~(size_t)0) / limbs / row_len) return HE_ERR_RANGE;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    const size_t total = rows * limbs * row_len;
+    const u32 blocks = (u32)std::min<size_t>((total + 255) / 256, 256 * 32);
+    hipStream_t s = (hipStream_t)stream;
+    // (this call waits for the stream, so it is never part of a captured graph)
+    HE_HIP(hipMemsetAsync(ctx->bad_count, 0, sizeof(u64), s));
+    hipLaunchKernelGGL(check_reduced_kernel, dim3(blocks), dim3(256), 0, s, ctx->limbs, limbs, data, total, row_len,
+                       (unsigned long long*)ctx->bad_count);
+    HE_HIP(hipGetLastError());
+    u64 bad = 0;
+    HE_HIP(hipMemcpyAsync(&bad, ctx->bad_count, sizeof bad, hipMemcpyDeviceToHost, s));
+    HE_HIP(hipStreamSynchronize(s));
+    *n_bad = bad;
+    return HE_OK;
 }
 
 int he_ntt_fwd(he_ctx* ctx, uint32_t limbs, uint64_t* data, uint32_t n_polys, void* stream) {
@@ -731,11 +779,17 @@ int he_ct_pt_mac32(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint3
     {
         const size_t row = (size_t)ctx->N * sizeof(u32);
         const size_t out_bytes = (size_t)plan->n_out * 2 * ((flags & HE_RESCALE) ? limbs - 1 : limbs) * row;
+        const size_t in_bytes = (size_t)plan->n_in * 2 * limbs * row;
         const size_t pt_bytes = (size_t)plan->n_pt * limbs * (pt_kind == HE_PT_POLY ? row : sizeof(u64));
-        if (overlaps(ct_out, out_bytes, ct_in, (size_t)plan->n_in * 2 * limbs * row) || overlaps(ct_out, out_bytes, pt, pt_bytes) ||
-            overlaps(ct_out, out_bytes, bias, (size_t)plan->n_out * limbs * sizeof(u64)) || overlaps(ct_out, out_bytes, workspace, need))
+        const size_t bias_bytes = (size_t)plan->n_out * limbs * sizeof(u64);
+        if (overlaps(ct_out, out_bytes, ct_in, in_bytes) || overlaps(ct_out, out_bytes, pt, pt_bytes) ||
+            overlaps(ct_out, out_bytes, bias, bias_bytes) || overlaps(ct_out, out_bytes, workspace, need) ||
+            overlaps(workspace, need, ct_in, in_bytes) || overlaps(workspace, need, pt, pt_bytes) ||
+            overlaps(workspace, need, bias, bias_bytes))
             return HE_ERR_ARG;
     }
+    if ((rc = check_mac32_launch(ctx, plan, limbs, pt_kind)) != HE_OK) return rc;
+    if ((flags & HE_RESCALE) && plan->n_out > 0x3FFFFFFFu) return HE_ERR_RANGE;
     if ((rc = need_device(ctx)) != HE_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (flags & HE_RESCALE) {
@@ -743,10 +797,10 @@ int he_ct_pt_mac32(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint3
         char* ws = (char*)workspace;
         if (pt_kind == HE_PT_SCALAR) ws += align256((size_t)plan->wtab_elems * limbs * sizeof(u64));
         u32* acc = (u32*)ws;
-        if ((rc = launch_mac32(ctx, plan, limbs, ct_in, pt, pt_kind, bias, acc, workspace, s)) != HE_OK) return rc;
+        if ((rc = launch_mac32(ctx, plan, limbs, ct_in, pt, pt_kind, bias, acc, workspace, 0, s)) != HE_OK) return rc;
         return launch_rescale32(ctx, limbs, acc, ct_out, plan->n_out, s);
     }
-    return launch_mac32(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, workspace, s);
+    return launch_mac32(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, workspace, (flags & HE_ACCUMULATE) ? 1u : 0u, s);
 }
 
 int he_ct_pt_add32(he_ctx* ctx, uint32_t limbs, uint32_t* ct, uint32_t n, const void* pt, int pt_kind, void* stream) {
@@ -814,8 +868,8 @@ uint32_t he_host_shoup32(uint32_t y, uint32_t w, uint32_t q) { return shoup32(y,
 
 int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s) {
     if (!ctx || !ops_per_s || limb >= ctx->L || iters == 0 || iters > (1u << 20)) return HE_ERR_ARG;
-    if (kind < HE_RATE_MAD32 || kind > HE_RATE_BUTTERFLY_FP64) return HE_ERR_ARG;
-    if (kind == HE_RATE_BUTTERFLY_FP64 && ctx->q[limb] >= (1ull << 50)) return HE_ERR_MODULUS;
+    if (kind < HE_RATE_MAD32 || kind > HE_RATE_MAC_TERM3) return HE_ERR_ARG;
+    if (kind == HE_RATE_MAC_TERM3 && ctx->limbs.c[limb].kara_terms == 0) return HE_ERR_MODULUS;  // the limb never takes that form
     // the lazier butterflies assume the room their modes are chosen by
     const u32 mode = ctx->limbs.c[limb].ntt_mode;
     if ((kind == HE_RATE_BUTTERFLY_MODE2 && mode < 2) || ((kind == HE_RATE_BUTTERFLY_MODE1 || kind == HE_RATE_BUTTERFLY_INV) && mode < 1))

@@ -65,6 +65,7 @@ struct he_ctx {
     Limb32Table limbs32;
     u32* tw32_fwd;    // [L][N][2]: (psi^brv(k), floor(that * 2^32 / q)) for limbs below 2^30, else zeros
     u32* tw32_inv;    // [L][N][2]: the same for psi^-brv(k)
+    u64* bad_count;   // [1]: the counter of he_check_reduced
 };
 
 // One group of outputs that read the same ciphertexts in the same order.
@@ -120,8 +121,9 @@ inline int allow_dynamic_lds(const void* kernel, size_t bytes, int device, std::
     return HE_OK;
 }
 
+int check_mac_launch(he_ctx* ctx, const he_plan* plan, u32 limbs, int pt_kind);
 int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, const u64* pt, int pt_kind,
-               const u64* bias, u64* out, u64* wtab, hipStream_t s);
+               const u64* bias, u64* out, u64* wtab, u32 accumulate, hipStream_t s);
 int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s);
 int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s);
 int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s);
@@ -133,8 +135,9 @@ int launch_square_relin(he_ctx* ctx, u32 limbs, const u64* ct_in, u32 n, const u
 // packed 32-bit storage (he_packed32.hip)
 int launch_pack32(he_ctx* ctx, const u64* in, u32* out, size_t count, hipStream_t s);
 int launch_unpack32(he_ctx* ctx, const u32* in, u64* out, size_t count, hipStream_t s);
+int check_mac32_launch(he_ctx* ctx, const he_plan* plan, u32 limbs, int pt_kind);
 int launch_mac32(he_ctx* ctx, const he_plan* plan, u32 limbs, const u32* ct_in, const void* pt, int pt_kind, const u64* bias,
-                 u32* out, void* workspace, hipStream_t s);
+                 u32* out, void* workspace, u32 accumulate, hipStream_t s);
 int launch_add32(he_ctx* ctx, u32 limbs, u32* ct, u32 n, const void* pt, int pt_kind, hipStream_t s);
 int launch_ntt32(he_ctx* ctx, u32 limbs, u32* data, u32 rows, bool inverse, hipStream_t s);
 int launch_rescale32(he_ctx* ctx, u32 limbs, const u32* in, u32* out, u32 n, hipStream_t s);

@@ -180,10 +180,11 @@ __device__ __forceinline__ const u64* input_at(const u64* x_base, u32 ct, u32 ct
 // Final reduction, bias (Alg. 4, component 0 only) and store of one group of outputs; the cheaper
 // reduction where it applies, chosen once so that the per-output code has no branch.  The group's
 // bias residues come in with one load (lane g of every wave fetches output g's) and are handed out
-// with lane reads, so the outputs do not each wait for a load of their own.
+// with lane reads, so the outputs do not each wait for a load of their own.  accumulate: the canonical
+// residue already at the output's place is added as well (HE_ACCUMULATE); the branch is uniform.
 template <int G>
 __device__ __forceinline__ void store_group(MacAcc (&acc)[G], u32 out0, u32 count, const LimbConst& c, const u64* bias, u32 comp,
-                                            u32 limb, u32 limbs, u32 N, u32 n, u64* out) {
+                                            u32 limb, u32 limbs, u32 N, u32 n, u64* out, u32 accumulate) {
     const u32 lane = threadIdx.x % 64;
     u64 bias_lane = 0;
     if (bias != nullptr && comp == 0 && lane < count) bias_lane = bias[(size_t)(out0 + lane) * limbs + limb];
@@ -197,8 +198,9 @@ __device__ __forceinline__ void store_group(MacAcc (&acc)[G], u32 out0, u32 coun
 #pragma unroll
         for (int g = 0; g < G; g++) {
             if ((u32)g < count) {
-                const u64 b = (u64)(u32)__builtin_amdgcn_readlane((int)(u32)bias_lane, g) |
-                              ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(bias_lane >> 32), g) << 32);
+                u64 b = (u64)(u32)__builtin_amdgcn_readlane((int)(u32)bias_lane, g) |
+                        ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(bias_lane >> 32), g) << 32);
+                if (accumulate) b = add_mod(b, dst[g * out_stride], k.q);
                 dst[g * out_stride] = acc_reduce_add(acc[g], b, k);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -207,8 +209,9 @@ __device__ __forceinline__ void store_group(MacAcc (&acc)[G], u32 out0, u32 coun
 #pragma unroll
         for (int g = 0; g < G; g++) {
             if ((u32)g < count) {
-                const u64 b = (u64)(u32)__builtin_amdgcn_readlane((int)(u32)bias_lane, g) |
-                              ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(bias_lane >> 32), g) << 32);
+                u64 b = (u64)(u32)__builtin_amdgcn_readlane((int)(u32)bias_lane, g) |
+                        ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(bias_lane >> 32), g) << 32);
+                if (accumulate) b = add_mod(b, dst[g * out_stride], c.q);
                 dst[g * out_stride] = add_mod(acc_reduce(acc[g], c), b, c.q);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -222,7 +225,7 @@ template <int G, bool KARA>
 __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, u32 N, const Tile* tiles, u32 tile_first, u32 tile_end,
                                                  const u64* wbase, const u32* term_ct, const u64* wtab, u64 wtab_elems,
                                                  const u64* x_base, u32 ct_stride_bytes, const u64* bias, u32 comp, u32 limb, u32 n,
-                                                 u64* out) {
+                                                 u64* out, u32 accumulate) {
     constexpr u32 WS = TermStride<G>::WORDS;
     MacAcc acc[G];
     // Terms run in blocks of four (terms K..Kp-1 are padding: zero weights, input K-1 again).
@@ -340,7 +343,7 @@ __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, 
 #pragma unroll
         for (int g = 0; g < G; g++) acc_uncross(acc[g]);
     }
-    store_group<G>(acc, out0, count, c, bias, comp, limb, limbs, N, n, out);
+    store_group<G>(acc, out0, count, c, bias, comp, limb, limbs, N, n, out, accumulate);
         list0 += Kp;
         u_last -= Kp;
         Kp = padded_terms(next_K);
@@ -356,7 +359,7 @@ __device__ __forceinline__ void scalar_main_path(const LimbConst& c, u32 limbs, 
 template <int G>
 __device__ __forceinline__ void mac_scalar_body(u32 b, const LimbTable& lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg,
                                                 u32 max_terms, const u64* wbase, const u32* term_ct, const u64* wtab, u64 wtab_elems,
-                                                const u64* ct_in, const u64* bias, u64* out) {
+                                                const u64* ct_in, const u64* bias, u64* out, u32 accumulate) {
     const u32 chunks = N / MAC_THREADS;
     const u32 n_wg_tiles = (n_tiles + per_wg - 1) / per_wg;
     // Order: slice of the row fastest, then run of groups, then (component, limb).  Workgroups go
@@ -378,10 +381,10 @@ __device__ __forceinline__ void mac_scalar_body(u32 b, const LimbTable& lt, u32 
         // three products per term where every group of the launch fits the sums (16-output groups only)
         if (G == 16 && max_terms <= c.kara_terms)
             scalar_main_path<G, G == 16>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base,
-                                         (u32)(ct_stride * 8), bias, comp, limb, n, out);
+                                         (u32)(ct_stride * 8), bias, comp, limb, n, out, accumulate);
         else
             scalar_main_path<G, false>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base,
-                                       (u32)(ct_stride * 8), bias, comp, limb, n, out);
+                                       (u32)(ct_stride * 8), bias, comp, limb, n, out, accumulate);
         return;
     }
     // Every other case, one group at a time: moduli above 2^60 (they fold more often than once per
@@ -402,15 +405,15 @@ __device__ __forceinline__ void mac_scalar_body(u32 b, const LimbTable& lt, u32 
             ++r;
             if (t + 1 < K) housekeeping<G>(acc, f, r, c.fold_every, c.reduce_every, c);
         }
-        store_group<G>(acc, tile.out0, tile.count, c, bias, comp, limb, limbs, N, n, out);
+        store_group<G>(acc, tile.out0, tile.count, c, bias, comp, limb, limbs, N, n, out, accumulate);
     }
 }
 
 template <int G>
 __global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8)))
 mac_scalar_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg, u32 max_terms, const u64* wbase,
-                  const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
-    mac_scalar_body<G>(blockIdx.x, lt, limbs, N, tiles, n_tiles, per_wg, max_terms, wbase, term_ct, wtab, wtab_elems, ct_in, bias, out);
+                  const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out, u32 accumulate) {
+    mac_scalar_body<G>(blockIdx.x, lt, limbs, N, tiles, n_tiles, per_wg, max_terms, wbase, term_ct, wtab, wtab_elems, ct_in, bias, out, accumulate);
 }
 
 // A plan's groups of 5..16 outputs and its groups of 2..4 in one launch: the first `blocks16` workgroups
@@ -423,13 +426,13 @@ struct ScalarClass {
 };
 __global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8)))
 mac_scalar_two_class_kernel(LimbTable lt, u32 limbs, u32 N, ScalarClass c16, ScalarClass c4, const u32* term_ct, const u64* wtab,
-                            u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
+                            u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out, u32 accumulate) {
     if (blockIdx.x < c16.blocks)
         mac_scalar_body<16>(blockIdx.x, lt, limbs, N, c16.tiles, c16.n_tiles, c16.per_wg, c16.max_terms, c16.wbase, term_ct, wtab,
-                            wtab_elems, ct_in, bias, out);
+                            wtab_elems, ct_in, bias, out, accumulate);
     else
         mac_scalar_body<4>(blockIdx.x - c16.blocks, lt, limbs, N, c4.tiles, c4.n_tiles, c4.per_wg, c4.max_terms, c4.wbase, term_ct, wtab,
-                           wtab_elems, ct_in, bias, out);
+                           wtab_elems, ct_in, bias, out, accumulate);
 }
 
 // The main path for launches whose groups all have at most eight outputs (a convolution with five
@@ -441,7 +444,7 @@ template <bool KARA>
 __device__ __forceinline__ void scalar_eight_path(const LimbConst& c, u32 limbs, u32 N, const Tile* tiles, u32 tile_first, u32 tile_end,
                                                   const u64* wbase, const u32* term_ct, const u64* wtab, u64 wtab_elems,
                                                   const u64* x_base, u32 ct_stride_bytes, const u64* bias, u32 comp, u32 limb, u32 n,
-                                                  u64* out) {
+                                                  u64* out, u32 accumulate) {
     constexpr u32 WS = TermStride<16>::WORDS;
     static_assert(BLOCK_TERMS % 2 == 0, "the weight sets alternate term by term");
     MacAcc acc[8];
@@ -523,7 +526,7 @@ __device__ __forceinline__ void scalar_eight_path(const LimbConst& c, u32 limbs,
 #pragma unroll
             for (int g = 0; g < 8; g++) acc_uncross(acc[g]);
         }
-        store_group<8>(acc, out0, count, c, bias, comp, limb, limbs, N, n, out);
+        store_group<8>(acc, out0, count, c, bias, comp, limb, limbs, N, n, out, accumulate);
         list0 += Kp;
         u_last -= Kp;
         Kp = padded_terms(next_K);
@@ -535,7 +538,7 @@ __device__ __forceinline__ void scalar_eight_path(const LimbConst& c, u32 limbs,
 // than once per block, no group without terms).  Same grid and block order.
 __global__ void __launch_bounds__(MAC_THREADS) __attribute__((amdgpu_waves_per_eu(5, 8)))
 mac_scalar_eight_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, u32 per_wg, u32 max_terms, const u64* wbase,
-                        const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
+                        const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out, u32 accumulate) {
     const u32 chunks = N / MAC_THREADS;
     const u32 n_wg_tiles = (n_tiles + per_wg - 1) / per_wg;
     u32 b = blockIdx.x;
@@ -550,10 +553,10 @@ mac_scalar_eight_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n
     const u64* x_base = ct_in + ((size_t)comp * limbs + limb) * N + n;
     if (max_terms <= c.kara_terms)
         scalar_eight_path<true>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base, ct_stride_bytes, bias,
-                                comp, limb, n, out);
+                                comp, limb, n, out, accumulate);
     else
         scalar_eight_path<false>(c, limbs, N, tiles, tile_first, tile_end, wbase, term_ct, wtab, wtab_elems, x_base, ct_stride_bytes, bias,
-                                 comp, limb, n, out);
+                                 comp, limb, n, out, accumulate);
 }
 
 // Outputs that share their inputs with no other output (one multiply per output is the extreme
@@ -563,7 +566,7 @@ mac_scalar_eight_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n
 template <int SL>
 __global__ void __launch_bounds__(MAC_THREADS)
 mac_scalar_single_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u64* wbase,
-                         const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out) {
+                         const u32* term_ct, const u64* wtab, u64 wtab_elems, const u64* ct_in, const u64* bias, u64* out, u32 accumulate) {
     const u32 per_block = MAC_THREADS * 2 * SL;
     const u32 blocks_per_row = N / per_block;
     u32 b = blockIdx.x;
@@ -620,6 +623,11 @@ mac_scalar_single_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 
         ulonglong2 v;
         v.x = add_mod(acc_reduce(acc[s][0], c), bv, c.q);
         v.y = add_mod(acc_reduce(acc[s][1], c), bv, c.q);
+        if (accumulate) {
+            const ulonglong2 old = dst[s * MAC_THREADS + threadIdx.x];
+            v.x = add_mod(v.x, old.x, c.q);
+            v.y = add_mod(v.y, old.y, c.q);
+        }
         dst[s * MAC_THREADS + threadIdx.x] = v;
     }
 }
@@ -630,7 +638,7 @@ mac_scalar_single_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 
 template <int G>
 __global__ void __launch_bounds__(MAC_THREADS)
 mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u32* off, const u32* term_ct, const u32* term_pt,
-                const u64* pt, const u64* ct_in, const u64* bias, u64* out) {
+                const u64* pt, const u64* ct_in, const u64* bias, u64* out, u32 accumulate) {
     const u32 chunks = N / (2 * MAC_THREADS);
     u32 b = blockIdx.x;  // same order as the scalar kernel: slice, group of outputs, limb
     const u32 chunk = b % chunks; b /= chunks;
@@ -700,6 +708,13 @@ mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, 
             v1.x = acc_reduce(acc[4 * g + 2], c);
             v1.y = acc_reduce(acc[4 * g + 3], c);
             u64* dst = out + ((size_t)o * 2 * limbs + limb) * N + n;
+            if (accumulate) {
+                const ulonglong2 o0 = *reinterpret_cast<const ulonglong2*>(dst), o1 = *reinterpret_cast<const ulonglong2*>(dst + comp_stride);
+                v0.x = add_mod(v0.x, o0.x, c.q);
+                v0.y = add_mod(v0.y, o0.y, c.q);
+                v1.x = add_mod(v1.x, o1.x, c.q);
+                v1.y = add_mod(v1.y, o1.y, c.q);
+            }
             *reinterpret_cast<ulonglong2*>(dst) = v0;
             *reinterpret_cast<ulonglong2*>(dst + comp_stride) = v1;
             __builtin_amdgcn_sched_barrier(0);
@@ -743,7 +758,7 @@ static bool eight_outputs_suffice(he_ctx* ctx, const he_plan* plan, u32 limbs) {
 
 template <int G>
 static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, const u64* ct_in, const u64* pt,
-                               const u64* bias, u64* out, u64* wtab, hipStream_t s) {
+                               const u64* bias, u64* out, u64* wtab, u32 accumulate, hipStream_t s) {
     const u32 begin = plan->class_begin_s[cls], count = plan->class_begin_s[cls + 1] - begin;
     if (count == 0) return HE_OK;
     const Tile* tiles = plan->tiles_s_dev + begin;
@@ -755,10 +770,10 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
         if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
         if (sl == 4)
             hipLaunchKernelGGL((mac_scalar_single_kernel<4>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
-                               tiles, count, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+                               tiles, count, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out, accumulate);
         else
             hipLaunchKernelGGL((mac_scalar_single_kernel<2>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
-                               tiles, count, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+                               tiles, count, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out, accumulate);
         HE_HIP(hipGetLastError());
         return HE_OK;
     } else {
@@ -766,10 +781,10 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
         if (int rc = scalar_class_grid(ctx, plan, cls, limbs, g)) return rc;
         if (G == 16 && eight_outputs_suffice(ctx, plan, limbs))
             hipLaunchKernelGGL(mac_scalar_eight_kernel, dim3(g.blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles, count,
-                               g.per_wg, g.max_terms, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+                               g.per_wg, g.max_terms, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out, accumulate);
         else
             hipLaunchKernelGGL((mac_scalar_kernel<G>), dim3(g.blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, tiles, count,
-                               g.per_wg, g.max_terms, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+                               g.per_wg, g.max_terms, wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out, accumulate);
         HE_HIP(hipGetLastError());
         return HE_OK;
     }
@@ -777,11 +792,11 @@ static int launch_scalar_class(he_ctx* ctx, const he_plan* plan, int cls, u32 li
 
 // Classes 1 (2..4 outputs) and 2 (5..16 outputs) together, in one launch, when the plan has both.
 static int launch_scalar_classes_4_16(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, const u64* pt, const u64* bias,
-                                      u64* out, u64* wtab, hipStream_t s) {
+                                      u64* out, u64* wtab, u32 accumulate, hipStream_t s) {
     const bool has4 = plan->class_begin_s[2] > plan->class_begin_s[1], has16 = plan->class_begin_s[3] > plan->class_begin_s[2];
     if (!has4 || !has16 || eight_outputs_suffice(ctx, plan, limbs)) {
-        if (int rc = launch_scalar_class<4>(ctx, plan, 1, limbs, ct_in, pt, bias, out, wtab, s)) return rc;
-        return launch_scalar_class<16>(ctx, plan, 2, limbs, ct_in, pt, bias, out, wtab, s);
+        if (int rc = launch_scalar_class<4>(ctx, plan, 1, limbs, ct_in, pt, bias, out, wtab, accumulate, s)) return rc;
+        return launch_scalar_class<16>(ctx, plan, 2, limbs, ct_in, pt, bias, out, wtab, accumulate, s);
     }
     ScalarClass c4, c16;
     if (int rc = scalar_class_grid(ctx, plan, 1, limbs, c4)) return rc;
@@ -789,34 +804,58 @@ static int launch_scalar_classes_4_16(he_ctx* ctx, const he_plan* plan, u32 limb
     if (int rc = gather_scalar_class<4>(ctx, plan, 1, limbs, pt, wtab, s)) return rc;
     if (int rc = gather_scalar_class<16>(ctx, plan, 2, limbs, pt, wtab, s)) return rc;
     hipLaunchKernelGGL(mac_scalar_two_class_kernel, dim3(c16.blocks + c4.blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N, c16, c4,
-                       plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+                       plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out, accumulate);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
 
 template <int G>
 static int launch_poly_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, const u64* ct_in, const u64* pt,
-                             const u64* bias, u64* out, hipStream_t s) {
+                             const u64* bias, u64* out, u32 accumulate, hipStream_t s) {
     const u32 begin = plan->class_begin_p[cls], count = plan->class_begin_p[cls + 1] - begin;
     if (count == 0) return HE_OK;
     const u64 blocks = (u64)count * limbs * (ctx->N / (2 * MAC_THREADS));
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     hipLaunchKernelGGL((mac_poly_kernel<G>), dim3((u32)blocks), dim3(MAC_THREADS), 0, s, ctx->limbs, limbs, ctx->N,
-                       plan->tiles_p_dev + begin, count, plan->off_dev, plan->term_ct_dev, plan->term_pt_dev, pt, ct_in, bias, out);
+                       plan->tiles_p_dev + begin, count, plan->off_dev, plan->term_ct_dev, plan->term_pt_dev, pt, ct_in, bias, out, accumulate);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
 
+// The grid sizes launch_mac would use, checked without launching anything (the entry point calls this first,
+// so that a plan too large for a grid is refused before any kernel of the call is on the stream).
+int check_mac_launch(he_ctx* ctx, const he_plan* plan, u32 limbs, int pt_kind) {
+    if (pt_kind == HE_PT_SCALAR) {
+        const u64 singles = plan->class_begin_s[1] - plan->class_begin_s[0];
+        const u32 sl = ctx->N >= 2048 ? 4 : 2;
+        if (singles * limbs * 2 * (ctx->N / (MAC_THREADS * 2 * sl)) > 0x7FFFFFFFull) return HE_ERR_RANGE;
+        u64 blocks = 0;
+        for (int cls = 1; cls <= 2; cls++) {
+            ScalarClass g;
+            if (plan->class_begin_s[cls + 1] == plan->class_begin_s[cls]) continue;
+            if (int rc = scalar_class_grid(ctx, plan, cls, limbs, g)) return rc;
+            blocks += g.blocks;
+        }
+        if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;  // the two classes may share one launch
+    } else {
+        for (int cls = 0; cls < 3; cls++) {
+            const u64 count = plan->class_begin_p[cls + 1] - plan->class_begin_p[cls];
+            if (count * limbs * (ctx->N / (2 * MAC_THREADS)) > 0x7FFFFFFFull) return HE_ERR_RANGE;
+        }
+    }
+    return HE_OK;
+}
+
 int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, const u64* pt, int pt_kind, const u64* bias,
-               u64* out, u64* wtab, hipStream_t s) {
+               u64* out, u64* wtab, u32 accumulate, hipStream_t s) {
     int rc;
     if (pt_kind == HE_PT_SCALAR) {
-        if ((rc = launch_scalar_class<1>(ctx, plan, 0, limbs, ct_in, pt, bias, out, wtab, s)) != HE_OK) return rc;
-        if ((rc = launch_scalar_classes_4_16(ctx, plan, limbs, ct_in, pt, bias, out, wtab, s)) != HE_OK) return rc;
+        if ((rc = launch_scalar_class<1>(ctx, plan, 0, limbs, ct_in, pt, bias, out, wtab, accumulate, s)) != HE_OK) return rc;
+        if ((rc = launch_scalar_classes_4_16(ctx, plan, limbs, ct_in, pt, bias, out, wtab, accumulate, s)) != HE_OK) return rc;
     } else {
-        if ((rc = launch_poly_class<1>(ctx, plan, 0, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
-        if ((rc = launch_poly_class<2>(ctx, plan, 1, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
-        if ((rc = launch_poly_class<4>(ctx, plan, 2, limbs, ct_in, pt, bias, out, s)) != HE_OK) return rc;
+        if ((rc = launch_poly_class<1>(ctx, plan, 0, limbs, ct_in, pt, bias, out, accumulate, s)) != HE_OK) return rc;
+        if ((rc = launch_poly_class<2>(ctx, plan, 1, limbs, ct_in, pt, bias, out, accumulate, s)) != HE_OK) return rc;
+        if ((rc = launch_poly_class<4>(ctx, plan, 2, limbs, ct_in, pt, bias, out, accumulate, s)) != HE_OK) return rc;
     }
     return HE_OK;
 }

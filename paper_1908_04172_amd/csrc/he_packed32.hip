@@ -79,7 +79,7 @@ __global__ void __launch_bounds__(256) gather_weights32_kernel(const Tile* tiles
 template <int G>
 __global__ void __launch_bounds__(MAC32_THREADS)
 mac_scalar32_kernel(Limb32Table lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u64* wbase, const u32* term_ct,
-                    const u32* wtab, u64 wtab_elems, const u32* ct_in, const u64* bias, u32* out) {
+                    const u32* wtab, u64 wtab_elems, const u32* ct_in, const u64* bias, u32* out, u32 accumulate) {
     const u32 slices = N / MAC32_SLICE;
     u32 b = blockIdx.x;
     const u32 slice = b % slices; b /= slices;
@@ -143,7 +143,13 @@ mac_scalar32_kernel(Limb32Table lt, u32 limbs, u32 N, const Tile* tiles, u32 n_t
                 r0 = add_mod32(r0, bv, c.q);
                 r1 = add_mod32(r1, bv, c.q);
             }
-            reinterpret_cast<uint2*>(out)[(((size_t)o * 2 + comp) * limbs + limb) * (N / 2) + pair] = make_uint2(r0, r1);
+            uint2* dst = reinterpret_cast<uint2*>(out) + (((size_t)o * 2 + comp) * limbs + limb) * (N / 2) + pair;
+            if (accumulate) {  // HE_ACCUMULATE: add what the output holds (uniform branch)
+                const uint2 old = *dst;
+                r0 = add_mod32(r0, old.x, c.q);
+                r1 = add_mod32(r1, old.y, c.q);
+            }
+            *dst = make_uint2(r0, r1);
         }
     }
 }
@@ -153,7 +159,7 @@ mac_scalar32_kernel(Limb32Table lt, u32 limbs, u32 N, const Tile* tiles, u32 n_t
 template <int G>
 __global__ void __launch_bounds__(MAC32_THREADS)
 mac_poly32_kernel(Limb32Table lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u32* off, const u32* term_ct,
-                  const u32* term_pt, const u32* pt, const u32* ct_in, const u64* bias, u32* out) {
+                  const u32* term_pt, const u32* pt, const u32* ct_in, const u64* bias, u32* out, u32 accumulate) {
     const u32 slices = N / MAC32_SLICE;
     u32 b = blockIdx.x;
     const u32 slice = b % slices; b /= slices;
@@ -206,7 +212,13 @@ mac_poly32_kernel(Limb32Table lt, u32 limbs, u32 N, const Tile* tiles, u32 n_til
                     r0 = add_mod32(r0, bv, c.q);
                     r1 = add_mod32(r1, bv, c.q);
                 }
-                reinterpret_cast<uint2*>(out)[(((size_t)o * 2 + k) * limbs + limb) * row_pairs + pair] = make_uint2(r0, r1);
+                uint2* dst = reinterpret_cast<uint2*>(out) + (((size_t)o * 2 + k) * limbs + limb) * row_pairs + pair;
+                if (accumulate) {
+                    const uint2 old = *dst;
+                    r0 = add_mod32(r0, old.x, c.q);
+                    r1 = add_mod32(r1, old.y, c.q);
+                }
+                *dst = make_uint2(r0, r1);
             }
         }
     }
@@ -426,7 +438,7 @@ int launch_unpack32(he_ctx* ctx, const u32* in, u64* out, size_t count, hipStrea
 
 template <int G>
 static int launch_scalar32_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, const u32* ct_in, const u64* pt,
-                                 const u64* bias, u32* out, u32* wtab, hipStream_t s) {
+                                 const u64* bias, u32* out, u32* wtab, u32 accumulate, hipStream_t s) {
     const u32 begin = plan->class_begin_s[cls], count = plan->class_begin_s[cls + 1] - begin;
     if (count == 0) return HE_OK;
     const Tile* tiles = plan->tiles_s_dev + begin;
@@ -437,38 +449,48 @@ static int launch_scalar32_class(he_ctx* ctx, const he_plan* plan, int cls, u32 
     const u64 blocks = (u64)count * limbs * 2 * (ctx->N / MAC32_SLICE);
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     hipLaunchKernelGGL((mac_scalar32_kernel<G>), dim3((u32)blocks), dim3(MAC32_THREADS), 0, s, ctx->limbs32, limbs, ctx->N, tiles, count,
-                       wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out);
+                       wbase, plan->term_ct_dev, wtab, plan->wtab_elems, ct_in, bias, out, accumulate);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
 
 template <int G>
 static int launch_poly32_class(he_ctx* ctx, const he_plan* plan, int cls, u32 limbs, const u32* ct_in, const u32* pt, const u64* bias,
-                               u32* out, hipStream_t s) {
+                               u32* out, u32 accumulate, hipStream_t s) {
     const u32 begin = plan->class_begin_p[cls], count = plan->class_begin_p[cls + 1] - begin;
     if (count == 0) return HE_OK;
     const u64 blocks = (u64)count * limbs * (ctx->N / MAC32_SLICE);
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     hipLaunchKernelGGL((mac_poly32_kernel<G>), dim3((u32)blocks), dim3(MAC32_THREADS), 0, s, ctx->limbs32, limbs, ctx->N,
-                       plan->tiles_p_dev + begin, count, plan->off_dev, plan->term_ct_dev, plan->term_pt_dev, pt, ct_in, bias, out);
+                       plan->tiles_p_dev + begin, count, plan->off_dev, plan->term_ct_dev, plan->term_pt_dev, pt, ct_in, bias, out, accumulate);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
 
+// the grid sizes launch_mac32 would use, checked without launching anything
+int check_mac32_launch(he_ctx* ctx, const he_plan* plan, u32 limbs, int pt_kind) {
+    for (int cls = 0; cls < 3; cls++) {
+        const u64 count = pt_kind == HE_PT_SCALAR ? plan->class_begin_s[cls + 1] - plan->class_begin_s[cls]
+                                                  : plan->class_begin_p[cls + 1] - plan->class_begin_p[cls];
+        if (count * limbs * (pt_kind == HE_PT_SCALAR ? 2 : 1) * (ctx->N / MAC32_SLICE) > 0x7FFFFFFFull) return HE_ERR_RANGE;
+    }
+    return HE_OK;
+}
+
 int launch_mac32(he_ctx* ctx, const he_plan* plan, u32 limbs, const u32* ct_in, const void* pt, int pt_kind, const u64* bias,
-                 u32* out, void* workspace, hipStream_t s) {
+                 u32* out, void* workspace, u32 accumulate, hipStream_t s) {
     int rc;
     if (pt_kind == HE_PT_SCALAR) {
         const u64* p = static_cast<const u64*>(pt);
         u32* wtab = static_cast<u32*>(workspace);
-        if ((rc = launch_scalar32_class<1>(ctx, plan, 0, limbs, ct_in, p, bias, out, wtab, s)) != HE_OK) return rc;
-        if ((rc = launch_scalar32_class<4>(ctx, plan, 1, limbs, ct_in, p, bias, out, wtab, s)) != HE_OK) return rc;
-        if ((rc = launch_scalar32_class<16>(ctx, plan, 2, limbs, ct_in, p, bias, out, wtab, s)) != HE_OK) return rc;
+        if ((rc = launch_scalar32_class<1>(ctx, plan, 0, limbs, ct_in, p, bias, out, wtab, accumulate, s)) != HE_OK) return rc;
+        if ((rc = launch_scalar32_class<4>(ctx, plan, 1, limbs, ct_in, p, bias, out, wtab, accumulate, s)) != HE_OK) return rc;
+        if ((rc = launch_scalar32_class<16>(ctx, plan, 2, limbs, ct_in, p, bias, out, wtab, accumulate, s)) != HE_OK) return rc;
     } else {
         const u32* p = static_cast<const u32*>(pt);
-        if ((rc = launch_poly32_class<1>(ctx, plan, 0, limbs, ct_in, p, bias, out, s)) != HE_OK) return rc;
-        if ((rc = launch_poly32_class<2>(ctx, plan, 1, limbs, ct_in, p, bias, out, s)) != HE_OK) return rc;
-        if ((rc = launch_poly32_class<4>(ctx, plan, 2, limbs, ct_in, p, bias, out, s)) != HE_OK) return rc;
+        if ((rc = launch_poly32_class<1>(ctx, plan, 0, limbs, ct_in, p, bias, out, accumulate, s)) != HE_OK) return rc;
+        if ((rc = launch_poly32_class<2>(ctx, plan, 1, limbs, ct_in, p, bias, out, accumulate, s)) != HE_OK) return rc;
+        if ((rc = launch_poly32_class<4>(ctx, plan, 2, limbs, ct_in, p, bias, out, accumulate, s)) != HE_OK) return rc;
     }
     return HE_OK;
 }

@@ -4,6 +4,7 @@
 // many waves as the real kernels keep resident.  A measurement aid: nothing on the compute path
 // calls this file.
 #include "he_internal.h"
+#include "../../include/he_test.h"
 
 namespace {
 
@@ -25,17 +26,10 @@ __global__ void __launch_bounds__(THREADS) rate_kernel(LimbTable lt, u32 limb, u
         split_operand(x[i], c, xa[i], xb[i]);
     }
     const Twiddle t{w, w_shoup};
-    // operands of the double-precision probe
-    const double fq = (double)c.q, fw = (double)(w % c.q), fw_over_q = fw / fq;
-    double fx[CHAINS], fy[CHAINS];
-#pragma unroll
-    for (int i = 0; i < CHAINS; i++) {
-        fx[i] = (double)x[i];
-        fy[i] = (double)y[i];
-    }
     const u64 below_q = (1ull << c.mu_shift) - 1;  // mu_shift = bit length of q, minus 1
     u32 wa, wb;
     split_operand(w, c, wa, wb);
+    const u32 ws = wa + wb;
     for (u32 it = 0; it < iters; it++) {
 #pragma unroll
         for (int i = 0; i < CHAINS; i++) {
@@ -62,18 +56,13 @@ __global__ void __launch_bounds__(THREADS) rate_kernel(LimbTable lt, u32 limb, u
                 bfly_fwd<2>(x[i], y[i], t, c);
             } else if constexpr (KIND == HE_RATE_BUTTERFLY_INV) {
                 bfly_inv<1>(x[i], y[i], t, c);
-            } else if constexpr (KIND == HE_RATE_BUTTERFLY_FP64) {
-                // (X, Y) -> (X + W*Y, X - W*Y) mod q on doubles that hold integers in [0, q), q < 2^50:
-                // h + l = W*Y exactly (product and its rounding error), k = the quotient estimate, and
-                // h - k*q + l is exact because it is an integer below 2^52; two corrections bring it to [0, q)
-                const double h = fy[i] * fw, l = __builtin_fma(fy[i], fw, -h);
-                const double k = __builtin_rint(fy[i] * fw_over_q);
-                double v = __builtin_fma(-k, fq, h) + l;
-                v = v < 0.0 ? v + fq : v;
-                v = v >= fq ? v - fq : v;
-                const double s = fx[i] + v, d = fx[i] - v;
-                fx[i] = s >= fq ? s - fq : s;
-                fy[i] = d < 0.0 ? d + fq : d;
+            } else if constexpr (KIND == HE_RATE_MAC_TERM3) {
+                // the three-product form of a term (lo += xa*wa, mid += (xa+xb)*(wa+wb), hi += xb*wb): the sum
+                // wa + wb comes with the weights, xa + xb is one more addition per term
+                const u32 ta = (u32)acc[i].hi ^ xa[i], tb = (u32)acc[i].lo ^ xb[i];
+                acc[i].lo += (u64)ta * wa;
+                acc[i].mid += (u64)(ta + tb) * ws;
+                acc[i].hi += (u64)tb * wb;
             }
         }
         if constexpr (KIND == HE_RATE_BUTTERFLY_MODE2) {
@@ -88,7 +77,7 @@ __global__ void __launch_bounds__(THREADS) rate_kernel(LimbTable lt, u32 limb, u
     }
     u64 s = 0;
 #pragma unroll
-    for (int i = 0; i < CHAINS; i++) s += x[i] + y[i] + acc[i].lo + acc[i].mid + acc[i].hi + (u64)fx[i] + (u64)fy[i];
+    for (int i = 0; i < CHAINS; i++) s += x[i] + y[i] + acc[i].lo + acc[i].mid + acc[i].hi;
     sink[gid] = s;
 }
 
@@ -134,7 +123,7 @@ int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s) {
         case HE_RATE_BUTTERFLY_MODE1: return run_rate<HE_RATE_BUTTERFLY_MODE1>(ctx, limb, iters, ops_per_s);
         case HE_RATE_BUTTERFLY_MODE2: return run_rate<HE_RATE_BUTTERFLY_MODE2>(ctx, limb, iters, ops_per_s);
         case HE_RATE_BUTTERFLY_INV: return run_rate<HE_RATE_BUTTERFLY_INV>(ctx, limb, iters, ops_per_s);
-        case HE_RATE_BUTTERFLY_FP64: return run_rate<HE_RATE_BUTTERFLY_FP64>(ctx, limb, iters, ops_per_s);
+        case HE_RATE_MAC_TERM3: return run_rate<HE_RATE_MAC_TERM3>(ctx, limb, iters, ops_per_s);
     }
     return HE_ERR_ARG;
 }

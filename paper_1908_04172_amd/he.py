@@ -1,4 +1,4 @@
-"""ctypes binding of the C-ABI library (include/he.h).  Argument marshalling only: every step
+"""ctypes binding of the C-ABI library (include/he.h; the test hooks of include/he_test.h).  Argument marshalling only: every step
 runs in the library's kernels.  Device tensors are torch int64 tensors whose bit patterns are the
 uint64 residues; torch supplies memory and the current stream, nothing else.
 
@@ -15,10 +15,11 @@ import numpy as np
 
 RATE_MAD32, RATE_MAC_TERM, RATE_SHOUP_EXACT, RATE_SHOUP_CHEAP = 0, 1, 2, 3
 RATE_BUTTERFLY_MODE0, RATE_BUTTERFLY_MODE1, RATE_BUTTERFLY_MODE2, RATE_BUTTERFLY_INV = 4, 5, 6, 7
-RATE_BUTTERFLY_FP64 = 8
+RATE_MAC_TERM3 = 8
 PT_SCALAR = 0
 PT_POLY = 1
 RESCALE = 1
+ACCUMULATE = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhe_mi355x.so")
@@ -27,7 +28,7 @@ EXPORTS = [
     "he_strerror", "he_ctx_create", "he_ctx_destroy", "he_ctx_info", "he_encode_scalar", "he_encode_scalar_host",
     "he_encode_vector", "he_decode_vector",
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
-    "he_ntt_fwd", "he_ntt_inv", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
+    "he_ntt_fwd", "he_ntt_inv", "he_check_reduced", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_measure_rate",
     "he_host_barrett64", "he_host_shoup32", "he_host_mac_three_product_terms", "he_host_mac_accumulate_three_products", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
 ]
@@ -68,6 +69,7 @@ def lib():
         "he_rescale": (i32, [vp, u32, vp, vp, u32, vp]),
         "he_ntt_fwd": (i32, [vp, u32, vp, u32, vp]),
         "he_ntt_inv": (i32, [vp, u32, vp, u32, vp]),
+        "he_check_reduced": (i32, [vp, u32, vp, sz, u32, ctypes.POINTER(u64), vp]),
         "he_host_mulmod": (u64, [u64, u64, u64]),
         "he_host_reduce128": (u64, [u64, u64, u64]),
         "he_host_shoup_mulmod": (u64, [u64, u64, u64]),
@@ -226,6 +228,18 @@ class Context:
         _check(lib().he_rescale(self._h, limbs, _dev_ptr(ct, "in"), _dev_ptr(out, "out"), n, _stream()), "he_rescale")
         return out
 
+    def check_reduced(self, data, limbs: Optional[int] = None, row_len: Optional[int] = None) -> int:
+        """How many residues of data [...][limbs][row_len] are not below their limb's modulus (he_check_reduced;
+        waits for the stream).  row_len defaults to N for tensors of rank >= 3, limbs to the size of the limb axis."""
+        if row_len is None:
+            row_len = self.N if data.dim() >= 3 else 1
+        limbs = data.shape[-2 if row_len > 1 else -1] if limbs is None else limbs
+        assert data.numel() % (limbs * row_len) == 0
+        bad = ctypes.c_uint64()
+        _check(lib().he_check_reduced(self._h, limbs, _dev_ptr(data, "data"), data.numel() // (limbs * row_len), row_len,
+                                      ctypes.byref(bad), _stream()), "he_check_reduced")
+        return int(bad.value)
+
     # -- NTT
     def ntt_fwd(self, data):
         limbs, N = data.shape[-2:]
@@ -255,6 +269,7 @@ class Context:
             assert tuple(bias.shape) == (plan.n_out, limbs)
         out_limbs = limbs - 1 if flags & RESCALE else limbs
         if out is None:
+            assert not flags & ACCUMULATE, "HE_ACCUMULATE adds to an output the caller provides"
             out = torch.empty((plan.n_out, 2, out_limbs, self.N), dtype=torch.int64, device=ct_in.device)
         assert tuple(out.shape) == (plan.n_out, 2, out_limbs, self.N)
         need = plan.workspace_bytes(limbs, pt_kind, flags)
@@ -315,6 +330,7 @@ class Context:
             assert bias.dtype == torch.int64 and tuple(bias.shape) == (plan.n_out, limbs)
         out_limbs = limbs - 1 if flags & RESCALE else limbs
         if out is None:
+            assert not flags & ACCUMULATE, "HE_ACCUMULATE adds to an output the caller provides"
             out = torch.empty((plan.n_out, 2, out_limbs, self.N), dtype=torch.int32, device=ct_in.device)
         assert out.dtype == torch.int32 and tuple(out.shape) == (plan.n_out, 2, out_limbs, self.N)
         need = plan.workspace_bytes(limbs, pt_kind, flags)

@@ -367,6 +367,79 @@ def test_mac_scalar_chains_groups_with_changing_term_counts(he, bits, shared, la
         assert int(out[:, :, l].max()) < q[l] and int(out[:, :, l].min()) >= 0
 
 
+def split_plan(plan, seed):
+    """Two plans over the same outputs: each output's terms cut at a place of its own (possibly at an end, so
+    that some outputs get no term from one of the two calls); together they are `plan`."""
+    rng = np.random.default_rng(seed)
+    parts = [([0], [], []), ([0], [], [])]
+    cut_of_list = {}
+    for o in range(plan.n_out):
+        a, b = int(plan.off[o]), int(plan.off[o + 1])
+        key = tuple(plan.term_ct[a:b].tolist())                    # outputs of one group keep a common cut: they stay a group
+        cut = cut_of_list.setdefault(key, int(rng.integers(0, b - a + 1)))
+        for (off, tc, tp), (lo, hi) in zip(parts, ((a, a + cut), (a + cut, b))):
+            tc.extend(plan.term_ct[lo:hi].tolist())
+            tp.extend(plan.term_pt[lo:hi].tolist())
+            off.append(len(tc))
+    return [wl.Plan(plan.n_in, plan.n_out, plan.n_pt, np.asarray(off, np.uint32), np.asarray(tc, np.uint32), np.asarray(tp, np.uint32))
+            for off, tc, tp in parts]
+
+
+@pytest.mark.parametrize("log2N,bits", [(10, [30, 62, 50]), (12, [60, 57, 50])])
+def test_mac_accumulate_over_two_calls_equals_one_call(he, log2N, bits):
+    """HE_ACCUMULATE: a layer whose terms are split over two calls (the second adds into the output of the
+    first; the bias goes with either) gives the residues of the one-call oracle layer.  Scalar and polynomial
+    plaintexts, groups of every size class, outputs that get no term from one call."""
+    N = 1 << log2N
+    q = wl.modulus_chain(bits, N)
+    ctx = he.Context(log2N, q)
+    plans = [irregular_plan(11, 5)]
+    chained, _ = chained_groups_plan(37, 91, shared_weights=True, largest=8)
+    plans.append(chained.subset(list(range(0, 300)) + list(range(chained.n_out - 200, chained.n_out))))
+    for plan in plans:
+        first, second = split_plan(plan, 17)
+        h1 = ctx.plan(first.n_in, first.n_out, first.n_pt, first.off, first.term_ct, first.term_pt)
+        h2 = ctx.plan(second.n_in, second.n_out, second.n_pt, second.off, second.term_ct, second.term_pt)
+        ct = wl.uniform_residues((plan.n_in, 2), q, N, 141)
+        w = wl.uniform_residues((plan.n_pt,), q, 1, 142)[..., 0]
+        bias = wl.uniform_residues((plan.n_out,), q, 1, 143)[..., 0]
+        want = oracle.mac(ct, q, plan.off, plan.term_ct, plan.term_pt, w, oracle.PT_SCALAR, bias)
+        out = ctx.ct_pt_mac(h1, dev(ct), dev(w), he.PT_SCALAR, bias=dev(bias))
+        ctx.ct_pt_mac(h2, dev(ct), dev(w), he.PT_SCALAR, flags=he.ACCUMULATE, out=out)
+        assert np.array_equal(host(out), want)
+        out = ctx.ct_pt_mac(h1, dev(ct), dev(w), he.PT_SCALAR)                    # the bias with the second call
+        ctx.ct_pt_mac(h2, dev(ct), dev(w), he.PT_SCALAR, bias=dev(bias), flags=he.ACCUMULATE, out=out)
+        assert np.array_equal(host(out), want)
+        assert ctx.check_reduced(out) == 0
+        if plan is plans[0]:
+            wp = wl.uniform_residues((plan.n_pt,), q, N, 144)
+            wantp = oracle.mac(ct, q, plan.off, plan.term_ct, plan.term_pt, wp, oracle.PT_POLY, bias)
+            out = ctx.ct_pt_mac(h1, dev(ct), dev(wp), he.PT_POLY, bias=dev(bias))
+            ctx.ct_pt_mac(h2, dev(ct), dev(wp), he.PT_POLY, flags=he.ACCUMULATE, out=out)
+            assert np.array_equal(host(out), wantp)
+    with pytest.raises(he.HeError) as e:                                         # a rescaled output is no partial sum
+        ctx.ct_pt_mac(h2, dev(ct), dev(w), he.PT_SCALAR, flags=he.ACCUMULATE | he.RESCALE,
+                      out=torch.empty((plan.n_out, 2, len(q) - 1, N), dtype=torch.int64, device="cuda"))
+    assert e.value.status == -1
+
+
+def test_check_reduced_counts_residues_that_are_not_canonical(he):
+    c = wl.config(2)
+    ctx = he.Context(c.log2N, c.q)
+    ct = wl.uniform_residues((3, 2), c.q, c.N, 151)
+    assert ctx.check_reduced(dev(ct)) == 0
+    assert ctx.check_reduced(dev(ct[:, :, :2].copy())) == 0                       # a lower level
+    ct[0, 0, 0, 5] = c.q[0]
+    ct[2, 1, 3, c.N - 1] = 2**64 - 1
+    ct[1, 0, 1, 0] = c.q[0] - 1                                                   # canonical for limb 0, not for limb 1
+    assert ctx.check_reduced(dev(ct)) == 3
+    w = wl.uniform_residues((7,), c.q, 1, 152)[..., 0]                            # scalar plaintexts: [n][limbs]
+    assert ctx.check_reduced(dev(w)) == 0
+    w[6, 3] = c.q[3]
+    assert ctx.check_reduced(dev(w)) == 1
+    assert ctx.check_reduced(dev(ct[:0])) == 0
+
+
 def test_mac_long_sums_of_extreme_operands(he):
     # (q-1)*(q-1) summed 700 times: crosses every fold and reduce boundary of the accumulator
     N = 1 << 10
@@ -413,6 +486,13 @@ def test_mac_argument_errors(he):
     with pytest.raises(he.HeError) as e:
         ctx.rescale(ct, out=ct.view(-1)[c.N: 5 * c.N].view(2, 2, 1, c.N))
     assert e.value.status == -1
+    with pytest.raises(he.HeError) as e:                                            # the workspace over the plaintexts
+        ctx.ct_pt_mac(hp, ct, w, he.PT_SCALAR, workspace=w.view(torch.uint8))
+    assert e.value.status in (-1, -6)
+    big = torch.empty(1 << 20, dtype=torch.int64, device="cuda")
+    with pytest.raises(he.HeError) as e:                                            # the workspace over the input
+        ctx.ct_pt_mac(hp, big[: ct.numel()].view(ct.shape), w, he.PT_SCALAR, workspace=big.view(torch.uint8))
+    assert e.value.status == -1
     # a plan outlives its context without harm: its device arrays are freed on their own
     ctx2 = he.Context(c.log2N, c.q)
     hp2 = ctx2.plan(p.n_in, p.n_out, p.n_pt, p.off, p.term_ct, p.term_pt)
@@ -430,10 +510,8 @@ def test_measured_rates_are_plausible(he):
     b0, b1, b2 = (ctx.measure_rate(k, 2, 512) for k in (he.RATE_BUTTERFLY_MODE0, he.RATE_BUTTERFLY_MODE1,
                                                          he.RATE_BUTTERFLY_MODE2))
     assert b0 < b1 < b2 < mad / 4
-    assert 1e11 < ctx.measure_rate(he.RATE_BUTTERFLY_FP64, 2, 512) < 4e13            # the double-precision probe (50-bit limb)
-    with pytest.raises(he.HeError) as e:                                            # nor does a 60-bit limb fit doubles
-        ctx.measure_rate(he.RATE_BUTTERFLY_FP64, 0, 512)
-    assert e.value.status == -2
+    t4, t3 = ctx.measure_rate(he.RATE_MAC_TERM, 2, 512), ctx.measure_rate(he.RATE_MAC_TERM3, 2, 512)
+    assert mad / 6 < t4 < t3 < mad / 2                                              # four and three multiply-adds per term
     with pytest.raises(he.HeError) as e:                                            # a 60-bit limb has no mode 2
         ctx.measure_rate(he.RATE_BUTTERFLY_MODE2, 0, 512)
     assert e.value.status == -2
@@ -527,8 +605,7 @@ def test_config1_dense_layer_full_parity(he):
     check_outputs(c, ctx, plan, range(plan.n_out), out, lambda i: rows(ct, i), lambda i: rows(wenc, i), oracle.PT_SCALAR, host(benc))
 
 
-@pytest.mark.parametrize("cfg,sample", [(2, 12), (3, 5), (4, 6)])
-def test_scalar_layers_at_full_size_sampled_outputs(he, cfg, sample):
+def scalar_layer_inputs(he, cfg):
     c = wl.config(cfg)
     ctx = he.Context(c.log2N, c.q)
     plan = c.plan
@@ -538,33 +615,74 @@ def test_scalar_layers_at_full_size_sampled_outputs(he, cfg, sample):
     wenc = ctx.encode_scalar(w, 2.0**c.log2_scale)
     benc = ctx.encode_scalar(b, 2.0**c.log2_scale)
     assert np.array_equal(host(wenc[:50]), oracle.encode_scalars(w[:50].cpu().numpy(), 2.0**c.log2_scale, c.q))
-    out = run_layer(he, c, ctx, plan, ct, wenc, he.PT_SCALAR, benc)
-    rng = np.random.default_rng(c.seed)
-    outputs = sorted(set([0, plan.n_out - 1] + rng.integers(0, plan.n_out, sample).tolist()))
-    lens = np.diff(plan.off.astype(np.int64))
-    for k in np.unique(lens):                                   # every window size (padding rows/cols) is sampled
-        outputs.append(int(np.flatnonzero(lens == k)[-1]))
-    outputs = sorted(set(outputs))
-    check_outputs(c, ctx, plan, outputs, out, lambda i: rows(ct, i),
-                  lambda i: rows(wenc, i), oracle.PT_SCALAR, host(benc))
-    # properties that hold for every output at any size: canonical residues
+    return c, ctx, plan, ct, wenc, benc
+
+
+def assert_canonical(c, out):
+    """Holds for every output at any size: residues in [0, q_i)."""
     for l in range(c.L - 1):
         assert int(out[:, :, l].max()) < c.q[l] and int(out[:, :, l].min()) >= 0
 
 
+@pytest.mark.parametrize("cfg", [2, 3])
+def test_scalar_layers_at_full_size_every_output(he, cfg):
+    """cfg2 (convolution, 720 outputs) and cfg3 (dense, 100 outputs of 845 terms) as the one fused call the
+    benchmark times; EVERY output ciphertext against the oracle, in batches that bound the host memory."""
+    c, ctx, plan, ct, wenc, benc = scalar_layer_inputs(he, cfg)
+    out = run_layer(he, c, ctx, plan, ct, wenc, he.PT_SCALAR, benc)
+    hb = host(benc)
+    step = 180 if cfg == 2 else 50
+    for a in range(0, plan.n_out, step):
+        check_outputs(c, ctx, plan, range(a, min(a + step, plan.n_out)), out, lambda i: rows(ct, i),
+                      lambda i: rows(wenc, i), oracle.PT_SCALAR, hb)
+    assert_canonical(c, out)
+
+
+def test_config4_conv_layer_at_full_size_runs_of_groups(he):
+    """cfg4 at full size (4096 outputs = 256 windows x 16 channels; a workgroup of the MAC kernel runs through
+    8 consecutive windows = 128 outputs).  Checked against the oracle: the first and the last such run, two
+    runs at random places, one stretch of 128 outputs that straddles two runs, and the last window of every
+    window size (the padded last row and column have 18 and 12 terms): 640 + 48 outputs of 4096 (> 1/8)."""
+    c, ctx, plan, ct, wenc, benc = scalar_layer_inputs(he, 4)
+    out = run_layer(he, c, ctx, plan, ct, wenc, he.PT_SCALAR, benc)
+    run = 8 * 16
+    n_runs = plan.n_out // run
+    rng = np.random.default_rng(c.seed)
+    picks = sorted(set([0, n_runs - 1] + (1 + rng.permutation(n_runs - 2)[:2]).tolist()))
+    assert len(picks) == 4
+    chosen = set()
+    for r in picks:
+        chosen |= set(range(r * run, (r + 1) * run))
+    mid = int(rng.integers(2, n_runs - 2)) * run + run // 2            # half of one run, half of the next
+    chosen |= set(range(mid, mid + run))
+    lens = np.diff(plan.off.astype(np.int64))
+    for k in np.unique(lens):
+        last = int(np.flatnonzero(lens == k)[-1])
+        chosen |= set(range(last // 16 * 16, last // 16 * 16 + 16))      # the whole window
+    outputs = sorted(chosen)
+    assert len(outputs) >= 256 and {int(lens[o]) for o in outputs} == set(lens.tolist())
+    hb = host(benc)
+    for a in range(0, len(outputs), 128):
+        check_outputs(c, ctx, plan, outputs[a:a + 128], out, lambda i: rows(ct, i),
+                      lambda i: rows(wenc, i), oracle.PT_SCALAR, hb)
+    assert_canonical(c, out)
+
+
 def test_config5_full_poly_layer_sampled_outputs(he):
+    """cfg5 at full size (16 GiB of plaintext polynomials; the kernel handles 4 outputs per thread): the
+    first, the last and two inner groups of four, i.e. 16 of the 64 outputs and all four positions of a group."""
     c = wl.config(5)
     ctx = he.Context(c.log2N, c.q)
     plan = c.plan
     ct = wl.uniform_residues_torch((plan.n_in, 2), c.q, c.N, c.seed, "cuda")
     pt = wl.uniform_residues_torch((plan.n_pt,), c.q, c.N, c.seed + 100, "cuda")     # 16 GiB
     out = run_layer(he, c, ctx, plan, ct, pt, he.PT_POLY, None)
-    outputs = [0, 37, plan.n_out - 1]
-    for o in outputs:
-        check_outputs(c, ctx, plan, [o], out, lambda i: rows(ct, i),
+    outputs = [o for g in (0, 5, 10, 15) for o in range(4 * g, 4 * g + 4)]
+    assert len(outputs) == 16 and {o % 4 for o in outputs} == {0, 1, 2, 3}
+    for a in range(0, len(outputs), 4):                                # 4 outputs = 1024 plaintext polynomials = 1 GiB on the host
+        check_outputs(c, ctx, plan, outputs[a:a + 4], out, lambda i: rows(ct, i),
                       lambda i: rows(pt, i), oracle.PT_POLY, None)
-    for l in range(c.L - 1):
-        assert int(out[:, :, l].max()) < c.q[l] and int(out[:, :, l].min()) >= 0
+    assert_canonical(c, out)
     # the unfused route gives the same residues as the fused call
     hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
     acc = ctx.ct_pt_mac(hp, ct, pt, he.PT_POLY)
