@@ -157,6 +157,22 @@ int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_
                  uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * he_ct_pt_mac for callers that cannot allocate device memory or may not call an allocator: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same operation, arguments,
+ * flags and errors as he_ct_pt_mac, but the workspace is a fixed array of HE_STATIC_SCRATCH_BYTES inside
+ * the library's device code (each GPU a context was created on holds its copy until the process ends),
+ * and the call allocates nothing, on the host's HIP side or the device's.  A plan, level and flags whose
+ * he_plan_workspace_bytes() exceeds HE_STATIC_SCRATCH_BYTES is refused with HE_ERR_WORKSPACE (with
+ * HE_RESCALE the accumulators of all outputs must fit: use he_ct_pt_mac, or flags = 0 followed by
+ * he_rescale, for larger layers).  All calls on one GPU share that GPU's array, whatever their context or
+ * stream: calls that overlap in time on one GPU race; calls on one stream do not.  Nothing in the array
+ * has to be cleared between calls (every word a call reads it has written itself).
+ */
+#define HE_STATIC_SCRATCH_BYTES (32u << 20)
+int he_ct_pt_mac_static(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_t* ct_in, const uint64_t* pt,
+                        int pt_kind, const uint64_t* bias, uint64_t* ct_out, uint32_t flags, void* stream);
+
+/*
  * Ciphertext + plaintext, Alg. 3 (HE_PT_POLY: pt dev [n][limbs][N]) and Alg. 4 (HE_PT_SCALAR:
  * pt dev [n][limbs]), in place on component 0 of each of the n ciphertexts ct dev
  * [n][2][limbs][N]; component 1 is not touched.

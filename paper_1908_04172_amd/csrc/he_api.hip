@@ -4,10 +4,37 @@
 
 #include <algorithm>
 #include <map>
+#include <mutex>
 #include <new>
 
 #include "he_internal.h"
 #include "../../include/he_test.h"
+
+// ---- the scratch memory of he_ct_pt_mac_static: a fixed array in every GPU's copy of the library's code
+// object, in place of the caller's workspace.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address (one per GPU) is looked up once per device, with that device
+// current, when a context is created there, and every later use goes through that address.
+static __device__ __align__(256) unsigned char scratch[HE_STATIC_SCRATCH_BYTES];
+static constexpr int MAX_DEVICES = 64;
+static std::mutex scratch_mutex;
+static void* scratch_address[MAX_DEVICES];  // [device], null until looked up
+
+// the caller has made `device` current
+static int static_scratch(int device, void** out) {
+    *out = nullptr;
+    if (device < 0 || device >= MAX_DEVICES) return HE_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_address[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return HE_ERR_DEVICE;
+        }
+        scratch_address[device] = p;
+    }
+    *out = scratch_address[device];
+    return HE_OK;
+}
 
 // ------------------------------------------------------------------------------------------------
 // host number theory (context set-up only)
@@ -333,6 +360,7 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
         }
     if (device >= 0) {
         int rc = need_device(ctx);
+        if (rc == HE_OK) rc = static_scratch(device, &ctx->static_scratch);
         if (rc != HE_OK) { delete ctx; return rc; }
         std::vector<u64> fwd((size_t)L * N * 2), inv((size_t)L * N * 2);
         for (u32 i = 0; i < L; ++i) {
@@ -629,6 +657,19 @@ int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_
         return launch_rescale(ctx, limbs, acc, ct_out, plan->n_out, s);
     }
     return launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, wtab, (flags & HE_ACCUMULATE) ? 1u : 0u, s);
+}
+
+int he_ct_pt_mac_static(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_t* ct_in, const uint64_t* pt,
+                        int pt_kind, const uint64_t* bias, uint64_t* ct_out, uint32_t flags, void* stream) {
+    if (!ctx || !plan || plan->ctx != ctx) return HE_ERR_ARG;
+    size_t need = 0;
+    int rc = he_plan_workspace_bytes(plan, limbs, pt_kind, flags, &need);
+    if (rc != HE_OK) return rc;
+    if (need > HE_STATIC_SCRATCH_BYTES) return HE_ERR_WORKSPACE;  // the fixed array is all there is
+    if (ctx->device < 0 || !ctx->static_scratch) return HE_ERR_DEVICE;
+    // the same path as he_ct_pt_mac (whose host code allocates nothing), on this GPU's fixed array
+    return he_ct_pt_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, flags, ctx->static_scratch, HE_STATIC_SCRATCH_BYTES,
+                        stream);
 }
 
 int he_ct_pt_add(he_ctx* ctx, uint32_t limbs, uint64_t* ct, uint32_t n, const uint64_t* pt, int pt_kind,

@@ -66,6 +66,7 @@ struct he_ctx {
     u32* tw32_fwd;    // [L][N][2]: (psi^brv(k), floor(that * 2^32 / q)) for limbs below 2^30, else zeros
     u32* tw32_inv;    // [L][N][2]: the same for psi^-brv(k)
     u64* bad_count;   // [1]: the counter of he_check_reduced
+    void* static_scratch;  // this GPU's address of the library's fixed scratch array (he_ct_pt_mac_static); not owned
 };
 
 // One group of outputs that read the same ciphertexts in the same order.

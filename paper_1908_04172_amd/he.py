@@ -20,6 +20,7 @@ PT_SCALAR = 0
 PT_POLY = 1
 RESCALE = 1
 ACCUMULATE = 2
+STATIC_SCRATCH_BYTES = 32 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhe_mi355x.so")
@@ -27,7 +28,7 @@ LIB_PATH = os.path.join(_HERE, "libhe_mi355x.so")
 EXPORTS = [
     "he_strerror", "he_ctx_create", "he_ctx_destroy", "he_ctx_info", "he_encode_scalar", "he_encode_scalar_host",
     "he_encode_vector", "he_decode_vector",
-    "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_add", "he_rescale",
+    "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_mac_static", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_check_reduced", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_measure_rate",
     "he_host_barrett64", "he_host_shoup32", "he_host_mac_three_product_terms", "he_host_mac_accumulate_three_products", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
@@ -65,6 +66,7 @@ def lib():
         "he_plan_destroy": (i32, [vp]),
         "he_plan_workspace_bytes": (i32, [vp, u32, i32, u32, ctypes.POINTER(sz)]),
         "he_ct_pt_mac": (i32, [vp, vp, u32, vp, vp, i32, vp, vp, u32, vp, sz, vp]),
+        "he_ct_pt_mac_static": (i32, [vp, vp, u32, vp, vp, i32, vp, vp, u32, vp]),
         "he_ct_pt_add": (i32, [vp, u32, vp, u32, vp, i32, vp]),
         "he_rescale": (i32, [vp, u32, vp, vp, u32, vp]),
         "he_ntt_fwd": (i32, [vp, u32, vp, u32, vp]),
@@ -281,6 +283,17 @@ class Context:
                                   ws_bytes, _stream()), "he_ct_pt_mac")
         return out
 
+
+    def ct_pt_mac_static(self, plan: "Plan", ct_in, pt, pt_kind: int, out, bias=None, flags: int = 0):
+        """he_ct_pt_mac_static: the same operation on the library's fixed scratch array; the caller brings the output."""
+        limbs = ct_in.shape[2]
+        assert tuple(ct_in.shape) == (plan.n_in, 2, limbs, self.N)
+        assert tuple(pt.shape) == ((plan.n_pt, limbs) if pt_kind == PT_SCALAR else (plan.n_pt, limbs, self.N))
+        assert bias is None or tuple(bias.shape) == (plan.n_out, limbs)
+        assert tuple(out.shape) == (plan.n_out, 2, limbs - 1 if flags & RESCALE else limbs, self.N)
+        _check(lib().he_ct_pt_mac_static(self._h, plan._h, limbs, _dev_ptr(ct_in, "ct_in"), _dev_ptr(pt, "pt"), pt_kind,
+                                         _dev_ptr(bias, "bias"), _dev_ptr(out, "ct_out"), flags, _stream()), "he_ct_pt_mac_static")
+        return out
 
     # -- the x^2 activation: square + relinearise, the context's last limb being the special prime
     def square_relin_workspace_bytes(self, limbs: int, n: int) -> int:
