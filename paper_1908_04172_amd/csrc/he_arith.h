@@ -88,9 +88,11 @@ HE_HD u64 mad_wide(u32 a, u32 b, u64 c) {
 
 HE_HD u32 mul_hi32(u32 a, u32 b) { return (u32)(((u64)a * b) >> 32); }
 
-// y*w - qh*q modulo 2^64 on 32-bit pieces, as y*w + qh*(2^64 - q): the two products that reach the
-// low word chain through one accumulator, the four that reach only the high word through another.
-HE_HD u64 shoup_remainder(u64 y, u64 w, u64 qh, u64 q) {
+// base + y*w - qh*q modulo 2^64 on 32-bit pieces, as base + y*w + qh*(2^64 - q): the two products that reach
+// the low word chain through one accumulator that starts from `base`, the four that reach only the high
+// word through another.  (A butterfly passes its other operand as `base` and so gets X + W*Y out of the
+// multiply-add chain itself, with no addition of its own.)
+HE_HD u64 shoup_remainder_add(u64 y, u64 w, u64 qh, u64 q, u64 base) {
     const u32 y0 = (u32)y, y1 = (u32)(y >> 32), w0 = (u32)w, w1 = (u32)(w >> 32);
     const u32 h0 = (u32)qh, h1 = (u32)(qh >> 32);
     const u64 nq = 0 - q;
@@ -99,7 +101,7 @@ HE_HD u64 shoup_remainder(u64 y, u64 w, u64 qh, u64 q) {
     cross = mad_wide(y1, w0, cross);
     cross = mad_wide(h0, n1, cross);
     cross = mad_wide(h1, n0, cross);
-    u64 e = (u64)y0 * w0;
+    u64 e = (u64)y0 * w0 + base;
     e = (u64)h0 * n0 + e;
     u32 hi = (u32)(e >> 32) + (u32)cross;
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -108,25 +110,30 @@ HE_HD u64 shoup_remainder(u64 y, u64 w, u64 qh, u64 q) {
     return ((u64)hi << 32) | (u32)e;
 }
 
-// Shoup product with a fixed operand w < q and w' = floor(w * 2^64 / q): for ANY 64-bit y the
-// result is congruent to y*w and lies in [0, 2q) (Harvey's lazy form); needs q < 2^63.  The
-// quotient estimate qh = floor(y*w' / 2^64) is exact here.
-HE_HD u64 shoup_mul_lazy(u64 y, u64 w, u64 w_shoup, u64 q) {
+HE_HD u64 shoup_remainder(u64 y, u64 w, u64 qh, u64 q) { return shoup_remainder_add(y, w, qh, q, 0); }
+
+// The quotient estimates of the Shoup product y*w with w' = floor(w * 2^64 / q): the exact one,
+// floor(y*w' / 2^64), and the cheap one, short of it by at most 2 (see shoup_mul_lazy4).
+HE_HD u64 shoup_quotient(u64 y, u64 w_shoup) {
     const u32 y0 = (u32)y, y1 = (u32)(y >> 32), p0 = (u32)w_shoup, p1 = (u32)(w_shoup >> 32);
     const u64 b = (u64)y0 * p1 + mul_hi32(y0, p0);
     const u64 c = (u64)y1 * p0 + (u32)b;
-    const u64 qh = (u64)y1 * p1 + (b >> 32) + (c >> 32);
-    return shoup_remainder(y, w, qh, q);
+    return (u64)y1 * p1 + (b >> 32) + (c >> 32);
 }
+HE_HD u64 shoup_quotient_cheap(u64 y, u64 w_shoup) {
+    const u32 y0 = (u32)y, y1 = (u32)(y >> 32), p0 = (u32)w_shoup, p1 = (u32)(w_shoup >> 32);
+    return (u64)y1 * p1 + mul_hi32(y0, p1) + mul_hi32(y1, p0);
+}
+
+// Shoup product with a fixed operand w < q and w' = floor(w * 2^64 / q): for ANY 64-bit y the
+// result is congruent to y*w and lies in [0, 2q) (Harvey's lazy form); needs q < 2^63.  The
+// quotient estimate qh = floor(y*w' / 2^64) is exact here.
+HE_HD u64 shoup_mul_lazy(u64 y, u64 w, u64 w_shoup, u64 q) { return shoup_remainder(y, w, shoup_quotient(y, w_shoup), q); }
 
 // The same product with a cheaper quotient estimate: y1*p1 + floor(y0*p1 / 2^32) + floor(y1*p0 / 2^32)
 // leaves out the product y0*p0 and the fractions of the two middle products, so it is short of
 // floor(y*w' / 2^64) by at most 2 and the result lies in [0, 4q).  For ANY 64-bit y; needs q < 2^62.
-HE_HD u64 shoup_mul_lazy4(u64 y, u64 w, u64 w_shoup, u64 q) {
-    const u32 y0 = (u32)y, y1 = (u32)(y >> 32), p0 = (u32)w_shoup, p1 = (u32)(w_shoup >> 32);
-    const u64 qh = (u64)y1 * p1 + mul_hi32(y0, p1) + mul_hi32(y1, p0);
-    return shoup_remainder(y, w, qh, q);
-}
+HE_HD u64 shoup_mul_lazy4(u64 y, u64 w, u64 w_shoup, u64 q) { return shoup_remainder(y, w, shoup_quotient_cheap(y, w_shoup), q); }
 
 HE_HD u64 shoup_mul(u64 y, u64 w, u64 w_shoup, u64 q) {
     u64 r = shoup_mul_lazy(y, w, w_shoup, q);
@@ -299,23 +306,24 @@ struct Twiddle {
 //           through all stages.  (Inverse butterflies add their inputs, which would double the
 //           bound per stage, so the inverse transform runs as in mode 1.)
 
-// Forward butterfly: (X, Y) -> (X + W*Y, X - W*Y).
+// Forward butterfly: (X, Y) -> (X + W*Y, X - W*Y).  With U the (possibly reduced) X and V the lazy product
+// W*Y, the first output U + V comes out of the product's own multiply-add chain (U is its starting value), and
+// the second is (2U + m) - (U + V) = U + m - V for the mode's multiple m of q: a shift-and-add and a subtraction,
+// all modulo 2^64, the true values being below 2^64.
 template <int MODE>
 __device__ __forceinline__ void bfly_fwd(u64& x, u64& y, Twiddle t, const LimbConst& c) {
     if constexpr (MODE == 0) {
         const u64 u = sub_if_ge(x, c.neg_two_q);
-        const u64 v = shoup_mul_lazy(y, t.w, t.w_shoup, c.q);
-        x = u + v;
-        y = u + c.two_q - v;
+        x = shoup_remainder_add(y, t.w, shoup_quotient(y, t.w_shoup), c.q, u);
+        y = (u << 1) + c.two_q - x;
     } else if constexpr (MODE == 1) {
         const u64 u = sub_if_ge(x, c.neg_four_q);
-        const u64 v = shoup_mul_lazy4(y, t.w, t.w_shoup, c.q);
-        x = u + v;
-        y = u + c.four_q - v;
+        x = shoup_remainder_add(y, t.w, shoup_quotient_cheap(y, t.w_shoup), c.q, u);
+        y = (u << 1) + c.four_q - x;
     } else {
-        const u64 v = shoup_mul_lazy4(y, t.w, t.w_shoup, c.q);
-        y = x + c.four_q - v;
-        x = x + v;
+        const u64 u = x;
+        x = shoup_remainder_add(y, t.w, shoup_quotient_cheap(y, t.w_shoup), c.q, u);
+        y = (u << 1) + c.four_q - x;
     }
 }
 

@@ -200,14 +200,15 @@ __device__ __forceinline__ void ntt_forward(u64 (&a)[16], const u64* tw, u64* ld
     }
 }
 
-// The forward transform in the limb's mode, ending below `cap` (returned): 4q, 4q or (1+4*log2N)*q.
-// In mode 1 the values are brought from below 8q to below 4q, so that x + cap - value fits 64 bits
-// for any canonical x.
-template <int LOGN>
+// The forward transform in the limb's mode, of inputs below IN_Q * q (IN_Q <= 3: every mode takes them),
+// ending below `cap` (returned): 4q, 4q or (IN_Q + 4*log2N)*q.  In mode 1 the values are brought from below
+// 8q to below 4q, so that x + cap - value fits 64 bits for any canonical x.
+template <int LOGN, int IN_Q = 1>
 __device__ __forceinline__ u64 ntt_forward_any(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
+    static_assert(IN_Q >= 1 && IN_Q <= 3 && IN_Q + 4 * LOGN + 1 <= 64, "mode 2: (IN_Q + 4*log2N + 1) * q stays below 2^64 for q < 2^58");
     if (c.ntt_mode == 2) {
         ntt_forward<LOGN, 2>(a, tw, lds, tid, c);
-        return c.q * (4 * LOGN + 1);
+        return c.q * (4 * LOGN + IN_Q);
     }
     if (c.ntt_mode == 1) {
         ntt_forward<LOGN, 1>(a, tw, lds, tid, c);
@@ -406,20 +407,18 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, 
         const DropConst& d = drop.d[i];
         const u64* xrow = src + (size_t)i * G::N;
         u64* orow = dst + (size_t)i * G::N;
-        // t < p: bring it below q_i (nothing to do, one subtraction, or a full reduction, depending
-        // on how p compares with q_i), then subtract h mod q_i
+        // t < p is below 2*q_i unless p > 2*q_i (then a full reduction comes first); adding q_i - (h mod q_i)
+        // gives a value congruent to t - h and below 3*q_i, which the forward transform takes as it is
         if (d.reduce_mode == 2) {
 #pragma unroll
             for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
-        } else if (d.reduce_mode == 1) {
-#pragma unroll
-            for (u32 e = 0; e < 16; e++) a[e] = a[e] >= c.q ? a[e] - c.q : a[e];
         }
+        const u64 minus_half = c.q - d.half_mod;
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) a[e] = sub_mod(a[e], d.half_mod, c.q);
+        for (u32 e = 0; e < 16; e++) a[e] += minus_half;
         // the transformed correction stays below `cap` (a multiple of q), so x + cap - correction is
         // positive, congruent to x - correction and fits 64 bits; the Shoup product takes it as it is
-        u64 cap = ntt_forward_any<LOGN>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
+        u64 cap = ntt_forward_any<LOGN, 3>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
         if (c.ntt_mode == 0) {  // 5q need not fit 64 bits, 3q does
 #pragma unroll
             for (u32 e = 0; e < 16; e++) a[e] = sub_if_ge(a[e], c.neg_two_q);

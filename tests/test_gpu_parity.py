@@ -533,6 +533,26 @@ def test_rescale_matches_oracle(he, cfg):
         assert np.array_equal(host(ctx.rescale(dev(sub))), oracle.rescale(sub, c.q[:-1], ctx.psi[:-1]))
 
 
+@pytest.mark.parametrize("log2N", [11, 14])
+def test_rescale_with_dropped_modulus_above_and_below_the_kept_ones(he, log2N):
+    """The dropped modulus p against a kept q_i: p < q_i (t needs no reduction), q_i < p < 2 q_i, and p > 2 q_i
+    (a full reduction), for kept limbs of every butterfly mode (62-, 60-, 50-, 30-bit)."""
+    N = 1 << log2N
+    p50 = wl.ntt_primes(50, N, 30)
+    q = [p50[29], wl.ntt_primes(30, N, 1)[0], wl.ntt_primes(62, N, 1)[0], wl.ntt_primes(60, N, 1)[0], p50[1], p50[0]]
+    assert q[0] < q[-1] < 2 * q[0] and q[-1] > 2 * q[1] and q[-1] < q[2]
+    ctx = he.Context(log2N, q)
+    ct = wl.uniform_residues((3, 2), q, N, 160 + log2N)
+    ct[0, 0, -1] = 0
+    ct[0, 1, -1] = q[-1] - 1
+    assert np.array_equal(host(ctx.rescale(dev(ct))), oracle.rescale(ct, q, ctx.psi))
+    # the 62-bit limb dropped (every kept limb far below it), and a 50-bit limb dropped under a 60-bit one
+    for chain in ([q[0], q[1], q[3], q[2]], [q[3], q[1], q[4]]):
+        ctx2 = he.Context(log2N, chain)
+        ct2 = wl.uniform_residues((2, 2), chain, N, 170 + log2N)
+        assert np.array_equal(host(ctx2.rescale(dev(ct2))), oracle.rescale(ct2, chain, ctx2.psi))
+
+
 def test_maximum_sizes_and_degenerate_calls(he):
     # largest ring degree with the largest number of limbs, mixed widths including 61- and 62-bit moduli
     N, L = 1 << 14, 16
