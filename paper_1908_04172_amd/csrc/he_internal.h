@@ -111,9 +111,18 @@ struct he_plan {
 // hipFuncSetAttribute(MaxDynamicSharedMemorySize) for a kernel that needs more than the default
 // 64 KiB of LDS: once per kernel and device (`done` is a bit mask over device numbers, one static
 // per call site), not on every launch.
-inline int allow_dynamic_lds(const void* kernel, size_t bytes, int device, std::atomic<uint32_t>& done) {
+inline int allow_dynamic_lds(const void* kernel, size_t bytes, int device, std::atomic<uint32_t>& done, bool row_at_zero = false) {
     const uint32_t bit = 1u << (device & 31);
     if (device < 32 && (done.load(std::memory_order_acquire) & bit)) return HE_OK;
+    if (row_at_zero) {
+        // the transform kernels form LDS addresses on the premise that their dynamic row starts at LDS
+        // address 0, i.e. that the kernel has no static LDS in front of it (lds_row_starts_at_zero)
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, kernel) != hipSuccess || attr.sharedSizeBytes != 0) {
+            (void)hipGetLastError();
+            return HE_ERR_DEVICE;
+        }
+    }
     if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
         (void)hipGetLastError();
         return HE_ERR_DEVICE;

@@ -79,22 +79,34 @@ __device__ __forceinline__ void regroup(u64 (&a)[16], u64* lds, u32 tid) {
     u32 tid_w = tid, tid_r = tid;
     asm("; regroup %1 write" : "+v"(tid_w) : "n"(PFROM * 16 + PTO));
     asm("; regroup %1 read" : "+v"(tid_r) : "n"(PFROM * 16 + PTO));
-    const u32 from = lds_slot(reg_index<LOGN, PFROM>(tid_w, 0)), to = lds_slot(reg_index<LOGN, PTO>(tid_r, 0));
+    // Addresses are formed as LDS byte addresses outright, one XOR per access: (row + from) ^ constant equals
+    // row + (from ^ constant) because the row starts at LDS address 0 -- a workgroup's LDS addresses are relative
+    // to its own allocation, and these kernels have no static LDS in front of the dynamic row (the launchers
+    // check that: lds_row_starts_at_zero).
+    typedef __attribute__((address_space(3))) u64 lds_u64;
+    const u32 row = (u32)(uintptr_t)(lds_u64*)lds;
+    const u32 from = row + lds_slot(reg_index<LOGN, PFROM>(tid_w, 0)) * 8u, to = row + lds_slot(reg_index<LOGN, PTO>(tid_r, 0)) * 8u;
     // earlier readers of the slots written here are done: all waves, or (wave-local) this wave only,
     // since its block of slots is then touched by no other wave until the next workgroup-wide regrouping
     if constexpr (WAVE_LOCAL) lds_wave_order(); else lds_barrier();
 #pragma unroll
-    for (u32 e = 0; e < 16; e++) lds[from ^ lds_slot(reg_index<LOGN, PFROM>(0, e))] = a[e];
+    for (u32 e = 0; e < 16; e++) *(lds_u64*)(uintptr_t)(from ^ (lds_slot(reg_index<LOGN, PFROM>(0, e)) * 8u)) = a[e];
     if constexpr (WAVE_LOCAL) lds_wave_order(); else lds_barrier();
 #pragma unroll
-    for (u32 e = 0; e < 16; e++) a[e] = lds[to ^ lds_slot(reg_index<LOGN, PTO>(0, e))];
+    for (u32 e = 0; e < 16; e++) a[e] = *(const lds_u64*)(uintptr_t)(to ^ (lds_slot(reg_index<LOGN, PTO>(0, e)) * 8u));
 }
 
 template <bool UNIFORM>
 __device__ __forceinline__ Twiddle load_twiddle(const u64* tw, u32 k) {
-    if constexpr (UNIFORM) k = __builtin_amdgcn_readfirstlane(k);
-    const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(tw + 2 * (size_t)k);
-    return Twiddle{v.x, v.y};
+    if constexpr (UNIFORM) {
+        typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+        k = __builtin_amdgcn_readfirstlane(k);
+        const u64x2 v = *(const __attribute__((address_space(4))) u64x2*)(tw + 2 * (size_t)k);
+        return Twiddle{v.x, v.y};
+    } else {
+        const ulonglong2 v = *reinterpret_cast<const ulonglong2*>(tw + 2 * (size_t)k);
+        return Twiddle{v.x, v.y};
+    }
 }
 
 // Shape of pass P: its stages, and where the twiddle of (stage k, register e) sits among the
@@ -175,12 +187,13 @@ __device__ __forceinline__ void run_pass(u64 (&a)[16], const PassTwiddles<LOGN, 
 template <int LOGN, int MODE>
 __device__ __forceinline__ void ntt_forward(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
     using G = Geo<LOGN>;
+    static_assert(G::NPASS >= 2 && G::NPASS <= 4, "two to four passes");
     {
         PassTwiddles<LOGN, 0> t0;
         load_pass_twiddles<LOGN, 0>(t0, tw, tid);
         run_pass<LOGN, 0, false, MODE>(a, t0, c);
     }
-    if constexpr (G::NPASS > 1) {
+    {
         PassTwiddles<LOGN, 1> t1;
         load_pass_twiddles<LOGN, 1>(t1, tw, tid);
         regroup<LOGN, 0, 1>(a, lds, tid);
@@ -316,20 +329,11 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
 #pragma unroll
             for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
         }
-        if constexpr (!INVERSE) {
-            ntt_forward_any<LOGN>(a, tw, lds, tid, c);
-            if (c.ntt_mode == 2) {
-                // below 57q: a Shoup product by 1 (whose companion is floor(2^64/q)) brings it below 4q
-#pragma unroll
-                for (u32 e = 0; e < 16; e++) a[e] = shoup_mul_lazy4(a[e], 1, c.ratio_hi, c.q);
-            }
-#pragma unroll
-            for (u32 e = 0; e < 16; e++) a[e] = canon4(a[e], c.q, c.two_q);
-        } else {
-            ntt_inverse_any<LOGN>(a, tw, lds, tid, c);
-#pragma unroll
-            for (u32 e = 0; e < 16; e++) a[e] = a[e] >= c.q ? a[e] - c.q : a[e];
-        }
+        if constexpr (!INVERSE) ntt_forward_any<LOGN>(a, tw, lds, tid, c);
+        else ntt_inverse_any<LOGN>(a, tw, lds, tid, c);
+        // The next row is requested first, the last reductions of this row run while it travels, and it is
+        // waited for before this row's stores are issued: a wait for loads that have stores behind them would
+        // wait for the stores as well (loads and stores complete out of order with respect to each other).
         const u32 tid_s = fresh(tid);
         u64 next[16];
 #pragma unroll
@@ -341,6 +345,24 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
             const u64* p = SPREAD ? spread_src + (size_t)next_src * G::N : data + (size_t)nr * G::N;
 #pragma unroll
             for (u32 e = 0; e < 16; e++) next[e] = p[reg_index<LOGN, PIN>(tid_s, e)];
+        }
+        if constexpr (!INVERSE) {
+            if (c.ntt_mode == 2) {
+                // below 57q: a Shoup product by 1 (whose companion is floor(2^64/q)) brings it below 4q
+#pragma unroll
+                for (u32 e = 0; e < 16; e++) a[e] = shoup_mul_lazy4(a[e], 1, c.ratio_hi, c.q);
+            }
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) a[e] = canon4(a[e], c.q, c.two_q);
+        } else {
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) a[e] = a[e] >= c.q ? a[e] - c.q : a[e];
+        }
+        // (an inverse transform ends with one subtraction per value: too little to cover the loads, and waiting
+        // for them behind the stores costs less than waiting for them here)
+        if constexpr (!INVERSE) {
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) asm volatile("" : "+v"(next[e]) :: "memory");
         }
         u64* p = data + (size_t)row * G::N;
 #pragma unroll
@@ -357,14 +379,13 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
 // transform of the last limb ends in the register order in which a forward transform starts, so
 // the first kept limb takes t straight from the registers; for the others t is parked in memory.
 //
-// The parked t for limb i+1 is requested before the outputs of limb i are stored, so that the next
-// iteration does not queue behind those stores.
+// The parked t for limb i+1 is requested, and waited for, before the outputs of limb i are stored.
 template <int LOGN, bool SPLIT>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
 rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, u64* out, const u64* tw_fwd,
                const u64* tw_inv) {
     using G = Geo<LOGN>;
-    extern __shared__ u64 lds[];
+    extern __shared__ __align__(16) u64 lds[];
     // A polynomial is handled by `parts` workgroups when there are too few polynomials to fill the
     // chip: each repeats the inverse transform of the dropped limb and takes a contiguous share
     // [first, end) of the kept limbs.
@@ -416,8 +437,13 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, 
         const u64 minus_half = c.q - d.half_mod;
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] += minus_half;
-        // the transformed correction stays below `cap` (a multiple of q), so x + cap - correction is
-        // positive, congruent to x - correction and fits 64 bits; the Shoup product takes it as it is
+        // Vector loads and stores share one in-order counter per kind but complete out of order with respect
+        // to each other, so a wait for a load that has stores behind it waits for the stores as well (until they
+        // are acknowledged by the L2).  Hence the order below: every load the next iteration needs is issued AND
+        // waited for before this iteration's stores are issued, and the transform that follows starts on scalar
+        // loads (its first two passes' twiddles), with nothing to wait for behind the stores.
+        // The transformed correction stays below `cap` (a multiple of q), so x + cap - correction is
+        // positive, congruent to x - correction and fits 64 bits; the Shoup product takes it as it is.
         u64 cap = ntt_forward_any<LOGN, 3>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
         if (c.ntt_mode == 0) {  // 5q need not fit 64 bits, 3q does
 #pragma unroll
@@ -435,10 +461,14 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, 
             for (u32 e = 0; e < 16; e++) next[e] = park[reg_index<LOGN, 0>(tid_s, e)];
         }
 #pragma unroll
-        for (u32 e = 0; e < 16; e++)
-            orow[reg_index<LOGN, G::NPASS - 1>(tid_s, e)] = shoup_mul(x[e] + cap - a[e], d.p_inv, d.p_inv_shoup, c.q);
+        for (u32 e = 0; e < 16; e++) x[e] = shoup_mul(x[e] + cap - a[e], d.p_inv, d.p_inv_shoup, c.q);
 #pragma unroll
-        for (u32 e = 0; e < 16; e++) a[e] = next[e];
+        for (u32 e = 0; e < 16; e++) {
+            a[e] = next[e];
+            asm volatile("" : "+v"(a[e]) :: "memory");  // t for the next limb has arrived: nothing is left to wait for
+        }
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) orow[reg_index<LOGN, G::NPASS - 1>(tid_s, e)] = x[e];
     }
 }
 
@@ -452,11 +482,11 @@ int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipS
     const u32 grid = std::min<u32>(rows, 256 * per_cu);
     if (inverse) {
         static std::atomic<uint32_t> lds_allowed{0};
-        if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true>, lds, ctx->device, lds_allowed)) return rc;
+        if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true>, lds, ctx->device, lds_allowed, true)) return rc;
         hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, rows);
     } else {
         static std::atomic<uint32_t> lds_allowed{0};
-        if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false>, lds, ctx->device, lds_allowed)) return rc;
+        if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false>, lds, ctx->device, lds_allowed, true)) return rc;
         hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd, rows);
     }
     HE_HIP(hipGetLastError());
@@ -472,7 +502,7 @@ int launch_ntt_spread_t(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 ro
     const u32 per_cu = (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
     const u32 grid = std::min<u32>(rows, 256 * per_cu);
     static std::atomic<uint32_t> lds_allowed{0};
-    if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false, true>, lds, ctx->device, lds_allowed)) return rc;
+    if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false, true>, lds, ctx->device, lds_allowed, true)) return rc;
     hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false, true>), dim3(grid), dim3(G::T), lds, s, lt, limbs, out, ctx->tw_fwd, rows, src,
                        digits, ctx->L - 1);
     HE_HIP(hipGetLastError());
@@ -491,8 +521,8 @@ int launch_rescale_t(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* ou
     const u64* tw_inv = ctx->tw_inv + (size_t)(drop_id - (limbs - 1)) * G::N * 2;
     const size_t lds = (size_t)G::N * sizeof(u64);
     static std::atomic<uint32_t> lds_allowed{0}, lds_allowed_split{0};
-    if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN, false>, lds, ctx->device, lds_allowed)) return rc;
-    if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN, true>, lds, ctx->device, lds_allowed_split)) return rc;
+    if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN, false>, lds, ctx->device, lds_allowed, true)) return rc;
+    if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN, true>, lds, ctx->device, lds_allowed_split, true)) return rc;
     DropRow row;
     for (u32 i = 0; i < HE_MAX_LIMBS; i++) row.d[i] = ctx->drop[drop_id][i];
     // with fewer polynomials than workgroups the chip holds at once, split each over several workgroups
