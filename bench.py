@@ -25,16 +25,23 @@ HBM_PEAK_GBS = 8000.0
 INT_MUL32_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 MUL32_PER_MAC = 4          # a 64x64 -> 128-bit product is four 32x32 -> 64 multiply-adds
 MUL32_PER_SHOUP = 10       # hi64(y*w') 4, lo64(y*w) 3, lo64(qh*q) 3
-# HBM-side bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# benchmark, scaled by a plain kernel of known size (profiles/pmc_hbm_traffic_cfg4_cfg5.md).  Counters
-# cannot be read from inside this process, so these are the figures of the profiled build.
+# HBM-side bytes per launch (read + written) of the main kernels come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this benchmark, scaled by a plain kernel of known size: counters cannot be read from inside this
+# process, so they are taken from the summary of those runs, profiles/hbm_traffic.json, which names the commit
+# it was measured at.
 GIB = 1 << 30
-PROFILED_TRAFFIC_BYTES = {
-    "mac_scalar_cfg4": int((10.58 + 8.19) * GIB),
-    "mac_poly_cfg5": int((16.55 + 0.125) * GIB),
-    "rescale_cfg4": int((15.67 + 9.59) * GIB),
-    "rescale_cfg5": None,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def profiled_traffic():
+    """{kernel: bytes per launch} and where the figures come from (None, None if the summary is absent)."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            d = json.load(f)
+    except (OSError, ValueError):
+        return {}, None
+    per = {k: int(v["fetch_bytes"] + v["write_bytes"]) for k, v in d.get("kernels", {}).items()}
+    return per, {"file": "profiles/hbm_traffic.json", "commit": d.get("commit"), "counters": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE"}
 
 
 def main() -> int:
@@ -139,8 +146,9 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    phase_ms = {name: float(np.mean([events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)]))
+    phase_ms = {name: float(np.median([events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)]))
                 for i, name in enumerate(phases)}
+    traffic, traffic_source = profiled_traffic()
 
     # ---- algorithmic work (per step)
     ct_bytes = 2 * L * N * 8
@@ -160,12 +168,12 @@ def main() -> int:
     def alu(name, mul32):
         a = mul32 / (phase_ms[name] * 1e-3) / 1e12
         return {"kernel": name, "bound": "alu", "achieved": a, "peak": INT_MUL32_PEAK_TOPS, "unit": "Tmul32/s",
-                "frac": a / INT_MUL32_PEAK_TOPS, "traffic": PROFILED_TRAFFIC_BYTES.get(name)}
+                "frac": a / INT_MUL32_PEAK_TOPS, "traffic": traffic.get(name)}
     def hbm(name, nbytes):
         a = nbytes / (phase_ms[name] * 1e-3) / 1e9
         return {"kernel": name, "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": a / HBM_PEAK_GBS, "traffic": PROFILED_TRAFFIC_BYTES.get(name)}
-    rooflines["mac_scalar_cfg4"] = alu("mac_scalar_cfg4", macs4 * MUL32_PER_MAC)
+                "frac": a / HBM_PEAK_GBS, "traffic": traffic.get(name)}
+    rooflines["mac_scalar_cfg4"] = alu("mac_scalar_cfg4", macs4 * MUL32_PER_MAC)   # the four-product definition of a term
     rooflines["rescale_cfg4"] = alu("rescale_cfg4", rescale_mul32(p4.n_out))
     # the full-polynomial MAC streams every plaintext residue once: HBM-bound
     mac5_bytes = p5.n_pt * L * N * 8 + p5.n_in * ct_bytes + p5.n_out * ct_bytes
@@ -190,18 +198,18 @@ def main() -> int:
         for i in range(last):
             per_poly += bf / rate(fwd_kind[mode[i]], i) + N / rate(he.RATE_SHOUP_EXACT, i)
         return 2 * n_ct * per_poly
-    def mac_ideal_s(plan):
-        return sum(plan.n_terms * 2 * N / rate(he.RATE_MAC_TERM, i) for i in range(L))
-    ideal = {"mac_scalar_cfg4": mac_ideal_s(p4), "rescale_cfg4": rescale_ideal_s(p4.n_out),
-             "mac_poly_cfg5": mac_ideal_s(p5), "rescale_cfg5": rescale_ideal_s(p5.n_out)}
+    # the scalar MAC runs the three-product form of a term on the limbs that leave room for it
+    three = [he.host_mac_three_product_terms(qi) >= max(int(x) for x in np.diff(p4.off.astype(np.int64))) for qi in q]
+    def mac_ideal_s(plan, scalar):
+        return sum(plan.n_terms * 2 * N / rate(he.RATE_MAC_TERM3 if scalar and three[i] else he.RATE_MAC_TERM, i) for i in range(L))
+    ideal = {"mac_scalar_cfg4": mac_ideal_s(p4, True), "rescale_cfg4": rescale_ideal_s(p4.n_out),
+             "mac_poly_cfg5": mac_ideal_s(p5, False), "rescale_cfg5": rescale_ideal_s(p5.n_out)}
     for name, r in rooflines.items():
         if args.rates and not only:
             r["arithmetic_ms_at_measured_rate"] = ideal[name] * 1e3
             r["frac_of_measured_rate"] = ideal[name] * 1e3 / phase_ms[name]
     names = ["mad32", "mac_term", "shoup_exact", "shoup_cheap", "butterfly_mode0", "butterfly_mode1",
-             "butterfly_mode2", "butterfly_inverse", "butterfly_fp64_probe"]
-    if args.rates and not only:
-        rate(he.RATE_BUTTERFLY_FP64, L - 1)      # what a double-precision butterfly would cost on a 50-bit limb (no kernel uses it)
+             "butterfly_mode2", "butterfly_inverse", "mac_term_three_products"]
     measured_rates = {"unit": "G operations/s, register-resident, whole GPU",
                       "rates": {"%s@%dbit" % (names[k], q[limb].bit_length()): v / 1e9
                                 for (k, limb), v in sorted(rate_cache.items(), reverse=True)}}
@@ -226,6 +234,7 @@ def main() -> int:
         "phase_ms": phase_ms,
         "roofline": {k: v for k, v in rooflines[dominant].items()},
         "roofline_all": list(rooflines.values()),
+        "traffic_source": traffic_source,
         "measured_rates": measured_rates if args.rates else None,
     }
 

@@ -139,6 +139,7 @@ int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipSt
 int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s);
 int launch_rescale_drop(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* out, u32 n, hipStream_t s);
 int launch_ntt_spread(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 n_digit_rows, u32 digits, hipStream_t s);
+int launch_ntt_square(he_ctx* ctx, u32 limbs, const u64* ct, u64* d2, u64* digits, u32 n_ct, hipStream_t s);
 // square + relinearisation (he_relin.hip)
 size_t square_relin_workspace(const he_ctx* ctx, u32 limbs, u32 n);
 int launch_square_relin(he_ctx* ctx, u32 limbs, const u64* ct_in, u32 n, const u64* evk, u64* ct_out, void* workspace, hipStream_t s);

@@ -284,17 +284,24 @@ __device__ __forceinline__ u32 fresh(u32 tid) {
 // In-place transforms of `rows` rows of N residues, row r under limb r % limbs.  A workgroup takes
 // rows blockIdx.x, blockIdx.x + gridDim.x, ... and requests its next row before it stores the
 // current one, so that the loads do not queue behind the stores and arrive while those drain.
-// SPREAD (forward only): a row is not read from `data` but from a row of `spread_src`, a table of
+// KIND = ROWS_SPREAD (forward only): a row is not read from `data` but from a row of `spread_src`, a table of
 // coefficient rows [..][digits][N] whose row (.., j) holds integers below q_j; they are reduced
 // modulo the target limb first.  This is the digit expansion of a key switch: each
 // digit transformed under every limb, written to data [..][digits][limbs][N]; the limbs are
 // q_0..q_{limbs-2} and, at the last position, the special prime (limb `last_id` of the context).
-template <int LOGN, bool INVERSE, bool SPREAD = false>
+// KIND = ROWS_SQUARE (inverse only): row r = (ciphertext, limb j) is the slot-wise square of component 1 of that
+// ciphertext, read from spread_src [..][2][limbs][N]: the quadratic component of a squared ciphertext.  The squares
+// are stored as they are (NTT form) at row r * (limbs + 1) + j of `aux`, the place of digit j under its own limb
+// among the expanded digits, and their inverse transform, digit j as coefficients, goes to row r of `data`.
+enum { ROWS_PLAIN = 0, ROWS_SPREAD = 1, ROWS_SQUARE = 2 };
+template <int LOGN, bool INVERSE, int KIND = ROWS_PLAIN>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
 ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows, const u64* spread_src = nullptr,
-                u32 digits = 1, u32 last_id = 0) {
+                u32 digits = 1, u32 last_id = 0, u64* aux = nullptr) {
     using G = Geo<LOGN>;
+    constexpr bool SPREAD = KIND == ROWS_SPREAD, SQUARE = KIND == ROWS_SQUARE;
     static_assert(!(SPREAD && INVERSE), "the digit expansion is a forward transform");
+    static_assert(!SQUARE || INVERSE, "the squares are taken back to coefficients");
     constexpr int PIN = INVERSE ? G::NPASS - 1 : 0, POUT = INVERSE ? 0 : G::NPASS - 1;
     extern __shared__ u64 lds[];
     u64 a[16];
@@ -307,10 +314,20 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
         pos += pos >= src_row % digits;
         return src_row * limbs + pos;
     };
+    // where row w is read from
+    auto source = [&](u32 w) -> const u64* {
+        if constexpr (SPREAD) {
+            u32 src_row = 0;
+            (void)spread_row(w, src_row);
+            return spread_src + (size_t)src_row * G::N;
+        } else if constexpr (SQUARE) {
+            return spread_src + ((size_t)(w / limbs) * 2 + 1) * limbs * G::N + (size_t)(w % limbs) * G::N;
+        } else {
+            return data + (size_t)w * G::N;
+        }
+    };
     {
-        u32 src_row = 0;
-        if constexpr (SPREAD) (void)spread_row(blockIdx.x, src_row);
-        const u64* p = SPREAD ? spread_src + (size_t)src_row * G::N : data + (size_t)blockIdx.x * G::N;
+        const u64* p = source(blockIdx.x);
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, PIN>(threadIdx.x, e)];
     }
@@ -329,6 +346,14 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
 #pragma unroll
             for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
         }
+        if constexpr (SQUARE) {
+            u64* own = aux + ((size_t)row * (limbs + 1) + limb) * G::N;
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) {
+                a[e] = mul_mod(a[e], a[e], c);
+                own[reg_index<LOGN, PIN>(tid, e)] = a[e];
+            }
+        }
         if constexpr (!INVERSE) ntt_forward_any<LOGN>(a, tw, lds, tid, c);
         else ntt_inverse_any<LOGN>(a, tw, lds, tid, c);
         // The next row is requested first, the last reductions of this row run while it travels, and it is
@@ -339,10 +364,7 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
 #pragma unroll
         for (u32 e = 0; e < 16; e++) next[e] = 0;
         if (work + gridDim.x < rows) {
-            const u32 nr = work + gridDim.x;
-            u32 next_src = 0;
-            if constexpr (SPREAD) (void)spread_row(nr, next_src);
-            const u64* p = SPREAD ? spread_src + (size_t)next_src * G::N : data + (size_t)nr * G::N;
+            const u64* p = source(work + gridDim.x);
 #pragma unroll
             for (u32 e = 0; e < 16; e++) next[e] = p[reg_index<LOGN, PIN>(tid_s, e)];
         }
@@ -502,9 +524,25 @@ int launch_ntt_spread_t(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 ro
     const u32 per_cu = (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
     const u32 grid = std::min<u32>(rows, 256 * per_cu);
     static std::atomic<uint32_t> lds_allowed{0};
-    if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false, true>, lds, ctx->device, lds_allowed, true)) return rc;
-    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false, true>), dim3(grid), dim3(G::T), lds, s, lt, limbs, out, ctx->tw_fwd, rows, src,
+    if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false, ROWS_SPREAD>, lds, ctx->device, lds_allowed, true)) return rc;
+    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false, ROWS_SPREAD>), dim3(grid), dim3(G::T), lds, s, lt, limbs, out, ctx->tw_fwd, rows, src,
                        digits, ctx->L - 1);
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+// d2 [n_ct][limbs][N] = the coefficients of the square of component 1 of ct [n_ct][2][limbs][N] (slot-wise square, then
+// the inverse transform); the squares themselves go to digits [n_ct][limbs][limbs + 1][N] at (.., j, j).
+template <int LOGN>
+int launch_ntt_square_t(he_ctx* ctx, u32 limbs, const u64* ct, u64* d2, u64* digits, u32 rows, hipStream_t s) {
+    using G = Geo<LOGN>;
+    const size_t lds = (size_t)G::N * sizeof(u64);
+    const u32 per_cu = (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
+    const u32 grid = std::min<u32>(rows, 256 * per_cu);
+    static std::atomic<uint32_t> lds_allowed{0};
+    if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true, ROWS_SQUARE>, lds, ctx->device, lds_allowed, true)) return rc;
+    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true, ROWS_SQUARE>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, d2, ctx->tw_inv, rows, ct,
+                       1u, 0u, digits);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
@@ -571,6 +609,21 @@ int launch_ntt_spread(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 n_di
         case 12: return launch_ntt_spread_t<12>(ctx, limbs, src, out, rows, digits, s);
         case 13: return launch_ntt_spread_t<13>(ctx, limbs, src, out, rows, digits, s);
         case 14: return launch_ntt_spread_t<14>(ctx, limbs, src, out, rows, digits, s);
+    }
+    return HE_ERR_ARG;
+}
+
+int launch_ntt_square(he_ctx* ctx, u32 limbs, const u64* ct, u64* d2, u64* digits, u32 n_ct, hipStream_t s) {
+    const u64 rows64 = (u64)n_ct * limbs;
+    if (rows64 == 0) return HE_OK;
+    if (rows64 > 0x0FFFFFFFull) return HE_ERR_RANGE;
+    const u32 rows = (u32)rows64;
+    switch (ctx->log2N) {
+        case 10: return launch_ntt_square_t<10>(ctx, limbs, ct, d2, digits, rows, s);
+        case 11: return launch_ntt_square_t<11>(ctx, limbs, ct, d2, digits, rows, s);
+        case 12: return launch_ntt_square_t<12>(ctx, limbs, ct, d2, digits, rows, s);
+        case 13: return launch_ntt_square_t<13>(ctx, limbs, ct, d2, digits, rows, s);
+        case 14: return launch_ntt_square_t<14>(ctx, limbs, ct, d2, digits, rows, s);
     }
     return HE_ERR_ARG;
 }

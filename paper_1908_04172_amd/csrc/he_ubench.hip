@@ -30,7 +30,13 @@ __global__ void __launch_bounds__(THREADS) rate_kernel(LimbTable lt, u32 limb, u
     u32 wa, wb;
     split_operand(w, c, wa, wb);
     const u32 ws = wa + wb;
+    u32 ta = xa[0], tb = xb[0], ts = ta + tb;
     for (u32 it = 0; it < iters; it++) {
+        if constexpr (KIND == HE_RATE_MAC_TERM || KIND == HE_RATE_MAC_TERM3) {  // the next term's input residue
+            ta = ta * 0x9E3779B1u + 1u;
+            tb ^= ta >> 7;
+            ts = ta + tb;
+        }
 #pragma unroll
         for (int i = 0; i < CHAINS; i++) {
             if constexpr (KIND == HE_RATE_MAD32) {
@@ -38,9 +44,16 @@ __global__ void __launch_bounds__(THREADS) rate_kernel(LimbTable lt, u32 limb, u
             } else if constexpr (KIND == HE_RATE_MAC_TERM) {
                 // the four multiply-adds of one MAC term into the three running sums; the periodic
                 // folds and the final reduction are not part of the ceiling (the sums may wrap here,
-                // which only changes the discarded values)
-                // (operands taken from the sums themselves, so that no product is loop-invariant)
-                acc_mac(acc[i], (u32)acc[i].hi ^ xa[i], (u32)acc[i].lo ^ xb[i], wa, wb);
+                // which only changes the discarded values).  As in the kernels, the chains of a thread
+                // are outputs that share the input residue of the term (ta, tb: renewed once per
+                // iteration, below) and have a plaintext residue each.
+                acc_mac(acc[i], ta, tb, wa + i, wb + i);
+            } else if constexpr (KIND == HE_RATE_MAC_TERM3) {
+                // the three-product form of a term (lo += xa*wa, mid += (xa+xb)*(wa+wb), hi += xb*wb): the sum
+                // wa + wb comes with the weights, xa + xb is formed once per term for all outputs
+                acc[i].lo += (u64)ta * (wa + i);
+                acc[i].mid += (u64)ts * (ws + 2 * i);
+                acc[i].hi += (u64)tb * (wb + i);
             } else if constexpr (KIND == HE_RATE_SHOUP_EXACT) {
                 x[i] = shoup_mul_lazy(x[i], w, w_shoup, c.q);
             } else if constexpr (KIND == HE_RATE_SHOUP_CHEAP) {
