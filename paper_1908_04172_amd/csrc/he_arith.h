@@ -292,7 +292,12 @@ HE_HD u32 shoup32(u32 y, u32 w, u32 ws, u32 q) { return y * w - (u32)(((u64)y * 
 // ---------------------------------------------------------------------------------------------
 // NTT butterflies (Harvey's lazy forms with Shoup multiplication by a precomputed twiddle).
 struct Twiddle {
+    typedef u64 raw __attribute__((ext_vector_type(2)));  // a table entry as one 16-byte load
     u64 w, w_shoup;  // W and floor(W * 2^64 / q)
+};
+struct Twiddle32 {
+    typedef u32 raw __attribute__((ext_vector_type(2)));
+    u32 w, w_shoup;  // W and floor(W * 2^32 / q), for the packed 32-bit transforms
 };
 
 // How lazily the butterflies reduce depends on the room the modulus leaves in 64 bits

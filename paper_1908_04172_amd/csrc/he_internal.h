@@ -31,9 +31,10 @@ struct DropRow {
 // Per-limb constants of the 32-bit arithmetic.
 struct Limb32 {
     u32 q, two_q;
-    u32 n_inv, n_inv_shoup;  // N^-1 mod q and floor(N^-1 * 2^32 / q)
-    u64 ratio;               // floor(2^64 / q): the Barrett ratio of Alg. 6
-    u32 ok;                  // 1 if this limb's modulus is below 2^30 (else the limb has no 32-bit form)
+    u32 n_inv, n_inv_shoup;      // N^-1 mod q and floor(N^-1 * 2^32 / q)
+    u32 w1n_inv, w1n_inv_shoup;  // (psi^-brv(1)) * N^-1 and its companion: the last inverse butterfly merged with N^-1
+    u64 ratio;                   // floor(2^64 / q): the Barrett ratio of Alg. 6
+    u32 ok;                      // 1 if this limb's modulus is below 2^30 (else the limb has no 32-bit form)
     u32 pad;
 };
 struct Limb32Table {
@@ -43,7 +44,7 @@ struct Limb32Table {
 struct Drop32 {
     u32 p_inv, p_inv_shoup;  // q_j^-1 mod q_i and floor(that * 2^32 / q_i)
     u32 half_mod;            // floor(q_j / 2) mod q_i
-    u32 pad;
+    u32 reduce;              // 1 if q_j > 2 * q_i: a value below q_j is reduced modulo q_i first
 };
 struct Drop32Row {
     Drop32 d[HE_MAX_LIMBS];

@@ -4,11 +4,12 @@
 // bytes of the 64-bit form; a product of two residues fits 60 bits, so a MAC term is ONE 32x32+64-bit
 // multiply-add into a single 64-bit sum (four into three sums in the 64-bit path), fifteen terms go by
 // between two reductions, and a reduction is Alg. 6: one high product with floor(2^64 / q), one low
-// product, one conditional subtraction.  The transforms keep a whole row (and, in the rescale, the
-// dropped limb's coefficients beside it) in LDS.
+// product, one conditional subtraction.  The transforms are the register-resident ones of the 64-bit path
+// with 32-bit butterflies; the rescale keeps the dropped limb's coefficients in registers throughout.
 #include <algorithm>
 
 #include "he_internal.h"
+#include "he_ntt_core.h"
 
 namespace {
 
@@ -249,171 +250,217 @@ __global__ void __launch_bounds__(256) add32_kernel(Limb32Table lt, u32 limbs, u
 }
 
 // ---------------------------------------------------------------------------------------------
-// Negacyclic transforms of a row held in LDS (same root and output order as the 64-bit entry points:
-// slot j holds the value at psi^(2*bitrev(j)+1)).  Harvey's lazy butterflies in 32 bits: forward values
-// stay in [0, 4q), inverse values in [0, 2q); both need 4q < 2^32.  Two stages are taken per trip
-// through LDS (four values per thread in registers), a single one when the number of stages is odd.
-// The "lazy" transforms leave the last reduction (and, for the inverse, the factor N^-1) to the caller,
-// who applies finish_forward / finish_inverse to each value as it consumes it.  Every thread of the
-// workgroup must call; the caller has synchronised after filling `a`, and the transforms end with a
-// barrier.
+// Negacyclic transforms, register-resident like the 64-bit ones (he_ntt_core.h: sixteen residues per thread,
+// four stages per pass, regrouping through the LDS, the same root and output order: slot j holds the value at
+// psi^(2*bitrev(j)+1)).  Harvey's lazy butterflies in 32 bits: forward values stay in [0, 4q), inverse values
+// in [0, 2q); both need 4q < 2^32, hence moduli below 2^30.  A 32-bit Shoup product is one high product and
+// two multiply-adds (y*w, then - qh*q on top of it); as in the 64-bit butterflies the forward X + W*Y comes out
+// of that chain itself.
 
-__device__ __forceinline__ void bfly32_fwd(u32& x, u32& y, uint2 w, u32 q, u32 two_q) {  // (X, Y) -> (X + W*Y, X - W*Y)
-    const u32 u = x >= two_q ? x - two_q : x;
-    const u32 v = shoup32(y, w.x, w.y, q);
-    x = u + v;
-    y = u - v + two_q;
+// x - m if that is not negative, else x, for x < 2m < 2^32 (the difference wraps to a larger number exactly when x < m)
+__device__ __forceinline__ u32 csub32(u32 x, u32 m) { return min(x, x - m); }
+
+// base + y*w - floor(y*ws / 2^32)*q modulo 2^32: congruent to base + y*w, and below base + 2q
+__device__ __forceinline__ u32 shoup32_add(u32 y, Twiddle32 t, u32 q, u32 base) {
+    const u32 qh = mul_hi32(y, t.w_shoup);
+    const u64 lo = mad_wide(y, t.w, base);
+    return (u32)mad_wide(qh, 0u - q, lo);
 }
 
-__device__ __forceinline__ void bfly32_inv(u32& x, u32& y, uint2 w, u32 q, u32 two_q) {  // (X, Y) -> (X + Y, (X - Y)*W)
+__device__ __forceinline__ void bfly32_fwd(u32& x, u32& y, Twiddle32 t, const Limb32& c) {  // (X, Y) -> (X + W*Y, X - W*Y)
+    const u32 u = csub32(x, c.two_q);
+    x = shoup32_add(y, t, c.q, u);
+    y = (u << 1) + c.two_q - x;  // U + 2q - W*Y
+}
+
+__device__ __forceinline__ void bfly32_inv(u32& x, u32& y, Twiddle32 t, const Limb32& c) {  // (X, Y) -> (X + Y, (X - Y)*W)
     const u32 s = x + y;
-    const u32 d = x - y + two_q;
-    x = s >= two_q ? s - two_q : s;
-    y = shoup32(d, w.x, w.y, q);
+    const u32 d = x + c.two_q - y;
+    x = csub32(s, c.two_q);
+    y = shoup32_add(d, t, c.q, 0);
 }
 
-__device__ __forceinline__ u32 finish_forward(u32 v, const Limb32& c) {  // [0, 4q) -> [0, q)
-    v = v >= c.two_q ? v - c.two_q : v;
-    return v >= c.q ? v - c.q : v;
-}
-
-__device__ __forceinline__ u32 finish_inverse(u32 v, const Limb32& c) {  // [0, 2q) -> times N^-1, in [0, q)
-    v = shoup32(v, c.n_inv, c.n_inv_shoup, c.q);
-    return v >= c.q ? v - c.q : v;
-}
-
-__device__ void ntt32_forward_lazy(u32* a, const uint2* tw, u32 N, const Limb32& c) {
-    const u32 q = c.q, two_q = c.two_q;
-    u32 m = 1, t = N >> 1, logt = 31 - __clz(t);
-    while (m < N) {
-        if (2 * m < N) {  // the stages with distances t and t/2
-            const u32 h = t >> 1;
-            for (u32 b = threadIdx.x; b < N / 4; b += blockDim.x) {
-                const u32 i = b >> (logt - 1), j = b & (h - 1);
-                const u32 p = (i << (logt + 1)) + j;
-                u32 x0 = a[p], x1 = a[p + h], x2 = a[p + t], x3 = a[p + t + h];
-                const uint2 w1 = tw[m + i];
-                bfly32_fwd(x0, x2, w1, q, two_q);
-                bfly32_fwd(x1, x3, w1, q, two_q);
-                bfly32_fwd(x0, x1, tw[2 * m + 2 * i], q, two_q);
-                bfly32_fwd(x2, x3, tw[2 * m + 2 * i + 1], q, two_q);
-                a[p] = x0;
-                a[p + h] = x1;
-                a[p + t] = x2;
-                a[p + t + h] = x3;
+template <int LOGN, int P, bool INVERSE>
+__device__ __forceinline__ void run_pass32(u32 (&a)[16], const PassTwiddles<LOGN, P, Twiddle32>& pt, const Limb32& c) {
+    using S = PassShape<LOGN, P>;
+#pragma unroll
+    for (int kk = 0; kk < S::NST; kk++) {
+        const int k = INVERSE ? S::NST - 1 - kk : kk;
+        const int s = 4 * P + k;         // stage
+        const int bit = S::NST - 1 - k;  // register-index bit that the stage pairs
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) {
+            if (e & (1u << bit)) continue;
+            u32 &x = a[e], &y = a[e | (1u << bit)];
+            if constexpr (INVERSE) {
+                if (s == 0) {  // the last inverse stage, merged with the multiplication by N^-1
+                    const u32 sum = x + y, dif = x + c.two_q - y;
+                    x = shoup32_add(sum, Twiddle32{c.n_inv, c.n_inv_shoup}, c.q, 0);
+                    y = shoup32_add(dif, Twiddle32{c.w1n_inv, c.w1n_inv_shoup}, c.q, 0);
+                } else {
+                    bfly32_inv(x, y, pt.t[S::slot(k, e)], c);
+                }
+            } else {
+                bfly32_fwd(x, y, pt.t[S::slot(k, e)], c);
             }
-            m <<= 2;
-            t >>= 2;
-            logt -= 2;
-        } else {  // a last single stage (distance 1)
-            for (u32 b = threadIdx.x; b < N / 2; b += blockDim.x) {
-                u32 x = a[2 * b], y = a[2 * b + 1];
-                bfly32_fwd(x, y, tw[m + b], q, two_q);
-                a[2 * b] = x;
-                a[2 * b + 1] = y;
-            }
-            m <<= 1;
         }
-        __syncthreads();
     }
 }
 
-__device__ void ntt32_inverse_lazy(u32* a, const uint2* tw, u32 N, const Limb32& c) {
-    const u32 q = c.q, two_q = c.two_q;
-    u32 m = N >> 1, t = 1, logt = 0;  // m groups of butterflies at distance t
-    while (m >= 1) {
-        if (m >= 2) {  // the stages with distances t and 2t
-            for (u32 b = threadIdx.x; b < N / 4; b += blockDim.x) {
-                const u32 i = b >> logt, j = b & (t - 1);
-                const u32 p = (i << (logt + 2)) + j;
-                u32 x0 = a[p], x1 = a[p + t], x2 = a[p + 2 * t], x3 = a[p + 3 * t];
-                bfly32_inv(x0, x1, tw[m + 2 * i], q, two_q);
-                bfly32_inv(x2, x3, tw[m + 2 * i + 1], q, two_q);
-                const uint2 w = tw[(m >> 1) + i];
-                bfly32_inv(x0, x2, w, q, two_q);
-                bfly32_inv(x1, x3, w, q, two_q);
-                a[p] = x0;
-                a[p + t] = x1;
-                a[p + 2 * t] = x2;
-                a[p + 3 * t] = x3;
-            }
-            m >>= 2;
-            t <<= 2;
-            logt += 2;
-        } else {  // a last single stage (one group, distance N/2)
-            for (u32 b = threadIdx.x; b < N / 2; b += blockDim.x) {
-                u32 x = a[b], y = a[b + t];
-                bfly32_inv(x, y, tw[1], q, two_q);
-                a[b] = x;
-                a[b + t] = y;
-            }
-            m = 0;
-        }
-        __syncthreads();
+// Registers in pass-0 order, below 4q -> registers in last-pass order, below 4q.
+template <int LOGN>
+__device__ __forceinline__ void ntt32_forward(u32 (&a)[16], const Twiddle32* tw, u32* lds, u32 tid, const Limb32& c) {
+    using G = Geo<LOGN>;
+    static_assert(G::NPASS >= 2 && G::NPASS <= 4, "two to four passes");
+    {
+        PassTwiddles<LOGN, 0, Twiddle32> t0;
+        load_pass_twiddles<LOGN, 0>(t0, tw, tid);
+        run_pass32<LOGN, 0, false>(a, t0, c);
+    }
+    {
+        PassTwiddles<LOGN, 1, Twiddle32> t1;
+        load_pass_twiddles<LOGN, 1>(t1, tw, tid);
+        regroup<LOGN, 0, 1>(a, lds, tid);
+        run_pass32<LOGN, 1, false>(a, t1, c);
+    }
+    if constexpr (G::NPASS > 2) {
+        PassTwiddles<LOGN, 2, Twiddle32> t2;
+        load_pass_twiddles<LOGN, 2>(t2, tw, tid);
+        regroup<LOGN, 1, 2>(a, lds, tid);
+        run_pass32<LOGN, 2, false>(a, t2, c);
+    }
+    if constexpr (G::NPASS > 3) {
+        PassTwiddles<LOGN, 3, Twiddle32> t3;
+        load_pass_twiddles<LOGN, 3>(t3, tw, tid);
+        regroup<LOGN, 2, 3>(a, lds, tid);
+        run_pass32<LOGN, 3, false>(a, t3, c);
     }
 }
 
-template <bool INVERSE>
-__global__ void __launch_bounds__(1024) ntt32_rows_kernel(Limb32Table lt, u32 limbs, u32 N, u32* data, const u32* tw_all) {
+// Registers in last-pass order, below 2q -> registers in pass-0 order, below 2q, multiplied by N^-1.
+template <int LOGN>
+__device__ __forceinline__ void ntt32_inverse(u32 (&a)[16], const Twiddle32* tw, u32* lds, u32 tid, const Limb32& c) {
+    using G = Geo<LOGN>;
+    if constexpr (G::NPASS > 3) {
+        PassTwiddles<LOGN, 3, Twiddle32> t3;
+        load_pass_twiddles<LOGN, 3>(t3, tw, tid);
+        run_pass32<LOGN, 3, true>(a, t3, c);
+    }
+    if constexpr (G::NPASS > 2) {
+        PassTwiddles<LOGN, 2, Twiddle32> t2;
+        load_pass_twiddles<LOGN, 2>(t2, tw, tid);
+        if constexpr (G::NPASS > 3) regroup<LOGN, 3, 2>(a, lds, tid);
+        run_pass32<LOGN, 2, true>(a, t2, c);
+    }
+    {
+        PassTwiddles<LOGN, 1, Twiddle32> t1;
+        load_pass_twiddles<LOGN, 1>(t1, tw, tid);
+        if constexpr (G::NPASS > 2) regroup<LOGN, 2, 1>(a, lds, tid);
+        run_pass32<LOGN, 1, true>(a, t1, c);
+    }
+    {
+        PassTwiddles<LOGN, 0, Twiddle32> t0;
+        load_pass_twiddles<LOGN, 0>(t0, tw, tid);
+        regroup<LOGN, 1, 0>(a, lds, tid);
+        run_pass32<LOGN, 0, true>(a, t0, c);
+    }
+}
+
+// In-place transforms of `rows` rows of N residues, row r under limb r % limbs; a workgroup takes rows
+// blockIdx.x, blockIdx.x + gridDim.x, ... and has its next row in flight while it finishes the current one.
+template <int LOGN, bool INVERSE>
+__global__ void __launch_bounds__(Geo<LOGN>::T) ntt32_rows_kernel(Limb32Table lt, u32 limbs, u32* data, const u32* tw_all, u32 rows) {
+    using G = Geo<LOGN>;
+    constexpr int PIN = INVERSE ? G::NPASS - 1 : 0, POUT = INVERSE ? 0 : G::NPASS - 1;
     extern __shared__ u32 lds32[];
-    const size_t row_i = blockIdx.x;
-    const u32 limb = (u32)(row_i % limbs);
-    const Limb32& c = lt.c[limb];
-    u32* row = data + row_i * N;
-    const uint2* tw = reinterpret_cast<const uint2*>(tw_all) + (size_t)limb * N;
-    for (u32 k = threadIdx.x; k < N; k += blockDim.x) lds32[k] = row[k];
-    __syncthreads();
-    if (INVERSE) {
-        ntt32_inverse_lazy(lds32, tw, N, c);
-        for (u32 k = threadIdx.x; k < N; k += blockDim.x) row[k] = finish_inverse(lds32[k], c);
-    } else {
-        ntt32_forward_lazy(lds32, tw, N, c);
-        for (u32 k = threadIdx.x; k < N; k += blockDim.x) row[k] = finish_forward(lds32[k], c);
+    u32 a[16];
+    {
+        const u32* p = data + (size_t)blockIdx.x * G::N;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, PIN>(threadIdx.x, e)];
+    }
+    for (u32 row = blockIdx.x; row < rows; row += gridDim.x) {
+        const u32 tid = threadIdx.x;
+        const u32 limb = row % limbs;
+        const Limb32& c = lt.c[limb];
+        const Twiddle32* tw = reinterpret_cast<const Twiddle32*>(tw_all) + (size_t)limb * G::N;
+        u32 next[16];
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) next[e] = 0;
+        if (row + gridDim.x < rows) {  // sixteen registers: the next row travels while this one is transformed
+            const u32* p = data + (size_t)(row + gridDim.x) * G::N;
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) next[e] = p[reg_index<LOGN, PIN>(tid, e)];
+        }
+        if constexpr (INVERSE) {
+            ntt32_inverse<LOGN>(a, tw, lds32, tid, c);
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) a[e] = csub32(a[e], c.q);
+        } else {
+            ntt32_forward<LOGN>(a, tw, lds32, tid, c);
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) a[e] = csub32(csub32(a[e], c.two_q), c.q);
+        }
+        // (the next row is waited for before the stores are issued: see the 64-bit transform kernel)
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) asm volatile("" : "+v"(next[e])::"memory");
+        u32* p = data + (size_t)row * G::N;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) p[reg_index<LOGN, POUT>(tid, e)] = a[e];
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = next[e];
     }
 }
 
 // Rescale, Eq. (2) in RNS form, one workgroup per polynomial (ciphertext, component):
-//   t = (INTT(x_last) + floor(p/2)) mod p, kept in LDS for all kept limbs;
+//   t = (INTT(x_last) + floor(p/2)) mod p, sixteen residues per thread, kept in registers for all kept limbs;
 //   out_i = (x_i - NTT_i((t mod q_i) - (floor(p/2) mod q_i))) * p^-1 mod q_i.
-__global__ void __launch_bounds__(1024) rescale32_kernel(Limb32Table lt, Drop32Row drop, u32 limbs, u32 N, const u32* in, u32* out,
-                                                         const u32* tw_fwd, const u32* tw_inv) {
+// Every input row is read once and every output row written once; the row x_i is requested before the transform
+// of its correction and arrives while that runs.
+template <int LOGN>
+__global__ void __launch_bounds__(Geo<LOGN>::T) rescale32_kernel(Limb32Table lt, Drop32Row drop, u32 limbs, const u32* in, u32* out,
+                                                                  const u32* tw_fwd, const u32* tw_inv) {
+    using G = Geo<LOGN>;
+    constexpr int LAST_PASS = G::NPASS - 1;
     extern __shared__ u32 lds32[];
-    u32* trow = lds32;      // t, coefficient form, in [0, p)
-    u32* wrow = lds32 + N;  // the row being transformed
     const size_t poly = blockIdx.x;
+    const u32 tid = threadIdx.x;
     const u32 last = limbs - 1;
-    const u32* src = in + poly * limbs * N;
-    u32* dst = out + poly * (limbs - 1) * N;
+    const u32* src = in + poly * limbs * G::N;
+    u32* dst = out + poly * (limbs - 1) * G::N;
+    u32 t[16];
     {
         const Limb32& c = lt.c[last];
-        for (u32 k = threadIdx.x; k < N; k += blockDim.x) trow[k] = src[(size_t)last * N + k];
-        __syncthreads();
-        ntt32_inverse_lazy(trow, reinterpret_cast<const uint2*>(tw_inv) + (size_t)last * N, N, c);
-        // (in the loops below every thread touches only the elements k = tid mod blockDim, as here)
+        const u32* row = src + (size_t)last * G::N;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) t[e] = row[reg_index<LOGN, LAST_PASS>(tid, e)];
+        ntt32_inverse<LOGN>(t, reinterpret_cast<const Twiddle32*>(tw_inv) + (size_t)last * G::N, lds32, tid, c);
         const u32 half = c.q >> 1;
-        for (u32 k = threadIdx.x; k < N; k += blockDim.x) trow[k] = add_mod32(finish_inverse(trow[k], c), half, c.q);
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) t[e] = add_mod32(csub32(t[e], c.q), half, c.q);
     }
     for (u32 i = 0; i < last; i++) {
         const Limb32& c = lt.c[i];
         const Drop32 d = drop.d[i];
-        for (u32 k = threadIdx.x; k < N; k += blockDim.x) {
-            const u32 r = barrett64(trow[k], c);  // t mod q_i
-            wrow[k] = r >= d.half_mod ? r - d.half_mod : r + c.q - d.half_mod;
+        const u32* xrow = src + (size_t)i * G::N;
+        u32 x[16], a[16];
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) x[e] = xrow[reg_index<LOGN, LAST_PASS>(tid, e)];
+        // t < p is below 2*q_i unless p > 2*q_i (then Alg. 6 reduces it first); adding q_i - (h mod q_i) gives a
+        // value congruent to t - h and below 3*q_i, which the forward transform takes
+        const u32 minus_half = c.q - d.half_mod;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = (d.reduce ? barrett64(t[e], c) : t[e]) + minus_half;
+        ntt32_forward<LOGN>(a, reinterpret_cast<const Twiddle32*>(tw_fwd) + (size_t)i * G::N, lds32, tid, c);
+        u32* orow = dst + (size_t)i * G::N;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) {
+            const u32 corr = csub32(a[e], c.two_q);  // below 2q: x + 2q - corr is positive and below 3q < 2^32
+            const u32 v = shoup32_add(x[e] + c.two_q - corr, Twiddle32{d.p_inv, d.p_inv_shoup}, c.q, 0);
+            orow[reg_index<LOGN, LAST_PASS>(tid, e)] = csub32(v, c.q);
         }
-        __syncthreads();
-        ntt32_forward_lazy(wrow, reinterpret_cast<const uint2*>(tw_fwd) + (size_t)i * N, N, c);
-        for (u32 k = threadIdx.x; k < N; k += blockDim.x) {
-            u32 corr = wrow[k];  // below 4q
-            corr = corr >= c.two_q ? corr - c.two_q : corr;
-            const u32 v = shoup32(src[(size_t)i * N + k] + c.two_q - corr, d.p_inv, d.p_inv_shoup, c.q);  // argument below 3q < 2^32
-            dst[(size_t)i * N + k] = v >= c.q ? v - c.q : v;
-        }
-        // wrow is refilled by the next limb: each thread rewrites the elements it has just read
     }
 }
-
-// workgroup size of the transforms: two radix-4 groups per thread and trip (measured best of N/4, N/8, N/16)
-u32 transform_threads(u32 N) { return std::min<u32>(1024, N / 8); }
 
 }  // namespace
 
@@ -507,22 +554,50 @@ int launch_add32(he_ctx* ctx, u32 limbs, u32* ct, u32 n, const void* pt, int pt_
     return HE_OK;
 }
 
+template <int LOGN>
+static int launch_ntt32_t(he_ctx* ctx, u32 limbs, u32* data, u32 rows, bool inverse, hipStream_t s) {
+    using G = Geo<LOGN>;
+    const size_t lds = (size_t)G::N * sizeof(u32);
+    // as many workgroups as stay resident at once, each looping over its share of the rows
+    const u32 per_cu = (u32)std::max<size_t>(1, std::min<size_t>((160u << 10) / lds, 2048 / G::T));
+    const u32 grid = std::min<u32>(rows, 256 * per_cu);
+    if (inverse) {
+        static std::atomic<uint32_t> checked{0};
+        if (int rc = allow_dynamic_lds((const void*)ntt32_rows_kernel<LOGN, true>, lds, ctx->device, checked, true)) return rc;
+        hipLaunchKernelGGL((ntt32_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs32, limbs, data, ctx->tw32_inv, rows);
+    } else {
+        static std::atomic<uint32_t> checked{0};
+        if (int rc = allow_dynamic_lds((const void*)ntt32_rows_kernel<LOGN, false>, lds, ctx->device, checked, true)) return rc;
+        hipLaunchKernelGGL((ntt32_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs32, limbs, data, ctx->tw32_fwd, rows);
+    }
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
 int launch_ntt32(he_ctx* ctx, u32 limbs, u32* data, u32 rows, bool inverse, hipStream_t s) {
-    const size_t lds = (size_t)ctx->N * sizeof(u32);  // at most 64 KiB: the default limit
-    const u32 threads = transform_threads(ctx->N);
-    if (inverse)
-        hipLaunchKernelGGL(ntt32_rows_kernel<true>, dim3(rows), dim3(threads), lds, s, ctx->limbs32, limbs, ctx->N, data, ctx->tw32_inv);
-    else
-        hipLaunchKernelGGL(ntt32_rows_kernel<false>, dim3(rows), dim3(threads), lds, s, ctx->limbs32, limbs, ctx->N, data, ctx->tw32_fwd);
+    switch (ctx->log2N) {
+        case 10: return launch_ntt32_t<10>(ctx, limbs, data, rows, inverse, s);
+        case 11: return launch_ntt32_t<11>(ctx, limbs, data, rows, inverse, s);
+        case 12: return launch_ntt32_t<12>(ctx, limbs, data, rows, inverse, s);
+        case 13: return launch_ntt32_t<13>(ctx, limbs, data, rows, inverse, s);
+        case 14: return launch_ntt32_t<14>(ctx, limbs, data, rows, inverse, s);
+    }
+    return HE_ERR_ARG;
+}
+
+template <int LOGN>
+static int launch_rescale32_t(he_ctx* ctx, u32 limbs, const Drop32Row& row, const u32* in, u32* out, u32 n, hipStream_t s) {
+    using G = Geo<LOGN>;
+    const size_t lds = (size_t)G::N * sizeof(u32);
+    static std::atomic<uint32_t> checked{0};
+    if (int rc = allow_dynamic_lds((const void*)rescale32_kernel<LOGN>, lds, ctx->device, checked, true)) return rc;
+    hipLaunchKernelGGL((rescale32_kernel<LOGN>), dim3(n * 2), dim3(G::T), lds, s, ctx->limbs32, row, limbs, in, out, ctx->tw32_fwd,
+                       ctx->tw32_inv);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
 
 int launch_rescale32(he_ctx* ctx, u32 limbs, const u32* in, u32* out, u32 n, hipStream_t s) {
-    const size_t lds = (size_t)2 * ctx->N * sizeof(u32);  // up to 128 KiB
-    static std::atomic<uint32_t> lds_allowed{0};
-    if (lds > (64u << 10))
-        if (int rc = allow_dynamic_lds((const void*)rescale32_kernel, lds, ctx->device, lds_allowed)) return rc;
     Drop32Row row = {};
     const u32 last = limbs - 1;
     for (u32 i = 0; i < last; ++i) {
@@ -531,9 +606,14 @@ int launch_rescale32(he_ctx* ctx, u32 limbs, const u32* in, u32* out, u32 n, hip
         row.d[i].p_inv = (u32)d.p_inv;
         row.d[i].p_inv_shoup = (u32)((d.p_inv << 32) / qi);
         row.d[i].half_mod = (u32)d.half_mod;
+        row.d[i].reduce = d.reduce_mode == 2;
     }
-    hipLaunchKernelGGL(rescale32_kernel, dim3(n * 2), dim3(transform_threads(ctx->N)), lds, s, ctx->limbs32, row, limbs, ctx->N, in, out,
-                       ctx->tw32_fwd, ctx->tw32_inv);
-    HE_HIP(hipGetLastError());
-    return HE_OK;
+    switch (ctx->log2N) {
+        case 10: return launch_rescale32_t<10>(ctx, limbs, row, in, out, n, s);
+        case 11: return launch_rescale32_t<11>(ctx, limbs, row, in, out, n, s);
+        case 12: return launch_rescale32_t<12>(ctx, limbs, row, in, out, n, s);
+        case 13: return launch_rescale32_t<13>(ctx, limbs, row, in, out, n, s);
+        case 14: return launch_rescale32_t<14>(ctx, limbs, row, in, out, n, s);
+    }
+    return HE_ERR_ARG;
 }
