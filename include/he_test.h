@@ -28,6 +28,9 @@ uint64_t he_host_shoup_lazy(uint64_t y, uint64_t w, uint64_t q, int cheap_quotie
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q);
 /* The same with the kernels' final step: (sum + addend) mod q for an addend below q (the bias of Alg. 4). */
 uint64_t he_host_mac_accumulate_add(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
+/* The unreduced result that the MAC of a fused layer (he_ct_pt_mac with HE_RESCALE) leaves for the rescale kernel:
+ * congruent to (sum of x[t]*w[t] + addend) modulo q and below 12q, for an addend below 2q. */
+uint64_t he_host_mac_accumulate_lazy(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
 /* The three-product (Karatsuba) form of the MAC terms that the 16-output kernel uses on limbs that leave room
  * for it: the number of terms such sums can take for modulus q (0: the form is not used for q), and
  * (sum of x[t]*w[t] + addend) mod q computed that way for n terms (UINT64_MAX if n exceeds that number). */
@@ -38,6 +41,16 @@ uint64_t he_host_mac_accumulate_three_products(const uint64_t* x, const uint64_t
  * 32-bit y. */
 uint32_t he_host_barrett64(uint64_t z, uint32_t q);
 uint32_t he_host_shoup32(uint32_t y, uint32_t w, uint32_t q);
+
+/*
+ * The first kernel launches of he_ct_pt_mac(..., HE_RESCALE) on their own, for timing the two halves of a fused layer
+ * separately: acc_out dev [n_out][2][limbs][N] receives the accumulators (sums + bias) as the fused call leaves them in
+ * its workspace, where the kept limbs of scalar-plaintext sums are congruent to the result but not reduced below
+ * the modulus; he_rescale(limbs, acc_out, ...) then yields what the fused call yields.  workspace: as for
+ * he_ct_pt_mac with flags = 0.
+ */
+int he_test_mac_for_rescale(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_t* ct_in, const uint64_t* pt, int pt_kind,
+                            const uint64_t* bias, uint64_t* acc_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Measurement aid, not part of the compute path: the rate (operations per second, whole GPU) at

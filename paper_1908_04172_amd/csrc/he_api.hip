@@ -337,6 +337,12 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
         ctx->psi[i] = h_min_psi(moduli[i], N);
         if (!ctx->psi[i]) { delete ctx; return HE_ERR_MODULUS; }
         fill_limb_const(ctx->limbs.c[i], ctx->q[i], ctx->psi[i], N);
+        {   // x + cap - correction in the rescale's combine step must fit 64 bits for x below 12q, where cap bounds the
+            // transformed correction: (3 + 4 log2 N) q in butterfly mode 2, 4q in mode 1, 2q in mode 0
+            LimbConst& c = ctx->limbs.c[i];
+            const u128 cap_q = c.ntt_mode == 2 ? 3 + 4 * log2N : c.ntt_mode == 1 ? 4 : 2;
+            c.mac_lazy = (12 + cap_q) * (u128)c.q < ((u128)1 << 64);
+        }
         if (ctx->q[i] < (1ull << 30)) {  // the limb has a packed 32-bit form
             Limb32& c = ctx->limbs32.c[i];
             const u64 q = ctx->q[i], n_inv = ctx->limbs.c[i].n_inv;
@@ -655,10 +661,27 @@ int he_ct_pt_mac(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_
     hipStream_t s = (hipStream_t)stream;
     if (flags & HE_RESCALE) {
         u64* acc = (u64*)ws;
-        if ((rc = launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, acc, wtab, 0, s)) != HE_OK) return rc;
+        if ((rc = launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, acc, wtab, MAC_FOR_RESCALE, s)) != HE_OK) return rc;
         return launch_rescale(ctx, limbs, acc, ct_out, plan->n_out, s);
     }
-    return launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, wtab, (flags & HE_ACCUMULATE) ? 1u : 0u, s);
+    return launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, ct_out, wtab, (flags & HE_ACCUMULATE) ? MAC_ACCUMULATE : 0u, s);
+}
+
+// The first half of he_ct_pt_mac(HE_RESCALE) on its own (he_test.h): the accumulators as the fused call leaves them for
+// the rescale kernel.  Same checks as the fused call, by way of it.
+int he_test_mac_for_rescale(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_t* ct_in, const uint64_t* pt, int pt_kind,
+                            const uint64_t* bias, uint64_t* acc_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!ctx || !plan || plan->ctx != ctx) return HE_ERR_ARG;
+    size_t need = 0;
+    int rc = he_plan_workspace_bytes(plan, limbs, pt_kind, 0, &need);
+    if (rc != HE_OK) return rc;
+    if (limbs < 2) return HE_ERR_LEVEL;
+    if (plan->n_out == 0) return HE_OK;
+    if (!acc_out || (plan->n_terms && (!ct_in || !pt))) return HE_ERR_ARG;
+    if (need && (!workspace || workspace_bytes < need)) return HE_ERR_WORKSPACE;
+    if ((rc = check_mac_launch(ctx, plan, limbs, pt_kind)) != HE_OK) return rc;
+    if ((rc = need_device(ctx)) != HE_OK) return rc;
+    return launch_mac(ctx, plan, limbs, ct_in, pt, pt_kind, bias, acc_out, (u64*)workspace, MAC_FOR_RESCALE, (hipStream_t)stream);
 }
 
 int he_ct_pt_mac_static(he_ctx* ctx, const he_plan* plan, uint32_t limbs, const uint64_t* ct_in, const uint64_t* pt,
@@ -924,6 +947,26 @@ int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double
 
 uint64_t he_host_mac_accumulate(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q) {
     return he_host_mac_accumulate_add(x, w, n, q, 0);
+}
+
+// The unreduced result that a fused layer's MAC hands to its rescale kernel: congruent to sum + addend, below 12q.
+uint64_t he_host_mac_accumulate_lazy(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend) {
+    const LimbConst c = host_const(q);
+    MacAcc a;
+    acc_clear(a);
+    u32 f = 0, r = 0;
+    for (size_t t = 0; t < n; ++t) {
+        u32 xa, xb, wa, wb;
+        split_operand(x[t], c, xa, xb);
+        split_operand(w[t], c, wa, wb);
+        acc_mac(a, xa, xb, wa, wb);
+        ++f;
+        ++r;
+        if (r + 1 > c.reduce_every) { acc_restart(a, c); r = 0; f = 0; }
+        else if (f + 1 > c.fold_every) { acc_fold(a, c); f = 0; }
+    }
+    if (c.narrow && c.ntt_mode >= 1) return acc_reduce_add_lazy(a, addend, c);
+    return acc_reduce_lazy(a, addend, c);
 }
 
 uint64_t he_host_mac_accumulate_add(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend) {

@@ -28,7 +28,8 @@ struct LimbConst {
     u32 ntt_mode;     // how lazily the butterflies reduce: 0 for q >= 2^61, 1 for q >= 2^58, else 2 (see the butterflies at the end of this file)
     u64 neg_two_q, four_q, neg_four_q;  // 2^64 - 2q, 4q mod 2^64, 2^64 - 4q (4q is used only when it fits)
     u32 kara_terms;   // MAC terms whose three-product sums (see acc_uncross) fit 64 bits and the one-word Barrett; 0: never
-    u32 pad;
+    u32 mac_lazy;     // 1: the rescale kernel can combine a MAC result that is only congruent to the sum and below 12q
+                      // with its transformed correction without leaving 64 bits (depends on q, the butterfly mode and N)
 };
 
 HE_HD u64 mul_hi64(u64 a, u64 b) {
@@ -266,6 +267,42 @@ HE_HD u64 acc_reduce_add(MacAcc a, u64 addend, const LimbConst& c) {
     r = sub_if_ge(r, c.neg_four_q);
     r = sub_if_ge(r, c.neg_two_q);
     return sub_if_ge(r, 0 - c.q);
+}
+
+// The sums taken to a value that is only CONGRUENT to (accumulated value + addend) modulo q and lies below 12q,
+// for limbs with LimbConst::narrow set and an addend below 2q: what the MAC leaves for the rescale kernel, which
+// takes any representative that small (see LimbConst::mac_lazy).  The sums are used as they are, not folded:
+// with b the bit length of q and s the cut, x1 = (hi << (2s-b+1)) + (mid >> (b-1-s)) + (lo >> (b-1)) is
+// floor(value / 2^(b-1)) or up to 2 less and fits 64 bits; the one-word Barrett quotient of acc_reduce_add from
+// it is short of the true quotient by at most 3 + 3 + 2, so the remainder, taken modulo 2^64 from the low word
+// lo + (mid << s) + (hi << 2s) with the addend as the start of the multiply-add chain, is below 9q + 2q.
+HE_HD u64 acc_reduce_add_lazy(const MacAcc& a, u64 addend, const LimbConst& c) {
+    const u32 s = c.split_bits, sh = c.mu_shift;
+    const u64 x1 = (a.hi << (2 * s - sh)) + (a.mid >> (sh - s)) + (a.lo >> sh);
+    const u32 xl = (u32)x1, xh = (u32)(x1 >> 32), ml = (u32)c.mu, mh = (u32)(c.mu >> 32);
+    const u64 qe = (u64)xh * mh + mul_hi32(xl, mh) + mul_hi32(xh, ml);
+    const u64 low_word = a.lo + (a.mid << s) + (a.hi << (2 * s)) + addend;
+    const u64 nq = 0 - c.q;
+    const u32 n0 = (u32)nq, n1 = (u32)(nq >> 32), e0 = (u32)qe, e1 = (u32)(qe >> 32);
+    u64 cross = mad_wide(e0, n1, 0);
+    cross = mad_wide(e1, n0, cross);
+    const u64 low = (u64)e0 * n0 + low_word;
+    u32 top = (u32)(low >> 32) + (u32)cross;
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("" : "+v"(top));
+#endif
+    return ((u64)top << 32) | (u32)low;
+}
+
+// The same for the other limbs: the 128-bit Barrett remainder before its conditional subtractions, below 4q,
+// plus the addend (below 2q): below 6q.
+HE_HD u64 acc_reduce_lazy(MacAcc a, u64 addend, const LimbConst& c) {
+    acc_fold(a, c);
+    const u32 s2 = 2 * c.split_bits;
+    const u64 lo = a.lo | (a.mid << c.split_bits) | (a.hi << s2);
+    const u64 hi = a.hi >> (64 - s2);
+    const u64 qe = hi * c.ratio_hi + mul_hi64(lo, c.ratio_hi) + mul_hi64(hi, c.ratio_lo);
+    return lo - qe * c.q + addend;
 }
 
 HE_HD void acc_restart(MacAcc& a, const LimbConst& c) {  // reduce in place and keep accumulating

@@ -132,6 +132,12 @@ inline int allow_dynamic_lds(const void* kernel, size_t bytes, int device, std::
     return HE_OK;
 }
 
+// `accumulate` argument of the MAC launchers and kernels: bits
+enum : u32 {
+    MAC_ACCUMULATE = 1,   // add the canonical residues that the output holds (HE_ACCUMULATE)
+    MAC_FOR_RESCALE = 2   // the output is the accumulator tensor of a fused layer, read next by the rescale kernel: the
+                          // kept limbs of scalar-plaintext sums may be left unreduced (LimbConst::mac_lazy)
+};
 int check_mac_launch(he_ctx* ctx, const he_plan* plan, u32 limbs, int pt_kind);
 int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, const u64* pt, int pt_kind,
                const u64* bias, u64* out, u64* wtab, u32 accumulate, hipStream_t s);

@@ -180,28 +180,55 @@ __device__ __forceinline__ const u64* input_at(const u64* x_base, u32 ct, u32 ct
 // Final reduction, bias (Alg. 4, component 0 only) and store of one group of outputs; the cheaper
 // reduction where it applies, chosen once so that the per-output code has no branch.  The group's
 // bias residues come in with one load (lane g of every wave fetches output g's) and are handed out
-// with lane reads, so the outputs do not each wait for a load of their own.  accumulate: the canonical
-// residue already at the output's place is added as well (HE_ACCUMULATE); the branch is uniform.
+// with lane reads, so the outputs do not each wait for a load of their own.  mode & MAC_ACCUMULATE: the canonical
+// residue already at the output's place is added as well (HE_ACCUMULATE); the branches on `mode` are uniform.
 template <int G>
 __device__ __forceinline__ void store_group(MacAcc (&acc)[G], u32 out0, u32 count, const LimbConst& c, const u64* bias, u32 comp,
-                                            u32 limb, u32 limbs, u32 N, u32 n, u64* out, u32 accumulate) {
+                                            u32 limb, u32 limbs, u32 N, u32 n, u64* out, u32 mode) {
     const u32 lane = threadIdx.x % 64;
     u64 bias_lane = 0;
     if (bias != nullptr && comp == 0 && lane < count) bias_lane = bias[(size_t)(out0 + lane) * limbs + limb];
     u64* dst = out + (((size_t)out0 * 2 + comp) * limbs + limb) * N + n;
     const size_t out_stride = (size_t)2 * limbs * N;
+    const bool add_old = mode & MAC_ACCUMULATE;
+    // MAC_FOR_RESCALE: the output is the accumulator tensor that the rescale kernel reads next.  Its kept limbs
+    // need not be canonical there (LimbConst::mac_lazy): the final conditional subtractions, the folding of the
+    // sums and the exact quotient are left out, which is most of this step (about 20 vector instructions per
+    // output instead of about 70; with the short sums of a convolution window that is a third of the kernel).
+    const bool lazy = (mode & MAC_FOR_RESCALE) && limb + 1 < limbs && c.mac_lazy;
+    auto bias_of = [&](int g) -> u64 {
+        return (u64)(u32)__builtin_amdgcn_readlane((int)(u32)bias_lane, g) |
+               ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(bias_lane >> 32), g) << 32);
+    };
     if (c.narrow && c.ntt_mode >= 1) {
         // the constants of the reduction, fetched once and held in registers for all the outputs (left
         // to itself the compiler fetches them again for every output, and waits each time)
         LimbConst k = c;
         asm volatile("" : "+s"(k.q), "+s"(k.mu), "+s"(k.neg_four_q), "+s"(k.neg_two_q), "+s"(k.split_mask), "+s"(k.split_bits), "+s"(k.mu_shift));
+        if (lazy) {
+#pragma unroll
+            for (int g = 0; g < G; g++) {
+                if ((u32)g < count) {
+                    dst[g * out_stride] = acc_reduce_add_lazy(acc[g], bias_of(g), k);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int g = 0; g < G; g++) {
             if ((u32)g < count) {
-                u64 b = (u64)(u32)__builtin_amdgcn_readlane((int)(u32)bias_lane, g) |
-                        ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(bias_lane >> 32), g) << 32);
-                if (accumulate) b = add_mod(b, dst[g * out_stride], k.q);
+                u64 b = bias_of(g);
+                if (add_old) b = add_mod(b, dst[g * out_stride], k.q);
                 dst[g * out_stride] = acc_reduce_add(acc[g], b, k);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else if (lazy) {
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            if ((u32)g < count) {
+                dst[g * out_stride] = acc_reduce_lazy(acc[g], bias_of(g), c);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -209,9 +236,8 @@ __device__ __forceinline__ void store_group(MacAcc (&acc)[G], u32 out0, u32 coun
 #pragma unroll
         for (int g = 0; g < G; g++) {
             if ((u32)g < count) {
-                u64 b = (u64)(u32)__builtin_amdgcn_readlane((int)(u32)bias_lane, g) |
-                        ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(bias_lane >> 32), g) << 32);
-                if (accumulate) b = add_mod(b, dst[g * out_stride], c.q);
+                u64 b = bias_of(g);
+                if (add_old) b = add_mod(b, dst[g * out_stride], c.q);
                 dst[g * out_stride] = add_mod(acc_reduce(acc[g], c), b, c.q);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -623,7 +649,7 @@ mac_scalar_single_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 
         ulonglong2 v;
         v.x = add_mod(acc_reduce(acc[s][0], c), bv, c.q);
         v.y = add_mod(acc_reduce(acc[s][1], c), bv, c.q);
-        if (accumulate) {
+        if (accumulate & MAC_ACCUMULATE) {
             const ulonglong2 old = dst[s * MAC_THREADS + threadIdx.x];
             v.x = add_mod(v.x, old.x, c.q);
             v.y = add_mod(v.y, old.y, c.q);
@@ -708,7 +734,7 @@ mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, 
             v1.x = acc_reduce(acc[4 * g + 2], c);
             v1.y = acc_reduce(acc[4 * g + 3], c);
             u64* dst = out + ((size_t)o * 2 * limbs + limb) * N + n;
-            if (accumulate) {
+            if (accumulate & MAC_ACCUMULATE) {
                 const ulonglong2 o0 = *reinterpret_cast<const ulonglong2*>(dst), o1 = *reinterpret_cast<const ulonglong2*>(dst + comp_stride);
                 v0.x = add_mod(v0.x, o0.x, c.q);
                 v0.y = add_mod(v0.y, o0.y, c.q);

@@ -30,7 +30,7 @@ EXPORTS = [
     "he_encode_vector", "he_decode_vector",
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_mac_static", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_check_reduced", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
-    "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_measure_rate",
+    "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_host_mac_accumulate_lazy", "he_test_mac_for_rescale", "he_measure_rate",
     "he_host_barrett64", "he_host_shoup32", "he_host_mac_three_product_terms", "he_host_mac_accumulate_three_products", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
 ]
 
@@ -78,6 +78,8 @@ def lib():
         "he_host_shoup_lazy": (u64, [u64, u64, u64, ctypes.c_int]),
         "he_host_mac_accumulate_add": (u64, [vp, vp, sz, u64, u64]),
         "he_measure_rate": (i32, [vp, i32, u32, u32, ctypes.POINTER(ctypes.c_double)]),
+        "he_host_mac_accumulate_lazy": (u64, [vp, vp, sz, u64, u64]),
+        "he_test_mac_for_rescale": (i32, [vp, vp, u32, vp, vp, i32, vp, vp, vp, sz, vp]),
         "he_host_mac_accumulate": (u64, [vp, vp, sz, u64]),
         "he_square_relin_workspace_bytes": (i32, [vp, u32, u32, ctypes.POINTER(sz)]),
         "he_ct_square_relin": (i32, [vp, u32, vp, u32, vp, vp, vp, sz, vp]),
@@ -284,6 +286,19 @@ class Context:
         return out
 
 
+    def mac_for_rescale(self, plan: "Plan", ct_in, pt, pt_kind: int, out, bias=None, workspace=None):
+        """he_test_mac_for_rescale: the accumulators of a fused layer, as its rescale kernel receives them."""
+        import torch
+        limbs = ct_in.shape[2]
+        assert tuple(out.shape) == (plan.n_out, 2, limbs, self.N)
+        need = plan.workspace_bytes(limbs, pt_kind, 0)
+        if workspace is None and need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=ct_in.device)
+        _check(lib().he_test_mac_for_rescale(self._h, plan._h, limbs, _dev_ptr(ct_in, "ct_in"), _dev_ptr(pt, "pt"), pt_kind,
+                                             _dev_ptr(bias, "bias"), _dev_ptr(out, "acc_out"), _dev_ptr(workspace, "workspace"),
+                                             0 if workspace is None else workspace.numel(), _stream()), "he_test_mac_for_rescale")
+        return out
+
     def ct_pt_mac_static(self, plan: "Plan", ct_in, pt, pt_kind: int, out, bias=None, flags: int = 0):
         """he_ct_pt_mac_static: the same operation on the library's fixed scratch array; the caller brings the output."""
         limbs = ct_in.shape[2]
@@ -456,6 +471,12 @@ def host_barrett64(z: int, q: int) -> int:
 
 def host_shoup32(y: int, w: int, q: int) -> int:
     return int(lib().he_host_shoup32(y, w, q))
+
+
+def host_mac_accumulate_lazy(x, w, q: int, addend: int = 0) -> int:
+    x, w = _np64(x), _np64(w)
+    assert x.size == w.size
+    return int(lib().he_host_mac_accumulate_lazy(x.ctypes.data, w.ctypes.data, x.size, q, addend))
 
 
 def host_mac_accumulate(x, w, q: int, addend: int = 0) -> int:

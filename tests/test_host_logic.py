@@ -81,6 +81,20 @@ def test_mac_accumulator_fold_and_reduce_schedule():
                     assert he.host_mac_accumulate(x, w, q, b) == (want + b) % q, (q, n, mode, b)
 
 
+def test_unreduced_mac_result_is_congruent_and_small():
+    """What the MAC of a fused layer hands to the rescale kernel on kept limbs: congruent to sum + addend, below 12q."""
+    rnd = random.Random(14)
+    for q in primes():
+        for n in (0, 1, 2, 5, 12, 27, 28, 64, 255, 845, 4096, 9000):
+            for mode in ("max", "rand"):
+                x = [q - 1] * n if mode == "max" else [rnd.randrange(q) for _ in range(n)]
+                w = [q - 1] * n if mode == "max" else [rnd.randrange(q) for _ in range(n)]
+                for addend in (0, q - 1, 2 * q - 1, rnd.randrange(2 * q)):
+                    got = he.host_mac_accumulate_lazy(x, w, q, addend)
+                    assert got % q == (sum(a * b for a, b in zip(x, w)) + addend) % q, (q, n, mode)
+                    assert got < 12 * q, (q, n, mode, got // q)
+
+
 def test_context_validates_moduli():
     N = 1 << 12
     good = wl.modulus_chain([30, 30], N)
