@@ -220,30 +220,43 @@ __global__ void __launch_bounds__(256) encode_kernel(LimbTable lt, const double*
     for (u32 i = 0; i < limbs; ++i) out[j * limbs + i] = tmp[i];
 }
 
-// Alg. 4 / Alg. 3: component 0 of every ciphertext gets the plaintext added.  A thread handles two
-// adjacent residues (16-byte accesses); grid = ct * limbs * N/2 threads.
+// Alg. 4 / Alg. 3: component 0 of every ciphertext gets the plaintext added.  A thread handles ADD_UNROLL pairs of
+// adjacent residues (16-byte accesses, a workgroup's accesses contiguous), all loaded before the first is stored, so
+// that a wave has several requests in flight; total = ct * limbs * N/2 pairs.
+constexpr u32 ADD_UNROLL = 4;
 template <bool POLY>
 __global__ void __launch_bounds__(256) add_kernel(LimbTable lt, u32 limbs, u32 N, u64* ct, size_t n_ct, const u64* pt) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // pair index
     const size_t half = N / 2;
     const size_t total = n_ct * limbs * half;
-    if (i >= total) return;
-    const size_t k2 = i % half;
-    const size_t row = i / half;  // ct * limbs + limb
-    const u32 limb = (u32)(row % limbs);
-    const size_t c_idx = row / limbs;
-    const u64 q = lt.c[limb].q;
-    ulonglong2* p = reinterpret_cast<ulonglong2*>(ct + ((c_idx * 2) * limbs + limb) * N) + k2;
-    ulonglong2 v = *p;
-    ulonglong2 a;
-    if constexpr (POLY) {
-        a = reinterpret_cast<const ulonglong2*>(pt + row * N)[k2];
-    } else {
-        a.x = a.y = pt[row];
+    const size_t first = (size_t)blockIdx.x * (256 * ADD_UNROLL) + threadIdx.x;
+    ulonglong2* p[ADD_UNROLL];
+    ulonglong2 v[ADD_UNROLL], a[ADD_UNROLL];
+    u64 q[ADD_UNROLL];
+#pragma unroll
+    for (u32 u = 0; u < ADD_UNROLL; u++) {
+        const size_t i = first + (size_t)u * 256;  // pair index
+        p[u] = nullptr;
+        if (i >= total) continue;
+        const size_t k2 = i % half;
+        const size_t row = i / half;  // ct * limbs + limb
+        const u32 limb = (u32)(row % limbs);
+        const size_t c_idx = row / limbs;
+        q[u] = lt.c[limb].q;
+        p[u] = reinterpret_cast<ulonglong2*>(ct + ((c_idx * 2) * limbs + limb) * N) + k2;
+        v[u] = *p[u];
+        if constexpr (POLY) {
+            a[u] = reinterpret_cast<const ulonglong2*>(pt + row * N)[k2];
+        } else {
+            a[u].x = a[u].y = pt[row];
+        }
     }
-    v.x = add_mod(v.x, a.x, q);
-    v.y = add_mod(v.y, a.y, q);
-    *p = v;
+#pragma unroll
+    for (u32 u = 0; u < ADD_UNROLL; u++) {
+        if (p[u] == nullptr) continue;
+        v[u].x = add_mod(v[u].x, a[u].x, q[u]);
+        v[u].y = add_mod(v[u].y, a[u].y, q[u]);
+        *p[u] = v[u];
+    }
 }
 
 // he_check_reduced: residues of data [rows][limbs][row_len] that are not below their limb's modulus, counted
@@ -706,7 +719,7 @@ int he_ct_pt_add(he_ctx* ctx, uint32_t limbs, uint64_t* ct, uint32_t n, const ui
     if (!ct || !pt) return HE_ERR_ARG;
     if ((rc = need_device(ctx)) != HE_OK) return rc;
     const size_t total = (size_t)n * limbs * (ctx->N / 2);
-    const size_t blocks = (total + 255) / 256;
+    const size_t blocks = (total + 256 * ADD_UNROLL - 1) / (256 * ADD_UNROLL);
     if (blocks > 0x7FFFFFFFull) return HE_ERR_RANGE;
     if (pt_kind == HE_PT_POLY)
         hipLaunchKernelGGL(add_kernel<true>, dim3((u32)blocks), dim3(256), 0, (hipStream_t)stream, ctx->limbs, limbs, ctx->N,

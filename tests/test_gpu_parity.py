@@ -709,6 +709,36 @@ def test_config5_full_poly_layer_sampled_outputs(he):
     assert torch.equal(ctx.rescale(acc), out)
 
 
+def test_fused_layer_accumulators_are_congruent_and_rescale_to_the_layer(he):
+    """The accumulators a fused layer hands from its MAC to its rescale kernel (kept limbs of scalar-plaintext sums
+    are left unreduced): congruent to the oracle's sums modulo every limb, canonical on the dropped limb, below 12q,
+    and he_rescale of them is the fused call's output and the oracle's layer.  Chains with 62-, 60-, 57-, 50-, 40- and
+    30-bit limbs: every reduction path."""
+    for log2N, bits in ((11, [62, 60, 57, 50, 40, 30]), (13, [60, 40, 40, 40])):
+        N = 1 << log2N
+        q = wl.modulus_chain(bits, N)
+        ctx = he.Context(log2N, q)
+        plan = wl.conv_plan(7, 7, 3, 3, 3, 16, 2, "same")           # windows of 27, 18 and 12 terms, 16 outputs each
+        hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+        ct = wl.uniform_residues((plan.n_in, 2), q, N, 181)
+        w = wl.uniform_residues((plan.n_pt,), q, 1, 182)[..., 0]
+        b = wl.uniform_residues((plan.n_out,), q, 1, 183)[..., 0]
+        w[:16] = np.array(q, dtype=np.uint64) - 1                    # extreme operands in the first window
+        ct[:3] = (np.array(q, dtype=np.uint64) - 1)[None, None, :, None]
+        acc = torch.empty((plan.n_out, 2, len(q), N), dtype=torch.int64, device="cuda")
+        ctx.mac_for_rescale(hp, dev(ct), dev(w), he.PT_SCALAR, acc, bias=dev(b))
+        want = oracle.mac(ct, q, plan.off, plan.term_ct, plan.term_pt, w, oracle.PT_SCALAR, b)
+        got = host(acc)
+        qa = np.array(q, dtype=np.uint64)[None, None, :, None]
+        assert np.array_equal(got % qa, want)
+        assert np.array_equal(got[:, :, -1], want[:, :, -1])          # the dropped limb is canonical
+        assert np.all(got < 12 * qa.astype(object))
+        fused = ctx.ct_pt_mac(hp, dev(ct), dev(w), he.PT_SCALAR, bias=dev(b), flags=he.RESCALE)
+        assert torch.equal(ctx.rescale(acc), fused)
+        layer, _ = oracle.layer(ct, q, ctx.psi, plan.off, plan.term_ct, plan.term_pt, w, oracle.PT_SCALAR, b)
+        assert np.array_equal(host(fused), layer)
+
+
 def test_two_chained_layers_with_depth_aware_encoding(he):
     # Sec. "Depth-aware Encoding": the second layer runs one level down, its weights encoded at that level
     N = 1 << 12
