@@ -366,6 +366,7 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
             c.w1n_inv = (u32)ctx->limbs.c[i].w1n_inv;
             c.w1n_inv_shoup = (u32)((ctx->limbs.c[i].w1n_inv << 32) / q);
             c.ratio = (u64)((((u128)1) << 64) / q);
+            c.pow48 = (u32)((1ull << 48) % q);
             c.ok = 1;
         }
     }

@@ -35,7 +35,7 @@ struct Limb32 {
     u32 w1n_inv, w1n_inv_shoup;  // (psi^-brv(1)) * N^-1 and its companion: the last inverse butterfly merged with N^-1
     u64 ratio;                   // floor(2^64 / q): the Barrett ratio of Alg. 6
     u32 ok;                      // 1 if this limb's modulus is below 2^30 (else the limb has no 32-bit form)
-    u32 pad;
+    u32 pow48;                   // 2^48 mod q: what the part of a MAC sum above bit 48 is folded back with
 };
 struct Limb32Table {
     Limb32 c[HE_MAX_LIMBS];

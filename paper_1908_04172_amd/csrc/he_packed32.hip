@@ -13,7 +13,12 @@
 
 namespace {
 
-constexpr u32 TERMS_PER_REDUCTION = 15;  // r + 15 * (2^30 - 1)^2 < 2^64 for r < 2^30
+constexpr u32 TERMS_PER_REDUCTION = 15;  // r + 15 * (2^30 - 1)^2 < 2^64 for r < 2^49
+
+// Between two runs of TERMS_PER_REDUCTION terms a sum is not reduced modulo q but folded at bit 48: the part above
+// (16 bits) times 2^48 mod q goes back onto the part below, which leaves a congruent value below 2^48 + 2^46 for
+// three instructions instead of the dozen of Alg. 6; the one reduction at the end takes any 64-bit value.
+__device__ __forceinline__ u64 fold48(u64 z, const Limb32& c) { return (u64)(u32)(z >> 48) * c.pow48 + (z & 0xFFFFFFFFFFFFull); }
 
 __device__ __forceinline__ u32 barrett64(u64 z, const Limb32& c) { return ::barrett64(z, c.q, c.ratio); }
 
@@ -56,27 +61,36 @@ __global__ void __launch_bounds__(256) unpack32_kernel(const u32* in, u64* out, 
 constexpr u32 MAC32_THREADS = 256;
 constexpr u32 MAC32_SLICE = 2 * MAC32_THREADS;  // residues of a row one workgroup covers (two per thread)
 
-// wtab32[limb*wtab_elems + wbase + t*G + g] = pt[term_pt[off[out0+g] + t]][limb] for g < count, else 0: the
-// scalar plaintexts of a group laid out in the order the MAC loop reads them (the plan's table offsets
-// are shared with the 64-bit path; groups with the same plaintext indices share a table).
+constexpr u32 GATHER32_BLOCKS = 16;  // workgroups that share the gathering of one group's table
+constexpr u32 MAC32_BLOCK = 4;  // terms per unrolled block; an input is requested a block before its use
+__host__ __device__ inline u32 padded_terms32(u32 n_terms) { return (n_terms + MAC32_BLOCK - 1) / MAC32_BLOCK * MAC32_BLOCK; }
+
+// wtab32[limb*wtab_elems + wbase + t*G + g] = pt[term_pt[off[out0+g] + t]][limb] for g < count and t < n_terms, else 0,
+// for t up to n_terms rounded up to whole blocks: the scalar plaintexts of a group laid out in the order the MAC
+// loop reads them (the plan's table offsets are shared with the 64-bit path, whose entries are larger; groups with
+// the same plaintext indices share a table).
 template <int G>
 __global__ void __launch_bounds__(256) gather_weights32_kernel(const Tile* tiles, const u64* wbase, const u32* wowner, u32 n_tiles,
                                                                u32 limbs, const u32* off, const u32* term_pt, const u64* pt,
                                                                u32* wtab, u64 wtab_elems) {
-    const u32 tile_i = blockIdx.x;
+    const u32 tile_i = blockIdx.x / GATHER32_BLOCKS, sub = blockIdx.x % GATHER32_BLOCKS;
     if (tile_i >= n_tiles || !wowner[tile_i]) return;
     const Tile tile = tiles[tile_i];
-    const u64 per_limb = (u64)tile.n_terms * G;
+    const u64 per_limb = (u64)padded_terms32(tile.n_terms) * G;
     u32* dst = wtab + wbase[tile_i];
-    for (u64 i = threadIdx.x; i < per_limb * limbs; i += blockDim.x) {
+    for (u64 i = (u64)sub * blockDim.x + threadIdx.x; i < per_limb * limbs; i += (u64)GATHER32_BLOCKS * blockDim.x) {
         const u32 limb = (u32)(i / per_limb);
         const u64 rem = i % per_limb;
         const u32 t = (u32)(rem / G), g = (u32)(rem % G);
-        dst[(u64)limb * wtab_elems + rem] = g < tile.count ? (u32)pt[(size_t)term_pt[off[tile.out0 + g] + t] * limbs + limb] : 0;
+        dst[(u64)limb * wtab_elems + rem] =
+            g < tile.count && t < tile.n_terms ? (u32)pt[(size_t)term_pt[off[tile.out0 + g] + t] * limbs + limb] : 0;
     }
 }
 
-// One thread = two adjacent residues of one (component, limb) row x a group of G outputs.
+// One thread = two adjacent residues of one (component, limb) row x a group of G outputs.  Terms run in blocks of
+// four (the terms that pad a group to whole blocks have zero weights and the last real term's input again); a ring
+// of four inputs keeps each request a whole block of multiply-adds ahead of its use, and a term's G weights are
+// requested (scalar loads) while the term before is multiplied.
 template <int G>
 __global__ void __launch_bounds__(MAC32_THREADS)
 mac_scalar32_kernel(Limb32Table lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, const u64* wbase, const u32* term_ct,
@@ -98,38 +112,41 @@ mac_scalar32_kernel(Limb32Table lt, u32 limbs, u32 N, const Tile* tiles, u32 n_t
     u64 acc[G][2];
 #pragma unroll
     for (int g = 0; g < G; g++) acc[g][0] = acc[g][1] = 0;
-    u32 since = 0;
-    // the next term's input and weights are requested before this term's multiply-adds, so that the loads
-    // (the weights of a dense layer miss the scalar cache) are in flight while those run
-    uint2 x_next = make_uint2(0, 0);
-    u32 w_next[G];
-#pragma unroll
-    for (int g = 0; g < G; g++) w_next[g] = 0;
     if (K > 0) {
-        x_next = x_base[(size_t)uniform_load(tc) * ct_pairs];
+        const u32 Kp = padded_terms32(K), last = K - 1;
+        uint2 xq[MAC32_BLOCK];
+#pragma unroll
+        for (u32 j = 0; j < MAC32_BLOCK; j++) xq[j] = x_base[(size_t)uniform_load(tc + min(j, last)) * ct_pairs];
+        u32 w_next[G];
 #pragma unroll
         for (int g = 0; g < G; g++) w_next[g] = uniform_load(w + g);
-    }
-    for (u32 t = 0; t < K; ++t) {
-        const uint2 x = x_next;
-        u32 wv[G];
+        u32 since = 0;
+        for (u32 t = 0; t < Kp; t += MAC32_BLOCK) {
 #pragma unroll
-        for (int g = 0; g < G; g++) wv[g] = w_next[g];
-        const u32 tn = min(t + 1, K - 1);  // the last term asks for itself again: a repeat that is never used
-        x_next = x_base[(size_t)uniform_load(tc + tn) * ct_pairs];
+            for (u32 j = 0; j < MAC32_BLOCK; j++) {
+                const uint2 x = xq[j];
+                xq[j] = x_base[(size_t)uniform_load(tc + min(t + MAC32_BLOCK + j, last)) * ct_pairs];
+                u32 wv[G];
 #pragma unroll
-        for (int g = 0; g < G; g++) w_next[g] = uniform_load(w + (size_t)tn * G + g);
+                for (int g = 0; g < G; g++) wv[g] = w_next[g];
+                // (after the last term this reads the entry that follows the group's table: another table or the
+                // padding at the end of the limb's part; never used)
 #pragma unroll
-        for (int g = 0; g < G; g++) {
-            acc[g][0] += (u64)x.x * wv[g];
-            acc[g][1] += (u64)x.y * wv[g];
-        }
-        if (++since == TERMS_PER_REDUCTION && t + 1 < K) {
-            since = 0;
+                for (int g = 0; g < G; g++) w_next[g] = uniform_load(w + (size_t)(t + j + 1) * G + g);
 #pragma unroll
-            for (int g = 0; g < G; g++) {
-                acc[g][0] = barrett64(acc[g][0], c);
-                acc[g][1] = barrett64(acc[g][1], c);
+                for (int g = 0; g < G; g++) {
+                    acc[g][0] += (u64)x.x * wv[g];
+                    acc[g][1] += (u64)x.y * wv[g];
+                }
+            }
+            since += MAC32_BLOCK;
+            if (since + MAC32_BLOCK > TERMS_PER_REDUCTION && t + MAC32_BLOCK < Kp) {
+                since = 0;
+#pragma unroll
+                for (int g = 0; g < G; g++) {
+                    acc[g][0] = fold48(acc[g][0], c);
+                    acc[g][1] = fold48(acc[g][1], c);
+                }
             }
         }
     }
@@ -197,8 +214,8 @@ mac_poly32_kernel(Limb32Table lt, u32 limbs, u32 N, const Tile* tiles, u32 n_til
 #pragma unroll
             for (int g = 0; g < G; g++)
                 for (int k = 0; k < 2; k++) {
-                    acc[g][k][0] = barrett64(acc[g][k][0], c);
-                    acc[g][k][1] = barrett64(acc[g][k][1], c);
+                    acc[g][k][0] = fold48(acc[g][k][0], c);
+                    acc[g][k][1] = fold48(acc[g][k][1], c);
                 }
         }
     }
@@ -490,7 +507,7 @@ static int launch_scalar32_class(he_ctx* ctx, const he_plan* plan, int cls, u32 
     if (count == 0) return HE_OK;
     const Tile* tiles = plan->tiles_s_dev + begin;
     const u64* wbase = plan->wbase_s_dev + begin;
-    hipLaunchKernelGGL((gather_weights32_kernel<G>), dim3(count), dim3(256), 0, s, tiles, wbase, plan->wowner_s_dev + begin, count, limbs,
+    hipLaunchKernelGGL((gather_weights32_kernel<G>), dim3(count * GATHER32_BLOCKS), dim3(256), 0, s, tiles, wbase, plan->wowner_s_dev + begin, count, limbs,
                        plan->off_dev, plan->term_pt_dev, pt, wtab, plan->wtab_elems);
     HE_HIP(hipGetLastError());
     const u64 blocks = (u64)count * limbs * 2 * (ctx->N / MAC32_SLICE);
@@ -520,6 +537,7 @@ int check_mac32_launch(he_ctx* ctx, const he_plan* plan, u32 limbs, int pt_kind)
         const u64 count = pt_kind == HE_PT_SCALAR ? plan->class_begin_s[cls + 1] - plan->class_begin_s[cls]
                                                   : plan->class_begin_p[cls + 1] - plan->class_begin_p[cls];
         if (count * limbs * (pt_kind == HE_PT_SCALAR ? 2 : 1) * (ctx->N / MAC32_SLICE) > 0x7FFFFFFFull) return HE_ERR_RANGE;
+        if (pt_kind == HE_PT_SCALAR && count * GATHER32_BLOCKS > 0x7FFFFFFFull) return HE_ERR_RANGE;
     }
     return HE_OK;
 }
