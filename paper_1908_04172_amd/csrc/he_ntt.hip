@@ -1,13 +1,10 @@
-// Negacyclic NTT / INTT and the rescale of Eq. (2) for gfx950.
+// Negacyclic NTT / INTT and the rescale of Eq. (2) for gfx950, 64-bit residues.
 //
-// One workgroup transforms one polynomial limb (N residues).  Each of the T = N/16 threads keeps
-// 16 residues in registers and runs up to four butterfly stages on them (a "pass") before the
-// workgroup regroups the residues through LDS for the next pass.  Stage s (s = 0 .. log2N-1) pairs
-// indices that differ in bit log2N-1-s, so pass p owns index bits [log2N-1-4p .. log2N-4-4p]; the
-// last pass owns what is left at the bottom (1..4 stages) plus, to fill its 16 registers, the top
-// bits again, so that consecutive threads hold consecutive short runs and global stores stay dense.
-// Butterflies are Harvey's lazy ones (values in [0,4q) forward, [0,2q) inverse) with Shoup
-// multiplication by precomputed twiddles psi^bitrev(k); moduli are below 2^62, so 4q fits 64 bits.
+// One workgroup transforms one polynomial limb (N residues), sixteen residues per thread in registers, four
+// butterfly stages per pass, regrouping through the LDS between passes: geometry, regrouping and twiddle loading
+// are in he_ntt_core.h (shared with the packed 32-bit kernels); this file has the 64-bit butterfly passes and the
+// kernels built from them.  Butterflies are Harvey's lazy ones with Shoup multiplication by precomputed twiddles
+// psi^bitrev(k), in the laziness mode the limb's modulus leaves room for (he_arith.h); moduli are below 2^62.
 #include <algorithm>
 
 #include "he_internal.h"
