@@ -36,6 +36,13 @@ uint64_t he_host_mac_accumulate_lazy(const uint64_t* x, const uint64_t* w, size_
  * (sum of x[t]*w[t] + addend) mod q computed that way for n terms (UINT64_MAX if n exceeds that number). */
 uint32_t he_host_mac_three_product_terms(uint64_t q);
 uint64_t he_host_mac_accumulate_three_products(const uint64_t* x, const uint64_t* w, size_t n, uint64_t q, uint64_t addend);
+/* The forward negacyclic transform as the kernels run it on double-precision FMAs for moduli below 2^50 (the same
+ * inline butterfly and reductions, compiled for the host; works on a host-only context): in host [N], integers of
+ * magnitude at most q standing for residues of limb `limb`; out host [N], the canonical residues of the transform
+ * (the order of he_ntt).  *max_over_q (may be NULL) receives the largest |value| / q that any butterfly produced.
+ * HE_ERR_MODULUS if the limb's modulus is 2^50 or more, HE_ERR_RANGE if an input exceeds q in magnitude or an
+ * intermediate value was not an integer below 2^53 (which the bounds the kernels rely on exclude). */
+int he_host_ntt_forward_fp64(he_ctx* ctx, uint32_t limb, const int64_t* in, uint64_t* out, double* max_over_q);
 /* The two primitives of the packed 32-bit path, for q in [2, 2^30): BarrettReduction64 (Alg. 6), z mod q for
  * any 64-bit z; and the lazy 32-bit Shoup product, congruent to y*w mod q and in [0, 2q), for w < q and any
  * 32-bit y. */

@@ -160,6 +160,9 @@ void fill_limb_const(LimbConst& c, u64 q, u64 psi, u32 N) {
         if (c.narrow) c.reduce_every = (u32)std::min<u128>(c.reduce_every, lim);
     }
     c.ntt_mode = q < (1ull << 58) ? 2 : q < (1ull << 61) ? 1 : 0;
+    c.fp_ok = q < (1ull << 50);
+    c.pad = 0;
+    c.q_inv_f = 1.0 / (double)q;  // (a double holds q exactly; the division rounds to nearest)
     // three products per MAC term: the sum of (xa+xb)*(wa+wb) must fit 64 bits with xa+xb, wa+wb below 2^32,
     // and the total must stay within the one-word Barrett of acc_reduce_add (narrow limbs below 2^61)
     c.kara_terms = 0;
@@ -379,6 +382,7 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
             d.p_inv_shoup = h_shoup(d.p_inv, qi);
             d.half_mod = (p >> 1) % qi;
             d.reduce_mode = p <= qi ? 0 : (p <= 2 * qi ? 1 : 2);
+            d.fp64 = ctx->limbs.c[i].fp_ok && d.reduce_mode <= 1;
         }
     if (device >= 0) {
         int rc = need_device(ctx);
@@ -397,6 +401,20 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
                 pw = h_mulmod(pw, psi, q);
                 pwi = h_mulmod(pwi, psi_inv, q);
             }
+        }
+        // the forward twiddles as centred doubles, for the limbs whose transform can run on doubles
+        std::vector<double> fwd_f((size_t)L * N, 0.0);
+        for (u32 i = 0; i < L; ++i) {
+            if (!ctx->limbs.c[i].fp_ok) continue;
+            const u64 q = ctx->q[i];
+            for (size_t k = 0; k < N; ++k) {
+                const u64 w = fwd[((size_t)i * N + k) * 2];
+                fwd_f[(size_t)i * N + k] = w > q / 2 ? -(double)(q - w) : (double)w;
+            }
+        }
+        if (upload(&ctx->tw_fwd_f, fwd_f.data(), fwd_f.size()) != HE_OK) {
+            he_ctx_destroy(ctx);
+            return HE_ERR_DEVICE;
         }
         // 32-bit tables for the limbs that have a packed form (moduli below 2^30), zeros for the others
         std::vector<u32> fwd32((size_t)L * N * 2, 0), inv32((size_t)L * N * 2, 0);
@@ -459,6 +477,7 @@ int he_ctx_destroy(he_ctx* ctx) {
     if (ctx->device >= 0 && hipSetDevice(ctx->device) == hipSuccess) {
         if (ctx->tw_fwd) (void)hipFree(ctx->tw_fwd);
         if (ctx->tw_inv) (void)hipFree(ctx->tw_inv);
+        if (ctx->tw_fwd_f) (void)hipFree(ctx->tw_fwd_f);
         if (ctx->fft_tw) (void)hipFree(ctx->fft_tw);
         if (ctx->twist) (void)hipFree(ctx->twist);
         if (ctx->garner) (void)hipFree(ctx->garner);
@@ -1024,5 +1043,54 @@ uint64_t he_host_mac_accumulate_three_products(const uint64_t* x, const uint64_t
 }
 
 uint32_t he_host_mac_three_product_terms(uint64_t q) { return host_const(q).kara_terms; }
+
+// The double-precision forward transform (bfly_fwd_f, fp_reduce, the reduction points of ntt_forward_f) run on the
+// host, stage by stage in the textbook loop order.
+int he_host_ntt_forward_fp64(he_ctx* ctx, uint32_t limb, const int64_t* in, uint64_t* out, double* max_over_q) {
+    if (!ctx || !in || !out || limb >= ctx->L) return HE_ERR_ARG;
+    const LimbConst& c = ctx->limbs.c[limb];
+    if (!c.fp_ok) return HE_ERR_MODULUS;
+    const u32 N = ctx->N, log2N = ctx->log2N;
+    const u64 q = c.q;
+    const double qf = (double)q, q_inv = c.q_inv_f;
+    std::vector<double> tw(N), a(N);
+    {
+        u64 pw = 1;
+        for (u32 k = 0; k < N; ++k) {
+            tw[h_bitrev(k, log2N)] = pw > q / 2 ? -(double)(q - pw) : (double)pw;
+            pw = h_mulmod(pw, ctx->psi[limb], q);
+        }
+    }
+    double worst = 0.0;
+    bool exact = true;
+    auto seen = [&](double v) {
+        worst = std::max(worst, std::fabs(v) / qf);
+        exact = exact && std::fabs(v) < 9007199254740992.0 && v == std::nearbyint(v);
+    };
+    for (u32 j = 0; j < N; ++j) {
+        if ((u64)std::llabs(in[j]) > q) return HE_ERR_RANGE;
+        a[j] = (double)in[j];
+    }
+    const u32 npass = (log2N + 3) / 4, rem = log2N - 4 * (npass - 1);
+    for (u32 s = 0; s < log2N; ++s) {
+        const u32 pass = s / 4;
+        if (s % 4 == 0 && pass > 0 && !(pass == npass - 1 && pass >= 2 && rem <= 2))
+            for (u32 j = 0; j < N; ++j) a[j] = fp_reduce(a[j], qf, q_inv);
+        const u32 m = 1u << s, t = N >> (s + 1);
+        for (u32 i = 0; i < m; ++i)
+            for (u32 j = 2 * i * t; j < 2 * i * t + t; ++j) {
+                bfly_fwd_f(a[j], a[j + t], TwiddleF{tw[m + i]}, qf, q_inv);
+                seen(a[j]);
+                seen(a[j + t]);
+            }
+    }
+    for (u32 j = 0; j < N; ++j) {
+        const double y = fp_reduce(a[j], qf, q_inv);
+        const int64_t yi = (int64_t)(__builtin_bit_cast(u64, y + HE_FP_MAGIC) - __builtin_bit_cast(u64, HE_FP_MAGIC));
+        out[j] = yi < 0 ? (u64)(yi + (int64_t)q) : (u64)yi;
+    }
+    if (max_over_q) *max_over_q = worst;
+    return exact ? HE_OK : HE_ERR_RANGE;
+}
 
 }  // extern "C"

@@ -30,6 +30,9 @@ struct LimbConst {
     u32 kara_terms;   // MAC terms whose three-product sums (see acc_uncross) fit 64 bits and the one-word Barrett; 0: never
     u32 mac_lazy;     // 1: the rescale kernel can combine a MAC result that is only congruent to the sum and below 12q
                       // with its transformed correction without leaving 64 bits (depends on q, the butterfly mode and N)
+    u32 fp_ok;        // 1: q < 2^50, the forward transform can run on double-precision FMAs (see bfly_fwd_f)
+    u32 pad;
+    double q_inv_f;   // 1 / q, rounded to nearest
 };
 
 HE_HD u64 mul_hi64(u64 a, u64 b) {
@@ -383,3 +386,42 @@ __device__ __forceinline__ void bfly_inv(u64& x, u64& y, Twiddle t, const LimbCo
         y = shoup_mul_lazy4(d, t.w, t.w_shoup, c.q);
     }
 }
+
+// ---------------------------------------------------------------------------------------------
+// Forward butterflies on double-precision FMAs, for moduli below 2^50 (LimbConst::fp_ok).
+//
+// A residue is held as a double whose value is an integer congruent to it, of either sign and of magnitude below
+// 2^53, so every value, sum and difference below is exact.  The product W*Y is taken as h + l (the rounded
+// product and, by one FMA, its rounding error), the quotient k = rint(h / q) from a rounded multiply by 1/q, and
+// h - k*q (one FMA: the true value is an integer below 2^53 in magnitude, hence exact) plus l is congruent to W*Y.
+// With |W| <= q/2 (the table holds the centred twiddles) and |Y| <= B*q, the estimate of W*Y/q is off by at most
+// 3 roundings of 2^-53 relative to a value below B*q/2 < B*2^49, that is by less than 0.1875*B, so the result r
+// has |r| <= (0.5 + 0.1875*B) * q.  A butterfly therefore takes values bounded by B*q to values bounded by
+// (0.5 + 1.1875*B) * q: from B = 1, four stages end below 4.63q; from B = 0.5 (after fp_reduce), four stages end
+// below 3.64q, six below 6.22q, seven below 7.88q -- all below 2^53 for q < 2^50.  (The bound on r uses exactness,
+// not the other way round: h - k*q + l is W*Y - k*q whatever k is, as long as it stays below 2^53.)
+struct TwiddleF {
+    double w;  // the twiddle's representative in (-q/2, q/2)
+};
+
+HE_HD double fp_rint(double v) { return __builtin_rint(v); }
+HE_HD double fp_fma(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
+// x - q * rint(x / q): congruent to x, magnitude at most q/2 up to the rounding of x / q (below 0.5001 q)
+HE_HD double fp_reduce(double x, double q, double q_inv) { return fp_fma(-fp_rint(x * q_inv), q, x); }
+
+// (X, Y) -> (X + W*Y, X - W*Y), each congruent modulo q to the true value
+HE_HD void bfly_fwd_f(double& x, double& y, TwiddleF t, double q, double q_inv) {
+    const double h = t.w * y;
+    const double l = fp_fma(t.w, y, -h);
+    const double k = fp_rint(h * q_inv);
+    const double r = fp_fma(-k, q, h) + l;
+    y = x - r;
+    x = x + r;
+}
+
+// 1.5 * 2^52: adding it to an integer-valued double of magnitude below 2^51 puts that integer, as a two's
+// complement offset, into the low mantissa bits
+#define HE_FP_MAGIC 6755399441055744.0
+// a double holding the integer v < 2^52, from OR-ing it into the mantissa of 2^52
+HE_HD double fp_from_u52(u64 v) { return __builtin_bit_cast(double, v | 0x4330000000000000ull) - 4503599627370496.0; }

@@ -18,7 +18,7 @@ struct DropConst {
     u64 p_inv, p_inv_shoup;  // q_j^-1 mod q_i and its Shoup companion
     u64 half_mod;            // floor(q_j / 2) mod q_i
     u32 reduce_mode;         // a value below q_j is below q_i already (0), after one subtraction (1), or needs a full reduction (2)
-    u32 pad;
+    u32 fp64;                // 1: q_i < 2^50 and q_j <= 2*q_i: the correction's transform runs on doubles (ntt_forward_f)
 };
 
 // The constants of one dropped limb against every kept limb, passed to the rescale kernel by value
@@ -59,6 +59,7 @@ struct he_ctx {
     // device tables
     u64* tw_fwd;      // [L][N][2]: (psi^brv(k), Shoup companion), k in [0, N)
     u64* tw_inv;      // [L][N][2]: (psi^-brv(k), Shoup companion)
+    double* tw_fwd_f; // [L][N]: psi^brv(k) as the double in (-q/2, q/2), for limbs below 2^50 (LimbConst::fp_ok), else zeros
     double* fft_tw;   // [N/4][2]: e^(-2 pi i k / (N/2)), the twiddles of the encoder's complex FFT
     double* twist;    // [N/2][2]: e^(-i pi j / N), the twist that follows it
     u64* garner;      // [L][L][2]: (q_k^-1 mod q_i, Shoup companion) at [i][k], for the decoder's lift

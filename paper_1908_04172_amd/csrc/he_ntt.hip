@@ -92,6 +92,51 @@ __device__ __forceinline__ u64 ntt_forward_any(u64 (&a)[16], const u64* tw, u64*
     return 2 * c.two_q;
 }
 
+// The forward transform on double-precision FMAs, for limbs with LimbConst::fp_ok (see bfly_fwd_f): registers in
+// pass-0 order holding integers of magnitude at most q -> registers in last-pass order, magnitude below 6.22q
+// (3.64q when the last pass has four stages).  The values are brought back to q/2 before every pass but the
+// first and, when it has at most two stages and a full pass before it, the last: at most six stages run between
+// two reductions.
+template <int LOGN, int P>
+__device__ __forceinline__ void run_pass_f(double (&a)[16], const PassTwiddles<LOGN, P, TwiddleF>& pt, double q, double q_inv) {
+    using S = PassShape<LOGN, P>;
+#pragma unroll
+    for (int k = 0; k < S::NST; k++) {
+        const int bit = S::NST - 1 - k;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) {
+            if (e & (1u << bit)) continue;
+            bfly_fwd_f(a[e], a[e | (1u << bit)], pt.t[S::slot(k, e)], q, q_inv);
+        }
+    }
+}
+
+template <int LOGN, int P>
+__device__ __forceinline__ void pass_f(double (&a)[16], const TwiddleF* tw, double* lds, u32 tid, double q, double q_inv) {
+    using G = Geo<LOGN>;
+    constexpr bool KEEP = P == 0 || (P == G::NPASS - 1 && P >= 2 && G::REM <= 2);  // no reduction before this pass
+    PassTwiddles<LOGN, P, TwiddleF> t;
+    load_pass_twiddles<LOGN, P, TwiddleF>(t, tw, tid);
+    if constexpr (P > 0) regroup<LOGN, P - 1, P>(a, lds, tid);
+    if constexpr (!KEEP) {
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = fp_reduce(a[e], q, q_inv);
+    }
+    run_pass_f<LOGN, P>(a, t, q, q_inv);
+}
+
+template <int LOGN>
+__device__ __forceinline__ void ntt_forward_f(double (&a)[16], const double* tw, double* lds, u32 tid, const LimbConst& c) {
+    using G = Geo<LOGN>;
+    static_assert(G::NPASS >= 2 && G::NPASS <= 4, "two to four passes");
+    const double q = (double)c.q, q_inv = c.q_inv_f;
+    const TwiddleF* t = reinterpret_cast<const TwiddleF*>(tw);
+    pass_f<LOGN, 0>(a, t, lds, tid, q, q_inv);
+    pass_f<LOGN, 1>(a, t, lds, tid, q, q_inv);
+    if constexpr (G::NPASS > 2) pass_f<LOGN, 2>(a, t, lds, tid, q, q_inv);
+    if constexpr (G::NPASS > 3) pass_f<LOGN, 3>(a, t, lds, tid, q, q_inv);
+}
+
 // Registers in last-pass order, canonical -> registers in pass-0 order, below 2q, multiplied by N^-1.
 template <int LOGN, int MODE>
 __device__ __forceinline__ void ntt_inverse(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
@@ -256,7 +301,7 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
 template <int LOGN, bool SPLIT>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
 rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, u64* out, const u64* tw_fwd,
-               const u64* tw_inv) {
+               const u64* tw_inv, const double* tw_fwd_f) {
     using G = Geo<LOGN>;
     extern __shared__ __align__(16) u64 lds[];
     // A polynomial is handled by `parts` workgroups when there are too few polynomials to fill the
@@ -301,15 +346,6 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, 
         const DropConst& d = drop.d[i];
         const u64* xrow = src + (size_t)i * G::N;
         u64* orow = dst + (size_t)i * G::N;
-        // t < p is below 2*q_i unless p > 2*q_i (then a full reduction comes first); adding q_i - (h mod q_i)
-        // gives a value congruent to t - h and below 3*q_i, which the forward transform takes as it is
-        if (d.reduce_mode == 2) {
-#pragma unroll
-            for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
-        }
-        const u64 minus_half = c.q - d.half_mod;
-#pragma unroll
-        for (u32 e = 0; e < 16; e++) a[e] += minus_half;
         // Vector loads and stores share one in-order counter per kind but complete out of order with respect
         // to each other, so a wait for a load that has stores behind it waits for the stores as well (until they
         // are acknowledged by the L2).  Hence the order below: every load the next iteration needs is issued AND
@@ -317,11 +353,34 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, 
         // loads (its first two passes' twiddles), with nothing to wait for behind the stores.
         // The transformed correction stays below `cap` (a multiple of q), so x + cap - correction is
         // positive, congruent to x - correction and fits 64 bits; the Shoup product takes it as it is.
-        u64 cap = ntt_forward_any<LOGN, 3>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
-        if (c.ntt_mode == 0) {  // 5q need not fit 64 bits, 3q does
+        u64 cap;
+        if (d.fp64) {
+            // q_i < 2^50 and p <= 2*q_i: the transform runs on doubles.  t - h as an integer lies in [-h, h],
+            // within q_i in magnitude; it is formed from t < 2^52 directly as a double.
+            const double half_f = (double)(lt.c[last].q >> 1);
+            double f[16];
 #pragma unroll
-            for (u32 e = 0; e < 16; e++) a[e] = sub_if_ge(a[e], c.neg_two_q);
-            cap = c.two_q;
+            for (u32 e = 0; e < 16; e++) f[e] = fp_from_u52(a[e]) - half_f;
+            ntt_forward_f<LOGN>(f, tw_fwd_f + (size_t)i * G::N, reinterpret_cast<double*>(lds), tid, c);
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) a[e] = __builtin_bit_cast(u64, f[e]);
+            cap = c.q + __builtin_bit_cast(u64, HE_FP_MAGIC);
+        } else {
+            // t < p is below 2*q_i unless p > 2*q_i (then a full reduction comes first); adding q_i - (h mod q_i)
+            // gives a value congruent to t - h and below 3*q_i, which the forward transform takes as it is
+            if (d.reduce_mode == 2) {
+#pragma unroll
+                for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
+            }
+            const u64 minus_half = c.q - d.half_mod;
+#pragma unroll
+            for (u32 e = 0; e < 16; e++) a[e] += minus_half;
+            cap = ntt_forward_any<LOGN, 3>(a, tw_fwd + (size_t)i * G::N * 2, lds, tid, c);
+            if (c.ntt_mode == 0) {  // 5q need not fit 64 bits, 3q does
+#pragma unroll
+                for (u32 e = 0; e < 16; e++) a[e] = sub_if_ge(a[e], c.neg_two_q);
+                cap = c.two_q;
+            }
         }
         const u32 tid_s = fresh(tid);
         u64 x[16], next[16];
@@ -332,6 +391,14 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, 
         if (i + 1 < end) {
 #pragma unroll
             for (u32 e = 0; e < 16; e++) next[e] = park[reg_index<LOGN, 0>(tid_s, e)];
+        }
+        if (d.fp64) {
+            // the transformed correction y, reduced to |y| <= q/2 + 1, as the mantissa offset of y + 1.5 * 2^52:
+            // x + (q + bits of 1.5 * 2^52) - bits of (y + 1.5 * 2^52) = x + q - y, positive and below 14q
+            const double q_f = (double)c.q;
+#pragma unroll
+            for (u32 e = 0; e < 16; e++)
+                a[e] = __builtin_bit_cast(u64, fp_reduce(__builtin_bit_cast(double, a[e]), q_f, c.q_inv_f) + HE_FP_MAGIC);
         }
 #pragma unroll
         for (u32 e = 0; e < 16; e++) x[e] = shoup_mul(x[e] + cap - a[e], d.p_inv, d.p_inv_shoup, c.q);
@@ -420,10 +487,10 @@ int launch_rescale_t(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* ou
     const u32 parts = std::max(1u, std::min(limbs - 1, resident / (2 * n)));
     if (parts > 1)
         hipLaunchKernelGGL((rescale_kernel<LOGN, true>), dim3(2 * n * parts), dim3(G::T), lds, s, lt, row, limbs, parts,
-                           in, out, ctx->tw_fwd, tw_inv);
+                           in, out, ctx->tw_fwd, tw_inv, ctx->tw_fwd_f);
     else
         hipLaunchKernelGGL((rescale_kernel<LOGN, false>), dim3(2 * n), dim3(G::T), lds, s, lt, row, limbs, 1u, in, out,
-                           ctx->tw_fwd, tw_inv);
+                           ctx->tw_fwd, tw_inv, ctx->tw_fwd_f);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }

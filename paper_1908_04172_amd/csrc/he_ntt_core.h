@@ -101,20 +101,30 @@ __device__ __forceinline__ void regroup(V (&a)[16], V* lds, u32 tid) {
     for (u32 e = 0; e < 16; e++) a[e] = *(const lds_v*)(uintptr_t)(to ^ (lds_slot(reg_index<LOGN, PTO>(0, e)) * W));
 }
 
-// Tw: the twiddle type, Twiddle (two 64-bit words) or Twiddle32 (two 32-bit words): a table entry as it is stored.
-// Tw::raw is a vector type of the same layout, through which a wave-uniform entry is read with a scalar load.
+// Tw: the twiddle type, Twiddle (two 64-bit words), Twiddle32 (two 32-bit words) or TwiddleF (one double): a table
+// entry as it is stored.  For the two-word types Tw::raw is a vector type of the same layout, through which a
+// wave-uniform entry is read with a scalar load.
 template <typename Tw, bool UNIFORM>
 __device__ __forceinline__ Tw load_twiddle(const Tw* tw, u32 k) {
-    typedef typename Tw::raw raw;
-    static_assert(sizeof(raw) == sizeof(Tw), "a table entry is a pair of words");
-    raw v;
-    if constexpr (UNIFORM) {
-        k = __builtin_amdgcn_readfirstlane(k);
-        v = *(const __attribute__((address_space(4))) raw*)(tw + k);
+    if constexpr (__is_same(Tw, TwiddleF)) {  // one double per entry
+        if constexpr (UNIFORM) {
+            k = __builtin_amdgcn_readfirstlane(k);
+            return Tw{*(const __attribute__((address_space(4))) double*)(tw + k)};
+        } else {
+            return tw[k];
+        }
     } else {
-        v = *reinterpret_cast<const raw*>(tw + k);
+        typedef typename Tw::raw raw;
+        static_assert(sizeof(raw) == sizeof(Tw), "a table entry is a pair of words");
+        raw v;
+        if constexpr (UNIFORM) {
+            k = __builtin_amdgcn_readfirstlane(k);
+            v = *(const __attribute__((address_space(4))) raw*)(tw + k);
+        } else {
+            v = *reinterpret_cast<const raw*>(tw + k);
+        }
+        return Tw{v.x, v.y};
     }
-    return Tw{v.x, v.y};
 }
 
 // Shape of pass P: its stages, and where the twiddle of (stage k, register e) sits among the

@@ -205,3 +205,42 @@ def test_three_product_mac_terms_on_the_host():
         too_many = np.zeros(cap + 1, dtype=np.uint64)
         assert he.host_mac_accumulate_three_products(too_many, too_many, q) == 2**64 - 1
     assert he.host_mac_three_product_terms(wl.ntt_primes(62, 1 << 14, 1)[0]) == 0
+
+
+@pytest.mark.parametrize("log2N,bits", [(10, 50), (11, 49), (12, 40), (13, 50), (14, 50), (14, 31)])
+def test_double_precision_forward_transform_on_the_host(log2N, bits):
+    """The forward transform on double-precision FMAs (moduli below 2^50), compiled for the host, against the oracle's
+    direct transform: inputs of either sign up to q in magnitude, extreme and random; every intermediate an exact
+    integer, and none beyond the 6.22 q that the kernels' reduction points are placed for."""
+    N = 1 << log2N
+    q = wl.ntt_primes(bits, N, 1)[0]
+    big = wl.ntt_primes(60, N, 1)[0]
+    ctx = he.Context(log2N, [big, q], device=None)
+    psi = ctx.psi[1]
+    rng = np.random.default_rng(log2N * 100 + bits)
+    cases = [rng.integers(-q, q + 1, N), np.full(N, q), np.full(N, -q), np.where(rng.integers(0, 2, N) == 1, q, -q),
+             np.where(np.arange(N) % 2 == 0, q // 2, -(q // 2)), np.zeros(N, dtype=np.int64)]
+    for k, v in enumerate(cases):
+        got, worst = ctx.host_ntt_forward_fp64(1, v)
+        want = oracle.ntt_fwd(np.mod(v, q).astype(np.uint64)[None, :], [q], [psi])[0]
+        assert np.array_equal(got, want), (log2N, bits, k)
+        assert worst < 6.22, (log2N, bits, k, worst)
+    with pytest.raises(he.HeError) as e:                       # the 60-bit limb has no such form
+        ctx.host_ntt_forward_fp64(0, np.zeros(N, dtype=np.int64))
+    assert e.value.status == -2
+    with pytest.raises(he.HeError):                            # an input beyond q in magnitude
+        ctx.host_ntt_forward_fp64(1, np.full(N, q + 1))
+
+
+def test_double_precision_butterfly_bounds():
+    """The growth bound that places the reductions of the double-precision transform: with |W| <= q/2 and
+    |Y| <= B q the quotient estimate is off by less than 0.1875 B, so a butterfly takes B to 0.5 + 1.1875 B;
+    from 1 four stages, and from 0.5001 six, stay below 2^53 / 2^50 = 8."""
+    def after(b, stages):
+        for _ in range(stages):
+            b = 0.5 + 1.1875 * b
+        return b
+    assert after(1.0, 4) < 4.63 and after(0.5001, 4) < 3.64 and after(0.5001, 6) < 6.22 and after(0.5001, 7) < 7.88
+    assert after(0.5001, 8) > 8
+    # the estimate's error: three roundings of 2^-53 on a value below B * 2^49
+    assert 3 * 2.0 ** -53 * 2.0 ** 49 == 0.1875
