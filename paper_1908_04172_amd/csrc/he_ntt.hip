@@ -192,8 +192,8 @@ __device__ __forceinline__ u64 canon4(u64 v, u64 q, u64 two_q) {  // [0,4q) -> [
 enum { ROWS_PLAIN = 0, ROWS_SPREAD = 1, ROWS_SQUARE = 2 };
 template <int LOGN, bool INVERSE, int KIND = ROWS_PLAIN>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
-ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows, const u64* spread_src = nullptr,
-                u32 digits = 1, u32 last_id = 0, u64* aux = nullptr) {
+ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const double* tw_f_all, u32 rows,
+                const u64* spread_src = nullptr, u32 digits = 1, u32 last_id = 0, u64* aux = nullptr) {
     using G = Geo<LOGN>;
     constexpr bool SPREAD = KIND == ROWS_SPREAD, SQUARE = KIND == ROWS_SQUARE;
     static_assert(!(SPREAD && INVERSE), "the digit expansion is a forward transform");
@@ -237,7 +237,9 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
         const LimbConst& c = lt.c[limb];
         // (digit expansion: the last position is the special prime, whose twiddles sit at its own limb's
         // place in the table; `lt` comes with that limb's constants at the last position)
-        const u64* tw = tw_all + (size_t)(SPREAD && limb == limbs - 1 ? last_id : limb) * G::N * 2;
+        const u32 tw_limb = SPREAD && limb == limbs - 1 ? last_id : limb;
+        const u64* tw = tw_all + (size_t)tw_limb * G::N * 2;
+        const bool fp = !INVERSE && c.fp_ok;  // the forward transform of a limb below 2^50 runs on doubles
         if constexpr (SPREAD) {
 #pragma unroll
             for (u32 e = 0; e < 16; e++) a[e] = reduce64(a[e], c);
@@ -250,8 +252,20 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
                 own[reg_index<LOGN, PIN>(tid, e)] = a[e];
             }
         }
-        if constexpr (!INVERSE) ntt_forward_any<LOGN>(a, tw, lds, tid, c);
-        else ntt_inverse_any<LOGN>(a, tw, lds, tid, c);
+        if constexpr (!INVERSE) {
+            if (fp) {
+                double f[16];
+#pragma unroll
+                for (u32 e = 0; e < 16; e++) f[e] = fp_from_u52(a[e]);
+                ntt_forward_f<LOGN>(f, tw_f_all + (size_t)tw_limb * G::N, reinterpret_cast<double*>(lds), tid, c);
+#pragma unroll
+                for (u32 e = 0; e < 16; e++) a[e] = __builtin_bit_cast(u64, f[e]);
+            } else {
+                ntt_forward_any<LOGN>(a, tw, lds, tid, c);
+            }
+        } else {
+            ntt_inverse_any<LOGN>(a, tw, lds, tid, c);
+        }
         // The next row is requested first, the last reductions of this row run while it travels, and it is
         // waited for before this row's stores are issued: a wait for loads that have stores behind them would
         // wait for the stores as well (loads and stores complete out of order with respect to each other).
@@ -265,13 +279,24 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows,
             for (u32 e = 0; e < 16; e++) next[e] = p[reg_index<LOGN, PIN>(tid_s, e)];
         }
         if constexpr (!INVERSE) {
-            if (c.ntt_mode == 2) {
-                // below 57q: a Shoup product by 1 (whose companion is floor(2^64/q)) brings it below 4q
+            if (fp) {
+                // reduced to |y| <= q/2 + 1, read as an integer off the mantissa of y + 1.5 * 2^52, made non-negative
+                const double q_f = (double)c.q;
 #pragma unroll
-                for (u32 e = 0; e < 16; e++) a[e] = shoup_mul_lazy4(a[e], 1, c.ratio_hi, c.q);
+                for (u32 e = 0; e < 16; e++) {
+                    const double y = fp_reduce(__builtin_bit_cast(double, a[e]), q_f, c.q_inv_f);
+                    const int64_t v = (int64_t)(__builtin_bit_cast(u64, y + HE_FP_MAGIC) - __builtin_bit_cast(u64, HE_FP_MAGIC));
+                    a[e] = (u64)v + ((u64)(v >> 63) & c.q);
+                }
+            } else {
+                if (c.ntt_mode == 2) {
+                    // below 57q: a Shoup product by 1 (whose companion is floor(2^64/q)) brings it below 4q
+#pragma unroll
+                    for (u32 e = 0; e < 16; e++) a[e] = shoup_mul_lazy4(a[e], 1, c.ratio_hi, c.q);
+                }
+#pragma unroll
+                for (u32 e = 0; e < 16; e++) a[e] = canon4(a[e], c.q, c.two_q);
             }
-#pragma unroll
-            for (u32 e = 0; e < 16; e++) a[e] = canon4(a[e], c.q, c.two_q);
         } else {
 #pragma unroll
             for (u32 e = 0; e < 16; e++) a[e] = a[e] >= c.q ? a[e] - c.q : a[e];
@@ -423,11 +448,11 @@ int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipS
     if (inverse) {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true>, lds, ctx->device, lds_allowed, true)) return rc;
-        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, rows);
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, ctx->tw_fwd_f, rows);
     } else {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false>, lds, ctx->device, lds_allowed, true)) return rc;
-        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd, rows);
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd, ctx->tw_fwd_f, rows);
     }
     HE_HIP(hipGetLastError());
     return HE_OK;
@@ -443,8 +468,8 @@ int launch_ntt_spread_t(he_ctx* ctx, u32 limbs, const u64* src, u64* out, u32 ro
     const u32 grid = std::min<u32>(rows, 256 * per_cu);
     static std::atomic<uint32_t> lds_allowed{0};
     if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false, ROWS_SPREAD>, lds, ctx->device, lds_allowed, true)) return rc;
-    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false, ROWS_SPREAD>), dim3(grid), dim3(G::T), lds, s, lt, limbs, out, ctx->tw_fwd, rows, src,
-                       digits, ctx->L - 1);
+    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false, ROWS_SPREAD>), dim3(grid), dim3(G::T), lds, s, lt, limbs, out, ctx->tw_fwd, ctx->tw_fwd_f,
+                       rows, src, digits, ctx->L - 1);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
@@ -459,8 +484,8 @@ int launch_ntt_square_t(he_ctx* ctx, u32 limbs, const u64* ct, u64* d2, u64* dig
     const u32 grid = std::min<u32>(rows, 256 * per_cu);
     static std::atomic<uint32_t> lds_allowed{0};
     if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true, ROWS_SQUARE>, lds, ctx->device, lds_allowed, true)) return rc;
-    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true, ROWS_SQUARE>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, d2, ctx->tw_inv, rows, ct,
-                       1u, 0u, digits);
+    hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true, ROWS_SQUARE>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, d2, ctx->tw_inv,
+                       ctx->tw_fwd_f, rows, ct, 1u, 0u, digits);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
