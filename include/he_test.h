@@ -43,6 +43,10 @@ uint64_t he_host_mac_accumulate_three_products(const uint64_t* x, const uint64_t
  * HE_ERR_MODULUS if the limb's modulus is 2^50 or more, HE_ERR_RANGE if an input exceeds q in magnitude or an
  * intermediate value was not an integer below 2^53 (which the bounds the kernels rely on exclude). */
 int he_host_ntt_forward_fp64(he_ctx* ctx, uint32_t limb, const int64_t* in, uint64_t* out, double* max_over_q);
+/* The inverse transform the same way: in host [N], canonical residues in the order of he_ntt_fwd's output; out host [N],
+ * the canonical coefficients (multiplied by N^-1).  *max_over_q: the largest |value| / q among the sums, differences
+ * and products.  Errors as above (HE_ERR_RANGE also for an input that is not below q). */
+int he_host_ntt_inverse_fp64(he_ctx* ctx, uint32_t limb, const uint64_t* in, uint64_t* out, double* max_over_q);
 /* The two primitives of the packed 32-bit path, for q in [2, 2^30): BarrettReduction64 (Alg. 6), z mod q for
  * any 64-bit z; and the lazy 32-bit Shoup product, congruent to y*w mod q and in [0, 2q), for w < q and any
  * 32-bit y. */

@@ -403,16 +403,15 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
             }
         }
         // the forward twiddles as centred doubles, for the limbs whose transform can run on doubles
-        std::vector<double> fwd_f((size_t)L * N, 0.0);
+        std::vector<double> fwd_f((size_t)L * N, 0.0), inv_f((size_t)L * N, 0.0);
         for (u32 i = 0; i < L; ++i) {
             if (!ctx->limbs.c[i].fp_ok) continue;
-            const u64 q = ctx->q[i];
             for (size_t k = 0; k < N; ++k) {
-                const u64 w = fwd[((size_t)i * N + k) * 2];
-                fwd_f[(size_t)i * N + k] = w > q / 2 ? -(double)(q - w) : (double)w;
+                fwd_f[(size_t)i * N + k] = fp_centred(fwd[((size_t)i * N + k) * 2], ctx->q[i]);
+                inv_f[(size_t)i * N + k] = fp_centred(inv[((size_t)i * N + k) * 2], ctx->q[i]);
             }
         }
-        if (upload(&ctx->tw_fwd_f, fwd_f.data(), fwd_f.size()) != HE_OK) {
+        if (upload(&ctx->tw_fwd_f, fwd_f.data(), fwd_f.size()) != HE_OK || upload(&ctx->tw_inv_f, inv_f.data(), inv_f.size()) != HE_OK) {
             he_ctx_destroy(ctx);
             return HE_ERR_DEVICE;
         }
@@ -478,6 +477,7 @@ int he_ctx_destroy(he_ctx* ctx) {
         if (ctx->tw_fwd) (void)hipFree(ctx->tw_fwd);
         if (ctx->tw_inv) (void)hipFree(ctx->tw_inv);
         if (ctx->tw_fwd_f) (void)hipFree(ctx->tw_fwd_f);
+        if (ctx->tw_inv_f) (void)hipFree(ctx->tw_inv_f);
         if (ctx->fft_tw) (void)hipFree(ctx->fft_tw);
         if (ctx->twist) (void)hipFree(ctx->twist);
         if (ctx->garner) (void)hipFree(ctx->garner);
@@ -1057,7 +1057,7 @@ int he_host_ntt_forward_fp64(he_ctx* ctx, uint32_t limb, const int64_t* in, uint
     {
         u64 pw = 1;
         for (u32 k = 0; k < N; ++k) {
-            tw[h_bitrev(k, log2N)] = pw > q / 2 ? -(double)(q - pw) : (double)pw;
+            tw[h_bitrev(k, log2N)] = fp_centred(pw, q);
             pw = h_mulmod(pw, ctx->psi[limb], q);
         }
     }
@@ -1084,11 +1084,64 @@ int he_host_ntt_forward_fp64(he_ctx* ctx, uint32_t limb, const int64_t* in, uint
                 seen(a[j + t]);
             }
     }
-    for (u32 j = 0; j < N; ++j) {
-        const double y = fp_reduce(a[j], qf, q_inv);
-        const int64_t yi = (int64_t)(__builtin_bit_cast(u64, y + HE_FP_MAGIC) - __builtin_bit_cast(u64, HE_FP_MAGIC));
-        out[j] = yi < 0 ? (u64)(yi + (int64_t)q) : (u64)yi;
+    for (u32 j = 0; j < N; ++j) out[j] = fp_to_canonical(fp_reduce(a[j], qf, q_inv), q);
+    if (max_over_q) *max_over_q = worst;
+    return exact ? HE_OK : HE_ERR_RANGE;
+}
+
+// The inverse transform the same way (bfly_inv_f, the reduction points of ntt_inverse_f).
+int he_host_ntt_inverse_fp64(he_ctx* ctx, uint32_t limb, const uint64_t* in, uint64_t* out, double* max_over_q) {
+    if (!ctx || !in || !out || limb >= ctx->L) return HE_ERR_ARG;
+    const LimbConst& c = ctx->limbs.c[limb];
+    if (!c.fp_ok) return HE_ERR_MODULUS;
+    const u32 N = ctx->N, log2N = ctx->log2N;
+    const u64 q = c.q;
+    const double qf = (double)q, q_inv = c.q_inv_f;
+    std::vector<double> tw(N), a(N);
+    {
+        const u64 psi_inv = h_powmod(ctx->psi[limb], q - 2, q);
+        u64 pw = 1;
+        for (u32 k = 0; k < N; ++k) {
+            tw[h_bitrev(k, log2N)] = fp_centred(pw, q);
+            pw = h_mulmod(pw, psi_inv, q);
+        }
     }
+    double worst = 0.0;
+    bool exact = true;
+    auto seen = [&](double v) {
+        worst = std::max(worst, std::fabs(v) / qf);
+        exact = exact && std::fabs(v) < 9007199254740992.0 && v == std::nearbyint(v);
+    };
+    for (u32 j = 0; j < N; ++j) {
+        if (in[j] >= q) return HE_ERR_RANGE;
+        a[j] = fp_reduce(fp_from_u52(in[j]), qf, q_inv);
+    }
+    const u32 npass = (log2N + 3) / 4, rem = log2N - 4 * (npass - 1);
+    const double n_inv = fp_centred(c.n_inv, q), w1n_inv = fp_centred(c.w1n_inv, q);
+    for (int s = (int)log2N - 1; s >= 0; --s) {
+        const u32 pass = (u32)s / 4, nst = pass == npass - 1 ? rem : 4, k = (u32)s % 4;
+        if (k == nst - 1 && pass < npass - 1)  // the first stage a pass runs
+            for (u32 j = 0; j < N; ++j) a[j] = fp_reduce(a[j], qf, q_inv);
+        const u32 m = 1u << s, t = N >> (s + 1);
+        for (u32 i = 0; i < m; ++i)
+            for (u32 j = 2 * i * t; j < 2 * i * t + t; ++j) {
+                if (s == 0) {
+                    const double sum = a[j] + a[j + t], dif = a[j] - a[j + t];
+                    seen(sum);
+                    seen(dif);
+                    a[j] = fp_mulmod(n_inv, sum, qf, q_inv);
+                    a[j + t] = fp_mulmod(w1n_inv, dif, qf, q_inv);
+                } else {
+                    seen(a[j] - a[j + t]);
+                    bfly_inv_f(a[j], a[j + t], TwiddleF{tw[m + i]}, qf, q_inv);
+                    seen(a[j]);
+                    if (nst == 4 && k == 2) a[j] = fp_reduce(a[j], qf, q_inv);  // the sums of the second stage run
+                }
+                seen(a[j]);
+                seen(a[j + t]);
+            }
+    }
+    for (u32 j = 0; j < N; ++j) out[j] = fp_to_canonical(fp_reduce(a[j], qf, q_inv), q);
     if (max_over_q) *max_over_q = worst;
     return exact ? HE_OK : HE_ERR_RANGE;
 }

@@ -410,14 +410,38 @@ HE_HD double fp_fma(double a, double b, double c) { return __builtin_fma(a, b, c
 // x - q * rint(x / q): congruent to x, magnitude at most q/2 up to the rounding of x / q (below 0.5001 q)
 HE_HD double fp_reduce(double x, double q, double q_inv) { return fp_fma(-fp_rint(x * q_inv), q, x); }
 
+// w * y modulo q as described above: |result| <= (0.5 + 0.1875 * B) * q for |w| <= q/2, |y| <= B * q
+HE_HD double fp_mulmod(double w, double y, double q, double q_inv) {
+    const double h = w * y;
+    const double l = fp_fma(w, y, -h);
+    const double k = fp_rint(h * q_inv);
+    return fp_fma(-k, q, h) + l;
+}
+
 // (X, Y) -> (X + W*Y, X - W*Y), each congruent modulo q to the true value
 HE_HD void bfly_fwd_f(double& x, double& y, TwiddleF t, double q, double q_inv) {
-    const double h = t.w * y;
-    const double l = fp_fma(t.w, y, -h);
-    const double k = fp_rint(h * q_inv);
-    const double r = fp_fma(-k, q, h) + l;
+    const double r = fp_mulmod(t.w, y, q, q_inv);
     y = x - r;
     x = x + r;
+}
+
+// (X, Y) -> (X + Y, (X - Y) * W).  Sums double the bound per stage, products start again below
+// (0.5 + 0.1875 * 2B) * q: from values bounded by B = 0.5001 (after fp_reduce), two stages end below 2.0005q and
+// three below 4.001q; with the sums of the second stage reduced, the fourth stage ends below 3.501q.
+HE_HD void bfly_inv_f(double& x, double& y, TwiddleF t, double q, double q_inv) {
+    const double d = x - y;
+    x = x + y;
+    y = fp_mulmod(t.w, d, q, q_inv);
+}
+
+// the representative of v < q in (-q/2, q/2), as a double (q < 2^52)
+HE_HD double fp_centred(u64 v, u64 q) { return v > q / 2 ? -(double)(int64_t)(q - v) : (double)(int64_t)v; }
+
+// the canonical residue of an integer-valued double y with |y| below 2^51 that is within q of zero: the integer
+// is read off the mantissa of y + 1.5 * 2^52, and q is added to a negative one
+HE_HD u64 fp_to_canonical(double y, u64 q) {
+    const int64_t v = (int64_t)(__builtin_bit_cast(u64, y + 6755399441055744.0) - 0x4338000000000000ull);
+    return (u64)v + ((u64)(v >> 63) & q);
 }
 
 // 1.5 * 2^52: adding it to an integer-valued double of magnitude below 2^51 puts that integer, as a two's

@@ -60,6 +60,7 @@ struct he_ctx {
     u64* tw_fwd;      // [L][N][2]: (psi^brv(k), Shoup companion), k in [0, N)
     u64* tw_inv;      // [L][N][2]: (psi^-brv(k), Shoup companion)
     double* tw_fwd_f; // [L][N]: psi^brv(k) as the double in (-q/2, q/2), for limbs below 2^50 (LimbConst::fp_ok), else zeros
+    double* tw_inv_f; // [L][N]: the same for psi^-brv(k)
     double* fft_tw;   // [N/4][2]: e^(-2 pi i k / (N/2)), the twiddles of the encoder's complex FFT
     double* twist;    // [N/2][2]: e^(-i pi j / N), the twist that follows it
     u64* garner;      // [L][L][2]: (q_k^-1 mod q_i, Shoup companion) at [i][k], for the decoder's lift

@@ -166,10 +166,73 @@ __device__ __forceinline__ void ntt_inverse(u64 (&a)[16], const u64* tw, u64* ld
     }
 }
 
+// The inverse transform on double-precision FMAs (see bfly_inv_f): registers in last-pass order, magnitude at most
+// 0.5001q -> registers in pass-0 order, multiplied by N^-1, magnitude below 1.16q (every output of the last stage
+// is a product).  The values are reduced before every pass but the first one run, and the sums of the second stage
+// of a four-stage pass are reduced again, so that no value exceeds 4.001q.
+template <int LOGN, int P>
+__device__ __forceinline__ void pass_inv_f(double (&a)[16], const TwiddleF* tw, double* lds, u32 tid, double q, double q_inv,
+                                           double n_inv, double w1n_inv) {
+    using G = Geo<LOGN>;
+    using S = PassShape<LOGN, P>;
+    PassTwiddles<LOGN, P, TwiddleF> t;
+    load_pass_twiddles<LOGN, P, TwiddleF>(t, tw, tid);
+    if constexpr (P < G::NPASS - 1) {
+        regroup<LOGN, P + 1, P>(a, lds, tid);
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = fp_reduce(a[e], q, q_inv);
+    }
+#pragma unroll
+    for (int kk = 0; kk < S::NST; kk++) {
+        const int k = S::NST - 1 - kk;
+        const int s = 4 * P + k;
+        const int bit = S::NST - 1 - k;
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) {
+            if (e & (1u << bit)) continue;
+            double& x = a[e];
+            double& y = a[e | (1u << bit)];
+            if (s == 0) {  // merged with the multiplication by N^-1
+                const double sum = x + y, dif = x - y;
+                x = fp_mulmod(n_inv, sum, q, q_inv);
+                y = fp_mulmod(w1n_inv, dif, q, q_inv);
+            } else {
+                bfly_inv_f(x, y, t.t[S::slot(k, e)], q, q_inv);
+                if (S::NST == 4 && kk == 1) x = fp_reduce(x, q, q_inv);
+            }
+        }
+    }
+}
+
 template <int LOGN>
-__device__ __forceinline__ void ntt_inverse_any(u64 (&a)[16], const u64* tw, u64* lds, u32 tid, const LimbConst& c) {
-    if (c.ntt_mode != 0) ntt_inverse<LOGN, 1>(a, tw, lds, tid, c);
-    else ntt_inverse<LOGN, 0>(a, tw, lds, tid, c);
+__device__ __forceinline__ void ntt_inverse_f(double (&a)[16], const double* tw, double* lds, u32 tid, const LimbConst& c) {
+    using G = Geo<LOGN>;
+    const double q = (double)c.q, q_inv = c.q_inv_f;
+    const double n_inv = fp_centred(c.n_inv, c.q), w1n_inv = fp_centred(c.w1n_inv, c.q);
+    const TwiddleF* t = reinterpret_cast<const TwiddleF*>(tw);
+    if constexpr (G::NPASS > 3) pass_inv_f<LOGN, 3>(a, t, lds, tid, q, q_inv, n_inv, w1n_inv);
+    if constexpr (G::NPASS > 2) pass_inv_f<LOGN, 2>(a, t, lds, tid, q, q_inv, n_inv, w1n_inv);
+    pass_inv_f<LOGN, 1>(a, t, lds, tid, q, q_inv, n_inv, w1n_inv);
+    pass_inv_f<LOGN, 0>(a, t, lds, tid, q, q_inv, n_inv, w1n_inv);
+}
+
+// The inverse transform of canonical values in the limb's form: on doubles for a limb below 2^50 (canonical
+// results), else on the integer butterflies (results below 2q).
+template <int LOGN>
+__device__ __forceinline__ void ntt_inverse_any(u64 (&a)[16], const u64* tw, const double* tw_f, u64* lds, u32 tid, const LimbConst& c) {
+    if (c.fp_ok) {
+        const double q_f = (double)c.q;
+        double f[16];
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) f[e] = fp_reduce(fp_from_u52(a[e]), q_f, c.q_inv_f);
+        ntt_inverse_f<LOGN>(f, tw_f, reinterpret_cast<double*>(lds), tid, c);
+#pragma unroll
+        for (u32 e = 0; e < 16; e++) a[e] = fp_to_canonical(fp_reduce(f[e], q_f, c.q_inv_f), c.q);
+    } else if (c.ntt_mode != 0) {
+        ntt_inverse<LOGN, 1>(a, tw, lds, tid, c);
+    } else {
+        ntt_inverse<LOGN, 0>(a, tw, lds, tid, c);
+    }
 }
 
 __device__ __forceinline__ u64 canon4(u64 v, u64 q, u64 two_q) {  // [0,4q) -> [0,q)
@@ -264,7 +327,7 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
                 ntt_forward_any<LOGN>(a, tw, lds, tid, c);
             }
         } else {
-            ntt_inverse_any<LOGN>(a, tw, lds, tid, c);
+            ntt_inverse_any<LOGN>(a, tw, tw_f_all + (size_t)tw_limb * G::N, lds, tid, c);
         }
         // The next row is requested first, the last reductions of this row run while it travels, and it is
         // waited for before this row's stores are issued: a wait for loads that have stores behind them would
@@ -280,14 +343,10 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
         }
         if constexpr (!INVERSE) {
             if (fp) {
-                // reduced to |y| <= q/2 + 1, read as an integer off the mantissa of y + 1.5 * 2^52, made non-negative
+                // reduced to |y| <= q/2 + 1, then the canonical residue
                 const double q_f = (double)c.q;
 #pragma unroll
-                for (u32 e = 0; e < 16; e++) {
-                    const double y = fp_reduce(__builtin_bit_cast(double, a[e]), q_f, c.q_inv_f);
-                    const int64_t v = (int64_t)(__builtin_bit_cast(u64, y + HE_FP_MAGIC) - __builtin_bit_cast(u64, HE_FP_MAGIC));
-                    a[e] = (u64)v + ((u64)(v >> 63) & c.q);
-                }
+                for (u32 e = 0; e < 16; e++) a[e] = fp_to_canonical(fp_reduce(__builtin_bit_cast(double, a[e]), q_f, c.q_inv_f), c.q);
             } else {
                 if (c.ntt_mode == 2) {
                     // below 57q: a Shoup product by 1 (whose companion is floor(2^64/q)) brings it below 4q
@@ -326,7 +385,7 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
 template <int LOGN, bool SPLIT>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
 rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, u64* out, const u64* tw_fwd,
-               const u64* tw_inv, const double* tw_fwd_f) {
+               const u64* tw_inv, const double* tw_fwd_f, const double* tw_inv_f) {
     using G = Geo<LOGN>;
     extern __shared__ __align__(16) u64 lds[];
     // A polynomial is handled by `parts` workgroups when there are too few polynomials to fill the
@@ -350,7 +409,7 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, 
         const u64* row = src + (size_t)last * G::N;
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = row[reg_index<LOGN, G::NPASS - 1>(tid, e)];
-        ntt_inverse_any<LOGN>(a, tw_inv + (size_t)last * G::N * 2, lds, tid, c);
+        ntt_inverse_any<LOGN>(a, tw_inv + (size_t)last * G::N * 2, tw_inv_f + (size_t)last * G::N, lds, tid, c);
         const u64 half = c.q >> 1;
         const u32 tid_s = fresh(tid);
 #pragma unroll
@@ -448,7 +507,7 @@ int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipS
     if (inverse) {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true>, lds, ctx->device, lds_allowed, true)) return rc;
-        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, ctx->tw_fwd_f, rows);
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, ctx->tw_inv_f, rows);
     } else {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false>, lds, ctx->device, lds_allowed, true)) return rc;
@@ -485,7 +544,7 @@ int launch_ntt_square_t(he_ctx* ctx, u32 limbs, const u64* ct, u64* d2, u64* dig
     static std::atomic<uint32_t> lds_allowed{0};
     if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true, ROWS_SQUARE>, lds, ctx->device, lds_allowed, true)) return rc;
     hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true, ROWS_SQUARE>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, d2, ctx->tw_inv,
-                       ctx->tw_fwd_f, rows, ct, 1u, 0u, digits);
+                       ctx->tw_inv_f, rows, ct, 1u, 0u, digits);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }
@@ -500,6 +559,7 @@ int launch_rescale_t(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* ou
     LimbTable lt = ctx->limbs;
     lt.c[limbs - 1] = ctx->limbs.c[drop_id];
     const u64* tw_inv = ctx->tw_inv + (size_t)(drop_id - (limbs - 1)) * G::N * 2;
+    const double* tw_inv_f = ctx->tw_inv_f + (size_t)(drop_id - (limbs - 1)) * G::N;
     const size_t lds = (size_t)G::N * sizeof(u64);
     static std::atomic<uint32_t> lds_allowed{0}, lds_allowed_split{0};
     if (int rc = allow_dynamic_lds((const void*)rescale_kernel<LOGN, false>, lds, ctx->device, lds_allowed, true)) return rc;
@@ -512,10 +572,10 @@ int launch_rescale_t(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* ou
     const u32 parts = std::max(1u, std::min(limbs - 1, resident / (2 * n)));
     if (parts > 1)
         hipLaunchKernelGGL((rescale_kernel<LOGN, true>), dim3(2 * n * parts), dim3(G::T), lds, s, lt, row, limbs, parts,
-                           in, out, ctx->tw_fwd, tw_inv, ctx->tw_fwd_f);
+                           in, out, ctx->tw_fwd, tw_inv, ctx->tw_fwd_f, tw_inv_f);
     else
         hipLaunchKernelGGL((rescale_kernel<LOGN, false>), dim3(2 * n), dim3(G::T), lds, s, lt, row, limbs, 1u, in, out,
-                           ctx->tw_fwd, tw_inv, ctx->tw_fwd_f);
+                           ctx->tw_fwd, tw_inv, ctx->tw_fwd_f, tw_inv_f);
     HE_HIP(hipGetLastError());
     return HE_OK;
 }

@@ -31,7 +31,7 @@ EXPORTS = [
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_mac_static", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_check_reduced", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_host_mac_accumulate_lazy", "he_test_mac_for_rescale", "he_measure_rate",
-    "he_host_barrett64", "he_host_shoup32", "he_host_mac_three_product_terms", "he_host_mac_accumulate_three_products", "he_host_ntt_forward_fp64", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
+    "he_host_barrett64", "he_host_shoup32", "he_host_mac_three_product_terms", "he_host_mac_accumulate_three_products", "he_host_ntt_forward_fp64", "he_host_ntt_inverse_fp64", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
 ]
 
 _lib = None
@@ -86,6 +86,7 @@ def lib():
         "he_host_mac_three_product_terms": (u32, [u64]),
         "he_host_mac_accumulate_three_products": (u64, [vp, vp, sz, u64, u64]),
         "he_host_ntt_forward_fp64": (i32, [vp, u32, vp, vp, ctypes.POINTER(ctypes.c_double)]),
+        "he_host_ntt_inverse_fp64": (i32, [vp, u32, vp, vp, ctypes.POINTER(ctypes.c_double)]),
         "he_host_barrett64": (u32, [u64, u32]),
         "he_host_shoup32": (u32, [u32, u32, u32]),
         "he_pack32": (i32, [vp, vp, vp, sz, vp]),
@@ -169,6 +170,17 @@ class Context:
         worst = ctypes.c_double()
         _check(lib().he_host_ntt_forward_fp64(self._h, limb, v.ctypes.data, out.ctypes.data, ctypes.byref(worst)),
                "he_host_ntt_forward_fp64")
+        return out, float(worst.value)
+
+    def host_ntt_inverse_fp64(self, limb: int, values) -> "tuple[np.ndarray, float]":
+        """he_host_ntt_inverse_fp64: canonical residues in transform order -> (canonical coefficients, largest
+        |intermediate| / q)."""
+        v = _np64(values)
+        assert v.shape == (self.N,)
+        out = np.zeros(self.N, dtype=np.uint64)
+        worst = ctypes.c_double()
+        _check(lib().he_host_ntt_inverse_fp64(self._h, limb, v.ctypes.data, out.ctypes.data, ctypes.byref(worst)),
+               "he_host_ntt_inverse_fp64")
         return out, float(worst.value)
 
     def measure_rate(self, kind: int, limb: int = 0, iters: int = 4096) -> float:

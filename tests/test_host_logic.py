@@ -225,6 +225,13 @@ def test_double_precision_forward_transform_on_the_host(log2N, bits):
         want = oracle.ntt_fwd(np.mod(v, q).astype(np.uint64)[None, :], [q], [psi])[0]
         assert np.array_equal(got, want), (log2N, bits, k)
         assert worst < 6.22, (log2N, bits, k, worst)
+    # the inverse transform: canonical inputs, extreme and random; sums, differences and products stay below 4.001 q
+    for k, v in enumerate([rng.integers(0, q, N), np.full(N, q - 1), np.where(np.arange(N) % 2 == 0, q - 1, 0),
+                           np.where(rng.integers(0, 2, N) == 1, (q - 1) // 2, (q + 1) // 2), np.zeros(N, dtype=np.int64)]):
+        v = v.astype(np.uint64)
+        got, worst = ctx.host_ntt_inverse_fp64(1, v)
+        assert np.array_equal(got, oracle.ntt_inv(v[None, :], [q], [psi])[0]), (log2N, bits, k)
+        assert worst < 4.001, (log2N, bits, k, worst)
     with pytest.raises(he.HeError) as e:                       # the 60-bit limb has no such form
         ctx.host_ntt_forward_fp64(0, np.zeros(N, dtype=np.int64))
     assert e.value.status == -2
@@ -242,5 +249,16 @@ def test_double_precision_butterfly_bounds():
         return b
     assert after(1.0, 4) < 4.63 and after(0.5001, 4) < 3.64 and after(0.5001, 6) < 6.22 and after(0.5001, 7) < 7.88
     assert after(0.5001, 8) > 8
+    # inverse butterflies: sums double, products of differences bounded by 2B start again at 0.5 + 0.375 B
+    b = 0.5001
+    sums, prods = 2 * b, 0.5 + 0.375 * b                      # first stage
+    sums, prods = 2 * max(sums, prods), 0.5 + 0.375 * max(sums, prods)
+    assert sums < 2.0005
+    three = 2 * max(sums, prods)
+    assert three < 4.001                                       # a three-stage pass ends here
+    m = max(0.5001, prods)                                     # four stages: the second stage's sums are reduced
+    sums, prods = 2 * m, 0.5 + 0.375 * m
+    m = max(sums, prods)
+    assert 2 * m < 3.501 and 0.5 + 0.375 * m < 1.16
     # the estimate's error: three roundings of 2^-53 on a value below B * 2^49
     assert 3 * 2.0 ** -53 * 2.0 ** 49 == 0.1875
