@@ -230,11 +230,14 @@ def main() -> int:
     fwd_kind = {0: he.RATE_BUTTERFLY_MODE0, 1: he.RATE_BUTTERFLY_MODE1, 2: he.RATE_BUTTERFLY_MODE2}
     bf = (N // 2) * c4.log2N
     def rescale_ideal_s(n_ct):
+        # limbs below 2^50 are transformed on double-precision FMAs (forward: when the dropped modulus is at most twice theirs)
         last = L - 1
-        inv = he.RATE_BUTTERFLY_INV if mode[last] else he.RATE_BUTTERFLY_MODE0
+        fp = [qi < (1 << 50) for qi in q]
+        inv = he.RATE_BUTTERFLY_FP64_INV if fp[last] else he.RATE_BUTTERFLY_INV if mode[last] else he.RATE_BUTTERFLY_MODE0
         per_poly = bf / rate(inv, last)
         for i in range(last):
-            per_poly += bf / rate(fwd_kind[mode[i]], i) + N / rate(he.RATE_SHOUP_EXACT, i)
+            fwd = he.RATE_BUTTERFLY_FP64 if fp[i] and q[last] <= 2 * q[i] else fwd_kind[mode[i]]
+            per_poly += bf / rate(fwd, i) + N / rate(he.RATE_SHOUP_EXACT, i)
         return 2 * n_ct * per_poly
     # the scalar MAC runs the three-product form of a term on the limbs that leave room for it
     three = [he.host_mac_three_product_terms(qi) >= max(int(x) for x in np.diff(p4.off.astype(np.int64))) for qi in q]
@@ -247,7 +250,7 @@ def main() -> int:
             r["arithmetic_ms_at_measured_rate"] = ideal[name] * 1e3
             r["frac_of_measured_rate"] = ideal[name] * 1e3 / phase_ms[name]
     names = ["mad32", "mac_term", "shoup_exact", "shoup_cheap", "butterfly_mode0", "butterfly_mode1",
-             "butterfly_mode2", "butterfly_inverse", "mac_term_three_products"]
+             "butterfly_mode2", "butterfly_inverse", "mac_term_three_products", "butterfly_fp64", "butterfly_fp64_inverse"]
     measured_rates = {"unit": "G operations/s, register-resident, whole GPU",
                       "rates": {"%s@%dbit" % (names[k], q[limb].bit_length()): v / 1e9
                                 for (k, limb), v in sorted(rate_cache.items(), reverse=True)}}

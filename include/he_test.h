@@ -80,7 +80,11 @@ enum {
     HE_RATE_BUTTERFLY_MODE1 = 5, /* forward butterfly for moduli below 2^61 */
     HE_RATE_BUTTERFLY_MODE2 = 6, /* forward butterfly for moduli below 2^58 */
     HE_RATE_BUTTERFLY_INV = 7,   /* inverse butterfly for moduli below 2^61 */
-    HE_RATE_MAC_TERM3 = 8        /* the three multiply-adds of one MAC term in the three-product form */
+    HE_RATE_MAC_TERM3 = 8,       /* the three multiply-adds of one MAC term in the three-product form */
+    HE_RATE_BUTTERFLY_FP64 = 9,  /* forward butterfly on double-precision FMAs for moduli below 2^50, with the transform's
+                                    share of reductions (both values once per four butterflies) */
+    HE_RATE_BUTTERFLY_FP64_INV = 10 /* inverse butterfly the same way (both values once per four butterflies, the sum
+                                    once more) */
 };
 int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s);
 

@@ -967,7 +967,8 @@ uint32_t he_host_shoup32(uint32_t y, uint32_t w, uint32_t q) { return shoup32(y,
 
 int he_measure_rate(he_ctx* ctx, int kind, uint32_t limb, uint32_t iters, double* ops_per_s) {
     if (!ctx || !ops_per_s || limb >= ctx->L || iters == 0 || iters > (1u << 20)) return HE_ERR_ARG;
-    if (kind < HE_RATE_MAD32 || kind > HE_RATE_MAC_TERM3) return HE_ERR_ARG;
+    if (kind < HE_RATE_MAD32 || kind > HE_RATE_BUTTERFLY_FP64_INV) return HE_ERR_ARG;
+    if ((kind == HE_RATE_BUTTERFLY_FP64 || kind == HE_RATE_BUTTERFLY_FP64_INV) && !ctx->limbs.c[limb].fp_ok) return HE_ERR_MODULUS;
     if (kind == HE_RATE_MAC_TERM3 && ctx->limbs.c[limb].kara_terms == 0) return HE_ERR_MODULUS;  // the limb never takes that form
     // the lazier butterflies assume the room their modes are chosen by
     const u32 mode = ctx->limbs.c[limb].ntt_mode;

@@ -1,4 +1,4 @@
-// Register-resident rates of the library's own arithmetic on this GPU: the integer-ALU ceilings that
+// Register-resident rates of the library's own arithmetic on this GPU: the vector-ALU ceilings that
 // the kernels' throughputs are quoted against.  Each thread runs CHAINS independent dependency chains
 // of one primitive with no memory traffic inside the timed loop; the grid fills every SIMD with as
 // many waves as the real kernels keep resident.  A measurement aid: nothing on the compute path
@@ -26,6 +26,15 @@ __global__ void __launch_bounds__(THREADS) rate_kernel(LimbTable lt, u32 limb, u
         split_operand(x[i], c, xa[i], xb[i]);
     }
     const Twiddle t{w, w_shoup};
+    // operands of the double-precision butterflies
+    const double q_f = (double)c.q;
+    const TwiddleF tf{fp_centred(w % c.q, c.q)};
+    double fx[CHAINS], fy[CHAINS];
+#pragma unroll
+    for (int i = 0; i < CHAINS; i++) {
+        fx[i] = fp_centred(x[i], c.q);
+        fy[i] = fp_centred(y[i], c.q);
+    }
     const u64 below_q = (1ull << c.mu_shift) - 1;  // mu_shift = bit length of q, minus 1
     u32 wa, wb;
     split_operand(w, c, wa, wb);
@@ -69,13 +78,26 @@ __global__ void __launch_bounds__(THREADS) rate_kernel(LimbTable lt, u32 limb, u
                 bfly_fwd<2>(x[i], y[i], t, c);
             } else if constexpr (KIND == HE_RATE_BUTTERFLY_INV) {
                 bfly_inv<1>(x[i], y[i], t, c);
-            } else if constexpr (KIND == HE_RATE_MAC_TERM3) {
-                // the three-product form of a term (lo += xa*wa, mid += (xa+xb)*(wa+wb), hi += xb*wb): the sum
-                // wa + wb comes with the weights, xa + xb is one more addition per term
-                const u32 ta = (u32)acc[i].hi ^ xa[i], tb = (u32)acc[i].lo ^ xb[i];
-                acc[i].lo += (u64)ta * wa;
-                acc[i].mid += (u64)(ta + tb) * ws;
-                acc[i].hi += (u64)tb * wb;
+            } else if constexpr (KIND == HE_RATE_BUTTERFLY_FP64) {
+                bfly_fwd_f(fx[i], fy[i], tf, q_f, c.q_inv_f);
+            } else if constexpr (KIND == HE_RATE_BUTTERFLY_FP64_INV) {
+                bfly_inv_f(fx[i], fy[i], tf, q_f, c.q_inv_f);
+            }
+        }
+        if constexpr (KIND == HE_RATE_BUTTERFLY_FP64 || KIND == HE_RATE_BUTTERFLY_FP64_INV) {
+            // the reductions a transform spends on four stages: every value once, in the inverse the sums once more
+            if ((it & 3) == 3) {
+#pragma unroll
+                for (int i = 0; i < CHAINS; i++) {
+                    fx[i] = fp_reduce(fx[i], q_f, c.q_inv_f);
+                    fy[i] = fp_reduce(fy[i], q_f, c.q_inv_f);
+                }
+            }
+            if constexpr (KIND == HE_RATE_BUTTERFLY_FP64_INV) {
+                if ((it & 3) == 1) {
+#pragma unroll
+                    for (int i = 0; i < CHAINS; i++) fx[i] = fp_reduce(fx[i], q_f, c.q_inv_f);
+                }
             }
         }
         if constexpr (KIND == HE_RATE_BUTTERFLY_MODE2) {
@@ -90,7 +112,8 @@ __global__ void __launch_bounds__(THREADS) rate_kernel(LimbTable lt, u32 limb, u
     }
     u64 s = 0;
 #pragma unroll
-    for (int i = 0; i < CHAINS; i++) s += x[i] + y[i] + acc[i].lo + acc[i].mid + acc[i].hi;
+    for (int i = 0; i < CHAINS; i++)
+        s += x[i] + y[i] + acc[i].lo + acc[i].mid + acc[i].hi + __builtin_bit_cast(u64, fx[i]) + __builtin_bit_cast(u64, fy[i]);
     sink[gid] = s;
 }
 
@@ -137,6 +160,8 @@ int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s) {
         case HE_RATE_BUTTERFLY_MODE2: return run_rate<HE_RATE_BUTTERFLY_MODE2>(ctx, limb, iters, ops_per_s);
         case HE_RATE_BUTTERFLY_INV: return run_rate<HE_RATE_BUTTERFLY_INV>(ctx, limb, iters, ops_per_s);
         case HE_RATE_MAC_TERM3: return run_rate<HE_RATE_MAC_TERM3>(ctx, limb, iters, ops_per_s);
+        case HE_RATE_BUTTERFLY_FP64: return run_rate<HE_RATE_BUTTERFLY_FP64>(ctx, limb, iters, ops_per_s);
+        case HE_RATE_BUTTERFLY_FP64_INV: return run_rate<HE_RATE_BUTTERFLY_FP64_INV>(ctx, limb, iters, ops_per_s);
     }
     return HE_ERR_ARG;
 }

@@ -16,6 +16,7 @@ import numpy as np
 RATE_MAD32, RATE_MAC_TERM, RATE_SHOUP_EXACT, RATE_SHOUP_CHEAP = 0, 1, 2, 3
 RATE_BUTTERFLY_MODE0, RATE_BUTTERFLY_MODE1, RATE_BUTTERFLY_MODE2, RATE_BUTTERFLY_INV = 4, 5, 6, 7
 RATE_MAC_TERM3 = 8
+RATE_BUTTERFLY_FP64, RATE_BUTTERFLY_FP64_INV = 9, 10
 PT_SCALAR = 0
 PT_POLY = 1
 RESCALE = 1

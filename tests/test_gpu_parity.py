@@ -512,9 +512,12 @@ def test_measured_rates_are_plausible(he):
     assert b0 < b1 < b2 < mad / 4
     t4, t3 = ctx.measure_rate(he.RATE_MAC_TERM, 2, 512), ctx.measure_rate(he.RATE_MAC_TERM3, 2, 512)
     assert mad / 6 < t4 < t3 < mad / 2                                              # four and three multiply-adds per term
-    with pytest.raises(he.HeError) as e:                                            # a 60-bit limb has no mode 2
-        ctx.measure_rate(he.RATE_BUTTERFLY_MODE2, 0, 512)
-    assert e.value.status == -2
+    f_fwd, f_inv = ctx.measure_rate(he.RATE_BUTTERFLY_FP64, 2, 512), ctx.measure_rate(he.RATE_BUTTERFLY_FP64_INV, 2, 512)
+    assert b2 < f_inv < f_fwd < mad / 4                                             # the double-precision butterflies of a 50-bit limb
+    for kind in (he.RATE_BUTTERFLY_MODE2, he.RATE_BUTTERFLY_FP64, he.RATE_BUTTERFLY_FP64_INV):
+        with pytest.raises(he.HeError) as e:                                        # a 60-bit limb has no mode 2 and no double form
+            ctx.measure_rate(kind, 0, 512)
+        assert e.value.status == -2
 
 
 # ----------------------------------------------------------------------------- Eq. (2)
