@@ -1,4 +1,5 @@
-// Modular arithmetic on 64-bit residues for gfx950 integer ALUs.  Every function is
+// Modular arithmetic on 64-bit residues for gfx950's vector ALU: 32-bit integer multiply-adds, and for moduli
+// below 2^50 the double-precision FMAs of the transforms (last section).  Every function is
 // __host__ __device__ so that the host-side check entry points run exactly the code the
 // kernels run.  Moduli are primes below 2^62.
 #pragma once

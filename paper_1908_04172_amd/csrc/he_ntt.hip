@@ -5,6 +5,8 @@
 // are in he_ntt_core.h (shared with the packed 32-bit kernels); this file has the 64-bit butterfly passes and the
 // kernels built from them.  Butterflies are Harvey's lazy ones with Shoup multiplication by precomputed twiddles
 // psi^bitrev(k), in the laziness mode the limb's modulus leaves room for (he_arith.h); moduli are below 2^62.
+// A limb below 2^50 is transformed on double-precision FMAs instead (ntt_forward_f, ntt_inverse_f): eight
+// operations per butterfly, the same residues.
 #include <algorithm>
 
 #include "he_internal.h"
