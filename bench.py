@@ -369,6 +369,20 @@ def main() -> int:
                                               "pct_hbm_peak": 100 * str_bytes / (ms_str * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                               "bytes": str_bytes, "what": "1024 ciphertexts times one scalar each: 2 GiB read, 2 GiB written"}}
 
+    # ---- the two arithmetics of the transforms on the same launch: the limbs below 2^50 on double-precision FMAs (the
+    # library's choice, timed above) against integer butterflies for every limb; the residues must be the same
+    if not only:
+        ms_fp = timed(lambda: ctx.rescale(acc4, out=out4k))
+        ctx.integer_transforms(True)
+        out_int = torch.empty_like(out4k)
+        ms_int = timed(lambda: ctx.rescale(acc4, out=out_int))
+        ctx.integer_transforms(False)
+        same = bool(torch.equal(out_int, out4k))
+        del out_int
+        result["rescale_cfg4_transform_arithmetic"] = {
+            "ms_double_precision_below_2^50": ms_fp, "ms_integer_butterflies_only": ms_int, "same_residues": same,
+            "what": "he_rescale on cfg4's accumulators with he_test_integer_transforms off / on"}
+
     # ---- Alg. 1 on the GPU: the plaintext polynomials a layer like cfg5 consumes, encoded from slots
     if not only:
         n_vec = 1024
@@ -514,6 +528,9 @@ def main() -> int:
     print(json.dumps(result))
     if not same_as_one_call:
         print("bench.py: the two-call form of a layer differs from he_ct_pt_mac(HE_RESCALE)", file=sys.stderr)
+        return 3
+    if not result.get("rescale_cfg4_transform_arithmetic", {}).get("same_residues", True):
+        print("bench.py: integer and double-precision transforms disagree", file=sys.stderr)
         return 3
     if "cpu_baseline" in result and not result["cpu_baseline"]["gpu_outputs_match_oracle"]:
         print("bench.py: the timed GPU outputs differ from the oracle's", file=sys.stderr)

@@ -64,6 +64,15 @@ int he_test_mac_for_rescale(he_ctx* ctx, const he_plan* plan, uint32_t limbs, co
                             const uint64_t* bias, uint64_t* acc_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The transforms of limbs below 2^50 run on double-precision FMAs, those of larger limbs on integer butterflies; both
+ * produce the same residues.  integer_only = 1 makes every later call on this context use the integer butterflies for
+ * all limbs (for tests of those butterflies on such limbs, and for timing one arithmetic against the other);
+ * integer_only = 0 restores the state a context is created in.  Not to be called while work of this context is being
+ * enqueued from another thread.
+ */
+int he_test_integer_transforms(he_ctx* ctx, int integer_only);
+
+/*
  * Measurement aid, not part of the compute path: the rate (operations per second, whole GPU) at
  * which this device runs one of the library's arithmetic primitives on register-resident data, with
  * the constants of limb `limb` of the context.  These are the integer-ALU ceilings against which

@@ -1045,6 +1045,17 @@ uint64_t he_host_mac_accumulate_three_products(const uint64_t* x, const uint64_t
 
 uint32_t he_host_mac_three_product_terms(uint64_t q) { return host_const(q).kara_terms; }
 
+// Which arithmetic the transforms of limbs below 2^50 use from now on: integer butterflies only (1), or the
+// double-precision ones (0, the state a context is created in).
+int he_test_integer_transforms(he_ctx* ctx, int integer_only) {
+    if (!ctx) return HE_ERR_ARG;
+    for (u32 i = 0; i < ctx->L; ++i) ctx->limbs.c[i].fp_ok = !integer_only && ctx->q[i] < (1ull << 50);
+    for (u32 j = 0; j < ctx->L; ++j)
+        for (u32 i = 0; i < ctx->L; ++i)
+            if (i != j) ctx->drop[j][i].fp64 = ctx->limbs.c[i].fp_ok && ctx->drop[j][i].reduce_mode <= 1;
+    return HE_OK;
+}
+
 // The double-precision forward transform (bfly_fwd_f, fp_reduce, the reduction points of ntt_forward_f) run on the
 // host, stage by stage in the textbook loop order.
 int he_host_ntt_forward_fp64(he_ctx* ctx, uint32_t limb, const int64_t* in, uint64_t* out, double* max_over_q) {

@@ -32,7 +32,7 @@ EXPORTS = [
     "he_plan_create", "he_plan_destroy", "he_plan_workspace_bytes", "he_ct_pt_mac", "he_ct_pt_mac_static", "he_ct_pt_add", "he_rescale",
     "he_ntt_fwd", "he_ntt_inv", "he_check_reduced", "he_host_mulmod", "he_host_reduce128", "he_host_shoup_mulmod", "he_host_shoup_lazy",
     "he_host_mac_accumulate", "he_host_mac_accumulate_add", "he_host_mac_accumulate_lazy", "he_test_mac_for_rescale", "he_measure_rate",
-    "he_host_barrett64", "he_host_shoup32", "he_host_mac_three_product_terms", "he_host_mac_accumulate_three_products", "he_host_ntt_forward_fp64", "he_host_ntt_inverse_fp64", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
+    "he_host_barrett64", "he_host_shoup32", "he_host_mac_three_product_terms", "he_host_mac_accumulate_three_products", "he_host_ntt_forward_fp64", "he_host_ntt_inverse_fp64", "he_test_integer_transforms", "he_square_relin_workspace_bytes", "he_ct_square_relin", "he_pack32", "he_unpack32", "he_ct_pt_mac32", "he_ct_pt_add32", "he_rescale32", "he_ntt_fwd32", "he_ntt_inv32",
 ]
 
 _lib = None
@@ -88,6 +88,7 @@ def lib():
         "he_host_mac_accumulate_three_products": (u64, [vp, vp, sz, u64, u64]),
         "he_host_ntt_forward_fp64": (i32, [vp, u32, vp, vp, ctypes.POINTER(ctypes.c_double)]),
         "he_host_ntt_inverse_fp64": (i32, [vp, u32, vp, vp, ctypes.POINTER(ctypes.c_double)]),
+        "he_test_integer_transforms": (i32, [vp, i32]),
         "he_host_barrett64": (u32, [u64, u32]),
         "he_host_shoup32": (u32, [u32, u32, u32]),
         "he_pack32": (i32, [vp, vp, vp, sz, vp]),
@@ -161,6 +162,10 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def integer_transforms(self, integer_only: bool) -> None:
+        """he_test_integer_transforms: integer butterflies for every limb (True), or the default (False)."""
+        _check(lib().he_test_integer_transforms(self._h, int(bool(integer_only))), "he_test_integer_transforms")
 
     def host_ntt_forward_fp64(self, limb: int, values) -> "tuple[np.ndarray, float]":
         """he_host_ntt_forward_fp64: the double-precision forward transform run on the host.  values: N integers of

@@ -536,15 +536,18 @@ def test_rescale_matches_oracle(he, cfg):
         assert np.array_equal(host(ctx.rescale(dev(sub))), oracle.rescale(sub, c.q[:-1], ctx.psi[:-1]))
 
 
+@pytest.mark.parametrize("integer_only", [False, True])
 @pytest.mark.parametrize("log2N", [11, 14])
-def test_rescale_with_dropped_modulus_above_and_below_the_kept_ones(he, log2N):
+def test_rescale_with_dropped_modulus_above_and_below_the_kept_ones(he, log2N, integer_only):
     """The dropped modulus p against a kept q_i: p < q_i (t needs no reduction), q_i < p < 2 q_i, and p > 2 q_i
-    (a full reduction), for kept limbs of every butterfly mode (62-, 60-, 50-, 30-bit)."""
+    (a full reduction), for kept limbs of every butterfly mode (62-, 60-, 50-, 30-bit), with the limbs below 2^50 on
+    the double-precision transforms (the default) and on the integer butterflies."""
     N = 1 << log2N
     p50 = wl.ntt_primes(50, N, 30)
     q = [p50[29], wl.ntt_primes(30, N, 1)[0], wl.ntt_primes(62, N, 1)[0], wl.ntt_primes(60, N, 1)[0], p50[1], p50[0]]
     assert q[0] < q[-1] < 2 * q[0] and q[-1] > 2 * q[1] and q[-1] < q[2]
     ctx = he.Context(log2N, q)
+    ctx.integer_transforms(integer_only)
     ct = wl.uniform_residues((3, 2), q, N, 160 + log2N)
     ct[0, 0, -1] = 0
     ct[0, 1, -1] = q[-1] - 1
@@ -552,8 +555,42 @@ def test_rescale_with_dropped_modulus_above_and_below_the_kept_ones(he, log2N):
     # the 62-bit limb dropped (every kept limb far below it), and a 50-bit limb dropped under a 60-bit one
     for chain in ([q[0], q[1], q[3], q[2]], [q[3], q[1], q[4]]):
         ctx2 = he.Context(log2N, chain)
+        ctx2.integer_transforms(integer_only)
         ct2 = wl.uniform_residues((2, 2), chain, N, 170 + log2N)
         assert np.array_equal(host(ctx2.rescale(dev(ct2))), oracle.rescale(ct2, chain, ctx2.psi))
+
+
+@pytest.mark.parametrize("log2N", [10, 12, 13, 14])
+def test_integer_and_double_precision_transforms_give_the_same_residues(he, log2N):
+    """Limbs below 2^50 are transformed on double-precision FMAs, larger ones on integer butterflies.  With the
+    integer butterflies forced for every limb the transforms and the rescale still equal the oracle, so the two
+    arithmetics agree bit for bit (and the integer butterflies of small limbs stay tested)."""
+    N = 1 << log2N
+    q = wl.modulus_chain([60, 50, 49, 40, 31, 30], N)
+    ctx = he.Context(log2N, q)
+    a = wl.uniform_residues((5, 2), q, N, 3000 + log2N)
+    a[0, 0] = np.array(q, dtype=np.uint64)[:, None] - 1
+    a[0, 1] = 0
+    fwd, inv, res = oracle.ntt_fwd(a, q, ctx.psi), oracle.ntt_inv(a, q, ctx.psi), oracle.rescale(a, q, ctx.psi)
+    for integer_only in (True, False, True):
+        ctx.integer_transforms(integer_only)
+        d = dev(a)
+        ctx.ntt_fwd(d)
+        assert np.array_equal(host(d), fwd), integer_only
+        d = dev(a)
+        ctx.ntt_inv(d)
+        assert np.array_equal(host(d), inv), integer_only
+        assert np.array_equal(host(ctx.rescale(dev(a))), res), integer_only
+
+
+def test_config4_layer_is_the_same_with_integer_transforms(he):
+    """cfg4 at full size as one fused call: the 4096 outputs with the integer butterflies forced for every limb
+    equal those of the default (double-precision transforms for the 50-bit limbs), bit for bit."""
+    c, ctx, plan, ct, wenc, benc = scalar_layer_inputs(he, 4)
+    out = run_layer(he, c, ctx, plan, ct, wenc, he.PT_SCALAR, benc)
+    ctx.integer_transforms(True)
+    out_int = run_layer(he, c, ctx, plan, ct, wenc, he.PT_SCALAR, benc)
+    assert torch.equal(out, out_int)
 
 
 def test_maximum_sizes_and_degenerate_calls(he):
