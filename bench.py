@@ -56,6 +56,8 @@ def main() -> int:
                     help="also run three plain elementwise kernels over 2 GiB (counter calibration for rocprofv3 --pmc)")
     ap.add_argument("--no-rates", dest="rates", action="store_false",
                     help="skip the he_measure_rate probes (keeps a profiler's kernel list to the path's own kernels)")
+    ap.add_argument("--no-compare-arithmetic", dest="compare_arithmetic", action="store_false",
+                    help="skip the timing of cfg4's rescale with integer butterflies only (keeps a kernel trace's averages to the step's own launches)")
     ap.add_argument("--no-all-configs", dest="all_configs", action="store_false",
                     help="skip the per-config report of the five layers")
     ap.add_argument("--cpu-sample-cfg4", type=int, default=1024, help="cfg4 outputs the oracle is timed on")
@@ -371,7 +373,7 @@ def main() -> int:
 
     # ---- the two arithmetics of the transforms on the same launch: the limbs below 2^50 on double-precision FMAs (the
     # library's choice, timed above) against integer butterflies for every limb; the residues must be the same
-    if not only:
+    if not only and args.compare_arithmetic:
         ms_fp = timed(lambda: ctx.rescale(acc4, out=out4k))
         ctx.integer_transforms(True)
         out_int = torch.empty_like(out4k)
