@@ -410,6 +410,7 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
                 fwd_f[(size_t)i * N + k] = fp_centred(fwd[((size_t)i * N + k) * 2], ctx->q[i]);
                 inv_f[(size_t)i * N + k] = fp_centred(inv[((size_t)i * N + k) * 2], ctx->q[i]);
             }
+            inv_f[(size_t)i * N + 1] = fp_centred(ctx->limbs.c[i].w1n_inv, ctx->q[i]);  // last inverse stage: times N^-1
         }
         if (upload(&ctx->tw_fwd_f, fwd_f.data(), fwd_f.size()) != HE_OK || upload(&ctx->tw_inv_f, inv_f.data(), inv_f.size()) != HE_OK) {
             he_ctx_destroy(ctx);
@@ -458,6 +459,11 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
                 half[(size_t)l * HE_MAX_LIMBS + i] = (u64)(cur / 2);
                 rem = (u64)(cur % 2);
             }
+        }
+        // the entry of the last inverse stage carries N^-1 (the butterflies of that stage multiply by it anyway)
+        for (u32 i = 0; i < L; ++i) {
+            inv[((size_t)i * N + 1) * 2] = ctx->limbs.c[i].w1n_inv;
+            inv[((size_t)i * N + 1) * 2 + 1] = ctx->limbs.c[i].w1n_inv_shoup;
         }
         if (upload(&ctx->bad_count, (const u64*)nullptr, 1) != HE_OK ||
             upload(&ctx->garner, garner.data(), garner.size()) != HE_OK || upload(&ctx->half_digits, half.data(), half.size()) != HE_OK ||

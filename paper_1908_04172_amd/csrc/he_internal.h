@@ -58,7 +58,7 @@ struct he_ctx {
     DropConst drop[HE_MAX_LIMBS][HE_MAX_LIMBS];  // [dropped j][kept i]
     // device tables
     u64* tw_fwd;      // [L][N][2]: (psi^brv(k), Shoup companion), k in [0, N)
-    u64* tw_inv;      // [L][N][2]: (psi^-brv(k), Shoup companion)
+    u64* tw_inv;      // [L][N][2]: (psi^-brv(k), Shoup companion); entry 1, the last stage's, is psi^-brv(1) * N^-1
     double* tw_fwd_f; // [L][N]: psi^brv(k) as the double in (-q/2, q/2), for limbs below 2^50 (LimbConst::fp_ok), else zeros
     double* tw_inv_f; // [L][N]: the same for psi^-brv(k)
     double* fft_tw;   // [N/4][2]: e^(-2 pi i k / (N/2)), the twiddles of the encoder's complex FFT

@@ -28,11 +28,13 @@ __device__ __forceinline__ void run_pass(u64 (&a)[16], const PassTwiddles<LOGN, 
         for (u32 e = 0; e < 16; e++) {
             if (e & (1u << bit)) continue;
             if constexpr (INVERSE) {
-                if (s == 0) {  // merged with the multiplication by N^-1; the exact products end below 2q
+                if (s == 0) {  // merged with the multiplication by N^-1 (the table's entry of this stage is the
+                               // twiddle times N^-1); the exact products end below 2q
+                    const Twiddle w1n = pt.t[S::slot(k, e)];
                     u64 sum = a[e] + a[e | (1u << bit)];
                     u64 dif = a[e] + (MODE == 0 ? c.two_q : c.four_q) - a[e | (1u << bit)];
                     a[e] = shoup_mul_lazy(sum, c.n_inv, c.n_inv_shoup, c.q);
-                    a[e | (1u << bit)] = shoup_mul_lazy(dif, c.w1n_inv, c.w1n_inv_shoup, c.q);
+                    a[e | (1u << bit)] = shoup_mul_lazy(dif, w1n.w, w1n.w_shoup, c.q);
                 } else {
                     bfly_inv<MODE>(a[e], a[e | (1u << bit)], pt.t[S::slot(k, e)], c);
                 }
@@ -174,7 +176,7 @@ __device__ __forceinline__ void ntt_inverse(u64 (&a)[16], const u64* tw, u64* ld
 // of a four-stage pass are reduced again, so that no value exceeds 4.001q.
 template <int LOGN, int P>
 __device__ __forceinline__ void pass_inv_f(double (&a)[16], const TwiddleF* tw, double* lds, u32 tid, double q, double q_inv,
-                                           double n_inv, double w1n_inv) {
+                                           double n_inv) {
     using G = Geo<LOGN>;
     using S = PassShape<LOGN, P>;
     PassTwiddles<LOGN, P, TwiddleF> t;
@@ -194,10 +196,10 @@ __device__ __forceinline__ void pass_inv_f(double (&a)[16], const TwiddleF* tw, 
             if (e & (1u << bit)) continue;
             double& x = a[e];
             double& y = a[e | (1u << bit)];
-            if (s == 0) {  // merged with the multiplication by N^-1
+            if (s == 0) {  // merged with the multiplication by N^-1 (in the table's entry of this stage as well)
                 const double sum = x + y, dif = x - y;
                 x = fp_mulmod(n_inv, sum, q, q_inv);
-                y = fp_mulmod(w1n_inv, dif, q, q_inv);
+                y = fp_mulmod(t.t[S::slot(k, e)].w, dif, q, q_inv);
             } else {
                 bfly_inv_f(x, y, t.t[S::slot(k, e)], q, q_inv);
                 if (S::NST == 4 && kk == 1) x = fp_reduce(x, q, q_inv);
@@ -210,12 +212,12 @@ template <int LOGN>
 __device__ __forceinline__ void ntt_inverse_f(double (&a)[16], const double* tw, double* lds, u32 tid, const LimbConst& c) {
     using G = Geo<LOGN>;
     const double q = (double)c.q, q_inv = c.q_inv_f;
-    const double n_inv = fp_centred(c.n_inv, c.q), w1n_inv = fp_centred(c.w1n_inv, c.q);
+    const double n_inv = fp_centred(c.n_inv, c.q);
     const TwiddleF* t = reinterpret_cast<const TwiddleF*>(tw);
-    if constexpr (G::NPASS > 3) pass_inv_f<LOGN, 3>(a, t, lds, tid, q, q_inv, n_inv, w1n_inv);
-    if constexpr (G::NPASS > 2) pass_inv_f<LOGN, 2>(a, t, lds, tid, q, q_inv, n_inv, w1n_inv);
-    pass_inv_f<LOGN, 1>(a, t, lds, tid, q, q_inv, n_inv, w1n_inv);
-    pass_inv_f<LOGN, 0>(a, t, lds, tid, q, q_inv, n_inv, w1n_inv);
+    if constexpr (G::NPASS > 3) pass_inv_f<LOGN, 3>(a, t, lds, tid, q, q_inv, n_inv);
+    if constexpr (G::NPASS > 2) pass_inv_f<LOGN, 2>(a, t, lds, tid, q, q_inv, n_inv);
+    pass_inv_f<LOGN, 1>(a, t, lds, tid, q, q_inv, n_inv);
+    pass_inv_f<LOGN, 0>(a, t, lds, tid, q, q_inv, n_inv);
 }
 
 // The inverse transform of canonical values in the limb's form: on doubles for a limb below 2^50 (canonical
