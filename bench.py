@@ -527,6 +527,24 @@ def main() -> int:
                     "ciphertext at (2^14, 8) on its CPU" % n_sq}
         del ct_sq, evk, out_sq, down_sq, ws_sq
 
+    # ---- ring degree 2^15: rows beyond the LDS (one stage over global memory + two half-size transforms per row)
+    if not only and args.all_configs:
+        N15, n15 = 1 << 15, 512
+        q15 = wl.modulus_chain([60, 60] + [50] * 6, N15)
+        ctx15 = he.Context(15, q15)
+        ct15 = wl.uniform_residues_torch((n15, 2), q15, N15, 23, dev)
+        out15 = torch.empty((n15, 2, L - 1, N15), dtype=torch.int64, device=dev)
+        ms_r15 = timed(lambda: ctx15.rescale(ct15, out=out15), 5)
+        ms_f15 = timed(lambda: ctx15.ntt_fwd(ct15), 5)
+        bf15 = n15 * 2 * L * (N15 // 2) * 15
+        result["ring_degree_2_15"] = {
+            "rescale_ms": ms_r15, "rescaled_ct_per_s": n15 / (ms_r15 * 1e-3), "ntt_fwd_ms": ms_f15,
+            "ntt_fwd_G_butterflies_per_s": bf15 / (ms_f15 * 1e-3) / 1e9,
+            "what": "%d ciphertexts at N=2^15 with the moduli widths of the benchmark (2x60 + 6x50 bits): he_rescale, and "
+                    "he_ntt_fwd over all %d rows" % (n15, n15 * 2 * L)}
+        del ct15, out15
+        ctx15.close()
+
     print(json.dumps(result))
     if not same_as_one_call:
         print("bench.py: the two-call form of a layer differs from he_ct_pt_mac(HE_RESCALE)", file=sys.stderr)

@@ -48,7 +48,7 @@ typedef enum he_status {
 
 #define HE_MAX_LIMBS 16
 #define HE_MIN_LOG2N 10
-#define HE_MAX_LOG2N 14
+#define HE_MAX_LOG2N 15
 
 typedef struct he_ctx he_ctx;   /* moduli, roots, twiddle tables (device), per-limb constants */
 typedef struct he_plan he_plan; /* which ciphertext meets which plaintext in a layer */
@@ -62,6 +62,10 @@ const char* he_strerror(int status);
  * psi_i = the smallest primitive 2N-th root of unity modulo q_i; the NTT entry points are defined
  * with respect to it.  device >= 0 selects the GPU (tables are uploaded there); device = -1 makes a
  * host-only context on which only the *_host calls, he_ctx_info and the plan calls work.
+ * log2N in [HE_MIN_LOG2N, HE_MAX_LOG2N].  At log2N = 15 a row of residues no longer fits the LDS of a compute unit:
+ * he_ntt_fwd, he_ntt_inv and he_rescale (also inside he_ct_pt_mac with HE_RESCALE) run one butterfly stage over
+ * global memory and two half-size transforms per row, with the same results; he_encode_vector, he_decode_vector,
+ * he_ct_square_relin and the he_*32 calls return HE_ERR_ARG there.
  */
 int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* moduli, int device);
 int he_ctx_destroy(he_ctx* ctx);

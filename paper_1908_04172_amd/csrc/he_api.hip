@@ -460,10 +460,49 @@ int he_ctx_create(he_ctx** out, uint32_t log2N, uint32_t L, const uint64_t* modu
                 rem = (u64)(cur % 2);
             }
         }
-        // the entry of the last inverse stage carries N^-1 (the butterflies of that stage multiply by it anyway)
-        for (u32 i = 0; i < L; ++i) {
-            inv[((size_t)i * N + 1) * 2] = ctx->limbs.c[i].w1n_inv;
-            inv[((size_t)i * N + 1) * 2 + 1] = ctx->limbs.c[i].w1n_inv_shoup;
+        if (log2N <= 14) {
+            // the entry of the last inverse stage carries N^-1 (the butterflies of that stage multiply by it anyway)
+            for (u32 i = 0; i < L; ++i) {
+                inv[((size_t)i * N + 1) * 2] = ctx->limbs.c[i].w1n_inv;
+                inv[((size_t)i * N + 1) * 2 + 1] = ctx->limbs.c[i].w1n_inv_shoup;
+            }
+        } else {
+            // N = 2^15: a transform is one stage over global memory and two transforms of H = N/2 points (he_ntt.hip,
+            // ROWS_HALVES).  The tables become [L][2][H]: block (limb, half h) is the table of that half's transform,
+            // entry 2^s + r (stage s of the half = stage s + 1 of the whole, r < 2^s) being entry 2^(s+1) + h*2^s + r of
+            // the whole table; entry 0, which no half uses, holds the twiddle of the stage over global memory (entry 1 of
+            // the whole table); the inverse halves' entry 1 carries N^-1.
+            const size_t H = N / 2;
+            auto split = [&](auto& table, auto& table_f, bool inverse) {
+                auto whole = table;
+                for (u32 i = 0; i < L; ++i) {
+                    const u64 q = ctx->q[i];
+                    for (u32 h = 0; h < 2; ++h)
+                        for (size_t k = 0; k < H; ++k) {
+                            size_t src = 1;
+                            if (k > 0) {
+                                u32 st = 0;
+                                while ((size_t)2 << st <= k) ++st;  // 2^st <= k < 2^(st+1)
+                                src = ((size_t)2 << st) + ((size_t)h << st) + (k - ((size_t)1 << st));
+                            }
+                            u64 w = whole[((size_t)i * N + src) * 2];
+                            if (inverse && k == 1) w = h_mulmod(w, ctx->limbs.c[i].n_inv, q);
+                            const size_t dst = ((size_t)i * 2 + h) * H + k;
+                            table[dst * 2] = w;
+                            table[dst * 2 + 1] = h_shoup(w, q);
+                            table_f[dst] = ctx->limbs.c[i].fp_ok ? fp_centred(w, q) : 0.0;
+                        }
+                }
+            };
+            split(fwd, fwd_f, false);
+            split(inv, inv_f, true);
+            // (the double-precision tables were uploaded above in the whole-table layout: replace them)
+            if (hipMemcpy(ctx->tw_fwd_f, fwd_f.data(), fwd_f.size() * sizeof(double), hipMemcpyHostToDevice) != hipSuccess ||
+                hipMemcpy(ctx->tw_inv_f, inv_f.data(), inv_f.size() * sizeof(double), hipMemcpyHostToDevice) != hipSuccess) {
+                (void)hipGetLastError();
+                he_ctx_destroy(ctx);
+                return HE_ERR_DEVICE;
+            }
         }
         if (upload(&ctx->bad_count, (const u64*)nullptr, 1) != HE_OK ||
             upload(&ctx->garner, garner.data(), garner.size()) != HE_OK || upload(&ctx->half_digits, half.data(), half.size()) != HE_OK ||
@@ -527,6 +566,7 @@ int he_encode_vector(he_ctx* ctx, const double* slots, size_t n, double scale, u
                      void* stream) {
     int rc = check_level(ctx, limbs, 1);
     if (rc != HE_OK) return rc;
+    if (ctx->log2N > HE_MAX_LOG2N_IN_LDS) return HE_ERR_ARG;
     if (!(scale > 0.0) || !(scale <= 1.7976931348623157e308)) return HE_ERR_ARG;
     if (n == 0) return HE_OK;
     if (!slots || !out) return HE_ERR_ARG;
@@ -540,6 +580,7 @@ int he_decode_vector(he_ctx* ctx, const uint64_t* poly, size_t n, double scale, 
                      void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_level(ctx, limbs, 1);
     if (rc != HE_OK) return rc;
+    if (ctx->log2N > HE_MAX_LOG2N_IN_LDS) return HE_ERR_ARG;
     if (!(scale > 0.0) || !(scale <= 1.7976931348623157e308)) return HE_ERR_ARG;
     if (n == 0) return HE_OK;
     if (!poly || !slots) return HE_ERR_ARG;
@@ -822,7 +863,7 @@ int he_square_relin_workspace_bytes(const he_ctx* ctx, uint32_t limbs, uint32_t 
 
 int he_ct_square_relin(he_ctx* ctx, uint32_t limbs, const uint64_t* ct_in, uint32_t n, const uint64_t* evk,
                        uint64_t* ct_out, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!ctx) return HE_ERR_ARG;
+    if (!ctx || ctx->log2N > HE_MAX_LOG2N_IN_LDS) return HE_ERR_ARG;
     if (limbs < 1 || limbs + 1 > ctx->L) return HE_ERR_LEVEL;
     if (n == 0) return HE_OK;
     if (!ct_in || !evk || !ct_out) return HE_ERR_ARG;
@@ -845,6 +886,7 @@ int he_ct_square_relin(he_ctx* ctx, uint32_t limbs, const uint64_t* ct_in, uint3
 static int check_level32(const he_ctx* ctx, u32 limbs, u32 min_limbs) {
     int rc = check_level(ctx, limbs, min_limbs);
     if (rc != HE_OK) return rc;
+    if (ctx->log2N > HE_MAX_LOG2N_IN_LDS) return HE_ERR_ARG;
     for (u32 i = 0; i < limbs; ++i)
         if (!ctx->limbs32.c[i].ok) return HE_ERR_MODULUS;
     return HE_OK;
@@ -1065,7 +1107,7 @@ int he_test_integer_transforms(he_ctx* ctx, int integer_only) {
 // The double-precision forward transform (bfly_fwd_f, fp_reduce, the reduction points of ntt_forward_f) run on the
 // host, stage by stage in the textbook loop order.
 int he_host_ntt_forward_fp64(he_ctx* ctx, uint32_t limb, const int64_t* in, uint64_t* out, double* max_over_q) {
-    if (!ctx || !in || !out || limb >= ctx->L) return HE_ERR_ARG;
+    if (!ctx || !in || !out || limb >= ctx->L || ctx->log2N > 14) return HE_ERR_ARG;
     const LimbConst& c = ctx->limbs.c[limb];
     if (!c.fp_ok) return HE_ERR_MODULUS;
     const u32 N = ctx->N, log2N = ctx->log2N;
@@ -1109,7 +1151,7 @@ int he_host_ntt_forward_fp64(he_ctx* ctx, uint32_t limb, const int64_t* in, uint
 
 // The inverse transform the same way (bfly_inv_f, the reduction points of ntt_inverse_f).
 int he_host_ntt_inverse_fp64(he_ctx* ctx, uint32_t limb, const uint64_t* in, uint64_t* out, double* max_over_q) {
-    if (!ctx || !in || !out || limb >= ctx->L) return HE_ERR_ARG;
+    if (!ctx || !in || !out || limb >= ctx->L || ctx->log2N > 14) return HE_ERR_ARG;
     const LimbConst& c = ctx->limbs.c[limb];
     if (!c.fp_ok) return HE_ERR_MODULUS;
     const u32 N = ctx->N, log2N = ctx->log2N;

@@ -8,6 +8,11 @@
 #include "../../include/he.h"
 #include "he_arith.h"
 
+// The largest ring degree whose rows (8 * N bytes) fit the LDS of a compute unit: the transforms of larger rings are
+// split (he_ntt.hip), and the vector encoder and decoder, square + relinearisation and the packed 32-bit path, which are
+// built on one-row-per-workgroup kernels, stop here (HE_ERR_ARG above).
+#define HE_MAX_LOG2N_IN_LDS 14
+
 // Per-limb constants handed to kernels by value (16 x 80 B).
 struct LimbTable {
     LimbConst c[HE_MAX_LIMBS];

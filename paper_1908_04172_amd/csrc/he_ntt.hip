@@ -256,13 +256,23 @@ __device__ __forceinline__ u64 canon4(u64 v, u64 q, u64 two_q) {  // [0,4q) -> [
 // ciphertext, read from spread_src [..][2][limbs][N]: the quadratic component of a squared ciphertext.  The squares
 // are stored as they are (NTT form) at row r * (limbs + 1) + j of `aux`, the place of digit j under its own limb
 // among the expanded digits, and their inverse transform, digit j as coefficients, goes to row r of `data`.
-enum { ROWS_PLAIN = 0, ROWS_SPREAD = 1, ROWS_SQUARE = 2 };
+// KIND = ROWS_HALVES: the rows are the two halves of rows of 2N residues, a ring degree whose rows do not fit the LDS:
+// after the first stage of a forward transform of 2N points (before the last stage of an inverse one), which
+// split_top_kernel runs, each half is a transform of N points with twiddles of its own, laid out as a table of N
+// entries per (limb, half) (see he_ctx_create).  Work item w is half w % 2 of the long row (w / 2) * map.stride +
+// map.first, under limb map.limb_fixed if that is set, else under limb (long row) % limbs.
+enum { ROWS_PLAIN = 0, ROWS_SPREAD = 1, ROWS_SQUARE = 2, ROWS_HALVES = 3 };
+struct RowMap {
+    u32 stride, first, limb_fixed;  // limb_fixed = NO_LIMB: none
+};
+constexpr u32 NO_LIMB = 0xFFFFFFFFu;
 template <int LOGN, bool INVERSE, int KIND = ROWS_PLAIN>
 __global__ void __launch_bounds__(Geo<LOGN>::T)
 ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const double* tw_f_all, u32 rows,
-                const u64* spread_src = nullptr, u32 digits = 1, u32 last_id = 0, u64* aux = nullptr) {
+                const u64* spread_src = nullptr, u32 digits = 1, u32 last_id = 0, u64* aux = nullptr,
+                RowMap map = RowMap{1, 0, NO_LIMB}) {
     using G = Geo<LOGN>;
-    constexpr bool SPREAD = KIND == ROWS_SPREAD, SQUARE = KIND == ROWS_SQUARE;
+    constexpr bool SPREAD = KIND == ROWS_SPREAD, SQUARE = KIND == ROWS_SQUARE, HALVES = KIND == ROWS_HALVES;
     static_assert(!(SPREAD && INVERSE), "the digit expansion is a forward transform");
     static_assert(!SQUARE || INVERSE, "the squares are taken back to coefficients");
     constexpr int PIN = INVERSE ? G::NPASS - 1 : 0, POUT = INVERSE ? 0 : G::NPASS - 1;
@@ -285,6 +295,8 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
             return spread_src + (size_t)src_row * G::N;
         } else if constexpr (SQUARE) {
             return spread_src + ((size_t)(w / limbs) * 2 + 1) * limbs * G::N + (size_t)(w % limbs) * G::N;
+        } else if constexpr (HALVES) {
+            return data + ((size_t)((w >> 1) * map.stride + map.first) * 2 + (w & 1u)) * G::N;
         } else {
             return data + (size_t)w * G::N;
         }
@@ -300,11 +312,13 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
         const u32 tid = tid_i;
         u32 src_row_unused = 0;
         const u32 row = SPREAD ? spread_row(work, src_row_unused) : work;
-        const u32 limb = row % limbs;
+        const u32 long_row = (work >> 1) * map.stride + map.first;  // HALVES only
+        const u32 limb = HALVES ? (map.limb_fixed != NO_LIMB ? map.limb_fixed : long_row % limbs) : row % limbs;
         const LimbConst& c = lt.c[limb];
         // (digit expansion: the last position is the special prime, whose twiddles sit at its own limb's
         // place in the table; `lt` comes with that limb's constants at the last position)
-        const u32 tw_limb = SPREAD && limb == limbs - 1 ? last_id : limb;
+        // (halves: the table has a block of N entries per limb and half)
+        const u32 tw_limb = HALVES ? limb * 2 + (work & 1u) : SPREAD && limb == limbs - 1 ? last_id : limb;
         const u64* tw = tw_all + (size_t)tw_limb * G::N * 2;
         const bool fp = !INVERSE && c.fp_ok;  // the forward transform of a limb below 2^50 runs on doubles
         if constexpr (SPREAD) {
@@ -370,7 +384,7 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
 #pragma unroll
             for (u32 e = 0; e < 16; e++) asm volatile("" : "+v"(next[e]) :: "memory");
         }
-        u64* p = data + (size_t)row * G::N;
+        u64* p = HALVES ? const_cast<u64*>(source(work)) : data + (size_t)row * G::N;
 #pragma unroll
         for (u32 e = 0; e < 16; e++) p[reg_index<LOGN, POUT>(tid_s, e)] = a[e];
 #pragma unroll
@@ -500,6 +514,127 @@ rescale_kernel(LimbTable lt, DropRow drop, u32 limbs, u32 parts, const u64* in, 
     }
 }
 
+// ---- ring degree 2^15: a row (256 KiB) does not fit the LDS.  A transform of 2N = 2^15 points is its first stage
+// (last stage of the inverse), run by split_top_kernel over global memory, and two transforms of N = 2^14 points,
+// run by ntt_rows_kernel<14, ., ROWS_HALVES> with the twiddle tables laid out per half (he_ctx_create).
+
+constexpr u32 HALF_N = 1u << 14;
+
+// One butterfly per thread and step over the pairs (j, j + N) of `rows` long rows (mapped as in ROWS_HALVES):
+// forward (X, Y) -> (X + W*Y, X - W*Y), inverse (X, Y) -> (X + Y, (X - Y) * W), canonical in and out, W the
+// entry 0 of the limb's first table block (the root's power of the stage; N^-1 is applied by the halves).
+template <bool INVERSE>
+__global__ void __launch_bounds__(256) split_top_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, u32 rows, RowMap map) {
+    const size_t total = (size_t)rows * HALF_N;
+    for (size_t k = (size_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (size_t)gridDim.x * 256) {
+        const u32 r = (u32)(k / HALF_N), j = (u32)(k % HALF_N);
+        const u32 long_row = r * map.stride + map.first;
+        const u32 limb = map.limb_fixed != NO_LIMB ? map.limb_fixed : long_row % limbs;
+        const LimbConst& c = lt.c[limb];
+        const u64* tw = tw_all + (size_t)limb * 2 * HALF_N * 2;
+        const u64 w = tw[0], w_shoup = tw[1];
+        u64* p = data + (size_t)long_row * 2 * HALF_N;
+        const u64 x = p[j], y = p[j + HALF_N];
+        if constexpr (INVERSE) {
+            p[j] = add_mod(x, y, c.q);
+            p[j + HALF_N] = shoup_mul(sub_mod(x, y, c.q), w, w_shoup, c.q);
+        } else {
+            const u64 v = shoup_mul(y, w, w_shoup, c.q);
+            p[j] = add_mod(x, v, c.q);
+            p[j + HALF_N] = sub_mod(x, v, c.q);
+        }
+    }
+}
+
+u32 elementwise_grid(size_t total) { return (u32)std::min<size_t>((total + 255) / 256, 256 * 32); }
+
+// Transforms of `rows` long rows of 2^15 residues in place (mapped by `map`; tw / tw_f: the tables of the direction).
+int launch_split_transform(he_ctx* ctx, const LimbTable& lt, u32 limbs, u64* data, u32 rows, bool inverse, const u64* tw,
+                           const double* tw_f, RowMap map, hipStream_t s) {
+    using G = Geo<14>;
+    const size_t lds = (size_t)G::N * sizeof(u64);
+    const u32 halves = rows * 2;
+    const u32 grid = std::min<u32>(halves, 256);
+    if (inverse) {
+        static std::atomic<uint32_t> lds_allowed{0};
+        if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<14, true, ROWS_HALVES>, lds, ctx->device, lds_allowed, true)) return rc;
+        hipLaunchKernelGGL((ntt_rows_kernel<14, true, ROWS_HALVES>), dim3(grid), dim3(G::T), lds, s, lt, limbs, data, tw, tw_f, halves,
+                           (const u64*)nullptr, 1u, 0u, (u64*)nullptr, map);
+        hipLaunchKernelGGL((split_top_kernel<true>), dim3(elementwise_grid((size_t)rows * HALF_N)), dim3(256), 0, s, lt, limbs, data, tw,
+                           rows, map);
+    } else {
+        static std::atomic<uint32_t> lds_allowed{0};
+        if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<14, false, ROWS_HALVES>, lds, ctx->device, lds_allowed, true)) return rc;
+        hipLaunchKernelGGL((split_top_kernel<false>), dim3(elementwise_grid((size_t)rows * HALF_N)), dim3(256), 0, s, lt, limbs, data, tw,
+                           rows, map);
+        hipLaunchKernelGGL((ntt_rows_kernel<14, false, ROWS_HALVES>), dim3(grid), dim3(G::T), lds, s, lt, limbs, data, tw, tw_f, halves,
+                           (const u64*)nullptr, 1u, 0u, (u64*)nullptr, map);
+    }
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
+// The rescale at ring degree 2^15, in the output tensor itself: the dropped limb's rows are copied into the rows of
+// the last kept limb and brought back to coefficients there (t); one pass writes, for every kept limb i, t - h
+// reduced modulo q_i into row i (the last kept row in place: a thread reads its t before it writes); all rows are
+// transformed; the last pass combines them with the input rows: out_i = (x_i - correction_i) * p^-1.
+__global__ void __launch_bounds__(256) split_copy_last_kernel(u32 limbs, const u64* in, u64* out, u32 polys) {
+    const size_t total = (size_t)polys * 2 * HALF_N;
+    for (size_t k = (size_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (size_t)gridDim.x * 256) {
+        const size_t p = k / (2 * HALF_N), j = k % (2 * HALF_N);
+        out[(p * (limbs - 1) + (limbs - 2)) * 2 * HALF_N + j] = in[(p * limbs + (limbs - 1)) * 2 * HALF_N + j];
+    }
+}
+
+__global__ void __launch_bounds__(256) split_corrections_kernel(LimbTable lt, DropRow drop, u32 limbs, u64* out, u32 polys) {
+    const size_t total = (size_t)polys * 2 * HALF_N;
+    const u64 p_mod = lt.c[limbs - 1].q, half = p_mod >> 1;
+    for (size_t k = (size_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (size_t)gridDim.x * 256) {
+        const size_t p = k / (2 * HALF_N), j = k % (2 * HALF_N);
+        u64* rows = out + p * (limbs - 1) * 2 * HALF_N + j;
+        const u64 t = add_mod(rows[(size_t)(limbs - 2) * 2 * HALF_N], half, p_mod);  // (r + h) mod p
+        for (u32 i = 0; i + 1 < limbs; i++) {
+            const LimbConst& c = lt.c[i];
+            const u64 v = drop.d[i].reduce_mode == 0 ? t : reduce64(t, c);
+            rows[(size_t)i * 2 * HALF_N] = sub_mod(v, drop.d[i].half_mod, c.q);
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) split_combine_kernel(LimbTable lt, DropRow drop, u32 limbs, const u64* in, u64* out, u32 polys) {
+    const size_t total = (size_t)polys * (limbs - 1) * 2 * HALF_N;
+    for (size_t k = (size_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (size_t)gridDim.x * 256) {
+        const size_t row = k / (2 * HALF_N), j = k % (2 * HALF_N);
+        const size_t p = row / (limbs - 1);
+        const u32 i = (u32)(row % (limbs - 1));
+        const LimbConst& c = lt.c[i];
+        // x may be the unreduced accumulator of a fused layer (below 12q where LimbConst::mac_lazy allows it)
+        const u64 x = in[(p * limbs + i) * 2 * HALF_N + j];
+        out[k] = shoup_mul(x + c.q - out[k], drop.d[i].p_inv, drop.d[i].p_inv_shoup, c.q);
+    }
+}
+
+int launch_rescale_split(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* out, u32 n, hipStream_t s) {
+    LimbTable lt = ctx->limbs;
+    lt.c[limbs - 1] = ctx->limbs.c[drop_id];
+    DropRow row;
+    for (u32 i = 0; i < HE_MAX_LIMBS; i++) row.d[i] = ctx->drop[drop_id][i];
+    const u32 polys = 2 * n;
+    const size_t per_limb = (size_t)2 * HALF_N;
+    hipLaunchKernelGGL(split_copy_last_kernel, dim3(elementwise_grid((size_t)polys * per_limb)), dim3(256), 0, s, limbs, in, out, polys);
+    // the dropped limb's constants sit at position limbs - 1 of `lt`; its tables are found from that position
+    const u64* tw_inv = ctx->tw_inv + ((size_t)drop_id - (limbs - 1)) * per_limb * 2;
+    const double* tw_inv_f = ctx->tw_inv_f + ((size_t)drop_id - (limbs - 1)) * per_limb;
+    if (int rc = launch_split_transform(ctx, lt, limbs, out, polys, true, tw_inv, tw_inv_f, RowMap{limbs - 1, limbs - 2, limbs - 1}, s)) return rc;
+    hipLaunchKernelGGL(split_corrections_kernel, dim3(elementwise_grid((size_t)polys * per_limb)), dim3(256), 0, s, lt, row, limbs, out, polys);
+    if (int rc = launch_split_transform(ctx, lt, limbs - 1, out, polys * (limbs - 1), false, ctx->tw_fwd, ctx->tw_fwd_f, RowMap{1, 0, NO_LIMB}, s))
+        return rc;
+    hipLaunchKernelGGL(split_combine_kernel, dim3(elementwise_grid((size_t)polys * (limbs - 1) * per_limb)), dim3(256), 0, s, lt, row, limbs, in,
+                       out, polys);
+    HE_HIP(hipGetLastError());
+    return HE_OK;
+}
+
 template <int LOGN>
 int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipStream_t s) {
     using G = Geo<LOGN>;
@@ -597,6 +732,10 @@ int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hip
         case 12: return launch_ntt_t<12>(ctx, limbs, data, rows, inverse, s);
         case 13: return launch_ntt_t<13>(ctx, limbs, data, rows, inverse, s);
         case 14: return launch_ntt_t<14>(ctx, limbs, data, rows, inverse, s);
+        case 15:
+            if (rows > 0x3FFFFFFFu) return HE_ERR_RANGE;  // two halves per row
+            return launch_split_transform(ctx, ctx->limbs, limbs, data, rows, inverse, inverse ? ctx->tw_inv : ctx->tw_fwd,
+                                          inverse ? ctx->tw_inv_f : ctx->tw_fwd_f, RowMap{1, 0, NO_LIMB}, s);
     }
     return HE_ERR_ARG;
 }
@@ -649,6 +788,9 @@ int launch_rescale_drop(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64*
         case 12: return launch_rescale_t<12>(ctx, limbs, drop_id, in, out, n, s);
         case 13: return launch_rescale_t<13>(ctx, limbs, drop_id, in, out, n, s);
         case 14: return launch_rescale_t<14>(ctx, limbs, drop_id, in, out, n, s);
+        case 15:
+            if ((u64)n * 2 * (limbs - 1) > 0x3FFFFFFFull) return HE_ERR_RANGE;
+            return launch_rescale_split(ctx, limbs, drop_id, in, out, n, s);
     }
     return HE_ERR_ARG;
 }

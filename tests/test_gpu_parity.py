@@ -832,3 +832,88 @@ def test_encrypted_dense_layer_decrypts_to_float_layer(he):
         got = sc.decrypt(out[o], scale_out).real
         worst = max(worst, float(np.max(np.abs(got - want[:, o]) / np.maximum(1.0, np.abs(want[:, o])))))
     assert worst <= 2.0**-10, worst
+
+
+# ----------------------------------------------------------------------------- ring degree 2^15 (rows beyond the LDS)
+
+def test_ring_degree_2_15_transforms_and_rescale(he):
+    """log2N = 15: a row is 256 KiB and the transforms run as one stage over global memory plus two half-size
+    transforms.  he_ntt_fwd / he_ntt_inv against the oracle (the monomial X pins root and ordering, q-1 everywhere the
+    ranges), he_rescale against the oracle at two levels, with the limbs below 2^50 on either arithmetic."""
+    log2N, N = 15, 1 << 15
+    q = wl.modulus_chain([60, 50, 50, 40, 31], N)
+    ctx = he.Context(log2N, q)
+    assert ctx.psi == oracle.find_psis(q, N)
+    a = wl.uniform_residues((3, 2), q, N, 1500)
+    a[0, 0] = 0
+    a[0, 0, :, 1] = 1
+    a[0, 1] = np.array(q, dtype=np.uint64)[:, None] - 1
+    fwd, inv = oracle.ntt_fwd(a, q, ctx.psi), oracle.ntt_inv(a, q, ctx.psi)
+    res = oracle.rescale(a, q, ctx.psi)
+    sub = np.ascontiguousarray(a[:, :, :3])
+    res_sub = oracle.rescale(sub, q[:3], ctx.psi[:3])
+    for integer_only in (False, True):
+        ctx.integer_transforms(integer_only)
+        d = dev(a)
+        ctx.ntt_fwd(d)
+        assert np.array_equal(host(d), fwd), integer_only
+        ctx.ntt_inv(d)
+        assert np.array_equal(host(d), a), integer_only
+        d = dev(a)
+        ctx.ntt_inv(d)
+        assert np.array_equal(host(d), inv), integer_only
+        assert np.array_equal(host(ctx.rescale(dev(a))), res), integer_only
+        assert np.array_equal(host(ctx.rescale(dev(sub))), res_sub), integer_only
+    # lower level, one polynomial, one limb
+    b = wl.uniform_residues((1, 1), q[:1], N, 1501)
+    db = dev(b)
+    ctx.ntt_fwd(db)
+    assert np.array_equal(host(db), oracle.ntt_fwd(b, q[:1], ctx.psi[:1]))
+
+
+def test_ring_degree_2_15_layers_match_oracle(he):
+    """log2N = 15: the MAC kernels do not depend on the ring degree; a fused layer (scalar and full-polynomial
+    plaintexts, bias, one rescale per output) and the plaintext addition against the oracle on the irregular plan."""
+    log2N, N = 15, 1 << 15
+    q = wl.modulus_chain([60, 50, 50], N)
+    ctx = he.Context(log2N, q)
+    plan = irregular_plan(7, 15)
+    hp = ctx.plan(plan.n_in, plan.n_out, plan.n_pt, plan.off, plan.term_ct, plan.term_pt)
+    ct = wl.uniform_residues((plan.n_in, 2), q, N, 1510)
+    w = wl.uniform_residues((plan.n_pt,), q, 1, 1511)[..., 0]
+    bias = wl.uniform_residues((plan.n_out,), q, 1, 1512)[..., 0]
+    got = host(ctx.ct_pt_mac(hp, dev(ct), dev(w), he.PT_SCALAR, bias=dev(bias), flags=he.RESCALE))
+    want, n_rescales = oracle.layer(ct, q, ctx.psi, plan.off, plan.term_ct, plan.term_pt, w, oracle.PT_SCALAR, bias)
+    assert n_rescales == plan.n_out and np.array_equal(got, want)
+    assert np.array_equal(host(ctx.ct_pt_mac(hp, dev(ct), dev(w), he.PT_SCALAR, bias=dev(bias))),
+                          oracle.mac(ct, q, plan.off, plan.term_ct, plan.term_pt, w, oracle.PT_SCALAR, bias))
+    wp = wl.uniform_residues((plan.n_pt,), q, N, 1513)
+    got = host(ctx.ct_pt_mac(hp, dev(ct), dev(wp), he.PT_POLY, flags=he.RESCALE))
+    want, _ = oracle.layer(ct, q, ctx.psi, plan.off, plan.term_ct, plan.term_pt, wp, oracle.PT_POLY, None)
+    assert np.array_equal(got, want)
+    pt = wl.uniform_residues((plan.n_in,), q, 1, 1514)[..., 0]
+    d = dev(ct)
+    ctx.ct_pt_add(d, dev(pt), he.PT_SCALAR)
+    assert np.array_equal(host(d), oracle.add(ct, q, pt, oracle.PT_SCALAR))
+    bad = ctx.check_reduced(d)
+    assert bad == 0
+
+
+def test_ring_degree_2_15_calls_built_on_one_row_per_workgroup_are_refused(he):
+    """The vector encoder and decoder, square + relinearisation and the packed 32-bit path stop at log2N = 14:
+    HE_ERR_ARG at 15, with nothing enqueued."""
+    log2N, N = 15, 1 << 15
+    q = wl.modulus_chain([30, 30, 30], N)
+    ctx = he.Context(log2N, q)
+    z = torch.zeros((1, N // 2), dtype=torch.complex128, device="cuda")
+    poly = torch.zeros((1, 3, N), dtype=torch.int64, device="cuda")
+    ct = torch.zeros((1, 2, 2, N), dtype=torch.int64, device="cuda")
+    ct32 = torch.zeros((1, 2, 2, N), dtype=torch.int32, device="cuda")
+    evk = torch.zeros((2, 2, 3, N), dtype=torch.int64, device="cuda")
+    calls = [lambda: ctx.encode_vector(z, 2.0**20), lambda: ctx.decode_vector(poly, 2.0**20),
+             lambda: ctx.ct_square_relin(ct, evk), lambda: ctx.rescale32(ct32), lambda: ctx.ntt_fwd32(ct32)]
+    for f in calls:
+        with pytest.raises(he.HeError) as e:
+            f()
+        assert e.value.status == -1
+    assert torch.zeros(4, device="cuda").sum().item() == 0

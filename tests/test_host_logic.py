@@ -99,6 +99,7 @@ def test_context_validates_moduli():
     N = 1 << 12
     good = wl.modulus_chain([30, 30], N)
     he.Context(12, good, device=None).close()
+    he.Context(15, wl.modulus_chain([30, 60], 1 << 15), device=None).close()      # the largest ring degree
     bad_sets = [
         [good[0], good[0]],                      # repeated
         [good[0], good[1] + 2 * N],              # = 1 mod 2N but (here) composite
@@ -110,7 +111,7 @@ def test_context_validates_moduli():
         with pytest.raises(he.HeError) as e:
             he.Context(12, mods, device=None)
         assert e.value.status == -2
-    for log2N in (9, 15):
+    for log2N in (9, 16):
         with pytest.raises(he.HeError) as e:
             he.Context(log2N, good, device=None)
         assert e.value.status == -1
