@@ -163,6 +163,8 @@ void fill_limb_const(LimbConst& c, u64 q, u64 psi, u32 N) {
     c.fp_ok = q < (1ull << 50);
     c.pad = 0;
     c.q_inv_f = 1.0 / (double)q;  // (a double holds q exactly; the division rounds to nearest)
+    c.pow64 = (u64)((((u128)1) << 64) % q);
+    c.pow64_shoup = h_shoup(c.pow64, q);
     // three products per MAC term: the sum of (xa+xb)*(wa+wb) must fit 64 bits with xa+xb, wa+wb below 2^32,
     // and the total must stay within the one-word Barrett of acc_reduce_add (narrow limbs below 2^61)
     c.kara_terms = 0;

@@ -34,6 +34,7 @@ struct LimbConst {
     u32 fp_ok;        // 1: q < 2^50, the forward transform can run on double-precision FMAs (see bfly_fwd_f)
     u32 pad;
     double q_inv_f;   // 1 / q, rounded to nearest
+    u64 pow64, pow64_shoup;  // 2^64 mod q and its Shoup companion (acc_reduce_lazy)
 };
 
 HE_HD u64 mul_hi64(u64 a, u64 b) {
@@ -298,15 +299,19 @@ HE_HD u64 acc_reduce_add_lazy(const MacAcc& a, u64 addend, const LimbConst& c) {
     return ((u64)top << 32) | (u32)low;
 }
 
-// The same for the other limbs: the 128-bit Barrett remainder before its conditional subtractions, below 4q,
-// plus the addend (below 2q): below 6q.
-HE_HD u64 acc_reduce_lazy(MacAcc a, u64 addend, const LimbConst& c) {
-    acc_fold(a, c);
-    const u32 s2 = 2 * c.split_bits;
-    const u64 lo = a.lo | (a.mid << c.split_bits) | (a.hi << s2);
-    const u64 hi = a.hi >> (64 - s2);
-    const u64 qe = hi * c.ratio_hi + mul_hi64(lo, c.ratio_hi) + mul_hi64(hi, c.ratio_lo);
-    return lo - qe * c.q + addend;
+// The same for the other limbs (moduli below 2^62): two lazy Shoup products, below 4q each, plus the addend
+// (below 2q): below 10q.
+HE_HD u64 acc_reduce_lazy(const MacAcc& a, u64 addend, const LimbConst& c) {
+    // the value lo + mid * 2^s + hi * 2^(2s) as two words (it is below 2^128; the sums are used as they are)
+    const u32 s = c.split_bits;
+    const u64 mid_lo = a.mid << s, hi_lo = a.hi << (2 * s);
+    const u64 t = a.lo + mid_lo;
+    const u64 low = t + hi_lo;
+    const u64 high = (a.mid >> (64 - s)) + (a.hi >> (64 - 2 * s)) + (u64)(t < mid_lo) + (u64)(low < hi_lo);
+    // low + high * 2^64 = low * 1 + high * (2^64 mod q), each as a lazy Shoup product (below 4q; the companion of 1
+    // is floor(2^64 / q)), the addend and the first product being the starting values of the multiply-add chains
+    const u64 r0 = shoup_remainder_add(low, 1, shoup_quotient_cheap(low, c.ratio_hi), c.q, addend);
+    return shoup_remainder_add(high, c.pow64, shoup_quotient_cheap(high, c.pow64_shoup), c.q, r0);
 }
 
 HE_HD void acc_restart(MacAcc& a, const LimbConst& c) {  // reduce in place and keep accumulating

@@ -13,7 +13,8 @@
 // built on one-row-per-workgroup kernels, stop here (HE_ERR_ARG above).
 #define HE_MAX_LOG2N_IN_LDS 14
 
-// Per-limb constants handed to kernels by value (16 x 80 B).
+// Per-limb constants handed to kernels by value (16 x 168 B; with the other arguments of the largest kernel well
+// below the 4 KiB that kernel arguments may take).
 struct LimbTable {
     LimbConst c[HE_MAX_LIMBS];
 };
