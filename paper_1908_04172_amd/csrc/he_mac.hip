@@ -688,22 +688,28 @@ mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, 
 #pragma unroll
     for (int g = 0; g < 4 * G; g++) acc_clear(acc[g]);
     u32 f = 0, r = 0;
-    for (u32 t = 0; t < K; t++) {
+    // The operands of term t + 1 are requested before term t is multiplied: twice the bytes in flight per wave
+    // (the kernel is bound by HBM latency times the bytes outstanding).  Outputs beyond the group's count read the
+    // first output's plaintexts again (tp[g] points there) and are not stored.
+    ulonglong2 x0, x1, p[G];
+    auto request = [&](u32 t, ulonglong2& a0, ulonglong2& a1, ulonglong2 (&w)[G]) {
         const u64* xp = x_base + (size_t)tc[t] * ct_stride;
-        const ulonglong2 x0 = *reinterpret_cast<const ulonglong2*>(xp);
-        const ulonglong2 x1 = *reinterpret_cast<const ulonglong2*>(xp + comp_stride);
-        ulonglong2 p[G];
+        a0 = *reinterpret_cast<const ulonglong2*>(xp);
+        a1 = *reinterpret_cast<const ulonglong2*>(xp + comp_stride);
 #pragma unroll
         for (int g = 0; g < G; g++) {
             // read once: a non-temporal load keeps it from displacing the reused ciphertext rows in L2
-            if ((u32)g < tile.count) {
-                const u64* src = p_base + (size_t)tp[g][t] * pt_stride;
-                p[g].x = __builtin_nontemporal_load(src);
-                p[g].y = __builtin_nontemporal_load(src + 1);
-            } else {
-                p[g].x = p[g].y = 0;
-            }
+            const u64* src = p_base + (size_t)tp[g][t] * pt_stride;
+            w[g].x = __builtin_nontemporal_load(src);
+            w[g].y = __builtin_nontemporal_load(src + 1);
         }
+    };
+    if (K > 0) request(0, x0, x1, p);
+    for (u32 t = 0; t < K; t++) {
+        ulonglong2 x0n = x0, x1n = x1, pn[G];
+#pragma unroll
+        for (int g = 0; g < G; g++) pn[g] = p[g];
+        if (t + 1 < K) request(t + 1, x0n, x1n, pn);
         u32 xa[4], xb[4];  // [component][slot]
         split_operand(x0.x, c, xa[0], xb[0]);
         split_operand(x0.y, c, xa[1], xb[1]);
@@ -722,6 +728,10 @@ mac_poly_kernel(LimbTable lt, u32 limbs, u32 N, const Tile* tiles, u32 n_tiles, 
         ++f;
         ++r;
         if (t + 1 < K) housekeeping<4 * G>(acc, f, r, c.fold_every, c.reduce_every, c);
+        x0 = x0n;
+        x1 = x1n;
+#pragma unroll
+        for (int g = 0; g < G; g++) p[g] = pn[g];
     }
 #pragma unroll
     for (int g = 0; g < G; g++) {
