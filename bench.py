@@ -266,6 +266,9 @@ def main() -> int:
                                "4096 outputs) + cfg5 (dense 256->64, full-poly pt: MAC+lazy rescale, 64 outputs), "
                                "N=2^14, L=8 (2x60-bit + 6x50-bit)",
                    "value_definition": "algorithmic bytes of the step (inputs once + outputs once) / step time",
+                   "arithmetic": "residues are uint64; MAC, bias add and the rescale's combine step on 32-bit integer multiply-adds; "
+                                 "the transforms of the 50-bit limbs on double-precision FMAs, those of the 60-bit limbs on integer "
+                                 "Shoup butterflies (identical residues either way)",
                    "algorithmic_bytes_per_step": total_bytes},
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "rescaled_ct_per_s": n_rescaled / (ms_per_step * 1e-3),
