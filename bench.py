@@ -406,7 +406,7 @@ def main() -> int:
         result["decode_vector"] = {"ms": ms_dec, "vectors_per_s": n_vec / (ms_dec * 1e-3),
                                    "GBps": enc_bytes / (ms_dec * 1e-3) / 1e9,
                                    "max_abs_error_of_round_trip": float((dec_out - zs).abs().max().item()),
-                                   "what": "the inverse map on the same %d polynomials (copy + INTT kernel + lift/FFT kernel); "
+                                   "what": "the inverse map on the same %d polynomials (INTT kernel into the workspace + lift/FFT kernel); "
                                            "bytes = residues once + slots once" % n_vec}
         del zs, enc_out, dec_out, dec_ws
 

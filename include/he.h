@@ -113,8 +113,8 @@ int he_encode_vector(he_ctx* ctx, const double* slots, size_t n, double scale, u
  * m being the polynomial whose coefficients are the integers of smallest magnitude with the given
  * residues (an exact lift, then IEEE double arithmetic: a result is accurate to about
  * N * max|m_j| * 2^-53 * 4 * log2(N) / scale).  poly is not modified; workspace: device memory of at
- * least n*limbs*N*8 bytes (HE_ERR_WORKSPACE otherwise) that overlaps neither poly nor slots.  A copy
- * and two kernels on `stream`.
+ * least n*limbs*N*8 bytes (HE_ERR_WORKSPACE otherwise) that overlaps neither poly nor slots (it receives the
+ * coefficients).  Two kernels on `stream`.
  */
 int he_decode_vector(he_ctx* ctx, const uint64_t* poly, size_t n, double scale, uint32_t limbs,
                      double* slots, void* workspace, size_t workspace_bytes, void* stream);

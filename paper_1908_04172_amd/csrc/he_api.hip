@@ -593,8 +593,8 @@ int he_decode_vector(he_ctx* ctx, const uint64_t* poly, size_t n, double scale, 
         return HE_ERR_ARG;
     if ((rc = need_device(ctx)) != HE_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
-    HE_HIP(hipMemcpyAsync(workspace, poly, bytes, hipMemcpyDeviceToDevice, s));
-    if ((rc = launch_ntt(ctx, limbs, (u64*)workspace, (u32)n, true, s)) != HE_OK) return rc;
+    // the inverse transform reads the caller's rows and writes the workspace
+    if ((rc = launch_ntt(ctx, limbs, (u64*)workspace, (u32)n, true, s, poly)) != HE_OK) return rc;
     return launch_decode_vector(ctx, limbs, (const u64*)workspace, (u32)n, scale, slots, s);
 }
 

@@ -149,7 +149,7 @@ enum : u32 {
 int check_mac_launch(he_ctx* ctx, const he_plan* plan, u32 limbs, int pt_kind);
 int launch_mac(he_ctx* ctx, const he_plan* plan, u32 limbs, const u64* ct_in, const u64* pt, int pt_kind,
                const u64* bias, u64* out, u64* wtab, u32 accumulate, hipStream_t s);
-int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s);
+int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s, const u64* src = nullptr);
 int launch_rescale(he_ctx* ctx, u32 limbs, const u64* in, u64* out, u32 n, hipStream_t s);
 int launch_rate(he_ctx* ctx, int kind, u32 limb, u32 iters, double* ops_per_s);
 int launch_rescale_drop(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* out, u32 n, hipStream_t s);

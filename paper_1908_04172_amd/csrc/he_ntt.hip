@@ -298,7 +298,8 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
         } else if constexpr (HALVES) {
             return data + ((size_t)((w >> 1) * map.stride + map.first) * 2 + (w & 1u)) * G::N;
         } else {
-            return data + (size_t)w * G::N;
+            // (plain rows: from `spread_src` if the caller gave one, the transform then being out of place)
+            return (spread_src != nullptr ? spread_src : data) + (size_t)w * G::N;
         }
     };
     {
@@ -636,7 +637,7 @@ int launch_rescale_split(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64
 }
 
 template <int LOGN>
-int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipStream_t s) {
+int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, const u64* src, hipStream_t s) {
     using G = Geo<LOGN>;
     const size_t lds = (size_t)G::N * sizeof(u64);
     // as many workgroups as stay resident at once (LDS and the 2048 threads of a compute unit bound
@@ -646,11 +647,11 @@ int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, hipS
     if (inverse) {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true>, lds, ctx->device, lds_allowed, true)) return rc;
-        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, ctx->tw_inv_f, rows);
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, ctx->tw_inv_f, rows, src);
     } else {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false>, lds, ctx->device, lds_allowed, true)) return rc;
-        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd, ctx->tw_fwd_f, rows);
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd, ctx->tw_fwd_f, rows, src);
     }
     HE_HIP(hipGetLastError());
     return HE_OK;
@@ -721,19 +722,21 @@ int launch_rescale_t(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64* ou
 
 }  // namespace
 
-int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s) {
+// src: where the rows are read from (nullptr: from `data`, in place); not available at ring degree 2^15
+int launch_ntt(he_ctx* ctx, u32 limbs, u64* data, u32 n_polys, bool inverse, hipStream_t s, const u64* src) {
     const u64 rows64 = (u64)n_polys * limbs;
     if (rows64 == 0) return HE_OK;
     if (rows64 > 0x7FFFFFFFull) return HE_ERR_RANGE;
     const u32 rows = (u32)rows64;
     switch (ctx->log2N) {
-        case 10: return launch_ntt_t<10>(ctx, limbs, data, rows, inverse, s);
-        case 11: return launch_ntt_t<11>(ctx, limbs, data, rows, inverse, s);
-        case 12: return launch_ntt_t<12>(ctx, limbs, data, rows, inverse, s);
-        case 13: return launch_ntt_t<13>(ctx, limbs, data, rows, inverse, s);
-        case 14: return launch_ntt_t<14>(ctx, limbs, data, rows, inverse, s);
+        case 10: return launch_ntt_t<10>(ctx, limbs, data, rows, inverse, src, s);
+        case 11: return launch_ntt_t<11>(ctx, limbs, data, rows, inverse, src, s);
+        case 12: return launch_ntt_t<12>(ctx, limbs, data, rows, inverse, src, s);
+        case 13: return launch_ntt_t<13>(ctx, limbs, data, rows, inverse, src, s);
+        case 14: return launch_ntt_t<14>(ctx, limbs, data, rows, inverse, src, s);
         case 15:
             if (rows > 0x3FFFFFFFu) return HE_ERR_RANGE;  // two halves per row
+            if (src != nullptr) return HE_ERR_ARG;
             return launch_split_transform(ctx, ctx->limbs, limbs, data, rows, inverse, inverse ? ctx->tw_inv : ctx->tw_fwd,
                                           inverse ? ctx->tw_inv_f : ctx->tw_fwd_f, RowMap{1, 0, NO_LIMB}, s);
     }
