@@ -550,8 +550,9 @@ __global__ void __launch_bounds__(256) split_top_kernel(LimbTable lt, u32 limbs,
 u32 elementwise_grid(size_t total) { return (u32)std::min<size_t>((total + 255) / 256, 256 * 32); }
 
 // Transforms of `rows` long rows of 2^15 residues in place (mapped by `map`; tw / tw_f: the tables of the direction).
+// top_done: the stage over global memory has been run by the caller (forward only).
 int launch_split_transform(he_ctx* ctx, const LimbTable& lt, u32 limbs, u64* data, u32 rows, bool inverse, const u64* tw,
-                           const double* tw_f, RowMap map, hipStream_t s) {
+                           const double* tw_f, RowMap map, hipStream_t s, bool top_done = false) {
     using G = Geo<14>;
     const size_t lds = (size_t)G::N * sizeof(u64);
     const u32 halves = rows * 2;
@@ -566,8 +567,9 @@ int launch_split_transform(he_ctx* ctx, const LimbTable& lt, u32 limbs, u64* dat
     } else {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<14, false, ROWS_HALVES>, lds, ctx->device, lds_allowed, true)) return rc;
-        hipLaunchKernelGGL((split_top_kernel<false>), dim3(elementwise_grid((size_t)rows * HALF_N)), dim3(256), 0, s, lt, limbs, data, tw,
-                           rows, map);
+        if (!top_done)
+            hipLaunchKernelGGL((split_top_kernel<false>), dim3(elementwise_grid((size_t)rows * HALF_N)), dim3(256), 0, s, lt, limbs, data,
+                               tw, rows, map);
         hipLaunchKernelGGL((ntt_rows_kernel<14, false, ROWS_HALVES>), dim3(grid), dim3(G::T), lds, s, lt, limbs, data, tw, tw_f, halves,
                            (const u64*)nullptr, 1u, 0u, (u64*)nullptr, map);
     }
@@ -577,8 +579,9 @@ int launch_split_transform(he_ctx* ctx, const LimbTable& lt, u32 limbs, u64* dat
 
 // The rescale at ring degree 2^15, in the output tensor itself: the dropped limb's rows are copied into the rows of
 // the last kept limb and brought back to coefficients there (t); one pass writes, for every kept limb i, t - h
-// reduced modulo q_i into row i (the last kept row in place: a thread reads its t before it writes); all rows are
-// transformed; the last pass combines them with the input rows: out_i = (x_i - correction_i) * p^-1.
+// reduced modulo q_i into row i, already through the first stage of its forward transform (the last kept row in
+// place: a thread reads its two values of t before it writes); the half rows are transformed; the last pass combines
+// them with the input rows: out_i = (x_i - correction_i) * p^-1.
 __global__ void __launch_bounds__(256) split_copy_last_kernel(u32 limbs, const u64* in, u64* out, u32 polys) {
     const size_t total = (size_t)polys * 2 * HALF_N;
     for (size_t k = (size_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (size_t)gridDim.x * 256) {
@@ -587,17 +590,24 @@ __global__ void __launch_bounds__(256) split_copy_last_kernel(u32 limbs, const u
     }
 }
 
-__global__ void __launch_bounds__(256) split_corrections_kernel(LimbTable lt, DropRow drop, u32 limbs, u64* out, u32 polys) {
-    const size_t total = (size_t)polys * 2 * HALF_N;
+// (with the first stage of the corrections' forward transforms: a thread takes the pair (j, j + N/2) of its polynomial)
+__global__ void __launch_bounds__(256) split_corrections_kernel(LimbTable lt, DropRow drop, u32 limbs, u64* out, const u64* tw_fwd, u32 polys) {
+    const size_t total = (size_t)polys * HALF_N;
     const u64 p_mod = lt.c[limbs - 1].q, half = p_mod >> 1;
     for (size_t k = (size_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (size_t)gridDim.x * 256) {
-        const size_t p = k / (2 * HALF_N), j = k % (2 * HALF_N);
+        const size_t p = k / HALF_N, j = k % HALF_N;
         u64* rows = out + p * (limbs - 1) * 2 * HALF_N + j;
-        const u64 t = add_mod(rows[(size_t)(limbs - 2) * 2 * HALF_N], half, p_mod);  // (r + h) mod p
+        const u64* r = rows + (size_t)(limbs - 2) * 2 * HALF_N;
+        const u64 t0 = add_mod(r[0], half, p_mod), t1 = add_mod(r[HALF_N], half, p_mod);  // (r + h) mod p
         for (u32 i = 0; i + 1 < limbs; i++) {
             const LimbConst& c = lt.c[i];
-            const u64 v = drop.d[i].reduce_mode == 0 ? t : reduce64(t, c);
-            rows[(size_t)i * 2 * HALF_N] = sub_mod(v, drop.d[i].half_mod, c.q);
+            const DropConst& d = drop.d[i];
+            const u64 x = sub_mod(d.reduce_mode == 0 ? t0 : reduce64(t0, c), d.half_mod, c.q);
+            const u64 y = sub_mod(d.reduce_mode == 0 ? t1 : reduce64(t1, c), d.half_mod, c.q);
+            const u64* tw = tw_fwd + (size_t)i * 2 * HALF_N * 2;  // entry 0 of the limb's first block: the stage's twiddle
+            const u64 v = shoup_mul(y, tw[0], tw[1], c.q);
+            rows[(size_t)i * 2 * HALF_N] = add_mod(x, v, c.q);
+            rows[(size_t)i * 2 * HALF_N + HALF_N] = sub_mod(x, v, c.q);
         }
     }
 }
@@ -627,8 +637,10 @@ int launch_rescale_split(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64
     const u64* tw_inv = ctx->tw_inv + ((size_t)drop_id - (limbs - 1)) * per_limb * 2;
     const double* tw_inv_f = ctx->tw_inv_f + ((size_t)drop_id - (limbs - 1)) * per_limb;
     if (int rc = launch_split_transform(ctx, lt, limbs, out, polys, true, tw_inv, tw_inv_f, RowMap{limbs - 1, limbs - 2, limbs - 1}, s)) return rc;
-    hipLaunchKernelGGL(split_corrections_kernel, dim3(elementwise_grid((size_t)polys * per_limb)), dim3(256), 0, s, lt, row, limbs, out, polys);
-    if (int rc = launch_split_transform(ctx, lt, limbs - 1, out, polys * (limbs - 1), false, ctx->tw_fwd, ctx->tw_fwd_f, RowMap{1, 0, NO_LIMB}, s))
+    hipLaunchKernelGGL(split_corrections_kernel, dim3(elementwise_grid((size_t)polys * HALF_N)), dim3(256), 0, s, lt, row, limbs, out,
+                       ctx->tw_fwd, polys);
+    if (int rc = launch_split_transform(ctx, lt, limbs - 1, out, polys * (limbs - 1), false, ctx->tw_fwd, ctx->tw_fwd_f, RowMap{1, 0, NO_LIMB}, s,
+                                        /*top_done=*/true))
         return rc;
     hipLaunchKernelGGL(split_combine_kernel, dim3(elementwise_grid((size_t)polys * (limbs - 1) * per_limb)), dim3(256), 0, s, lt, row, limbs, in,
                        out, polys);
