@@ -388,6 +388,29 @@ def main() -> int:
             "ms_double_precision_below_2^50": ms_fp, "ms_integer_butterflies_only": ms_int, "same_residues": same,
             "what": "he_rescale on cfg4's accumulators with he_test_integer_transforms off / on"}
 
+    # ---- the batched transforms on their own (he_ntt_fwd / he_ntt_inv over cfg4's 65 536 accumulator rows, in place)
+    if not only:
+        rows_t = p4.n_out * 2 * L
+        bfl = rows_t * (N // 2) * c4.log2N
+        acc4.copy_(wl.uniform_residues_torch((p4.n_out, 2), q, N, 31, dev))     # canonical residues
+        ms_nf = timed(lambda: ctx.ntt_fwd(acc4))
+        ms_ni = timed(lambda: ctx.ntt_inv(acc4))
+        def at_rate(kinds):
+            return sum((rows_t // L) * (N // 2) * c4.log2N / rate(kinds(i), i) for i in range(L)) * 1e3 if args.rates else None
+        fp_l = [qi < (1 << 50) for qi in q]
+        ideal_f = at_rate(lambda i: he.RATE_BUTTERFLY_FP64 if fp_l[i] else fwd_kind[mode[i]])
+        ideal_i = at_rate(lambda i: he.RATE_BUTTERFLY_FP64_INV if fp_l[i] else he.RATE_BUTTERFLY_INV if mode[i] else he.RATE_BUTTERFLY_MODE0)
+        result["transforms"] = {
+            "rows": rows_t, "ntt_fwd_ms": ms_nf, "ntt_inv_ms": ms_ni,
+            "ntt_fwd_T_butterflies_per_s": bfl / (ms_nf * 1e-3) / 1e12, "ntt_inv_T_butterflies_per_s": bfl / (ms_ni * 1e-3) / 1e12,
+            "ntt_fwd_Tmul32_per_s": bfl * MUL32_PER_SHOUP / (ms_nf * 1e-3) / 1e12,
+            "ntt_fwd_frac_of_integer_peak": bfl * MUL32_PER_SHOUP / (ms_nf * 1e-3) / 1e12 / INT_MUL32_PEAK_TOPS,
+            "ntt_fwd_frac_of_measured_rate": None if ideal_f is None else ideal_f / ms_nf,
+            "ntt_inv_frac_of_measured_rate": None if ideal_i is None else ideal_i / ms_ni,
+            "GBps_fwd": rows_t * N * 16 / (ms_nf * 1e-3) / 1e9,
+            "what": "he_ntt_fwd and he_ntt_inv in place over %d rows of N=2^14 (2 x 60-bit + 6 x 50-bit limbs); a butterfly counts "
+                    "%d 32-bit multiplies as in the rescale's roofline" % (rows_t, MUL32_PER_SHOUP)}
+
     # ---- Alg. 1 on the GPU: the plaintext polynomials a layer like cfg5 consumes, encoded from slots
     if not only:
         n_vec = 1024

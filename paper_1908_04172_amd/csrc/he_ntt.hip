@@ -244,9 +244,9 @@ __device__ __forceinline__ u64 canon4(u64 v, u64 q, u64 two_q) {  // [0,4q) -> [
     return v >= q ? v - q : v;
 }
 
-// In-place transforms of `rows` rows of N residues, row r under limb r % limbs.  A workgroup takes
-// rows blockIdx.x, blockIdx.x + gridDim.x, ... and requests its next row before it stores the
-// current one, so that the loads do not queue behind the stores and arrive while those drain.
+// In-place transforms of `rows` rows of N residues, row r under limb r % limbs.  A workgroup takes one row of every
+// slab of gridDim.x rows (a different place in each slab, see the loop) and requests its next row before it stores
+// the current one, so that the loads do not queue behind the stores and arrive while those drain.
 // KIND = ROWS_SPREAD (forward only): a row is not read from `data` but from a row of `spread_src`, a table of
 // coefficient rows [..][digits][N] whose row (.., j) holds integers below q_j; they are reduced
 // modulo the target limb first.  This is the digit expansion of a key switch: each
@@ -264,6 +264,7 @@ __device__ __forceinline__ u64 canon4(u64 v, u64 q, u64 two_q) {  // [0,4q) -> [
 enum { ROWS_PLAIN = 0, ROWS_SPREAD = 1, ROWS_SQUARE = 2, ROWS_HALVES = 3 };
 struct RowMap {
     u32 stride, first, limb_fixed;  // limb_fixed = NO_LIMB: none
+    u32 rotate = 0;                 // 1: workgroups change their place from slab to slab (see the loop of ntt_rows_kernel)
 };
 constexpr u32 NO_LIMB = 0xFFFFFFFFu;
 template <int LOGN, bool INVERSE, int KIND = ROWS_PLAIN>
@@ -307,7 +308,28 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = p[reg_index<LOGN, PIN>(threadIdx.x, e)];
     }
-    for (u32 work = blockIdx.x; work < rows; work += gridDim.x) {
+    // Work items are taken in slabs of gridDim.x, workgroup b taking item (b + k / hold) % gridDim.x of slab k: with a plain
+    // stride a workgroup would meet the same limb in every slab whenever the limb count divides the grid, and the
+    // workgroups of the wide limbs (integer butterflies) would finish long after those of the narrow ones.
+    // The place moves on every `hold` slabs only: the workgroups of an XCD are at the same limb at any time (they are
+    // dispatched round-robin, so they share blockIdx.x % 8), and its L2 keeps that limb's twiddle table for `hold` rows
+    // per workgroup instead of fetching another one for every row.
+    // The launcher asks for this (map.rotate) only when the limbs differ in cost: with equal limbs the plain stride is a
+    // few per cent faster.
+    const u32 slabs = (rows + gridDim.x - 1) / gridDim.x;
+    const u32 hold = min(8u, max(1u, slabs / (2 * limbs)));  // (once per workgroup)
+    // (the place and the slab are stepped, not computed: no division in the loop)
+    u32 place = blockIdx.x, held = 0;
+    u32 work = blockIdx.x;  // < rows: the grid has at most `rows` workgroups
+    while (true) {
+        // this workgroup's item of the next slab, or `rows` if there is none
+        u32 next_place = place, next_held = held + 1;
+        if (map.rotate && next_held == hold) {
+            next_held = 0;
+            next_place = place + 1 == gridDim.x ? 0 : place + 1;
+        }
+        const u32 next_base = work - place + gridDim.x;
+        const u32 next_work = next_base < rows && next_base + next_place < rows ? next_base + next_place : rows;
         u32 tid_i = threadIdx.x;  // opaque per iteration: addresses are recomputed, not kept live
         asm volatile("" : "+v"(tid_i));
         const u32 tid = tid_i;
@@ -355,8 +377,8 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
         u64 next[16];
 #pragma unroll
         for (u32 e = 0; e < 16; e++) next[e] = 0;
-        if (work + gridDim.x < rows) {
-            const u64* p = source(work + gridDim.x);
+        if (next_work < rows) {
+            const u64* p = source(next_work);
 #pragma unroll
             for (u32 e = 0; e < 16; e++) next[e] = p[reg_index<LOGN, PIN>(tid_s, e)];
         }
@@ -390,6 +412,10 @@ ntt_rows_kernel(LimbTable lt, u32 limbs, u64* data, const u64* tw_all, const dou
         for (u32 e = 0; e < 16; e++) p[reg_index<LOGN, POUT>(tid_s, e)] = a[e];
 #pragma unroll
         for (u32 e = 0; e < 16; e++) a[e] = next[e];
+        if (next_work >= rows) break;
+        work = next_work;
+        place = next_place;
+        held = next_held;
     }
 }
 
@@ -547,6 +573,15 @@ __global__ void __launch_bounds__(256) split_top_kernel(LimbTable lt, u32 limbs,
     }
 }
 
+// Whether the first `limbs` limbs of a table differ in the arithmetic their transforms run on (double precision, or
+// one of the integer butterflies' modes), i.e. in cost per row.
+u32 limbs_differ(const LimbTable& lt, u32 limbs) {
+    auto kind = [&](u32 i) { return lt.c[i].fp_ok ? 3u : lt.c[i].ntt_mode; };
+    for (u32 i = 1; i < limbs; i++)
+        if (kind(i) != kind(0)) return 1;
+    return 0;
+}
+
 u32 elementwise_grid(size_t total) { return (u32)std::min<size_t>((total + 255) / 256, 256 * 32); }
 
 // Transforms of `rows` long rows of 2^15 residues in place (mapped by `map`; tw / tw_f: the tables of the direction).
@@ -557,6 +592,7 @@ int launch_split_transform(he_ctx* ctx, const LimbTable& lt, u32 limbs, u64* dat
     const size_t lds = (size_t)G::N * sizeof(u64);
     const u32 halves = rows * 2;
     const u32 grid = std::min<u32>(halves, 256);
+    if (map.limb_fixed == NO_LIMB) map.rotate = limbs_differ(lt, limbs);
     if (inverse) {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<14, true, ROWS_HALVES>, lds, ctx->device, lds_allowed, true)) return rc;
@@ -651,6 +687,7 @@ int launch_rescale_split(he_ctx* ctx, u32 limbs, u32 drop_id, const u64* in, u64
 template <int LOGN>
 int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, const u64* src, hipStream_t s) {
     using G = Geo<LOGN>;
+    const RowMap map{1, 0, NO_LIMB, limbs_differ(ctx->limbs, limbs)};
     const size_t lds = (size_t)G::N * sizeof(u64);
     // as many workgroups as stay resident at once (LDS and the 2048 threads of a compute unit bound
     // that), each looping over its share of the rows
@@ -659,11 +696,11 @@ int launch_ntt_t(he_ctx* ctx, u32 limbs, u64* data, u32 rows, bool inverse, cons
     if (inverse) {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, true>, lds, ctx->device, lds_allowed, true)) return rc;
-        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, ctx->tw_inv_f, rows, src);
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, true>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_inv, ctx->tw_inv_f, rows, src, 1u, 0u, (u64*)nullptr, map);
     } else {
         static std::atomic<uint32_t> lds_allowed{0};
         if (int rc = allow_dynamic_lds((const void*)ntt_rows_kernel<LOGN, false>, lds, ctx->device, lds_allowed, true)) return rc;
-        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd, ctx->tw_fwd_f, rows, src);
+        hipLaunchKernelGGL((ntt_rows_kernel<LOGN, false>), dim3(grid), dim3(G::T), lds, s, ctx->limbs, limbs, data, ctx->tw_fwd, ctx->tw_fwd_f, rows, src, 1u, 0u, (u64*)nullptr, map);
     }
     HE_HIP(hipGetLastError());
     return HE_OK;
