@@ -103,11 +103,13 @@ struct GarnerInv {
     u64 inv, inv_shoup;  // q_k^-1 mod q_i and its Shoup companion, at [i * HE_MAX_LIMBS + k]
 };
 
+// (LMAX: a compile-time bound on `limbs`, 8 or HE_MAX_LIMBS: the unrolled loops and the digit registers are that many)
+template <int LMAX>
 __device__ __forceinline__ double lift_centred(const u64* col, size_t limb_stride, u32 limbs, const LimbTable& lt,
                                                const GarnerInv* g, const u64* half_digits) {
-    u64 v[HE_MAX_LIMBS];
+    u64 v[LMAX];
 #pragma unroll
-    for (u32 i = 0; i < HE_MAX_LIMBS; i++) {
+    for (u32 i = 0; i < (u32)LMAX; i++) {
         if (i < limbs) {
             const LimbConst& c = lt.c[i];
             u64 t = col[i * limb_stride];
@@ -121,7 +123,7 @@ __device__ __forceinline__ double lift_centred(const u64* col, size_t limb_strid
     }
     bool above = false, decided = false;
 #pragma unroll
-    for (int i = HE_MAX_LIMBS - 1; i >= 0; i--) {
+    for (int i = LMAX - 1; i >= 0; i--) {
         if ((u32)i < limbs && !decided && v[i] != half_digits[i]) {
             above = v[i] > half_digits[i];
             decided = true;
@@ -130,7 +132,7 @@ __device__ __forceinline__ double lift_centred(const u64* col, size_t limb_strid
     if (above) {  // digits of Q - x = (Q - 1 - x) + 1
         bool carry = true;
 #pragma unroll
-        for (u32 i = 0; i < HE_MAX_LIMBS; i++) {
+        for (u32 i = 0; i < (u32)LMAX; i++) {
             if (i < limbs) {
                 u64 d = lt.c[i].q - 1 - v[i];
                 if (carry) {
@@ -144,12 +146,12 @@ __device__ __forceinline__ double lift_centred(const u64* col, size_t limb_strid
     }
     double acc = 0.0;
 #pragma unroll
-    for (int i = HE_MAX_LIMBS - 1; i >= 0; i--)
+    for (int i = LMAX - 1; i >= 0; i--)
         if ((u32)i < limbs) acc = acc * (double)lt.c[i].q + (double)v[i];
     return above ? -acc : acc;
 }
 
-template <int LOGN>
+template <int LOGN, int LMAX>
 __global__ void __launch_bounds__((1 << LOGN) / 16)
 decode_vector_kernel(LimbTable lt, u32 limbs, const u64* coef, double inv_scale, const GarnerInv* garner,
                      const u64* half_digits, const cplx* fft_tw, const cplx* twist, cplx* slots) {
@@ -159,8 +161,8 @@ decode_vector_kernel(LimbTable lt, u32 limbs, const u64* coef, double inv_scale,
     const u32 tid = threadIdx.x;
     const u64* rows = coef + (size_t)blockIdx.x * limbs * N;
     for (u32 j = tid; j < n; j += T) {
-        const double re = lift_centred(rows + j, N, limbs, lt, garner, half_digits) * inv_scale;
-        const double im = lift_centred(rows + n + j, N, limbs, lt, garner, half_digits) * inv_scale;
+        const double re = lift_centred<LMAX>(rows + j, N, limbs, lt, garner, half_digits) * inv_scale;
+        const double im = lift_centred<LMAX>(rows + n + j, N, limbs, lt, garner, half_digits) * inv_scale;
         const cplx tw = twist[j];
         buf[j] = cmul(cplx{re, im}, cplx{tw.re, -tw.im});  // times xi^j
     }
@@ -202,14 +204,18 @@ template <int LOGN>
 int launch_decode_t(he_ctx* ctx, u32 limbs, const u64* coef, u32 n, double scale, double* slots, hipStream_t s) {
     constexpr u32 N = 1u << LOGN;
     const size_t lds = (size_t)N * 8;
-    static std::atomic<uint32_t> lds_allowed{0};
-    if (int rc = allow_dynamic_lds((const void*)decode_vector_kernel<LOGN>, lds, ctx->device, lds_allowed)) return rc;
-    hipLaunchKernelGGL((decode_vector_kernel<LOGN>), dim3(n), dim3(N / 16), lds, s, ctx->limbs, limbs, coef, 1.0 / scale,
-                       reinterpret_cast<const GarnerInv*>(ctx->garner), ctx->half_digits + (size_t)limbs * HE_MAX_LIMBS,
-                       reinterpret_cast<const cplx*>(ctx->fft_tw), reinterpret_cast<const cplx*>(ctx->twist),
-                       reinterpret_cast<cplx*>(slots));
-    HE_HIP(hipGetLastError());
-    return HE_OK;
+    auto launch = [&](auto kernel, std::atomic<uint32_t>& lds_allowed) -> int {
+        if (int rc = allow_dynamic_lds((const void*)kernel, lds, ctx->device, lds_allowed)) return rc;
+        hipLaunchKernelGGL(kernel, dim3(n), dim3(N / 16), lds, s, ctx->limbs, limbs, coef, 1.0 / scale,
+                           reinterpret_cast<const GarnerInv*>(ctx->garner), ctx->half_digits + (size_t)limbs * HE_MAX_LIMBS,
+                           reinterpret_cast<const cplx*>(ctx->fft_tw), reinterpret_cast<const cplx*>(ctx->twist),
+                           reinterpret_cast<cplx*>(slots));
+        HE_HIP(hipGetLastError());
+        return HE_OK;
+    };
+    static std::atomic<uint32_t> lds_allowed_8{0}, lds_allowed_all{0};
+    if (limbs <= 8) return launch(decode_vector_kernel<LOGN, 8>, lds_allowed_8);
+    return launch(decode_vector_kernel<LOGN, HE_MAX_LIMBS>, lds_allowed_all);
 }
 
 }  // namespace
